@@ -1,0 +1,202 @@
+/*
+ * pkv.h -- C ABI of the paged-KV decode-attention / KV-block-swap library for
+ * AMD CDNA4 (gfx950).
+ *
+ * The paper (arXiv 2602.07878) studies a serving stack whose decode step
+ * streams the whole KV history of every running request from HBM (Sec. 4.2,
+ * the un-numbered execution-time model T_exec ~ N_ctx * d * sizeof(T) / BW_HBM)
+ * out of a cache that is partitioned into fixed-size, physically
+ * non-contiguous blocks (Sec. 2.2, "KV-Cache"), and whose scheduler, on
+ * preemption, moves a victim's KV blocks out of the pool and back (Sec. 5.1.2,
+ * "Swapping").  This library implements those two data-parallel operations.
+ *
+ * General conventions
+ *  - Every data pointer is a DEVICE pointer owned by the caller unless the
+ *    parameter name ends in `_host`.  The library allocates no device memory,
+ *    keeps no state between calls and never synchronises: all work is enqueued
+ *    on `hip_stream` (a hipStream_t passed as void*; NULL = default stream).
+ *  - Inputs are only read; `out`, `workspace` and `dst` are overwritten.
+ *  - Every base pointer must be 16-byte aligned and every stride must keep
+ *    16-byte alignment of a token row (PKV_ERR_ALIGN otherwise).
+ *  - Anything checkable on the host is checked before any kernel is enqueued;
+ *    on a non-zero status nothing was enqueued.  Values that live in device
+ *    memory (block ids, context lengths, mapping entries) are NOT checked on
+ *    the fast path; out-of-range values there are undefined behaviour.  The
+ *    pkv_validate_* calls copy them to the host (synchronising) and check them.
+ */
+#ifndef PKV_H
+#define PKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum pkv_status {
+  PKV_OK = 0,
+  PKV_ERR_NULL = 1,      /* a required pointer is NULL                          */
+  PKV_ERR_SHAPE = 2,     /* a size is non-positive, inconsistent or unsupported */
+  PKV_ERR_DTYPE = 3,     /* unknown / unsupported element type                  */
+  PKV_ERR_ALIGN = 4,     /* pointer or stride breaks the 16-byte rule           */
+  PKV_ERR_WORKSPACE = 5, /* workspace smaller than pkv_attn_workspace_bytes()   */
+  PKV_ERR_INDEX = 6,     /* (validators only) an index is out of range          */
+  PKV_ERR_HIP = 7        /* the HIP runtime reported an error on launch         */
+} pkv_status;
+
+typedef enum pkv_dtype { PKV_F32 = 0, PKV_BF16 = 1 } pkv_dtype;
+
+/*
+ * Geometry of one paged_decode_attention call (one layer, one decode step).
+ *
+ * Notation: B sequences, Hq query heads, Hkv KV heads, G = Hq/Hkv (query heads
+ * g*G .. g*G+G-1 share KV head g), D head dim, bs tokens per block, n_i the
+ * context length of sequence i INCLUDING the token being decoded (its K/V are
+ * already in the pool; this call never writes KV).
+ *
+ * Pool layout: element (block b, kv head g, token slot s, dim d) of K lives at
+ *   k_pool[b*k_stride_block + g*k_stride_head + s*k_stride_token + d]
+ * (strides in ELEMENTS, d is unit stride); likewise V.  The recommended layout
+ * is head-major [num_pool_blocks][Hkv][bs][D] (a 4 KiB contiguous tile per
+ * (block, head) for bf16, D = 128, bs = 16).
+ */
+typedef struct pkv_attn_desc {
+  int32_t batch;              /* B  >= 0 (0 enqueues nothing)                    */
+  int32_t num_q_heads;        /* Hq, a multiple of num_kv_heads                  */
+  int32_t num_kv_heads;       /* Hkv                                             */
+  int32_t head_dim;           /* D; row bytes D*sizeof(elem) must be 128/256/512 */
+  int32_t block_size;         /* bs, a multiple of 16                            */
+  int32_t num_pool_blocks;    /* blocks in k_pool / v_pool (validators only)     */
+  int32_t max_blocks_per_seq; /* row stride (entries) of block_tables            */
+  int32_t max_context_len;    /* host-known upper bound of all n_i; sizes grid   */
+  int32_t partition_tokens;   /* split-K partition, multiple of 64; 0 = default  */
+  int32_t kv_dtype;           /* pkv_dtype of q, k_pool and v_pool               */
+  int32_t out_dtype;          /* pkv_dtype of out: PKV_F32 or PKV_BF16           */
+  int32_t reserved;           /* must be 0                                       */
+  int64_t k_stride_block, k_stride_head, k_stride_token;
+  int64_t v_stride_block, v_stride_head, v_stride_token;
+} pkv_attn_desc;
+
+/*
+ * Geometry of one kv_block_swap call.  The pool is seen as `num_planes` planes
+ * (layers x {K,V}); plane p of the source starts at src + p*src_plane_stride
+ * bytes and holds src_num_blocks chunks of block_bytes bytes each, back to
+ * back; the same for dst.
+ */
+typedef struct pkv_swap_desc {
+  int32_t num_planes;             /* >= 1                                        */
+  int32_t src_num_blocks;         /* chunks per source plane                     */
+  int32_t dst_num_blocks;         /* chunks per destination plane                */
+  int32_t reserved;               /* must be 0                                   */
+  int64_t block_bytes;            /* bytes per (plane, block) chunk; mult. of 16 */
+  int64_t src_plane_stride_bytes; /* >= src_num_blocks*block_bytes, mult. of 16  */
+  int64_t dst_plane_stride_bytes; /* >= dst_num_blocks*block_bytes, mult. of 16  */
+} pkv_swap_desc;
+
+/* Library version as major*10000 + minor*100 + patch. */
+int32_t pkv_version(void);
+
+/* Static, NUL-terminated name of a status code ("PKV_OK", ...). */
+const char* pkv_status_string(int32_t status);
+
+/*
+ * Split-K partition length in tokens the library will use for `desc`
+ * (desc->partition_tokens, or the default when that is 0).  Returns 0 if
+ * desc is NULL or the value is unsupported.
+ */
+int32_t pkv_attn_partition_tokens(const pkv_attn_desc* desc);
+
+/*
+ * Bytes of device scratch paged_decode_attention needs for `desc`: fp32
+ * partial results (running max, normaliser, un-normalised output row) per
+ * (sequence, query head, partition) of the flash-decoding split of the context
+ * named by the paper's kernel profile ("splitkv", Sec. 4.2 / App. "System
+ * Profile").  Returns 0 when no workspace is needed (every context fits one
+ * partition) and also when desc is invalid (the attention call reports why).
+ */
+size_t pkv_attn_workspace_bytes(const pkv_attn_desc* desc);
+
+/*
+ * Decode attention over a paged KV pool (Sec. 2.2 "KV-Cache": fixed-size
+ * non-contiguous blocks; Sec. 4.2: every step streams the whole KV history).
+ * For each sequence i and query head h (KV head g = h / G), with
+ * K_t, V_t the rows of logical token t = 0..n_i-1 found at block
+ * block_tables[i*max_blocks_per_seq + t/bs], slot t%bs:
+ *     s_t = scale * <q[i,h,:], K_t>,   w = softmax_t(s),
+ *     out[i,h,:] = sum_t w_t * V_t.
+ * n_i = 0 gives a zero row.  Slots >= n_i of the last block, blocks not named
+ * by the first ceil(n_i/bs) table entries, and table entries beyond those are
+ * never read.
+ *
+ *  q            [B][Hq][D]   kv_dtype, contiguous
+ *  k_pool/v_pool             kv_dtype, layout per desc strides
+ *  block_tables [B][max_blocks_per_seq] int32 physical block ids
+ *  context_lens [B] int32, 0 <= n_i <= max_context_len
+ *  scale        softmax scale (callers normally pass 1/sqrt(D))
+ *  out          [B][Hq][D]   out_dtype, contiguous
+ *  workspace    >= pkv_attn_workspace_bytes(desc) bytes, 16-byte aligned; may
+ *               be NULL when that size is 0.  Contents on return are
+ *               unspecified.
+ * Accumulation is fp32.  The result does not depend on where blocks sit in
+ * the pool; for a fixed partition length it is bit-reproducible run to run.
+ */
+int32_t paged_decode_attention(const pkv_attn_desc* desc, const void* q,
+                               const void* k_pool, const void* v_pool,
+                               const int32_t* block_tables,
+                               const int32_t* context_lens, float scale,
+                               void* out, void* workspace,
+                               size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Block gather/scatter of the preemption swap path (Sec. 5.1.2 "Swapping":
+ * the victim's KV blocks leave the pool and are later migrated back, in
+ * general to different physical blocks).  For every plane p and every pair
+ * j < n_pairs with (s, d) = (block_mapping[2j], block_mapping[2j+1]):
+ *   copy block_bytes bytes from src_pool + p*src_plane_stride_bytes + s*block_bytes
+ *                            to dst      + p*dst_plane_stride_bytes + d*block_bytes.
+ * Gather (pool -> contiguous staging) and scatter (staging -> fresh blocks)
+ * are this same call with the roles of pool and staging exchanged.  The copy
+ * is bytewise exact.  src and dst must not overlap; a destination block named
+ * twice is a data race (undefined); a source block may repeat.  n_pairs = 0
+ * enqueues nothing.
+ */
+int32_t kv_block_swap(const pkv_swap_desc* desc, const void* src_pool,
+                      void* dst, const int32_t* block_mapping,
+                      int32_t n_pairs, void* hip_stream);
+
+/*
+ * Host-side range checks of the index arrays the fast path trusts.
+ * *_host variants take HOST pointers and touch no GPU; the others take device
+ * pointers, copy them to the host on `hip_stream` and wait for that copy.
+ * Return PKV_ERR_INDEX for: n_i < 0 or > max_context_len or needing more than
+ * max_blocks_per_seq blocks; a used table entry outside [0, num_pool_blocks);
+ * a mapping entry outside its plane; a destination block named twice.
+ */
+int32_t pkv_validate_tables_host(const pkv_attn_desc* desc,
+                                 const int32_t* block_tables_host,
+                                 const int32_t* context_lens_host);
+int32_t pkv_validate_mapping_host(const pkv_swap_desc* desc,
+                                  const int32_t* block_mapping_host,
+                                  int32_t n_pairs);
+int32_t pkv_validate_tables(const pkv_attn_desc* desc,
+                            const int32_t* block_tables,
+                            const int32_t* context_lens, void* hip_stream);
+int32_t pkv_validate_mapping(const pkv_swap_desc* desc,
+                             const int32_t* block_mapping, int32_t n_pairs,
+                             void* hip_stream);
+
+/*
+ * Bandwidth probes used by the benchmark to measure this machine's streaming
+ * ceilings with the same access idiom as the product kernels (16 bytes per
+ * lane): pkv_probe_copy copies `bytes` (multiple of 16) from src to dst;
+ * pkv_probe_read reads `bytes` from src and writes one 16-byte checksum per
+ * workgroup to `sink` (>= 64 KiB).
+ */
+int32_t pkv_probe_copy(const void* src, void* dst, size_t bytes, void* hip_stream);
+int32_t pkv_probe_read(const void* src, void* sink, size_t bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PKV_H */

@@ -1,0 +1,140 @@
+"""fp64 CPU oracle -- TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the benchmark's CPU-baseline leg may import
+this package; the product path (the HIP library and its binding) never does.
+The arithmetic lives in ``pkv_oracle.c`` (plain C, fp64, straight from the
+definition); this file only compiles it with gcc and marshals numpy arrays.
+
+bfloat16 tensors are passed as ``numpy.uint16`` arrays holding the raw bits.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+import threading
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "pkv_oracle.c")
+_LIB = os.path.join(_HERE, "libpkv_oracle.so")
+_lock = threading.Lock()
+_lib = None
+
+F32, BF16 = 0, 1
+
+
+def build(force: bool = False) -> str:
+    """Compile pkv_oracle.c into libpkv_oracle.so next to it (gcc, OpenMP)."""
+    with _lock:
+        stale = (not os.path.exists(_LIB)
+                 or os.path.getmtime(_LIB) < os.path.getmtime(_SRC))
+        if force or stale:
+            tmp = _LIB + f".tmp{os.getpid()}"
+            subprocess.check_call(
+                ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared",
+                 "-ffp-contract=off", "-Wall", "-Wextra", "-o", tmp, _SRC, "-lm"])
+            os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        i32, i64, vp = ctypes.c_int, ctypes.c_int64, ctypes.c_void_p
+        lib.orc_paged_decode_attention.restype = ctypes.c_int
+        lib.orc_paged_decode_attention.argtypes = (
+            [i32] * 8 + [i64] * 6 + [vp] * 5 + [ctypes.c_float, vp, vp, i32])
+        lib.orc_kv_block_swap.restype = ctypes.c_int
+        lib.orc_kv_block_swap.argtypes = [i32, i64, i64, i64, i32, i32, vp, vp, vp, i32]
+        lib.orc_num_threads.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def num_threads() -> int:
+    return int(_load().orc_num_threads())
+
+
+def _dtype_code(a: np.ndarray) -> int:
+    if a.dtype == np.float32:
+        return F32
+    if a.dtype == np.uint16:
+        return BF16
+    raise TypeError(f"oracle takes float32 or uint16 (bf16 bits), got {a.dtype}")
+
+
+def _ptr(a: np.ndarray) -> int:
+    return a.ctypes.data
+
+
+def paged_decode_attention(q, k_pool, v_pool, block_tables, context_lens, scale,
+                           *, block_size, k_strides=None, v_strides=None,
+                           return_weights=False):
+    """out[i,h,:] = softmax_t(scale * q[i,h] . K_t) @ V over the paged pool.
+
+    q [B,Hq,D]; k_pool/v_pool [num_blocks,Hkv,bs,D] C-contiguous unless
+    element strides (block, head, token) are given, in which case the pools may
+    be any 1-D/N-D contiguous buffers and ``Hkv`` is taken from ``k_pool.shape[1]``.
+    Returns float64 [B,Hq,D] (and the weights [B,Hq,max_ctx] when asked).
+    """
+    lib = _load()
+    q = np.ascontiguousarray(q)
+    k_pool = np.ascontiguousarray(k_pool)
+    v_pool = np.ascontiguousarray(v_pool)
+    bt = np.ascontiguousarray(block_tables, dtype=np.int32)
+    cl = np.ascontiguousarray(context_lens, dtype=np.int32)
+    code = _dtype_code(q)
+    if _dtype_code(k_pool) != code or _dtype_code(v_pool) != code:
+        raise TypeError("q, k_pool, v_pool must share one dtype")
+    B, Hq, D = q.shape
+    nblk, Hkv = k_pool.shape[0], k_pool.shape[1]
+    if k_strides is None:
+        assert k_pool.shape == (nblk, Hkv, block_size, D), k_pool.shape
+        k_strides = (Hkv * block_size * D, block_size * D, D)
+    if v_strides is None:
+        assert v_pool.shape == (nblk, Hkv, block_size, D), v_pool.shape
+        v_strides = (Hkv * block_size * D, block_size * D, D)
+    assert bt.ndim == 2 and bt.shape[0] == B and cl.shape == (B,)
+    out = np.empty((B, Hq, D), dtype=np.float64)
+    max_ctx = int(cl.max()) if (return_weights and B > 0) else 0
+    w = np.zeros((B, Hq, max_ctx), dtype=np.float64) if return_weights else None
+    rc = lib.orc_paged_decode_attention(
+        B, Hq, Hkv, D, block_size, nblk, bt.shape[1], code,
+        *[int(x) for x in k_strides], *[int(x) for x in v_strides],
+        _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(bt), _ptr(cl),
+        float(np.float32(scale)), _ptr(out), _ptr(w) if w is not None else None,
+        max_ctx)
+    if rc != 0:
+        raise IndexError(f"oracle: index outside pool/table (code {rc})")
+    return (out, w) if return_weights else out
+
+
+def kv_block_swap(src, dst, mapping, *, num_planes, block_bytes,
+                  src_plane_stride=None, dst_plane_stride=None,
+                  src_num_blocks=None, dst_num_blocks=None):
+    """Bytewise block copy src -> dst (uint8 views, dst modified in place)."""
+    lib = _load()
+    s8 = src.reshape(-1).view(np.uint8)
+    d8 = dst.reshape(-1).view(np.uint8)
+    assert s8.flags.c_contiguous and d8.flags.c_contiguous and d8.flags.writeable
+    mp = np.ascontiguousarray(mapping, dtype=np.int32).reshape(-1, 2)
+    if src_plane_stride is None:
+        src_plane_stride = s8.size // num_planes
+    if dst_plane_stride is None:
+        dst_plane_stride = d8.size // num_planes
+    if src_num_blocks is None:
+        src_num_blocks = src_plane_stride // block_bytes
+    if dst_num_blocks is None:
+        dst_num_blocks = dst_plane_stride // block_bytes
+    assert (num_planes - 1) * src_plane_stride + src_num_blocks * block_bytes <= s8.size
+    assert (num_planes - 1) * dst_plane_stride + dst_num_blocks * block_bytes <= d8.size
+    rc = lib.orc_kv_block_swap(num_planes, block_bytes, src_plane_stride,
+                               dst_plane_stride, src_num_blocks, dst_num_blocks,
+                               _ptr(s8), _ptr(d8), _ptr(mp), mp.shape[0])
+    if rc != 0:
+        raise IndexError("oracle: mapping entry outside its plane")
+    return dst

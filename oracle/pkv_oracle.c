@@ -1,0 +1,176 @@
+/*
+ * pkv_oracle.c -- TEST INFRASTRUCTURE, not part of the product.
+ *
+ * Slow, plain CPU reference for the two operations of the library: decode
+ * attention over a paged KV pool and the block copy of the preemption swap
+ * path.  Everything is computed in fp64 straight from the definition; there is
+ * no blocking, no online softmax, no reordering.  It shares no code, header or
+ * table with the GPU implementation and takes only host pointers.
+ *
+ * What is computed and where it comes from (arXiv 2602.07878):
+ *  - Sec. 2.2 "KV-Cache": the cache is cut into fixed-size blocks that are
+ *    non-contiguous in physical memory -> a per-sequence table of physical
+ *    block ids; logical token t lives in table entry t / block_size at slot
+ *    t % block_size.
+ *  - Sec. 2.1 / Sec. 4.2: each decode step attends from the one new query to
+ *    the K/V of all tokens so far (the whole history is streamed every step).
+ *    The paper prints no attention formula; the standard scaled dot-product
+ *    attention of its reference [attention] is used:
+ *        s_t = scale * sum_d q_d K_{t,d},  w = softmax(s),  out = sum_t w_t V_t.
+ *  - Sec. 5.1.2 "Swapping": a victim's blocks are copied out of the pool and
+ *    later copied back (to other physical blocks) -> a per-(plane, block)
+ *    memcpy driven by a list of (source block, destination block) pairs.
+ *
+ * Pins (tests/test_oracle_pins.py): 1-token context, identical keys, block
+ * placement permutation, token-order permutation, weight sum / convex hull,
+ * key shift invariance, one-hot limit, GQA = replicated MHA, split-merge
+ * algebra, a library attention routine in fp64, exact-rational brute force on
+ * tiny inputs, NaN poison outside the defined reads; for the copy: identity,
+ * permutation and inverse, round trip, untouched bytes.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { ORC_F32 = 0, ORC_BF16 = 1 };
+
+/* bfloat16 = the upper 16 bits of an IEEE-754 binary32: widening is exact. */
+static double bf16_bits_to_double(uint16_t bits) {
+  uint32_t w = ((uint32_t)bits) << 16;
+  float f;
+  memcpy(&f, &w, sizeof f);
+  return (double)f;
+}
+
+static double load_elem(const void* base, int64_t index, int dtype) {
+  if (dtype == ORC_BF16) return bf16_bits_to_double(((const uint16_t*)base)[index]);
+  return (double)((const float*)base)[index];
+}
+
+/*
+ * Decode attention, one call = all sequences and query heads.
+ *   q            [B][Hq][D]                         (dtype)
+ *   k_pool       element (b,g,s,d) at b*ksb + g*ksh + s*kst + d   (dtype)
+ *   v_pool       same with vsb, vsh, vst
+ *   block_tables [B][max_blocks_per_seq] int32
+ *   context_lens [B] int32  (n_i counts every token whose K/V is in the pool)
+ *   out          [B][Hq][D] double
+ *   weights_out  optional [B][Hq][max_ctx] double: softmax weights (tests)
+ * Returns 0, or a negative number for an index that leaves the pool/table.
+ */
+int orc_paged_decode_attention(
+    int B, int Hq, int Hkv, int D, int block_size, int num_pool_blocks,
+    int max_blocks_per_seq, int dtype, int64_t ksb, int64_t ksh, int64_t kst,
+    int64_t vsb, int64_t vsh, int64_t vst, const void* q, const void* k_pool,
+    const void* v_pool, const int32_t* block_tables,
+    const int32_t* context_lens, float scale, double* out, double* weights_out,
+    int max_ctx) {
+  if (Hkv <= 0 || Hq % Hkv != 0) return -1;
+  const int G = Hq / Hkv;
+  int status = 0;
+
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+  for (int i = 0; i < B; ++i) {
+    for (int h = 0; h < Hq; ++h) {
+      const int n = context_lens[i];
+      double* o = out + ((int64_t)i * Hq + h) * D;
+      for (int d = 0; d < D; ++d) o[d] = 0.0;
+      if (n <= 0) continue; /* empty context: zero row, nothing is read */
+      if ((n + block_size - 1) / block_size > max_blocks_per_seq) {
+#pragma omp atomic write
+        status = -2;
+        continue;
+      }
+      const int g = h / G; /* contiguous groups of G query heads per KV head */
+
+      /* 1. gather the n rows of K and V contiguously, exactly, as fp64 */
+      double* Kc = (double*)malloc(sizeof(double) * (size_t)n * D);
+      double* Vc = (double*)malloc(sizeof(double) * (size_t)n * D);
+      double* s = (double*)malloc(sizeof(double) * (size_t)n);
+      int bad = 0;
+      for (int t = 0; t < n; ++t) {
+        const int blk = block_tables[(int64_t)i * max_blocks_per_seq + t / block_size];
+        const int slot = t % block_size;
+        if (blk < 0 || blk >= num_pool_blocks) {
+          bad = 1;
+          break;
+        }
+        const int64_t kbase = blk * ksb + g * ksh + slot * kst;
+        const int64_t vbase = blk * vsb + g * vsh + slot * vst;
+        for (int d = 0; d < D; ++d) {
+          Kc[(int64_t)t * D + d] = load_elem(k_pool, kbase + d, dtype);
+          Vc[(int64_t)t * D + d] = load_elem(v_pool, vbase + d, dtype);
+        }
+      }
+      if (bad) {
+#pragma omp atomic write
+        status = -3;
+        free(Kc); free(Vc); free(s);
+        continue;
+      }
+
+      /* 2. scores: plain left-to-right dot product, then the scale */
+      const int64_t qbase = ((int64_t)i * Hq + h) * D;
+      for (int t = 0; t < n; ++t) {
+        double acc = 0.0;
+        for (int d = 0; d < D; ++d)
+          acc += load_elem(q, qbase + d, dtype) * Kc[(int64_t)t * D + d];
+        s[t] = (double)scale * acc;
+      }
+
+      /* 3. softmax with the maximum subtracted */
+      double m = s[0];
+      for (int t = 1; t < n; ++t) if (s[t] > m) m = s[t];
+      double Z = 0.0;
+      for (int t = 0; t < n; ++t) { s[t] = exp(s[t] - m); Z += s[t]; }
+      for (int t = 0; t < n; ++t) s[t] /= Z;
+      if (weights_out) {
+        double* w = weights_out + ((int64_t)i * Hq + h) * max_ctx;
+        for (int t = 0; t < n && t < max_ctx; ++t) w[t] = s[t];
+      }
+
+      /* 4. weighted sum of the value rows */
+      for (int t = 0; t < n; ++t)
+        for (int d = 0; d < D; ++d) o[d] += s[t] * Vc[(int64_t)t * D + d];
+
+      free(Kc); free(Vc); free(s);
+    }
+  }
+  return status;
+}
+
+/*
+ * Block copy of the swap path: for every plane p and pair j,
+ *   dst[p*dst_plane_stride + d_j*block_bytes .. +block_bytes) =
+ *   src[p*src_plane_stride + s_j*block_bytes .. +block_bytes).
+ * mapping is [n_pairs][2] = (s_j, d_j).  Returns 0, or negative when a pair
+ * leaves its plane.
+ */
+int orc_kv_block_swap(int num_planes, int64_t block_bytes,
+                      int64_t src_plane_stride, int64_t dst_plane_stride,
+                      int src_num_blocks, int dst_num_blocks,
+                      const uint8_t* src, uint8_t* dst, const int32_t* mapping,
+                      int n_pairs) {
+  for (int j = 0; j < n_pairs; ++j) {
+    const int s = mapping[2 * j], d = mapping[2 * j + 1];
+    if (s < 0 || s >= src_num_blocks || d < 0 || d >= dst_num_blocks) return -1;
+  }
+#pragma omp parallel for schedule(static)
+  for (int64_t pj = 0; pj < (int64_t)num_planes * n_pairs; ++pj) {
+    const int p = (int)(pj / n_pairs), j = (int)(pj % n_pairs);
+    const int64_t s = mapping[2 * j], d = mapping[2 * j + 1];
+    memcpy(dst + p * dst_plane_stride + d * block_bytes,
+           src + p * src_plane_stride + s * block_bytes, (size_t)block_bytes);
+  }
+  return 0;
+}
+
+int orc_num_threads(void) {
+  int n = 1;
+#ifdef _OPENMP
+  extern int omp_get_max_threads(void);
+  n = omp_get_max_threads();
+#endif
+  return n;
+}
