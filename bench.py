@@ -1,0 +1,242 @@
+#!/usr/bin/env python3
+"""Benchmark of the paged-KV decode hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+A step is one paged_decode_attention layer-call (block-table walk, K/V
+streaming, scores, softmax, accumulate, split-K merge) over the batch of the
+Llama-3-8B-shaped configuration (batch 64, 32/8 heads, D 128, bf16, contexts
+uniform in [128, 4096]); consecutive steps cycle over distinct per-layer KV
+pools, as the layers of one decode iteration do, so every step streams data that
+is not in any cache.  The preemption-swap legs (gather to staging, scatter to
+fresh blocks) of the Squeeze configuration are timed in the same run and
+reported under "swap".  One JSON line is printed on stdout.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def upload_attn(w, layers, torch):
+    import numpy as np
+    dev = "cuda:0"
+    if w.dtype == "bf16":
+        conv = lambda a: torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
+    else:
+        conv = lambda a: torch.from_numpy(a).to(dev)
+    k0, v0 = conv(w.k_pool), conv(w.v_pool)
+    # every layer gets its own allocation (same values: only addresses matter for timing)
+    ks = [k0] + [k0.clone() for _ in range(layers - 1)]
+    vs = [v0] + [v0.clone() for _ in range(layers - 1)]
+    return dict(q=conv(w.q), ks=ks, vs=vs,
+                bt=torch.from_numpy(w.block_tables).to(dev),
+                cl=torch.from_numpy(w.context_lens).to(dev))
+
+
+def time_attention(w, d, steps, warmup, torch, binding):
+    out = torch.empty(w.B, w.Hq, w.D, dtype=torch.float32, device="cuda:0")
+    desc = binding.attn_desc_for(d["q"], d["ks"][0], d["vs"][0], d["bt"],
+                                 max_context_len=w.max_context_len,
+                                 partition_tokens=w.partition_tokens)
+    ws = torch.empty(max(16, binding.attn_workspace_bytes(desc)), dtype=torch.uint8, device="cuda:0")
+    L = len(d["ks"])
+
+    def step(i):
+        binding.paged_decode_attention(d["q"], d["ks"][i % L], d["vs"][i % L], d["bt"], d["cl"],
+                                       w.scale, out, max_context_len=w.max_context_len,
+                                       workspace=ws, desc=desc)
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(steps):
+        step(i)
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    ev_ms = e0.elapsed_time(e1)
+    return out, ev_ms / steps, wall_ms / steps
+
+
+def time_swap(sw, reps, torch, binding):
+    """Gather the victims' blocks to contiguous staging, then scatter to fresh blocks."""
+    g = torch.Generator(device="cuda:0")
+    g.manual_seed(sw.seed)
+    pool = torch.randint(-2**31, 2**31 - 1, (sw.pool_bytes // 4,), dtype=torch.int32,
+                         device="cuda:0", generator=g)
+    staging = torch.zeros(sw.staging_bytes // 4, dtype=torch.int32, device="cuda:0")
+    gm = torch.from_numpy(sw.gather_mapping).cuda()
+    sm = torch.from_numpy(sw.scatter_mapping).cuda()
+    dg = binding.swap_desc(sw.num_planes, sw.block_bytes, sw.num_pool_blocks, sw.n_blocks)
+    ds = binding.swap_desc(sw.num_planes, sw.block_bytes, sw.n_blocks, sw.num_pool_blocks)
+    res = {}
+    for name, fn in (("gather", lambda: binding.kv_block_swap(dg, pool, staging, gm)),
+                     ("scatter", lambda: binding.kv_block_swap(ds, staging, pool, sm))):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        res[name] = {"ms": ms, "payload_GBps": sw.payload_bytes / ms / 1e6,
+                     "traffic_GBps": 2 * sw.payload_bytes / ms / 1e6,
+                     "frac_hbm_peak": 2 * sw.payload_bytes / ms / 1e6 / HBM_PEAK_GBS}
+    # bit-exact round trip of the victims' blocks (sampled planes), on the device
+    v = pool.view(sw.num_planes, sw.num_pool_blocks, sw.block_bytes // 4)
+    s = staging.view(sw.num_planes, sw.n_blocks, sw.block_bytes // 4)
+    idx = torch.from_numpy(sw.new_blocks).long().cuda()
+    ok = all(bool(torch.equal(v[p][idx], s[p])) for p in (0, sw.num_planes // 2, sw.num_planes - 1))
+    res["round_trip_bit_exact_sampled"] = ok
+    res["payload_GB"] = sw.payload_bytes / 1e9
+    res["victims"] = int(sw.victim_lens.size)
+    res["blocks"] = sw.n_blocks
+    del pool, staging
+    torch.cuda.empty_cache()
+    return res
+
+
+def probe_ceilings(torch, binding, nbytes=4 << 30, reps=5):
+    a = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0").random_(0, 255)
+    b = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
+    sink = torch.empty(1 << 16, dtype=torch.uint8, device="cuda:0")
+    out = {}
+    for name, fn, traffic in (("read", lambda: binding.probe_read(a, sink, nbytes), nbytes),
+                              ("copy", lambda: binding.probe_copy(a, b, nbytes), 2 * nbytes)):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        out[name + "_GBps"] = traffic / (e0.elapsed_time(e1) / reps) / 1e6
+    del a, b
+    torch.cuda.empty_cache()
+    return out
+
+
+def cpu_baseline(w, reps=3):
+    """The fp64 oracle, untouched, timed on this host's cores on the same workload."""
+    import oracle
+    best = None
+    for _ in range(reps):
+        t = time.perf_counter()
+        ref = oracle.paged_decode_attention(w.q, w.k_pool, w.v_pool, w.block_tables,
+                                            w.context_lens, w.scale, block_size=w.block_size)
+        dt = time.perf_counter() - t
+        best = dt if best is None else min(best, dt)
+    return ref, {"value": w.kv_bytes / best / 1e9, "unit": "KV GB/s", "cores": oracle.num_threads(),
+                 "kind": "oracle", "seconds": best,
+                 "sample": f"the full {w.name} workload (all {w.B} sequences, {w.Hq} heads), "
+                           f"best of {reps} runs"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--layers", type=int, default=16, help="distinct KV layer pools cycled over")
+    ap.add_argument("--no-swap", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--extra", action="store_true", help="also time the Fill and long-context configs")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus must be 1 (no multi-GPU path "
+              "exists: the kernels need no collective, see DESIGN.md)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2602_07878_amd import binding, workloads as W
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    binding.lib()   # fail loudly if the HIP library is missing
+
+    t = time.time()
+    w = W.config2_llama8b()
+    log(f"[bench] generated {w.name}: T={w.total_tokens} tokens, KV bytes/call={w.kv_bytes/1e6:.1f} MB "
+        f"({time.time()-t:.1f}s)")
+    d = upload_attn(w, args.layers, torch)
+    out, ms, wall_ms = time_attention(w, d, args.steps, args.warmup, torch, binding)
+    gbps = w.kv_bytes / ms / 1e6
+    log(f"[bench] attention: {ms*1e3:.1f} us/call, {gbps:.0f} KV GB/s = {gbps/HBM_PEAK_GBS:.1%} of HBM peak")
+
+    result = {
+        "metric": "decode-attention KV GB/s", "value": gbps, "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "batch": w.B, "q_heads": w.Hq, "kv_heads": w.Hkv,
+                   "head_dim": w.D, "block_size": w.block_size, "context_tokens": w.total_tokens,
+                   "kv_bytes_per_call": w.kv_bytes, "layer_pools_cycled": args.layers,
+                   "partition_tokens": int(binding.lib().pkv_attn_partition_tokens(
+                       __import__("ctypes").byref(binding.attn_desc_for(
+                           d["q"], d["ks"][0], d["vs"][0], d["bt"],
+                           max_context_len=w.max_context_len))))},
+        "frac_hbm_peak": gbps / HBM_PEAK_GBS,
+        "decode_tokens_per_s": w.B / (ms * 1e-3),
+        "kv_tokens_per_s": w.total_tokens / (ms * 1e-3),
+        "wall_ms_per_step": wall_ms,
+        "roofline": {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": gbps / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "attn_partial (per-call time incl. merge kernel)"},
+    }
+    result["ceilings"] = probe_ceilings(torch, binding)
+    log(f"[bench] ceilings: {result['ceilings']}")
+
+    if not args.no_cpu:
+        ref, cb = cpu_baseline(w)
+        err = float(np.abs(out.cpu().numpy().astype(np.float64) - ref).max())
+        result["cpu_baseline"] = cb
+        result["max_abs_err_vs_oracle"] = err
+        log(f"[bench] oracle: {cb['seconds']:.2f}s on {cb['cores']} threads = {cb['value']:.2f} KV GB/s; "
+            f"GPU max abs err {err:.2e}")
+    del d
+    torch.cuda.empty_cache()
+
+    if not args.no_swap:
+        swap = {}
+        for sw in (W.config4_squeeze(), W.config4_evict_all_256()):
+            swap[sw.name] = time_swap(sw, 5, torch, binding)
+            log(f"[bench] swap {sw.name}: {swap[sw.name]}")
+        result["swap"] = swap
+
+    if args.extra:
+        extra = {}
+        for mk, layers in ((W.config3_fill, 4), (W.config5_long70b, 2)):
+            t = time.time()
+            wx = mk()
+            dx = upload_attn(wx, layers, torch)
+            _, msx, _ = time_attention(wx, dx, 40, 8, torch, binding)
+            g = wx.kv_bytes / msx / 1e6
+            extra[wx.name] = {"ms": msx, "kv_GBps": g, "frac_hbm_peak": g / HBM_PEAK_GBS,
+                              "context_tokens": wx.total_tokens}
+            log(f"[bench] {wx.name}: {extra[wx.name]} (setup {time.time()-t:.0f}s)")
+            del dx
+            torch.cuda.empty_cache()
+        result["other_configs"] = extra
+
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

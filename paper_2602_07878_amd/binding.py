@@ -1,0 +1,209 @@
+"""Thin ctypes binding of libpkv.so: argument marshalling only.
+
+Every step of the hot path runs in the HIP kernels of the library; PyTorch is
+used for device memory and streams.  If the library has not been built this
+module raises -- there is no fallback implementation.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpkv.so")
+
+PKV_F32, PKV_BF16 = 0, 1
+PKV_OK = 0
+
+EXPORTS = [
+    "pkv_version", "pkv_status_string", "pkv_attn_partition_tokens", "pkv_attn_workspace_bytes",
+    "paged_decode_attention", "kv_block_swap", "pkv_validate_tables_host",
+    "pkv_validate_mapping_host", "pkv_validate_tables", "pkv_validate_mapping",
+    "pkv_probe_copy", "pkv_probe_read",
+]
+
+
+class AttnDesc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in (
+        "batch", "num_q_heads", "num_kv_heads", "head_dim", "block_size", "num_pool_blocks",
+        "max_blocks_per_seq", "max_context_len", "partition_tokens", "kv_dtype", "out_dtype",
+        "reserved")] + [(n, ctypes.c_int64) for n in (
+            "k_stride_block", "k_stride_head", "k_stride_token",
+            "v_stride_block", "v_stride_head", "v_stride_token")]
+
+
+class SwapDesc(ctypes.Structure):
+    _fields_ = [("num_planes", ctypes.c_int32), ("src_num_blocks", ctypes.c_int32),
+                ("dst_num_blocks", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("block_bytes", ctypes.c_int64), ("src_plane_stride_bytes", ctypes.c_int64),
+                ("dst_plane_stride_bytes", ctypes.c_int64)]
+
+
+class PkvError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)}")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Open libpkv.so (once).  A missing library is an error."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is not built; run `python -m paper_2602_07878_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+        L.pkv_version.restype = i32
+        L.pkv_version.argtypes = []
+        L.pkv_status_string.restype = ctypes.c_char_p
+        L.pkv_status_string.argtypes = [i32]
+        L.pkv_attn_partition_tokens.restype = i32
+        L.pkv_attn_partition_tokens.argtypes = [ctypes.POINTER(AttnDesc)]
+        L.pkv_attn_workspace_bytes.restype = sz
+        L.pkv_attn_workspace_bytes.argtypes = [ctypes.POINTER(AttnDesc)]
+        L.paged_decode_attention.restype = i32
+        L.paged_decode_attention.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp,
+                                             ctypes.c_float, vp, vp, sz, vp]
+        L.kv_block_swap.restype = i32
+        L.kv_block_swap.argtypes = [ctypes.POINTER(SwapDesc), vp, vp, vp, i32, vp]
+        L.pkv_validate_tables_host.restype = i32
+        L.pkv_validate_tables_host.argtypes = [ctypes.POINTER(AttnDesc), vp, vp]
+        L.pkv_validate_mapping_host.restype = i32
+        L.pkv_validate_mapping_host.argtypes = [ctypes.POINTER(SwapDesc), vp, i32]
+        L.pkv_validate_tables.restype = i32
+        L.pkv_validate_tables.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp]
+        L.pkv_validate_mapping.restype = i32
+        L.pkv_validate_mapping.argtypes = [ctypes.POINTER(SwapDesc), vp, i32, vp]
+        L.pkv_probe_copy.restype = i32
+        L.pkv_probe_copy.argtypes = [vp, vp, sz, vp]
+        L.pkv_probe_read.restype = i32
+        L.pkv_probe_read.argtypes = [vp, vp, sz, vp]
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().pkv_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str):
+    if status != PKV_OK:
+        raise PkvError(status, where)
+
+
+def _stream_ptr(stream) -> Optional[int]:
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _torch_dtype_code(t) -> int:
+    import torch
+    if t.dtype == torch.float32:
+        return PKV_F32
+    if t.dtype == torch.bfloat16:
+        return PKV_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def attn_desc_for(q, k_pool, v_pool, block_tables, *, max_context_len: int,
+                  partition_tokens: int = 0, out_dtype=None) -> AttnDesc:
+    """Descriptor for torch tensors: q [B,Hq,D]; pools [blocks,Hkv,bs,D] (any strides with a
+    unit-stride last dim); block_tables [B,max_blocks]."""
+    import torch
+    B, Hq, D = q.shape
+    nblk, Hkv, bs, Dk = k_pool.shape
+    assert Dk == D and v_pool.shape == k_pool.shape
+    assert k_pool.stride(3) == 1 and v_pool.stride(3) == 1 and q.is_contiguous()
+    code = _torch_dtype_code(q)
+    assert _torch_dtype_code(k_pool) == code and _torch_dtype_code(v_pool) == code
+    d = AttnDesc()
+    d.batch, d.num_q_heads, d.num_kv_heads, d.head_dim = B, Hq, Hkv, D
+    d.block_size, d.num_pool_blocks = bs, nblk
+    d.max_blocks_per_seq = block_tables.shape[1]
+    d.max_context_len = int(max_context_len)
+    d.partition_tokens = int(partition_tokens)
+    d.kv_dtype = code
+    d.out_dtype = PKV_F32 if out_dtype in (None, torch.float32) else PKV_BF16
+    d.reserved = 0
+    d.k_stride_block, d.k_stride_head, d.k_stride_token = (k_pool.stride(i) for i in range(3))
+    d.v_stride_block, d.v_stride_head, d.v_stride_token = (v_pool.stride(i) for i in range(3))
+    return d
+
+
+def attn_workspace_bytes(desc: AttnDesc) -> int:
+    return int(lib().pkv_attn_workspace_bytes(ctypes.byref(desc)))
+
+
+def paged_decode_attention(q, k_pool, v_pool, block_tables, context_lens, scale, out, *,
+                           max_context_len: int, partition_tokens: int = 0, workspace=None,
+                           desc: Optional[AttnDesc] = None, stream=None):
+    """out[i,h,:] = softmax_t(scale * q[i,h] . K_t) V_t over the paged pool (device tensors).
+    Returns the workspace tensor used (reusable by the caller)."""
+    import torch
+    L = lib()
+    if desc is None:
+        desc = attn_desc_for(q, k_pool, v_pool, block_tables, max_context_len=max_context_len,
+                             partition_tokens=partition_tokens, out_dtype=out.dtype)
+    assert block_tables.dtype == torch.int32 and context_lens.dtype == torch.int32
+    assert block_tables.is_contiguous() and context_lens.is_contiguous() and out.is_contiguous()
+    need = int(L.pkv_attn_workspace_bytes(ctypes.byref(desc)))
+    if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    st = L.paged_decode_attention(ctypes.byref(desc), q.data_ptr(), k_pool.data_ptr(),
+                                  v_pool.data_ptr(), block_tables.data_ptr(),
+                                  context_lens.data_ptr(), float(scale), out.data_ptr(),
+                                  ws_ptr, ws_bytes, _stream_ptr(stream))
+    _check(st, "paged_decode_attention")
+    return workspace
+
+
+def swap_desc(num_planes: int, block_bytes: int, src_num_blocks: int, dst_num_blocks: int,
+              src_plane_stride_bytes: Optional[int] = None,
+              dst_plane_stride_bytes: Optional[int] = None) -> SwapDesc:
+    d = SwapDesc()
+    d.num_planes, d.src_num_blocks, d.dst_num_blocks, d.reserved = (
+        num_planes, src_num_blocks, dst_num_blocks, 0)
+    d.block_bytes = block_bytes
+    d.src_plane_stride_bytes = (src_num_blocks * block_bytes if src_plane_stride_bytes is None
+                                else src_plane_stride_bytes)
+    d.dst_plane_stride_bytes = (dst_num_blocks * block_bytes if dst_plane_stride_bytes is None
+                                else dst_plane_stride_bytes)
+    return d
+
+
+def kv_block_swap(desc: SwapDesc, src_pool, dst, block_mapping, *, stream=None):
+    """Copy (plane, block) chunks src_pool -> dst per block_mapping [n,2] int32 (device)."""
+    import torch
+    assert block_mapping.dtype == torch.int32 and block_mapping.is_contiguous()
+    n_pairs = block_mapping.numel() // 2
+    st = lib().kv_block_swap(ctypes.byref(desc), src_pool.data_ptr(), dst.data_ptr(),
+                             block_mapping.data_ptr(), n_pairs, _stream_ptr(stream))
+    _check(st, "kv_block_swap")
+
+
+def validate_tables(desc: AttnDesc, block_tables, context_lens, *, stream=None) -> int:
+    return int(lib().pkv_validate_tables(ctypes.byref(desc), block_tables.data_ptr(),
+                                         context_lens.data_ptr(), _stream_ptr(stream)))
+
+
+def validate_mapping(desc: SwapDesc, block_mapping, *, stream=None) -> int:
+    return int(lib().pkv_validate_mapping(ctypes.byref(desc), block_mapping.data_ptr(),
+                                          block_mapping.numel() // 2, _stream_ptr(stream)))
+
+
+def probe_copy(src, dst, nbytes: int, *, stream=None):
+    _check(lib().pkv_probe_copy(src.data_ptr(), dst.data_ptr(), nbytes, _stream_ptr(stream)),
+           "pkv_probe_copy")
+
+
+def probe_read(src, sink, nbytes: int, *, stream=None):
+    _check(lib().pkv_probe_read(src.data_ptr(), sink.data_ptr(), nbytes, _stream_ptr(stream)),
+           "pkv_probe_read")

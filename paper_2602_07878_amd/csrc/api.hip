@@ -1,0 +1,259 @@
+// extern "C" entry points of libpkv: host-side validation and launch set-up.
+// Everything that can be checked without touching device memory is checked
+// here, before any kernel is enqueued.
+
+#include <cmath>
+#include <cstring>
+#include <vector>
+
+#include "pkv_internal.h"
+
+namespace {
+
+using namespace pkv;
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+inline int elem_bytes(int dtype) { return dtype == PKV_BF16 ? 2 : dtype == PKV_F32 ? 4 : 0; }
+
+int32_t partition_tokens_of(const pkv_attn_desc* d) {
+  if (!d) return 0;
+  const int pt = d->partition_tokens == 0 ? kDefaultPartition : d->partition_tokens;
+  if (pt < 64 || pt % 64 != 0) return 0;
+  return pt;
+}
+
+int32_t max_partitions_of(const pkv_attn_desc* d) {
+  const int pt = partition_tokens_of(d);
+  if (pt == 0) return 0;
+  const int64_t mc = d->max_context_len;
+  return mc <= 0 ? 1 : (int32_t)((mc + pt - 1) / pt);
+}
+
+// Static checks of an attention descriptor (no pointers).
+int32_t check_attn_desc(const pkv_attn_desc* d) {
+  if (!d) return PKV_ERR_NULL;
+  const int eb = elem_bytes(d->kv_dtype);
+  if (eb == 0) return PKV_ERR_DTYPE;
+  if (d->out_dtype != PKV_F32 && d->out_dtype != PKV_BF16) return PKV_ERR_DTYPE;
+  if (d->batch < 0 || d->num_q_heads <= 0 || d->num_kv_heads <= 0 || d->head_dim <= 0 ||
+      d->block_size <= 0 || d->num_pool_blocks <= 0 || d->max_blocks_per_seq <= 0 ||
+      d->max_context_len < 0 || d->partition_tokens < 0 || d->reserved != 0)
+    return PKV_ERR_SHAPE;
+  if (d->num_q_heads % d->num_kv_heads != 0) return PKV_ERR_SHAPE;
+  if (d->block_size % kTileTokens != 0) return PKV_ERR_SHAPE;
+  const int row_bytes = d->head_dim * eb;
+  if (row_bytes != 128 && row_bytes != 256 && row_bytes != 512) return PKV_ERR_SHAPE;
+  if (partition_tokens_of(d) == 0) return PKV_ERR_SHAPE;
+  if ((int64_t)d->max_blocks_per_seq * d->block_size < d->max_context_len) return PKV_ERR_SHAPE;
+  const int64_t st[6] = {d->k_stride_block, d->k_stride_head, d->k_stride_token,
+                         d->v_stride_block, d->v_stride_head, d->v_stride_token};
+  for (int i = 0; i < 6; ++i) {
+    if (st[i] < 0) return PKV_ERR_SHAPE;
+    if ((st[i] * eb) % 16 != 0) return PKV_ERR_ALIGN;
+  }
+  if (d->k_stride_token < d->head_dim || d->v_stride_token < d->head_dim) return PKV_ERR_SHAPE;
+  return PKV_OK;
+}
+
+int32_t check_swap_desc(const pkv_swap_desc* d) {
+  if (!d) return PKV_ERR_NULL;
+  if (d->num_planes <= 0 || d->src_num_blocks <= 0 || d->dst_num_blocks <= 0 ||
+      d->block_bytes <= 0 || d->reserved != 0)
+    return PKV_ERR_SHAPE;
+  if (d->block_bytes % 16 != 0 || d->src_plane_stride_bytes % 16 != 0 ||
+      d->dst_plane_stride_bytes % 16 != 0)
+    return PKV_ERR_ALIGN;
+  if (d->src_plane_stride_bytes < (int64_t)d->src_num_blocks * d->block_bytes ||
+      d->dst_plane_stride_bytes < (int64_t)d->dst_num_blocks * d->block_bytes)
+    return PKV_ERR_SHAPE;
+  return PKV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t pkv_version(void) { return 100; }
+
+const char* pkv_status_string(int32_t status) {
+  switch (status) {
+    case PKV_OK: return "PKV_OK";
+    case PKV_ERR_NULL: return "PKV_ERR_NULL";
+    case PKV_ERR_SHAPE: return "PKV_ERR_SHAPE";
+    case PKV_ERR_DTYPE: return "PKV_ERR_DTYPE";
+    case PKV_ERR_ALIGN: return "PKV_ERR_ALIGN";
+    case PKV_ERR_WORKSPACE: return "PKV_ERR_WORKSPACE";
+    case PKV_ERR_INDEX: return "PKV_ERR_INDEX";
+    case PKV_ERR_HIP: return "PKV_ERR_HIP";
+    default: return "PKV_ERR_UNKNOWN";
+  }
+}
+
+int32_t pkv_attn_partition_tokens(const pkv_attn_desc* desc) { return partition_tokens_of(desc); }
+
+size_t pkv_attn_workspace_bytes(const pkv_attn_desc* desc) {
+  if (check_attn_desc(desc) != PKV_OK) return 0;
+  const int64_t P = max_partitions_of(desc);
+  if (P <= 1 || desc->batch == 0) return 0;
+  const int64_t rows = (int64_t)desc->batch * desc->num_q_heads * P;
+  const int64_t ml = (rows * 2 * (int64_t)sizeof(float) + 255) / 256 * 256;
+  const int64_t o = rows * desc->head_dim * (int64_t)sizeof(float);
+  return (size_t)(ml + (o + 255) / 256 * 256);
+}
+
+int32_t paged_decode_attention(const pkv_attn_desc* desc, const void* q, const void* k_pool,
+                               const void* v_pool, const int32_t* block_tables,
+                               const int32_t* context_lens, float scale, void* out,
+                               void* workspace, size_t workspace_bytes, void* hip_stream) {
+  const int32_t st = check_attn_desc(desc);
+  if (st != PKV_OK) return st;
+  if (desc->batch == 0) return PKV_OK;
+  if (!q || !k_pool || !v_pool || !block_tables || !context_lens || !out) return PKV_ERR_NULL;
+  if (!aligned16(q) || !aligned16(k_pool) || !aligned16(v_pool) || !aligned16(out) ||
+      !aligned16(workspace) || (reinterpret_cast<uintptr_t>(block_tables) & 3u) ||
+      (reinterpret_cast<uintptr_t>(context_lens) & 3u))
+    return PKV_ERR_ALIGN;
+  if (!std::isfinite(scale)) return PKV_ERR_SHAPE;
+  const size_t need = pkv_attn_workspace_bytes(desc);
+  if (need > 0 && (!workspace || workspace_bytes < need)) return PKV_ERR_WORKSPACE;
+
+  const int eb = elem_bytes(desc->kv_dtype);
+  AttnParams p;
+  std::memset(&p, 0, sizeof p);
+  p.q = q; p.k_pool = k_pool; p.v_pool = v_pool;
+  p.block_tables = block_tables; p.context_lens = context_lens; p.out = out;
+  p.k_stride_block = desc->k_stride_block * eb;
+  p.k_stride_head = desc->k_stride_head * eb;
+  p.k_stride_token = desc->k_stride_token * eb;
+  p.v_stride_block = desc->v_stride_block * eb;
+  p.v_stride_head = desc->v_stride_head * eb;
+  p.v_stride_token = desc->v_stride_token * eb;
+  p.batch = desc->batch; p.num_q_heads = desc->num_q_heads; p.num_kv_heads = desc->num_kv_heads;
+  p.head_dim = desc->head_dim; p.block_size = desc->block_size;
+  p.max_blocks_per_seq = desc->max_blocks_per_seq;
+  p.group = desc->num_q_heads / desc->num_kv_heads;
+  p.group_tiles = 1;
+  p.partition_tokens = partition_tokens_of(desc);
+  p.max_partitions = max_partitions_of(desc);
+  p.out_is_bf16 = desc->out_dtype == PKV_BF16;
+  p.scale_log2e = scale * 1.4426950408889634f;
+  if (need > 0) {
+    const int64_t rows = (int64_t)desc->batch * desc->num_q_heads * p.max_partitions;
+    const int64_t ml = (rows * 2 * (int64_t)sizeof(float) + 255) / 256 * 256;
+    p.ws_ml = reinterpret_cast<float*>(workspace);
+    p.ws_o = reinterpret_cast<float*>(reinterpret_cast<uint8_t*>(workspace) + ml);
+  }
+  const hipError_t e = launch_attn_decode(p, desc->kv_dtype, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? PKV_OK : PKV_ERR_HIP;
+}
+
+int32_t kv_block_swap(const pkv_swap_desc* desc, const void* src_pool, void* dst,
+                      const int32_t* block_mapping, int32_t n_pairs, void* hip_stream) {
+  const int32_t st = check_swap_desc(desc);
+  if (st != PKV_OK) return st;
+  if (n_pairs < 0) return PKV_ERR_SHAPE;
+  if (n_pairs == 0) return PKV_OK;
+  if (!src_pool || !dst || !block_mapping) return PKV_ERR_NULL;
+  if (!aligned16(src_pool) || !aligned16(dst) || (reinterpret_cast<uintptr_t>(block_mapping) & 3u))
+    return PKV_ERR_ALIGN;
+  SwapParams p;
+  p.src = static_cast<const uint8_t*>(src_pool);
+  p.dst = static_cast<uint8_t*>(dst);
+  p.mapping = block_mapping;
+  p.block_bytes = desc->block_bytes;
+  p.src_plane_stride = desc->src_plane_stride_bytes;
+  p.dst_plane_stride = desc->dst_plane_stride_bytes;
+  p.num_planes = desc->num_planes;
+  p.n_pairs = n_pairs;
+  const hipError_t e = launch_swap(p, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? PKV_OK : PKV_ERR_HIP;
+}
+
+int32_t pkv_validate_tables_host(const pkv_attn_desc* desc, const int32_t* block_tables_host,
+                                 const int32_t* context_lens_host) {
+  const int32_t st = check_attn_desc(desc);
+  if (st != PKV_OK) return st;
+  if (desc->batch == 0) return PKV_OK;
+  if (!block_tables_host || !context_lens_host) return PKV_ERR_NULL;
+  for (int i = 0; i < desc->batch; ++i) {
+    const int64_t n = context_lens_host[i];
+    if (n < 0 || n > desc->max_context_len) return PKV_ERR_INDEX;
+    const int64_t nb = (n + desc->block_size - 1) / desc->block_size;
+    if (nb > desc->max_blocks_per_seq) return PKV_ERR_INDEX;
+    const int32_t* row = block_tables_host + (int64_t)i * desc->max_blocks_per_seq;
+    for (int64_t b = 0; b < nb; ++b)
+      if (row[b] < 0 || row[b] >= desc->num_pool_blocks) return PKV_ERR_INDEX;
+  }
+  return PKV_OK;
+}
+
+int32_t pkv_validate_mapping_host(const pkv_swap_desc* desc, const int32_t* block_mapping_host,
+                                  int32_t n_pairs) {
+  const int32_t st = check_swap_desc(desc);
+  if (st != PKV_OK) return st;
+  if (n_pairs < 0) return PKV_ERR_SHAPE;
+  if (n_pairs == 0) return PKV_OK;
+  if (!block_mapping_host) return PKV_ERR_NULL;
+  std::vector<uint8_t> seen((size_t)desc->dst_num_blocks, 0);
+  for (int j = 0; j < n_pairs; ++j) {
+    const int32_t s = block_mapping_host[2 * j], d = block_mapping_host[2 * j + 1];
+    if (s < 0 || s >= desc->src_num_blocks || d < 0 || d >= desc->dst_num_blocks)
+      return PKV_ERR_INDEX;
+    if (seen[d]) return PKV_ERR_INDEX;  // two writers of one destination block
+    seen[d] = 1;
+  }
+  return PKV_OK;
+}
+
+int32_t pkv_validate_tables(const pkv_attn_desc* desc, const int32_t* block_tables,
+                            const int32_t* context_lens, void* hip_stream) {
+  const int32_t st = check_attn_desc(desc);
+  if (st != PKV_OK) return st;
+  if (desc->batch == 0) return PKV_OK;
+  if (!block_tables || !context_lens) return PKV_ERR_NULL;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  std::vector<int32_t> lens((size_t)desc->batch);
+  std::vector<int32_t> tab((size_t)desc->batch * desc->max_blocks_per_seq);
+  if (hipMemcpyAsync(lens.data(), context_lens, lens.size() * 4, hipMemcpyDeviceToHost, s) !=
+          hipSuccess ||
+      hipMemcpyAsync(tab.data(), block_tables, tab.size() * 4, hipMemcpyDeviceToHost, s) !=
+          hipSuccess ||
+      hipStreamSynchronize(s) != hipSuccess)
+    return PKV_ERR_HIP;
+  return pkv_validate_tables_host(desc, tab.data(), lens.data());
+}
+
+int32_t pkv_validate_mapping(const pkv_swap_desc* desc, const int32_t* block_mapping,
+                             int32_t n_pairs, void* hip_stream) {
+  const int32_t st = check_swap_desc(desc);
+  if (st != PKV_OK) return st;
+  if (n_pairs < 0) return PKV_ERR_SHAPE;
+  if (n_pairs == 0) return PKV_OK;
+  if (!block_mapping) return PKV_ERR_NULL;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  std::vector<int32_t> m((size_t)n_pairs * 2);
+  if (hipMemcpyAsync(m.data(), block_mapping, m.size() * 4, hipMemcpyDeviceToHost, s) !=
+          hipSuccess ||
+      hipStreamSynchronize(s) != hipSuccess)
+    return PKV_ERR_HIP;
+  return pkv_validate_mapping_host(desc, m.data(), n_pairs);
+}
+
+int32_t pkv_probe_copy(const void* src, void* dst, size_t bytes, void* hip_stream) {
+  if (!src || !dst) return PKV_ERR_NULL;
+  if (!aligned16(src) || !aligned16(dst) || bytes % 16 != 0) return PKV_ERR_ALIGN;
+  if (bytes == 0) return PKV_OK;
+  return launch_probe_copy(src, dst, bytes, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+             ? PKV_OK : PKV_ERR_HIP;
+}
+
+int32_t pkv_probe_read(const void* src, void* sink, size_t bytes, void* hip_stream) {
+  if (!src || !sink) return PKV_ERR_NULL;
+  if (!aligned16(src) || !aligned16(sink) || bytes % 16 != 0) return PKV_ERR_ALIGN;
+  if (bytes == 0) return PKV_OK;
+  return launch_probe_read(src, sink, bytes, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+             ? PKV_OK : PKV_ERR_HIP;
+}
+
+}  // extern "C"

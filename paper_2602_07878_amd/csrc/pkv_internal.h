@@ -1,0 +1,52 @@
+// Internal declarations shared by the translation units of libpkv (gfx950).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "pkv.h"
+
+namespace pkv {
+
+constexpr int kWaveSize = 64;
+constexpr int kTileTokens = 16;          // tokens handled per inner tile
+constexpr int kDefaultPartition = 512;   // split-K partition length in tokens
+constexpr int kAttnThreads = 256;        // 4 wavefronts per workgroup
+
+// Launch geometry and pointers of one attention call, passed by value.
+struct AttnParams {
+  const void* q;
+  const void* k_pool;
+  const void* v_pool;
+  const int32_t* block_tables;
+  const int32_t* context_lens;
+  void* out;
+  float* ws_ml;   // [B][Hq][P][2]  (running max in log2 units, normaliser)
+  float* ws_o;    // [B][Hq][P][D]  un-normalised partial output rows
+  int64_t k_stride_block, k_stride_head, k_stride_token;  // BYTES
+  int64_t v_stride_block, v_stride_head, v_stride_token;  // BYTES
+  int32_t batch, num_q_heads, num_kv_heads, head_dim;
+  int32_t block_size, max_blocks_per_seq;
+  int32_t group;            // G = Hq / Hkv
+  int32_t group_tiles;      // ceil(G / GT): workgroups per KV head
+  int32_t partition_tokens; // PT
+  int32_t max_partitions;   // P
+  int32_t out_is_bf16;
+  float scale_log2e;        // scale * log2(e)
+};
+
+struct SwapParams {
+  const uint8_t* src;
+  uint8_t* dst;
+  const int32_t* mapping;  // [n_pairs][2]
+  int64_t block_bytes, src_plane_stride, dst_plane_stride;
+  int32_t num_planes, n_pairs;
+};
+
+// attn_decode.hip
+hipError_t launch_attn_decode(const AttnParams& p, int dtype, hipStream_t s);
+// swap.hip
+hipError_t launch_swap(const SwapParams& p, hipStream_t s);
+hipError_t launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t s);
+hipError_t launch_probe_read(const void* src, void* sink, size_t bytes, hipStream_t s);
+
+}  // namespace pkv

@@ -1,0 +1,142 @@
+"""GPU parity of paged_decode_attention (through the C ABI) against the fp64 oracle.
+
+Tolerances (max abs error over all output elements, outputs read as fp32):
+  fp32 inputs 1e-5, bf16 inputs with fp32 accumulation 2e-3."""
+import numpy as np
+import pytest
+
+from paper_2602_07878_amd import workloads as W
+from helpers import run_hip, run_oracle, to_device
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-3}
+
+
+def check(w, **kw):
+    got = run_hip(w, **kw)
+    ref = run_oracle(w)
+    assert np.all(np.isfinite(got)), "non-finite output (poison leaked?)"
+    err = np.abs(got - ref).max() if got.size else 0.0
+    print(f"{w.name}: B={w.B} Hq={w.Hq} Hkv={w.Hkv} D={w.D} T={w.total_tokens} "
+          f"max_abs_err={err:.3e}", flush=True)
+    assert err <= TOL[w.dtype], err
+    return got, ref
+
+
+def test_config1_tiny_fp32():
+    check(W.config1_tiny())
+
+
+def test_config1_with_split_partitions():
+    w = W.config1_tiny()
+    for pt in (64, 128, 256):
+        check(w, partition_tokens=pt)
+
+
+@pytest.mark.parametrize("dtype,Hq,Hkv,D", [
+    ("bf16", 32, 8, 128), ("bf16", 64, 8, 128), ("bf16", 8, 8, 128), ("bf16", 16, 8, 128),
+    ("bf16", 8, 2, 64), ("bf16", 4, 1, 256), ("f32", 8, 8, 64), ("f32", 8, 2, 128),
+    ("f32", 4, 4, 32), ("bf16", 24, 8, 128), ("bf16", 32, 2, 128), ("f32", 12, 4, 64),
+])
+def test_shapes_ragged_lengths(dtype, Hq, Hkv, D):
+    lens = [1, 15, 16, 17, 63, 64, 65, 511, 512, 513, 1000, 1025, 0, 2047]
+    w = W.make_attn_workload(f"ragged_{dtype}_{Hq}_{Hkv}_{D}", 42, dtype=dtype, Hq=Hq, Hkv=Hkv,
+                             D=D, block_size=16, context_lens=lens, pool_factor=1.3)
+    got, _ = check(w)
+    assert np.all(got[12] == 0.0)      # empty context -> zero row
+
+
+@pytest.mark.parametrize("bs", [16, 32, 64])
+def test_block_sizes(bs):
+    lens = [5, bs - 1, bs, bs + 1, 700, 1300]
+    w = W.make_attn_workload(f"bs{bs}", 43, dtype="bf16", Hq=32, Hkv=8, D=128, block_size=bs,
+                             context_lens=lens, pool_factor=1.2)
+    check(w)
+
+
+def test_config2_reduced_batch():
+    w = W.config2_llama8b(B=16)
+    check(w)
+
+
+def test_partition_size_independence():
+    w = W.make_attn_workload("parts", 44, dtype="bf16", Hq=32, Hkv=8, D=128, block_size=16,
+                             context_lens=[3000, 777, 4096, 129], pool_factor=1.1)
+    ref = run_oracle(w)
+    dev = to_device(w)
+    outs = {}
+    for pt in (128, 256, 512, 1024, 4096):
+        outs[pt] = run_hip(w, dev, partition_tokens=pt)
+        assert np.abs(outs[pt] - ref).max() <= TOL["bf16"]
+    # same launch twice is bit-reproducible
+    again = run_hip(w, dev, partition_tokens=512)
+    assert np.array_equal(again, outs[512])
+
+
+def test_physical_placement_invariance_bitwise():
+    w = W.make_attn_workload("perm", 45, dtype="bf16", Hq=32, Hkv=8, D=128, block_size=16,
+                             context_lens=[1500, 40, 513], pool_factor=1.5)
+    a = run_hip(w)
+    rng = np.random.default_rng(1)
+    perm = rng.permutation(w.num_pool_blocks)
+    k2, v2 = np.empty_like(w.k_pool), np.empty_like(w.v_pool)
+    k2[perm], v2[perm] = w.k_pool, w.v_pool
+    w.k_pool, w.v_pool = k2, v2
+    w.block_tables = np.where(w.block_tables >= 0, perm[np.maximum(w.block_tables, 0)],
+                              -1).astype(np.int32)
+    b = run_hip(w)
+    assert np.array_equal(a, b)
+
+
+def test_shared_prefix_blocks_and_extreme_scores():
+    w = W.make_attn_workload("shared", 46, dtype="f32", Hq=8, Hkv=2, D=64, block_size=16,
+                             context_lens=[100, 100, 37], pool_factor=1.2)
+    w.block_tables[1, :4] = w.block_tables[0, :4]       # two sequences share 64 prefix tokens
+    # a huge planted key: scores ~ +-1e3 must not overflow
+    blk = w.block_tables[0, 2]
+    w.k_pool[blk, 0, 3] = 300.0 * w.q[0, 0] / np.linalg.norm(w.q[0, 0])
+    w.scale = 1.0
+    check(w)
+
+
+def test_strided_token_major_pool_layout():
+    """Pools stored [blocks, bs, Hkv, D] (token-major) passed through strides."""
+    import torch
+    from paper_2602_07878_amd import binding
+    w = W.make_attn_workload("strided", 47, dtype="bf16", Hq=16, Hkv=4, D=128, block_size=16,
+                             context_lens=[300, 17, 1024], pool_factor=1.1)
+    ref = run_oracle(w)
+    dev = to_device(w)
+    k_tm = dev["k_pool"].permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)   # same values,
+    v_tm = dev["v_pool"].permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)   # other strides
+    assert not k_tm.is_contiguous()
+    out = torch.empty(w.B, w.Hq, w.D, dtype=torch.float32, device="cuda:0")
+    binding.paged_decode_attention(dev["q"], k_tm, v_tm, dev["block_tables"], dev["context_lens"],
+                                   w.scale, out, max_context_len=w.max_context_len)
+    torch.cuda.synchronize()
+    assert np.abs(out.cpu().numpy().astype(np.float64) - ref).max() <= TOL["bf16"]
+
+
+def test_bf16_output_option():
+    import torch
+    w = W.make_attn_workload("bf16out", 48, dtype="bf16", Hq=32, Hkv=8, D=128, block_size=16,
+                             context_lens=[900, 64, 2000], pool_factor=1.1)
+    got = run_hip(w, out_dtype=torch.bfloat16)
+    ref = run_oracle(w)
+    # one bf16 rounding of the fp32 result on top of the fp32-output tolerance
+    ulp = np.maximum(np.abs(ref), 2.0 ** -126) * 2.0 ** -8
+    assert np.all(np.abs(got - ref) <= TOL["bf16"] + ulp)
+
+
+def test_device_validators():
+    import torch
+    from paper_2602_07878_amd import binding
+    w = W.config1_tiny()
+    dev = to_device(w)
+    desc = binding.attn_desc_for(dev["q"], dev["k_pool"], dev["v_pool"], dev["block_tables"],
+                                 max_context_len=256)
+    assert binding.validate_tables(desc, dev["block_tables"], dev["context_lens"]) == 0
+    bad = dev["block_tables"].clone()
+    bad[3, 2] = 64
+    assert binding.validate_tables(desc, bad, dev["context_lens"]) == 6

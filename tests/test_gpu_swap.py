@@ -1,0 +1,96 @@
+"""GPU parity of kv_block_swap (through the C ABI) against the memcpy oracle: bytewise."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2602_07878_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+def gpu_swap(src_np, dst_np, mapping, **desc_kw):
+    import torch
+    from paper_2602_07878_amd import binding
+    src = torch.from_numpy(src_np).cuda()
+    dst = torch.from_numpy(dst_np).cuda()
+    m = torch.from_numpy(np.ascontiguousarray(mapping, dtype=np.int32)).cuda()
+    d = binding.swap_desc(**desc_kw)
+    assert binding.validate_mapping(d, m) == 0
+    binding.kv_block_swap(d, src, dst, m)
+    torch.cuda.synchronize()
+    return dst.cpu().numpy()
+
+
+@pytest.mark.parametrize("planes,bb,lens", [
+    (4, 32768, (100, 700, 16, 33)), (64, 4096, (512, 90)), (1, 16, (1, 17, 300)),
+    (3, 48, (5, 33, 16, 70)), (2, 32768 + 16, (64, 65)), (7, 1 << 20, (40,)),
+])
+def test_gather_scatter_round_trip_bitwise(planes, bb, lens):
+    sw = W.make_swap_workload("t", 7, victim_lens=lens, num_planes=planes, block_bytes=bb)
+    n, NB = sw.n_blocks, sw.num_pool_blocks
+    pool = W.random_bytes((planes * NB * bb + 7) // 8 * 8, 8)[:planes * NB * bb].copy()
+    # include NaN / -0 bit patterns: bytes are bytes
+    pool[:8] = np.frombuffer(np.array([np.nan, -0.0], np.float32).tobytes(), np.uint8)
+    staging0 = np.full(planes * n * bb, 0xAB, np.uint8)
+    kw = dict(num_planes=planes, block_bytes=bb)
+    got_st = gpu_swap(pool, staging0, sw.gather_mapping, src_num_blocks=NB, dst_num_blocks=n, **kw)
+    ref_st = staging0.copy()
+    oracle.kv_block_swap(pool, ref_st, sw.gather_mapping, **kw)
+    assert np.array_equal(got_st, ref_st)
+    pool2_0 = np.full_like(pool, 0xCD)
+    got_p2 = gpu_swap(got_st, pool2_0, sw.scatter_mapping, src_num_blocks=n, dst_num_blocks=NB, **kw)
+    ref_p2 = pool2_0.copy()
+    oracle.kv_block_swap(ref_st, ref_p2, sw.scatter_mapping, **kw)
+    assert np.array_equal(got_p2, ref_p2)          # includes every untouched 0xCD byte
+    p3 = got_p2.reshape(planes, NB, bb)
+    o3 = pool.reshape(planes, NB, bb)
+    assert np.array_equal(p3[:, sw.new_blocks], o3[:, sw.src_blocks])
+
+
+def test_plane_strides_and_fan_out():
+    planes, bb, NB = 3, 256, 10
+    pstride = NB * bb + 64
+    src = W.random_bytes(planes * pstride, 9).copy()
+    dst0 = np.full(planes * (4 * bb + 32), 0x11, np.uint8)
+    mapping = np.array([[2, 0], [2, 3], [9, 1]], np.int32)      # source block 2 copied twice
+    kw = dict(num_planes=planes, block_bytes=bb, src_num_blocks=NB, dst_num_blocks=4,
+              src_plane_stride_bytes=pstride, dst_plane_stride_bytes=4 * bb + 32)
+    got = gpu_swap(src, dst0, mapping, **kw)
+    ref = dst0.copy()
+    oracle.kv_block_swap(src, ref, mapping, num_planes=planes, block_bytes=bb,
+                         src_plane_stride=pstride, dst_plane_stride=4 * bb + 32,
+                         src_num_blocks=NB, dst_num_blocks=4)
+    assert np.array_equal(got, ref)
+
+
+def test_swap_is_transparent_to_attention():
+    """Evict a sequence to staging, bring it back into other blocks, rewrite its table:
+    the attention output is bit-identical (Sec. 5.1.2: the victim resumes where it stopped)."""
+    import torch
+    from paper_2602_07878_amd import binding
+    from helpers import run_hip, to_device
+    w = W.make_attn_workload("swapattn", 50, dtype="bf16", Hq=32, Hkv=8, D=128, block_size=16,
+                             context_lens=[700, 1300, 90], pool_factor=2.5, poison=False)
+    before = run_hip(w)
+    victim = 1
+    nb = int(W.blocks_needed(w.context_lens, 16)[victim])
+    old = w.block_tables[victim, :nb].copy()
+    used = set(int(b) for b in w.block_tables[w.block_tables >= 0])
+    free = np.array([b for b in range(w.num_pool_blocks) if b not in used], np.int32)
+    new = np.random.default_rng(3).permutation(free)[:nb].astype(np.int32)
+    bb = 8 * 16 * 128 * 2
+    dev = to_device(w)
+    pools = torch.stack([dev["k_pool"], dev["v_pool"]])            # 2 planes
+    staging = torch.zeros(2 * nb * bb, dtype=torch.uint8, device="cuda:0")
+    slots = np.arange(nb, dtype=np.int32)
+    g = torch.from_numpy(np.stack([old, slots], 1).astype(np.int32)).cuda()
+    s = torch.from_numpy(np.stack([slots, new], 1).astype(np.int32)).cuda()
+    binding.kv_block_swap(binding.swap_desc(2, bb, w.num_pool_blocks, nb), pools, staging, g)
+    pools[:, torch.from_numpy(old).long().cuda()] = float("nan")   # the old blocks are gone
+    binding.kv_block_swap(binding.swap_desc(2, bb, nb, w.num_pool_blocks), staging, pools, s)
+    torch.cuda.synchronize()
+    w.block_tables[victim, :nb] = new
+    dev2 = dict(dev, k_pool=pools[0], v_pool=pools[1],
+                block_tables=torch.from_numpy(w.block_tables).cuda())
+    after = run_hip(w, dev2)
+    assert np.array_equal(before, after)
