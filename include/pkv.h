@@ -47,6 +47,10 @@ typedef enum pkv_status {
 
 typedef enum pkv_dtype { PKV_F32 = 0, PKV_BF16 = 1 } pkv_dtype;
 
+/* Use the vector-ALU kernel even where the matrix-core kernel applies (a
+ * second, independent code path: tests run both against the oracle). */
+#define PKV_ATTN_FLAG_VECTOR_ALU 1
+
 /*
  * Geometry of one paged_decode_attention call (one layer, one decode step).
  *
@@ -73,7 +77,7 @@ typedef struct pkv_attn_desc {
   int32_t partition_tokens;   /* split-K partition, multiple of 64; 0 = default  */
   int32_t kv_dtype;           /* pkv_dtype of q, k_pool and v_pool               */
   int32_t out_dtype;          /* pkv_dtype of out: PKV_F32 or PKV_BF16           */
-  int32_t reserved;           /* must be 0                                       */
+  int32_t flags;              /* 0, or PKV_ATTN_FLAG_* bits                      */
   int64_t k_stride_block, k_stride_head, k_stride_token;
   int64_t v_stride_block, v_stride_head, v_stride_token;
 } pkv_attn_desc;

@@ -15,6 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libpkv.so")
 
 PKV_F32, PKV_BF16 = 0, 1
 PKV_OK = 0
+FLAG_VECTOR_ALU = 1
 
 EXPORTS = [
     "pkv_version", "pkv_status_string", "pkv_attn_partition_tokens", "pkv_attn_workspace_bytes",
@@ -28,7 +29,7 @@ class AttnDesc(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "batch", "num_q_heads", "num_kv_heads", "head_dim", "block_size", "num_pool_blocks",
         "max_blocks_per_seq", "max_context_len", "partition_tokens", "kv_dtype", "out_dtype",
-        "reserved")] + [(n, ctypes.c_int64) for n in (
+        "flags")] + [(n, ctypes.c_int64) for n in (
             "k_stride_block", "k_stride_head", "k_stride_token",
             "v_stride_block", "v_stride_head", "v_stride_token")]
 
@@ -112,7 +113,7 @@ def _torch_dtype_code(t) -> int:
 
 
 def attn_desc_for(q, k_pool, v_pool, block_tables, *, max_context_len: int,
-                  partition_tokens: int = 0, out_dtype=None) -> AttnDesc:
+                  partition_tokens: int = 0, out_dtype=None, flags: int = 0) -> AttnDesc:
     """Descriptor for torch tensors: q [B,Hq,D]; pools [blocks,Hkv,bs,D] (any strides with a
     unit-stride last dim); block_tables [B,max_blocks]."""
     import torch
@@ -130,7 +131,7 @@ def attn_desc_for(q, k_pool, v_pool, block_tables, *, max_context_len: int,
     d.partition_tokens = int(partition_tokens)
     d.kv_dtype = code
     d.out_dtype = PKV_F32 if out_dtype in (None, torch.float32) else PKV_BF16
-    d.reserved = 0
+    d.flags = int(flags)
     d.k_stride_block, d.k_stride_head, d.k_stride_token = (k_pool.stride(i) for i in range(3))
     d.v_stride_block, d.v_stride_head, d.v_stride_token = (v_pool.stride(i) for i in range(3))
     return d
@@ -142,14 +143,14 @@ def attn_workspace_bytes(desc: AttnDesc) -> int:
 
 def paged_decode_attention(q, k_pool, v_pool, block_tables, context_lens, scale, out, *,
                            max_context_len: int, partition_tokens: int = 0, workspace=None,
-                           desc: Optional[AttnDesc] = None, stream=None):
+                           desc: Optional[AttnDesc] = None, stream=None, flags: int = 0):
     """out[i,h,:] = softmax_t(scale * q[i,h] . K_t) V_t over the paged pool (device tensors).
     Returns the workspace tensor used (reusable by the caller)."""
     import torch
     L = lib()
     if desc is None:
         desc = attn_desc_for(q, k_pool, v_pool, block_tables, max_context_len=max_context_len,
-                             partition_tokens=partition_tokens, out_dtype=out.dtype)
+                             partition_tokens=partition_tokens, out_dtype=out.dtype, flags=flags)
     assert block_tables.dtype == torch.int32 and context_lens.dtype == torch.int32
     assert block_tables.is_contiguous() and context_lens.is_contiguous() and out.is_contiguous()
     need = int(L.pkv_attn_workspace_bytes(ctypes.byref(desc)))

@@ -38,7 +38,8 @@ int32_t check_attn_desc(const pkv_attn_desc* d) {
   if (d->out_dtype != PKV_F32 && d->out_dtype != PKV_BF16) return PKV_ERR_DTYPE;
   if (d->batch < 0 || d->num_q_heads <= 0 || d->num_kv_heads <= 0 || d->head_dim <= 0 ||
       d->block_size <= 0 || d->num_pool_blocks <= 0 || d->max_blocks_per_seq <= 0 ||
-      d->max_context_len < 0 || d->partition_tokens < 0 || d->reserved != 0)
+      d->max_context_len < 0 || d->partition_tokens < 0 ||
+      (d->flags & ~(int32_t)PKV_ATTN_FLAG_VECTOR_ALU) != 0)
     return PKV_ERR_SHAPE;
   if (d->num_q_heads % d->num_kv_heads != 0) return PKV_ERR_SHAPE;
   if (d->block_size % kTileTokens != 0) return PKV_ERR_SHAPE;
@@ -137,6 +138,7 @@ int32_t paged_decode_attention(const pkv_attn_desc* desc, const void* q, const v
   p.partition_tokens = partition_tokens_of(desc);
   p.max_partitions = max_partitions_of(desc);
   p.out_is_bf16 = desc->out_dtype == PKV_BF16;
+  p.no_mfma = (desc->flags & PKV_ATTN_FLAG_VECTOR_ALU) != 0;
   p.scale_log2e = scale * 1.4426950408889634f;
   if (need > 0) {
     const int64_t rows = (int64_t)desc->batch * desc->num_q_heads * p.max_partitions;

@@ -31,6 +31,8 @@ struct AttnParams {
   int32_t partition_tokens; // PT
   int32_t max_partitions;   // P
   int32_t out_is_bf16;
+  int32_t no_mfma;          // force the vector-ALU kernel
+  int32_t tpb_shift;        // log2(block_size / 16) (matrix-core kernel only)
   float scale_log2e;        // scale * log2(e)
 };
 
@@ -44,6 +46,9 @@ struct SwapParams {
 
 // attn_decode.hip
 hipError_t launch_attn_decode(const AttnParams& p, int dtype, hipStream_t s);
+// attn_decode_mfma.hip
+bool attn_mfma_supported(const AttnParams& p, int dtype);
+hipError_t launch_attn_partial_mfma(AttnParams& p, hipStream_t s);
 // swap.hip
 hipError_t launch_swap(const SwapParams& p, hipStream_t s);
 hipError_t launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t s);

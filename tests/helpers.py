@@ -15,7 +15,7 @@ def to_device(w, device="cuda:0"):
 
 
 def run_hip(w, dev=None, *, partition_tokens=None, out_dtype=None, max_context_len=None,
-            canary=True):
+            canary=True, flags=0):
     """Returns float64 numpy [B,Hq,D] from the HIP library (and checks canaries round `out`)."""
     import torch
     from paper_2602_07878_amd import binding
@@ -29,7 +29,7 @@ def run_hip(w, dev=None, *, partition_tokens=None, out_dtype=None, max_context_l
     mcl = w.max_context_len if max_context_len is None else max_context_len
     binding.paged_decode_attention(dev["q"], dev["k_pool"], dev["v_pool"], dev["block_tables"],
                                    dev["context_lens"], w.scale, out, max_context_len=mcl,
-                                   partition_tokens=pt)
+                                   partition_tokens=pt, flags=flags)
     torch.cuda.synchronize()
     if canary:
         assert torch.all(buf[:pad] == 12345.0) and torch.all(buf[pad + n:] == 12345.0)

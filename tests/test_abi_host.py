@@ -57,7 +57,7 @@ def call_attn(d, q=0x1000, k=0x2000, v=0x3000, bt=0x4000, cl=0x5000, out=0x6000,
     (dict(kv_dtype=7), "DTYPE"), (dict(out_dtype=9), "DTYPE"),
     (dict(num_q_heads=30), "SHAPE"), (dict(head_dim=96), "SHAPE"), (dict(block_size=8), "SHAPE"),
     (dict(block_size=24), "SHAPE"), (dict(partition_tokens=100), "SHAPE"),
-    (dict(partition_tokens=32), "SHAPE"), (dict(batch=-1), "SHAPE"), (dict(reserved=1), "SHAPE"),
+    (dict(partition_tokens=32), "SHAPE"), (dict(batch=-1), "SHAPE"), (dict(flags=2), "SHAPE"),
     (dict(max_context_len=16 * 64 + 1), "SHAPE"), (dict(k_stride_token=4), "ALIGN"),
     (dict(k_stride_token=64), "SHAPE"), (dict(v_stride_head=-128), "SHAPE"),
     (dict(num_pool_blocks=0), "SHAPE"),

@@ -43,11 +43,12 @@ def test_shapes_ragged_lengths(dtype, Hq, Hkv, D):
     lens = [1, 15, 16, 17, 63, 64, 65, 511, 512, 513, 1000, 1025, 0, 2047]
     w = W.make_attn_workload(f"ragged_{dtype}_{Hq}_{Hkv}_{D}", 42, dtype=dtype, Hq=Hq, Hkv=Hkv,
                              D=D, block_size=16, context_lens=lens, pool_factor=1.3)
-    got, _ = check(w)
-    assert np.all(got[12] == 0.0)      # empty context -> zero row
+    for flags in (0, 1):               # matrix-core kernel where it applies, then vector-ALU
+        got, _ = check(w, flags=flags)
+        assert np.all(got[12] == 0.0)      # empty context -> zero row
 
 
-@pytest.mark.parametrize("bs", [16, 32, 64])
+@pytest.mark.parametrize("bs", [16, 32, 48, 64, 128])
 def test_block_sizes(bs):
     lens = [5, bs - 1, bs, bs + 1, 700, 1300]
     w = W.make_attn_workload(f"bs{bs}", 43, dtype="bf16", Hq=32, Hkv=8, D=128, block_size=bs,
@@ -58,6 +59,24 @@ def test_block_sizes(bs):
 def test_config2_reduced_batch():
     w = W.config2_llama8b(B=16)
     check(w)
+    check(w, flags=1)
+
+
+def test_every_tile_count_and_tail_length():
+    """Contexts 1..132 and around the partition edge: every tail length of the last tile, every
+    split of tiles over the four wavefronts, one- and two-partition sequences."""
+    lens = list(range(1, 133)) + [500 + i for i in range(30)] + [1020 + i for i in range(10)]
+    w = W.make_attn_workload("tails", 49, dtype="bf16", Hq=8, Hkv=2, D=128, block_size=16,
+                             context_lens=lens, pool_factor=1.05)
+    check(w)
+    check(w, partition_tokens=64)
+
+
+def test_large_partitions_up_to_the_fast_path_limit():
+    w = W.make_attn_workload("bigpart", 51, dtype="bf16", Hq=8, Hkv=2, D=128, block_size=16,
+                             context_lens=[4096, 4095, 8192, 5000, 70], pool_factor=1.05)
+    for pt in (2048, 4096, 8192):      # 8192 exceeds the matrix-core kernel's limit: falls back
+        check(w, partition_tokens=pt)
 
 
 def test_partition_size_independence():
