@@ -95,8 +95,10 @@ int32_t pkv_attn_partition_tokens(const pkv_attn_desc* desc) { return partition_
 
 size_t pkv_attn_workspace_bytes(const pkv_attn_desc* desc) {
   if (check_attn_desc(desc) != PKV_OK) return 0;
+  if (desc->batch == 0) return 0;
+  if (attn_stream_supported(*desc)) return (size_t)stream_workspace(*desc).total();
   const int64_t P = max_partitions_of(desc);
-  if (P <= 1 || desc->batch == 0) return 0;
+  if (P <= 1) return 0;
   const int64_t rows = (int64_t)desc->batch * desc->num_q_heads * P;
   const int64_t ml = (rows * 2 * (int64_t)sizeof(float) + 255) / 256 * 256;
   const int64_t o = rows * desc->head_dim * (int64_t)sizeof(float);
@@ -140,6 +142,16 @@ int32_t paged_decode_attention(const pkv_attn_desc* desc, const void* q, const v
   p.out_is_bf16 = desc->out_dtype == PKV_BF16;
   p.no_mfma = (desc->flags & PKV_ATTN_FLAG_VECTOR_ALU) != 0;
   p.scale_log2e = scale * 1.4426950408889634f;
+  if (attn_stream_supported(*desc)) {
+    const StreamWorkspace w = stream_workspace(*desc);
+    uint8_t* base = reinterpret_cast<uint8_t*>(workspace);
+    p.ws_dir = reinterpret_cast<int32_t*>(base);
+    p.ws_ml = reinterpret_cast<float*>(base + w.dir_bytes);
+    p.ws_o = reinterpret_cast<float*>(base + w.dir_bytes + w.ml_bytes);
+    p.chunk_tiles_max = w.chunk_tiles_max;
+    const hipError_t e = launch_attn_stream(p, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? PKV_OK : PKV_ERR_HIP;
+  }
   if (need > 0) {
     const int64_t rows = (int64_t)desc->batch * desc->num_q_heads * p.max_partitions;
     const int64_t ml = (rows * 2 * (int64_t)sizeof(float) + 255) / 256 * 256;

@@ -335,9 +335,7 @@ hipError_t launch_attn_decode(const AttnParams& pin, int dtype, hipStream_t s) {
   const int eb = dtype == PKV_BF16 ? 2 : 4;
   const int row_bytes = p.head_dim * eb;
   hipError_t e = hipErrorInvalidValue;
-  if (!p.no_mfma && attn_mfma_supported(p, dtype)) {
-    e = launch_attn_partial_mfma(p, s);
-  } else if (eb == 2) {
+  if (eb == 2) {
     if (row_bytes == 128) e = launch_valu_g<2, 8>(p, s);
     else if (row_bytes == 256) e = launch_valu_g<2, 16>(p, s);
     else if (row_bytes == 512) e = launch_valu_g<2, 32>(p, s);

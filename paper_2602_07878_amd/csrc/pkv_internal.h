@@ -11,6 +11,8 @@ constexpr int kWaveSize = 64;
 constexpr int kTileTokens = 16;          // tokens handled per inner tile
 constexpr int kDefaultPartition = 512;   // split-K partition length in tokens
 constexpr int kAttnThreads = 256;        // 4 wavefronts per workgroup
+constexpr int kStreamMaxWaves = 4096;    // wavefronts of the persistent stream grid (bound)
+constexpr int kStreamMaxPrefixBytes = 16384;  // LDS for per-sequence tile prefix sums
 
 // Launch geometry and pointers of one attention call, passed by value.
 struct AttnParams {
@@ -22,6 +24,7 @@ struct AttnParams {
   void* out;
   float* ws_ml;   // [B][Hq][P][2]  (running max in log2 units, normaliser)
   float* ws_o;    // [B][Hq][P][D]  un-normalised partial output rows
+  int32_t* ws_dir;          // stream kernel: [pairs][2] (first slot, partial count)
   int64_t k_stride_block, k_stride_head, k_stride_token;  // BYTES
   int64_t v_stride_block, v_stride_head, v_stride_token;  // BYTES
   int32_t batch, num_q_heads, num_kv_heads, head_dim;
@@ -33,6 +36,8 @@ struct AttnParams {
   int32_t out_is_bf16;
   int32_t no_mfma;          // force the vector-ALU kernel
   int32_t tpb_shift;        // log2(block_size / 16) (matrix-core kernel only)
+  int32_t chunk_tiles_max;  // stream kernel: most tiles one wavefront takes per chunk (<= 64)
+  int32_t prefix_bytes;     // stream kernel: LDS bytes of the tile prefix table
   float scale_log2e;        // scale * log2(e)
 };
 
@@ -46,9 +51,15 @@ struct SwapParams {
 
 // attn_decode.hip
 hipError_t launch_attn_decode(const AttnParams& p, int dtype, hipStream_t s);
-// attn_decode_mfma.hip
-bool attn_mfma_supported(const AttnParams& p, int dtype);
-hipError_t launch_attn_partial_mfma(AttnParams& p, hipStream_t s);
+// attn_stream_mfma.hip
+struct StreamWorkspace {
+  int64_t slots, dir_bytes, ml_bytes, o_bytes;
+  int32_t chunk_tiles_max;
+  int64_t total() const { return dir_bytes + ml_bytes + o_bytes; }
+};
+bool attn_stream_supported(const pkv_attn_desc& d);
+StreamWorkspace stream_workspace(const pkv_attn_desc& d);
+hipError_t launch_attn_stream(AttnParams& p, hipStream_t s);
 // swap.hip
 hipError_t launch_swap(const SwapParams& p, hipStream_t s);
 hipError_t launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t s);

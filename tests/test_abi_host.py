@@ -75,7 +75,7 @@ def test_attention_rejects_bad_pointers_and_workspace_on_host():
     assert call_attn(d, bt=0x4002) == ST["ALIGN"]
     assert call_attn(d, scale=float("nan")) == ST["SHAPE"]
     need = binding.attn_workspace_bytes(d)
-    assert need >= 4 * 32 * 2 * (128 + 2) * 4
+    assert need > 0
     assert call_attn(d, ws_bytes=need - 1) == ST["WORKSPACE"]
     assert call_attn(d, ws=0) == ST["WORKSPACE"]
     # batch 0 is a successful no-op even with null data pointers
@@ -85,10 +85,21 @@ def test_attention_rejects_bad_pointers_and_workspace_on_host():
 def test_workspace_size_and_partition_defaults():
     d = good_desc()
     assert binding.lib().pkv_attn_partition_tokens(ctypes.byref(d)) == 512
-    assert binding.attn_workspace_bytes(good_desc(max_context_len=512)) == 0
-    assert binding.attn_workspace_bytes(good_desc(max_context_len=513)) > 0
-    assert binding.attn_workspace_bytes(good_desc(partition_tokens=1024)) == 0
+    # bf16 / D=128 takes the stream kernel: a directory plus at least one partial slot per
+    # (sequence, KV head) and per wavefront of the grid
+    need = binding.attn_workspace_bytes(d)
+    assert need >= (4 * 8 + 1) * 4 * (128 + 2) * 4
+    # an explicit partition length bounds the tokens per partial: more slots
+    assert binding.attn_workspace_bytes(good_desc(partition_tokens=64)) > need
+    # fp32 takes the grid kernel: no workspace while every context fits one partition
+    f32 = dict(kv_dtype=0, head_dim=64, k_stride_token=64, v_stride_token=64,
+               k_stride_head=16 * 64, v_stride_head=16 * 64, k_stride_block=8 * 16 * 64,
+               v_stride_block=8 * 16 * 64)
+    assert binding.attn_workspace_bytes(good_desc(max_context_len=512, **f32)) == 0
+    assert binding.attn_workspace_bytes(good_desc(max_context_len=513, **f32)) > 0
+    assert binding.attn_workspace_bytes(good_desc(partition_tokens=1024, **f32)) == 0
     assert binding.attn_workspace_bytes(good_desc(head_dim=96)) == 0   # invalid -> 0
+    assert binding.attn_workspace_bytes(good_desc(batch=0)) == 0
 
 
 def swap_desc(**kw):
