@@ -51,7 +51,7 @@ def time_attention(w, d, steps, warmup, torch, binding):
     desc = binding.attn_desc_for(d["q"], d["ks"][0], d["vs"][0], d["bt"],
                                  max_context_len=w.max_context_len,
                                  partition_tokens=w.partition_tokens)
-    ws = torch.empty(max(16, binding.attn_workspace_bytes(desc)), dtype=torch.uint8, device="cuda:0")
+    ws = binding.new_workspace(binding.attn_workspace_bytes(desc), "cuda:0")
     L = len(d["ks"])
 
     def step(i):

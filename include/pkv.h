@@ -74,7 +74,8 @@ typedef struct pkv_attn_desc {
   int32_t num_pool_blocks;    /* blocks in k_pool / v_pool (validators only)     */
   int32_t max_blocks_per_seq; /* row stride (entries) of block_tables            */
   int32_t max_context_len;    /* host-known upper bound of all n_i; sizes grid   */
-  int32_t partition_tokens;   /* split-K partition, multiple of 64; 0 = default  */
+  int32_t partition_tokens;   /* most tokens per split-K partial, multiple of 64;
+                                 0 = chosen by the library                       */
   int32_t kv_dtype;           /* pkv_dtype of q, k_pool and v_pool               */
   int32_t out_dtype;          /* pkv_dtype of out: PKV_F32 or PKV_BF16           */
   int32_t flags;              /* 0, or PKV_ATTN_FLAG_* bits                      */
@@ -141,7 +142,8 @@ size_t pkv_attn_workspace_bytes(const pkv_attn_desc* desc);
  *  out          [B][Hq][D]   out_dtype, contiguous
  *  workspace    >= pkv_attn_workspace_bytes(desc) bytes, 16-byte aligned; may
  *               be NULL when that size is 0.  Contents on return are
- *               unspecified.
+ *               unspecified; one buffer may serve calls with different
+ *               descriptors, but not two calls at the same time.
  * Accumulation is fp32.  The result does not depend on where blocks sit in
  * the pool; for a fixed partition length it is bit-reproducible run to run.
  */

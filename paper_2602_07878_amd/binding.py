@@ -141,6 +141,12 @@ def attn_workspace_bytes(desc: AttnDesc) -> int:
     return int(lib().pkv_attn_workspace_bytes(ctypes.byref(desc)))
 
 
+def new_workspace(nbytes: int, device, *, stream=None):
+    """Allocate a workspace tensor of `nbytes` bytes (contents need no initialisation)."""
+    import torch
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
 def paged_decode_attention(q, k_pool, v_pool, block_tables, context_lens, scale, out, *,
                            max_context_len: int, partition_tokens: int = 0, workspace=None,
                            desc: Optional[AttnDesc] = None, stream=None, flags: int = 0):
@@ -155,7 +161,7 @@ def paged_decode_attention(q, k_pool, v_pool, block_tables, context_lens, scale,
     assert block_tables.is_contiguous() and context_lens.is_contiguous() and out.is_contiguous()
     need = int(L.pkv_attn_workspace_bytes(ctypes.byref(desc)))
     if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
-        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+        workspace = new_workspace(need, q.device, stream=stream)
     ws_ptr = workspace.data_ptr() if workspace is not None else None
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     st = L.paged_decode_attention(ctypes.byref(desc), q.data_ptr(), k_pool.data_ptr(),

@@ -12,7 +12,9 @@
 // exist.  A chunk may cover parts of several (sequence, pair)s: each part is a segment
 // and ends in a flush -- the finished output row if the segment is the whole pair, else
 // an (m, l, O) partial that the merge kernel combines by log-sum-exp.  Wavefronts never
-// synchronise with each other after the set-up.
+// wait for each other after the set-up; the two wavefronts that share a SIMD only trade
+// issue priority so that neither falls behind (the older one would otherwise win every
+// arbitration tie and finish a third earlier, leaving the CU half empty at the end).
 //
 // Per tile:
 //  * K goes HBM -> LDS with direct-to-LDS 16-byte loads (no VGPR staging) into a 2-deep
@@ -45,12 +47,13 @@ typedef __attribute__((ext_vector_type(2))) int32_t i32x2;
 
 constexpr float kNegBig = -1.0e30f;
 constexpr float kSlack = 8.0f;             // log2 units the reference may lag the true max
-constexpr int kNW = kAttnThreads / kWaveSize;
+constexpr int kStreamThreads = 512;        // one workgroup of 8 wavefronts per CU
+constexpr int kNW = kStreamThreads / kWaveSize;
 constexpr int kTileBytes = 4096;           // 16 tokens x 256-byte rows
 constexpr int kStages = 2;
 constexpr int kDescBatch = 256;            // tile descriptors built per pass over the index arrays
 constexpr int kWaveLds = kStages * kTileBytes + 1024 + kDescBatch * 16;   // K ring + P tile + descriptors
-constexpr int kMinChunk = 4;               // tiles; keeps tiny calls from spraying 1-tile chunks
+constexpr int kMinGroupTiles = 32;         // tiles per workgroup range below which fewer workgroups work
 constexpr int D = 128;
 
 #define PKV_WAIT_VMCNT(n) \
@@ -86,25 +89,35 @@ __device__ __forceinline__ int rfl(int v) { return __builtin_amdgcn_readfirstlan
 typedef const void __attribute__((address_space(1)))* gptr_t;
 typedef void __attribute__((address_space(3)))* lptr_t;
 
-// Chunk geometry shared by the stream kernel and the merge kernel: T tiles over NU
-// wavefronts, at most rmax tiles per chunk.  k chunks per wavefront, R tiles per chunk.
-__device__ __forceinline__ void chunk_geometry(int T, int NU, int rmax, int& k, int& R) {
-  if (rmax <= 0 || T <= NU * rmax) {   // rmax 0: no cap, one chunk per wavefront
-    k = 1;
-    R = max(rmax > 0 ? min(kMinChunk, rmax) : kMinChunk, (T + NU - 1) / NU);
-  } else {
-    k = (T + NU * rmax - 1) / (NU * rmax);
-    R = (T + NU * k - 1) / (NU * k);
+// Chunk schedule.  The tile axis is cut into equal contiguous ranges, one per workgroup,
+// and each range into `ns` chunks of `rs` tiles: one per wavefront, or more and shorter ones
+// when the caller caps the tokens per partial (wavefront w then takes chunks w, w+8, ...).
+// Chunk ids grow along the axis: id = workgroup * ns + local id.
+struct ChunkPlan {
+  int lg, rs, ns;
+  __device__ __forceinline__ int chunk_of(int x) const {
+    const int g = x / lg;
+    return g * ns + (x - g * lg) / rs;
   }
+};
+
+__device__ __forceinline__ ChunkPlan plan_chunks(int T, int nwg, int cap) {
+  ChunkPlan pl;
+  pl.lg = max(kMinGroupTiles, (T + nwg - 1) / nwg);
+  pl.rs = (pl.lg + kNW - 1) / kNW;
+  if (cap > 0) pl.rs = min(pl.rs, cap);
+  pl.ns = (pl.lg + pl.rs - 1) / pl.rs;
+  return pl;
 }
 
 // GH = query heads accumulated per lane (1, 2, 4 or 8).
 template <int GH>
-__global__ __launch_bounds__(kAttnThreads, 2) void attn_stream_mfma_d128(const AttnParams p) {
+__global__ __launch_bounds__(kStreamThreads, 2) void attn_stream_mfma_d128(const AttnParams p) {
   constexpr int HS = GH >= 8 ? 8 : 4;   // distinct head slots among the 16 MFMA rows
 
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
   __shared__ int wave_total[kNW];
+  __shared__ int progress[kNW];   // tiles consumed so far, per wavefront
 
   const int tid = threadIdx.x;
   const int lane = tid & (kWaveSize - 1);
@@ -117,7 +130,8 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_stream_mfma_d128(const A
   // ---- set-up: exclusive prefix sums of per-sequence tile counts, in LDS ------------------
   int* prefix = reinterpret_cast<int*>(lds);       // [B + 1]
   {
-    const int per = (B + kAttnThreads - 1) / kAttnThreads;
+    if (tid < kNW) progress[tid] = 0;
+    const int per = (B + kStreamThreads - 1) / kStreamThreads;
     const int i0 = tid * per, i1 = min(B, i0 + per);
     int sum = 0;
     for (int i = i0; i < i1; ++i) sum += (max(p.context_lens[i], 0) + kTileTokens - 1) / kTileTokens;
@@ -141,12 +155,10 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_stream_mfma_d128(const A
   const int T = rfl(prefix[B]) * NP;               // tiles of the whole call
   if (T == 0) return;
 
-  const int NU = gridDim.x * kNW;
-  const int u = blockIdx.x * kNW + wave;
-  int k, R;
-  chunk_geometry(T, NU, p.chunk_tiles_max, k, R);
-  const int nchunks = (T + R - 1) / R;
-
+  const ChunkPlan plan = plan_chunks(T, gridDim.x, p.chunk_tiles_max);
+  const int g0 = blockIdx.x * plan.lg;                     // first tile of this workgroup's range
+  const int glen = min(plan.lg, T - g0);                   // its length (<= 0: nothing to do)
+  if (glen <= 0) return;
   // ---- per-lane, loop-invariant offsets -------------------------------------------------------
   uint32_t koff[4], voff[4], krd[4];
 #pragma unroll
@@ -163,6 +175,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_stream_mfma_d128(const A
   const uint8_t* vpool = reinterpret_cast<const uint8_t*>(p.v_pool);
   const int tile_mask = (1 << p.tpb_shift) - 1;
 
+  int tiles_done = 0;
   float m[4], l[4];
   float acc[GH][8];
   bf16x8 qfrag[4];
@@ -170,11 +183,10 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_stream_mfma_d128(const A
 
   u32x4* dtab = reinterpret_cast<u32x4*>(wlds + kStages * kTileBytes + 1024);   // [kDescBatch]
 
-  for (int kk = 0; kk < k; ++kk) {
-    const int c = u * k + kk;                       // chunk index on the tile axis
-    if (c >= nchunks) break;
-    const int x0 = c * R;
-    const int ntc = min(R, T - x0);                 // tiles of this chunk
+  for (int ci = wave; ci < plan.ns && ci * plan.rs < glen; ci += kNW) {   // local chunk id
+    const int c = blockIdx.x * plan.ns + ci;         // chunk id on the whole axis
+    const int x0 = g0 + ci * plan.rs;
+    const int ntc = min(glen, (ci + 1) * plan.rs) - ci * plan.rs;   // tiles of this chunk
 
     // state of the segment that is being accumulated (may span descriptor groups)
     bool open = false;
@@ -323,6 +335,12 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_stream_mfma_d128(const A
 #pragma unroll
               for (int e = 0; e < 8; ++e) acc[g][e] = fmaf(pv[g], vf[e], acc[g][e]);
           }
+          // The two wavefronts that share a SIMD (w and w+4) do not get equal issue slots: the
+          // older one wins every tie.  Whoever is behind raises its priority until it catches up.
+          ++tiles_done;
+          if (lane == 0) progress[wave] = tiles_done;
+          if (progress[wave ^ (kNW / 2)] > tiles_done) __builtin_amdgcn_s_setprio(2);
+          else __builtin_amdgcn_s_setprio(0);
         };
 
         // ---- segments of the group ----------------------------------------------------------------
@@ -440,7 +458,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_stream_mfma_d128(const A
               if (first && lane == 0) {
                 // directory entry of the pair: its partials sit in consecutive slots
                 const int tiles = seg_info0 >> 8;
-                const int c_last = (seg_x + tiles - 1) / R;
+                const int c_last = plan.chunk_of(seg_x + tiles - 1);
                 *reinterpret_cast<i32x2*>(p.ws_dir + 2 * (int64_t)prank) = i32x2{(int)slot, c_last - c + 1};
               }
             }
@@ -456,36 +474,62 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_stream_mfma_d128(const A
 // Merge of the partials of one (sequence, query head); also writes the zero rows of
 // empty contexts.  M = max m_p, L = sum l_p 2^(m_p-M), out = sum O_p 2^(m_p-M) / L, partials
 // taken in ascending order along the tile axis.
+constexpr int kMergeThreads = 256, kMW = kMergeThreads / kWaveSize;
+
 template <int GH>
-__global__ __launch_bounds__(D) void attn_stream_merge(const AttnParams p) {
-  const int h = blockIdx.x, seq = blockIdx.y, d = threadIdx.x;
-  const int64_t o = ((int64_t)seq * p.num_q_heads + h) * D + d;
-  if (p.context_lens[seq] <= 0) {
-    if (p.out_is_bf16) reinterpret_cast<uint16_t*>(p.out)[o] = 0;
-    else reinterpret_cast<float*>(p.out)[o] = 0.f;
-    return;
-  }
+__global__ __launch_bounds__(kMergeThreads) void attn_stream_merge(const AttnParams p) {
+  __shared__ float sM[kMW], sL[kMW];
+  __shared__ __attribute__((aligned(16))) float sO[kMW][D];
+  const int h = blockIdx.x, seq = blockIdx.y, tid = threadIdx.x;
+  const int lane = tid & (kWaveSize - 1), wave = tid / kWaveSize;
   const int kvh = h / p.group, gi = h - kvh * p.group;
   const int gtile = gi / GH, g = gi - gtile * GH;
   const int64_t prank = ((int64_t)seq * p.num_kv_heads + kvh) * p.group_tiles + gtile;
+  const int n = p.context_lens[seq];
+  const int64_t o = ((int64_t)seq * p.num_q_heads + h) * D;
+  if (n <= 0) {                          // block-uniform
+    if (tid < D) {
+      if (p.out_is_bf16) reinterpret_cast<uint16_t*>(p.out)[o + tid] = 0;
+      else reinterpret_cast<float*>(p.out)[o + tid] = 0.f;
+    }
+    return;
+  }
   const i32x2 de = *reinterpret_cast<const i32x2*>(p.ws_dir + 2 * prank);
   const int count = de[1];
-  if (count <= 1) return;              // finished by the stream kernel
+  if (count <= 1) return;                // finished by the stream kernel (block-uniform)
   const int64_t s0 = de[0];
+  const float* ml = p.ws_ml + (s0 * GH + g) * 2;            // partial q at ml[q*GH*2]
+  const float* ov = p.ws_o + (s0 * GH + g) * D + 2 * lane;  // partial q at ov[q*GH*D]
+
+  // reference maximum over all partials
   float M = kNegBig;
-  for (int q = 0; q < count; ++q) M = fmaxf(M, p.ws_ml[((s0 + q) * GH + g) * 2]);
-  float L = 0.f, O = 0.f;
-  for (int q = 0; q < count; ++q) {
-    const float f = __builtin_amdgcn_exp2f(p.ws_ml[((s0 + q) * GH + g) * 2] - M);
-    L = fmaf(p.ws_ml[((s0 + q) * GH + g) * 2 + 1], f, L);
-    O = fmaf(p.ws_o[((s0 + q) * GH + g) * D + d], f, O);
+  for (int q = tid; q < count; q += kMergeThreads) M = fmaxf(M, ml[(int64_t)q * GH * 2]);
+#pragma unroll
+  for (int off = 1; off < kWaveSize; off <<= 1) M = fmaxf(M, __shfl_xor(M, off, kWaveSize));
+  if (lane == 0) sM[wave] = M;
+  __syncthreads();
+  M = fmaxf(fmaxf(sM[0], sM[1]), fmaxf(sM[2], sM[3]));
+
+  // wave w sums partials w, w+4, ... (ascending); lane covers output dims 2*lane, 2*lane+1
+  float L = 0.f, O0 = 0.f, O1 = 0.f;
+#pragma unroll 4
+  for (int q = wave; q < count; q += kMW) {
+    const f32x2 mlq = *reinterpret_cast<const f32x2*>(ml + (int64_t)q * GH * 2);
+    const f32x2 oq = *reinterpret_cast<const f32x2*>(ov + (int64_t)q * GH * D);
+    const float f = __builtin_amdgcn_exp2f(mlq[0] - M);
+    L = fmaf(mlq[1], f, L);
+    O0 = fmaf(oq[0], f, O0);
+    O1 = fmaf(oq[1], f, O1);
   }
-  const float r = O / L;
-  if (p.out_is_bf16) {
-    const uint32_t w = pack_bf16x2_rne(r, 0.f);
-    reinterpret_cast<uint16_t*>(p.out)[o] = (uint16_t)(w & 0xFFFFu);
-  } else {
-    reinterpret_cast<float*>(p.out)[o] = r;
+  sO[wave][2 * lane] = O0;
+  sO[wave][2 * lane + 1] = O1;
+  if (lane == 0) sL[wave] = L;
+  __syncthreads();
+  if (tid < D) {
+    const float Lt = (sL[0] + sL[1]) + (sL[2] + sL[3]);
+    const float r = ((sO[0][tid] + sO[1][tid]) + (sO[2][tid] + sO[3][tid])) / Lt;
+    if (p.out_is_bf16) reinterpret_cast<uint16_t*>(p.out)[o + tid] = (uint16_t)(pack_bf16x2_rne(r, 0.f) & 0xFFFFu);
+    else reinterpret_cast<float*>(p.out)[o + tid] = r;
   }
 }
 
@@ -505,21 +549,18 @@ int num_cus() {
 template <int GH>
 hipError_t launch(const AttnParams& p, hipStream_t s) {
   const size_t lds = (size_t)p.prefix_bytes + (size_t)kNW * kWaveLds;
-  static int wgs_per_cu = 0;   // occupancy of this instantiation with the largest LDS request
-  if (wgs_per_cu == 0) {
-    int n = 0;
-    const size_t lds_max = (size_t)kStreamMaxPrefixBytes + (size_t)kNW * kWaveLds;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, attn_stream_mfma_d128<GH>, kAttnThreads,
-                                                     lds_max) != hipSuccess || n < 1)
-      n = 1;
-    wgs_per_cu = n > 4 ? 4 : n;
+  static bool prepared = false;   // more than 64 KiB of dynamic LDS has to be asked for once
+  if (!prepared) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_stream_mfma_d128<GH>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize,
+                                             kStreamMaxPrefixBytes + kNW * kWaveLds);
+    if (e != hipSuccess) return e;
+    prepared = true;
   }
-  int grid = num_cus() * wgs_per_cu;
-  if (grid * kNW > kStreamMaxWaves) grid = kStreamMaxWaves / kNW;
-  hipLaunchKernelGGL((attn_stream_mfma_d128<GH>), dim3(grid), dim3(kAttnThreads), lds, s, p);
+  hipLaunchKernelGGL((attn_stream_mfma_d128<GH>), dim3(num_cus()), dim3(kStreamThreads), lds, s, p);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((attn_stream_merge<GH>), dim3(p.num_q_heads, p.batch), dim3(D), 0, s, p);
+  hipLaunchKernelGGL((attn_stream_merge<GH>), dim3(p.num_q_heads, p.batch), dim3(kMergeThreads), 0, s, p);
   return hipGetLastError();
 }
 
@@ -557,7 +598,10 @@ StreamWorkspace stream_workspace(const pkv_attn_desc& d) {
   const int pt = d.partition_tokens == 0 ? kDefaultPartition : d.partition_tokens;
   // partition_tokens 0: no cap on what one wavefront accumulates before it writes a partial
   w.chunk_tiles_max = d.partition_tokens == 0 ? 0 : pt / kTileTokens;
-  w.slots = pairs + (w.chunk_tiles_max ? tiles_ub / w.chunk_tiles_max : 0) + kStreamMaxWaves + 1;
+  // chunk ids stay below workgroups * chunks-per-workgroup, see plan_chunks()
+  const int64_t ncu = num_cus();
+  const int64_t cap = w.chunk_tiles_max;
+  w.slots = pairs + (cap ? (tiles_ub + kMinGroupTiles * ncu) / cap + ncu : 0) + ncu * (kNW + 1) + 2;
   auto up = [](int64_t b) { return (b + 255) / 256 * 256; };
   w.dir_bytes = up(pairs * 2 * 4);
   w.ml_bytes = up(w.slots * gh * 2 * 4);

@@ -11,7 +11,6 @@ constexpr int kWaveSize = 64;
 constexpr int kTileTokens = 16;          // tokens handled per inner tile
 constexpr int kDefaultPartition = 512;   // split-K partition length in tokens
 constexpr int kAttnThreads = 256;        // 4 wavefronts per workgroup
-constexpr int kStreamMaxWaves = 4096;    // wavefronts of the persistent stream grid (bound)
 constexpr int kStreamMaxPrefixBytes = 16384;  // LDS for per-sequence tile prefix sums
 
 // Launch geometry and pointers of one attention call, passed by value.

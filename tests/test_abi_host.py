@@ -89,8 +89,9 @@ def test_workspace_size_and_partition_defaults():
     # (sequence, KV head) and per wavefront of the grid
     need = binding.attn_workspace_bytes(d)
     assert need >= (4 * 8 + 1) * 4 * (128 + 2) * 4
-    # an explicit partition length bounds the tokens per partial: more slots
-    assert binding.attn_workspace_bytes(good_desc(partition_tokens=64)) > need
+    assert binding.attn_workspace_bytes(good_desc(partition_tokens=64)) >= need
+    assert binding.attn_workspace_bytes(good_desc(batch=64, max_blocks_per_seq=256,
+                                                  max_context_len=4096)) < 64 << 20
     # fp32 takes the grid kernel: no workspace while every context fits one partition
     f32 = dict(kv_dtype=0, head_dim=64, k_stride_token=64, v_stride_token=64,
                k_stride_head=16 * 64, v_stride_head=16 * 64, k_stride_block=8 * 16 * 64,
