@@ -51,8 +51,8 @@ constexpr int kStreamThreads = 512;        // one workgroup of 8 wavefronts per 
 constexpr int kNW = kStreamThreads / kWaveSize;
 constexpr int kTileBytes = 4096;           // 16 tokens x 256-byte rows
 constexpr int kStages = 2;
-constexpr int kDescBatch = 256;            // tile descriptors built per pass over the index arrays
-constexpr int kWaveLds = kStages * kTileBytes + 1024 + kDescBatch * 16;   // K ring + P tile + descriptors
+constexpr int kDescBatch = 128;            // tile descriptors per table
+constexpr int kWaveLds = kStages * kTileBytes + 1024 + 2 * kDescBatch * 16;   // K ring + P tile + 2 descriptor tables
 constexpr int kMinGroupTiles = 32;         // tiles per workgroup range below which fewer workgroups work
 constexpr int D = 128;
 
@@ -158,6 +158,7 @@ __global__ __launch_bounds__(kStreamThreads, 2) void attn_stream_mfma_d128(const
   const ChunkPlan plan = plan_chunks(T, gridDim.x, p.chunk_tiles_max);
   const int g0 = blockIdx.x * plan.lg;                     // first tile of this workgroup's range
   const int glen = min(plan.lg, T - g0);                   // its length (<= 0: nothing to do)
+  const int rs = plan.rs;                                  // tiles per chunk
   if (glen <= 0) return;
   // ---- per-lane, loop-invariant offsets -------------------------------------------------------
   uint32_t koff[4], voff[4], krd[4];
@@ -181,299 +182,355 @@ __global__ __launch_bounds__(kStreamThreads, 2) void attn_stream_mfma_d128(const
   bf16x8 qfrag[4];
   u32x4 vreg[kStages][4];
 
-  u32x4* dtab = reinterpret_cast<u32x4*>(wlds + kStages * kTileBytes + 1024);   // [kDescBatch]
+  // two descriptor tables per wavefront: the one in use and the one filled ahead for the next chunk
+  u32x4* dtabs = reinterpret_cast<u32x4*>(wlds + kStages * kTileBytes + 1024);   // [2][kDescBatch]
 
-  for (int ci = wave; ci < plan.ns && ci * plan.rs < glen; ci += kNW) {   // local chunk id
+  // Tile descriptors of `count` (<= kDescBatch) tiles from axis position xb, built by the lanes:
+  //   x: byte offset / 16 of the tile's first K row      y: same for V
+  //   z: sequence << 8 | pair
+  //   w: valid tokens (1..16) | first-of-pair << 5 | last-of-pair << 6 | tiles of the pair << 8
+  auto build_desc = [&](int xb, int count, u32x4* tab) {
+#pragma unroll 1
+    for (int pass = 0; pass * kWaveSize < count; ++pass) {
+    const int idx = pass * kWaveSize + lane;
+    const int x = xb + min(idx, count - 1);
+    const int xq = x / NP;
+    int lo = 0, hi = B;                            // prefix[lo] <= xq < prefix[hi]
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (prefix[mid] <= xq) lo = mid; else hi = mid;
+    }
+    const int seq = lo;
+    const int pstart = prefix[seq];
+    const int tiles = prefix[seq + 1] - pstart;
+    const int rem = x - pstart * NP;
+    const int pp = rem / tiles;
+    const int t = rem - pp * tiles;
+    const int kvh = pp / p.group_tiles;
+    const int n = p.context_lens[seq];
+    const int blk = p.block_tables[(int64_t)seq * p.max_blocks_per_seq + (t >> p.tpb_shift)];
+    const int slot0 = (t & tile_mask) * kTileTokens;
+    u32x4 d;
+    d[0] = (uint32_t)((blk * p.k_stride_block + kvh * p.k_stride_head + slot0 * p.k_stride_token) >> 4);
+    d[1] = (uint32_t)((blk * p.v_stride_block + kvh * p.v_stride_head + slot0 * p.v_stride_token) >> 4);
+    d[2] = (uint32_t)((seq << 8) | pp);
+    const int ntok = min(kTileTokens, n - t * kTileTokens);
+    d[3] = (uint32_t)(ntok | ((t == 0) << 5) | ((t == tiles - 1) << 6) | (tiles << 8));
+    tab[idx] = d;
+    }
+  };
+
+  int d_k = 0, d_v = 0, d_sp = 0, d_info = 0;   // descriptors of the current group, one tile per lane
+
+  auto issue_at = [&](uint32_t sk, uint32_t sv, int stage) {
+    const uint8_t* kb = kpool + ((uint64_t)sk << 4);
+    const uint8_t* vb = vpool + ((uint64_t)sv << 4);
+    uint8_t* kl = wlds + stage * kTileBytes;
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj)
+      __builtin_amdgcn_global_load_lds((gptr_t)(kb + koff[jj]), (lptr_t)(kl + jj * 1024), 16, 0, 0);
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj)
+      vreg[stage][jj] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vb + voff[jj]));
+  };
+  auto issue = [&](int j, int stage) {
+    issue_at((uint32_t)__builtin_amdgcn_readlane(d_k, j), (uint32_t)__builtin_amdgcn_readlane(d_v, j), stage);
+  };
+
+  auto load_q = [&](int sp) {
+    const int seq = sp >> 8, pp = sp & 255;
+    const int kvh = pp / p.group_tiles, gtile = pp - kvh * p.group_tiles;
+    const int h0 = kvh * p.group + gtile * GH;
+    const int nheads = min(GH, p.group - gtile * GH);
+    const int hs = min(t16 % HS, nheads - 1);
+    const uint8_t* qp = reinterpret_cast<const uint8_t*>(p.q) +
+                        ((int64_t)seq * p.num_q_heads + h0 + hs) * (D * 2) + q4 * 16;
+#pragma unroll
+    for (int cidx = 0; cidx < 4; ++cidx)
+      qfrag[cidx] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(qp + cidx * 64));
+  };
+
+  // TAIL: the tile may hold fewer than 16 valid tokens (only the last tile of a pair can)
+  auto consume = [&](int j, int stage, auto tail_tag) {
+    constexpr bool TAIL = decltype(tail_tag)::value;
+    const int ntok = TAIL ? (__builtin_amdgcn_readlane(d_info, j) & 31) : kTileTokens;
+    const uint8_t* kl = wlds + stage * kTileBytes;
+    f32x4 cfr = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+      const bf16x8 kf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(kl + krd[jj]));
+      cfr = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qfrag[jj], kf, cfr, 0, 0, 0);
+    }
+    const bool dead = TAIL && (t16 >= ntok);
+    float s[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) s[r] = dead ? -INFINITY : cfr[r] * p.scale_log2e;
+
+    bool grow = false;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) grow |= s[r] > m[r] + kSlack;
+    if (__builtin_amdgcn_ballot_w64(grow) != 0) {      // wave-uniform, rare after a first tile
+      f32x4 alpha;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float mn = fmaxf(m[r], row16_max(s[r]));
+        alpha[r] = __builtin_amdgcn_exp2f(m[r] - mn);
+        m[r] = mn;
+        l[r] *= alpha[r];
+      }
+      // the rescale factors of all head slots are needed by every lane's accumulators
+      *reinterpret_cast<f32x4*>(pbuf + 4 * q4) = alpha;
+      float a[GH];
+#pragma unroll
+      for (int g = 0; g < GH; ++g) a[g] = pbuf[g];
+#pragma unroll
+      for (int g = 0; g < GH; ++g)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[g][e] *= a[g];
+    }
+
+    f32x4 pw;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      pw[r] = __builtin_amdgcn_exp2f(s[r] - m[r]);
+      l[r] += pw[r];
+    }
+    *reinterpret_cast<f32x4*>(pbuf + t16 * 16 + 4 * q4) = pw;
+
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+      const int tok = 4 * jj + q4;                      // V row held by this lane for load jj
+      float pv[GH];
+      if constexpr (GH >= 4) {
+#pragma unroll
+        for (int g4 = 0; g4 < GH / 4; ++g4) {
+          const f32x4 t = *reinterpret_cast<const f32x4*>(pbuf + tok * 16 + 4 * g4);
+          pv[4 * g4] = t[0]; pv[4 * g4 + 1] = t[1]; pv[4 * g4 + 2] = t[2]; pv[4 * g4 + 3] = t[3];
+        }
+      } else if constexpr (GH == 2) {
+        const f32x2 t = *reinterpret_cast<const f32x2*>(pbuf + tok * 16);
+        pv[0] = t[0]; pv[1] = t[1];
+      } else {
+        pv[0] = pbuf[tok * 16];
+      }
+      u32x4 vv = vreg[stage][jj];
+      if (TAIL && tok >= ntok) vv = u32x4{0, 0, 0, 0};   // stale slot: may hold NaN bits
+      float vf[8];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        vf[2 * e] = __builtin_bit_cast(float, vv[e] << 16);
+        vf[2 * e + 1] = __builtin_bit_cast(float, vv[e] & 0xFFFF0000u);
+      }
+#pragma unroll
+      for (int g = 0; g < GH; ++g)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[g][e] = fmaf(pv[g], vf[e], acc[g][e]);
+    }
+    // The two wavefronts that share a SIMD (w and w+4) do not get equal issue slots: the
+    // older one wins every tie.  Whoever is behind raises its priority until it catches up.
+    ++tiles_done;
+    if (lane == 0) progress[wave] = tiles_done;
+    if (progress[wave ^ (kNW / 2)] > tiles_done) __builtin_amdgcn_s_setprio(2);
+    else __builtin_amdgcn_s_setprio(0);
+  };
+
+
+  // state of the segment being accumulated (may span groups of one chunk) and of the pipeline
+  bool open = false;        // a segment is being accumulated
+  bool inflight = false;    // the first tile of the coming group is already issued, its query loaded
+  int seg_sp = 0, seg_info0 = 0, seg_x = 0, sp = 0, tab = 0;
+
+  auto chunk_valid = [&](int ci) { return ci < plan.ns && ci * rs < glen; };
+  auto chunk_tiles = [&](int ci) { return min(glen, (ci + 1) * rs) - ci * rs; };
+
+  if (chunk_valid(wave)) build_desc(g0 + wave * rs, min(kDescBatch, chunk_tiles(wave)), dtabs);
+  for (int ci = wave; chunk_valid(ci); ci += kNW) {   // local chunk id
     const int c = blockIdx.x * plan.ns + ci;         // chunk id on the whole axis
-    const int x0 = g0 + ci * plan.rs;
-    const int ntc = min(glen, (ci + 1) * plan.rs) - ci * plan.rs;   // tiles of this chunk
-
-    // state of the segment that is being accumulated (may span descriptor groups)
-    bool open = false;
-    int seg_sp = 0, seg_info0 = 0, seg_x = 0;
+    const int x0 = g0 + ci * rs;
+    const int ntc = chunk_tiles(ci);                 // tiles of this chunk
+    const bool has_next = chunk_valid(ci + kNW);
 
     for (int b0 = 0; b0 < ntc; b0 += kDescBatch) {
-      // ---- tile descriptors of up to kDescBatch tiles, built by the lanes, parked in LDS --------
-      //   x: byte offset / 16 of the tile's first K row      y: same for V
-      //   z: sequence << 8 | pair
-      //   w: valid tokens (1..16) | first-of-pair << 5 | last-of-pair << 6 | tiles of the pair << 8
       const int ntb = min(kDescBatch, ntc - b0);
-#pragma unroll 1
-      for (int pass = 0; pass < kDescBatch / kWaveSize; ++pass) {
-        if (pass * kWaveSize >= ntb) break;
-        const int idx = pass * kWaveSize + lane;
-        const int x = x0 + b0 + min(idx, ntb - 1);
-        const int xq = x / NP;
-        int lo = 0, hi = B;                            // prefix[lo] <= xq < prefix[hi]
-        while (hi - lo > 1) {
-          const int mid = (lo + hi) >> 1;
-          if (prefix[mid] <= xq) lo = mid; else hi = mid;
-        }
-        const int seq = lo;
-        const int pstart = prefix[seq];
-        const int tiles = prefix[seq + 1] - pstart;
-        const int rem = x - pstart * NP;
-        const int pp = rem / tiles;
-        const int t = rem - pp * tiles;
-        const int kvh = pp / p.group_tiles;
-        const int n = p.context_lens[seq];
-        const int blk = p.block_tables[(int64_t)seq * p.max_blocks_per_seq + (t >> p.tpb_shift)];
-        const int slot0 = (t & tile_mask) * kTileTokens;
-        u32x4 d;
-        d[0] = (uint32_t)((blk * p.k_stride_block + kvh * p.k_stride_head + slot0 * p.k_stride_token) >> 4);
-        d[1] = (uint32_t)((blk * p.v_stride_block + kvh * p.v_stride_head + slot0 * p.v_stride_token) >> 4);
-        d[2] = (uint32_t)((seq << 8) | pp);
-        const int ntok = min(kTileTokens, n - t * kTileTokens);
-        d[3] = (uint32_t)(ntok | ((t == 0) << 5) | ((t == tiles - 1) << 6) | (tiles << 8));
-        dtab[idx] = d;
-      }
+      u32x4* dtab = dtabs + tab * kDescBatch;
+      if (b0 > 0) build_desc(x0 + b0, ntb, dtab);   // a chunk's first batch was built ahead
+      const bool last_batch = b0 + ntb == ntc;
 
       for (int r0 = 0; r0 < ntb; r0 += kWaveSize) {
         const int nt = min(kWaveSize, ntb - r0);    // tiles of this group, one descriptor per lane
-        const u32x4 dreg = dtab[r0 + min(lane, nt - 1)];
-        const int d_k = (int)dreg[0], d_v = (int)dreg[1], d_sp = (int)dreg[2], d_info = (int)dreg[3];
+        {
+          const u32x4 dreg = dtab[r0 + min(lane, nt - 1)];
+          d_k = (int)dreg[0]; d_v = (int)dreg[1]; d_sp = (int)dreg[2]; d_info = (int)dreg[3];
+        }
         const bool chunk_ends_here = b0 + r0 + nt == ntc;
 
-        auto issue = [&](int j, int stage) {
-          const uint8_t* kb = kpool + ((uint64_t)(uint32_t)__builtin_amdgcn_readlane(d_k, j) << 4);
-          const uint8_t* vb = vpool + ((uint64_t)(uint32_t)__builtin_amdgcn_readlane(d_v, j) << 4);
-          uint8_t* kl = wlds + stage * kTileBytes;
-#pragma unroll
-          for (int jj = 0; jj < 4; ++jj)
-            __builtin_amdgcn_global_load_lds((gptr_t)(kb + koff[jj]), (lptr_t)(kl + jj * 1024), 16, 0, 0);
-#pragma unroll
-          for (int jj = 0; jj < 4; ++jj)
-            vreg[stage][jj] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vb + voff[jj]));
-        };
-
-        auto load_q = [&](int sp) {
-          const int seq = sp >> 8, pp = sp & 255;
-          const int kvh = pp / p.group_tiles, gtile = pp - kvh * p.group_tiles;
-          const int h0 = kvh * p.group + gtile * GH;
-          const int nheads = min(GH, p.group - gtile * GH);
-          const int hs = min(t16 % HS, nheads - 1);
-          const uint8_t* qp = reinterpret_cast<const uint8_t*>(p.q) +
-                              ((int64_t)seq * p.num_q_heads + h0 + hs) * (D * 2) + q4 * 16;
-#pragma unroll
-          for (int cidx = 0; cidx < 4; ++cidx)
-            qfrag[cidx] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(qp + cidx * 64));
-        };
-
-        // TAIL: the tile may hold fewer than 16 valid tokens (only the last tile of a pair can)
-        auto consume = [&](int j, int stage, auto tail_tag) {
-          constexpr bool TAIL = decltype(tail_tag)::value;
-          const int ntok = TAIL ? (__builtin_amdgcn_readlane(d_info, j) & 31) : kTileTokens;
-          const uint8_t* kl = wlds + stage * kTileBytes;
-          f32x4 cfr = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-          for (int jj = 0; jj < 4; ++jj) {
-            const bf16x8 kf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(kl + krd[jj]));
-            cfr = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qfrag[jj], kf, cfr, 0, 0, 0);
-          }
-          const bool dead = TAIL && (t16 >= ntok);
-          float s[4];
-#pragma unroll
-          for (int r = 0; r < 4; ++r) s[r] = dead ? -INFINITY : cfr[r] * p.scale_log2e;
-
-          bool grow = false;
-#pragma unroll
-          for (int r = 0; r < 4; ++r) grow |= s[r] > m[r] + kSlack;
-          if (__builtin_amdgcn_ballot_w64(grow) != 0) {      // wave-uniform, rare after a first tile
-            f32x4 alpha;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-              const float mn = fmaxf(m[r], row16_max(s[r]));
-              alpha[r] = __builtin_amdgcn_exp2f(m[r] - mn);
-              m[r] = mn;
-              l[r] *= alpha[r];
-            }
-            // the rescale factors of all head slots are needed by every lane's accumulators
-            *reinterpret_cast<f32x4*>(pbuf + 4 * q4) = alpha;
-            float a[GH];
-#pragma unroll
-            for (int g = 0; g < GH; ++g) a[g] = pbuf[g];
-#pragma unroll
-            for (int g = 0; g < GH; ++g)
-#pragma unroll
-              for (int e = 0; e < 8; ++e) acc[g][e] *= a[g];
-          }
-
-          f32x4 pw;
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            pw[r] = __builtin_amdgcn_exp2f(s[r] - m[r]);
-            l[r] += pw[r];
-          }
-          *reinterpret_cast<f32x4*>(pbuf + t16 * 16 + 4 * q4) = pw;
-
-#pragma unroll
-          for (int jj = 0; jj < 4; ++jj) {
-            const int tok = 4 * jj + q4;                      // V row held by this lane for load jj
-            float pv[GH];
-            if constexpr (GH >= 4) {
-#pragma unroll
-              for (int g4 = 0; g4 < GH / 4; ++g4) {
-                const f32x4 t = *reinterpret_cast<const f32x4*>(pbuf + tok * 16 + 4 * g4);
-                pv[4 * g4] = t[0]; pv[4 * g4 + 1] = t[1]; pv[4 * g4 + 2] = t[2]; pv[4 * g4 + 3] = t[3];
-              }
-            } else if constexpr (GH == 2) {
-              const f32x2 t = *reinterpret_cast<const f32x2*>(pbuf + tok * 16);
-              pv[0] = t[0]; pv[1] = t[1];
-            } else {
-              pv[0] = pbuf[tok * 16];
-            }
-            u32x4 vv = vreg[stage][jj];
-            if (TAIL && tok >= ntok) vv = u32x4{0, 0, 0, 0};   // stale slot: may hold NaN bits
-            float vf[8];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              vf[2 * e] = __builtin_bit_cast(float, vv[e] << 16);
-              vf[2 * e + 1] = __builtin_bit_cast(float, vv[e] & 0xFFFF0000u);
-            }
-#pragma unroll
-            for (int g = 0; g < GH; ++g)
-#pragma unroll
-              for (int e = 0; e < 8; ++e) acc[g][e] = fmaf(pv[g], vf[e], acc[g][e]);
-          }
-          // The two wavefronts that share a SIMD (w and w+4) do not get equal issue slots: the
-          // older one wins every tie.  Whoever is behind raises its priority until it catches up.
-          ++tiles_done;
-          if (lane == 0) progress[wave] = tiles_done;
-          if (progress[wave ^ (kNW / 2)] > tiles_done) __builtin_amdgcn_s_setprio(2);
-          else __builtin_amdgcn_s_setprio(0);
-        };
-
-        // ---- segments of the group ----------------------------------------------------------------
         int j0 = 0;
-        int sp = __builtin_amdgcn_readlane(d_sp, 0);
-        if (!open) load_q(sp);                      // an open segment continues with its query
-        issue(0, 0);
+        if (!inflight) {
+          // tile first, query second: the compiler drains the load queue before a
+          // direct-to-LDS load, so anything issued ahead of it would be waited for in full
+          sp = __builtin_amdgcn_readlane(d_sp, 0);
+          issue(0, 0);
+          if (!open) load_q(sp);                    // an open segment continues with its query
+        }
+        inflight = false;
+        // with this chunk's last stretch under way, describe the next chunk: its index loads ride
+        // along with the tile that is in flight
+        if (r0 == 0 && last_batch && has_next)
+          build_desc(g0 + (ci + kNW) * rs, min(kDescBatch, chunk_tiles(ci + kNW)),
+                     dtabs + (tab ^ 1) * kDescBatch);
+
         while (j0 < nt) {
           // tiles j0 .. j1-1 belong to (sequence, pair) sp; the first one is already in flight
           const uint64_t same = __builtin_amdgcn_ballot_w64(d_sp == sp && lane >= j0 && lane < nt);
           const int j1 = j0 + __builtin_popcountll(same);
           const int info1 = __builtin_amdgcn_readlane(d_info, j1 - 1);
 
-          if (!open) {
-            open = true;
-            seg_sp = sp;
-            seg_info0 = __builtin_amdgcn_readlane(d_info, j0);
-            seg_x = x0 + b0 + r0 + j0;
+        if (!open) {
+          open = true;
+          seg_sp = sp;
+          seg_info0 = __builtin_amdgcn_readlane(d_info, j0);
+          seg_x = x0 + b0 + r0 + j0;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) { m[r] = kNegBig; l[r] = 0.f; }
+          for (int r = 0; r < 4; ++r) { m[r] = kNegBig; l[r] = 0.f; }
 #pragma unroll
-            for (int g = 0; g < GH; ++g)
+          for (int g = 0; g < GH; ++g)
 #pragma unroll
-              for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
-          }
+            for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
+        }
 
-          {
-            using std::false_type;
-            using std::true_type;
-            int j = j0;
-            while (j + 2 < j1) {
-              issue(j + 1, 1); PKV_WAIT_VMCNT(8); consume(j, 0, false_type{});
-              issue(j + 2, 0); PKV_WAIT_VMCNT(8); consume(j + 1, 1, false_type{});
-              j += 2;
-            }
-            if (j + 2 == j1) {
-              issue(j + 1, 1); PKV_WAIT_VMCNT(8); consume(j, 0, false_type{});
-              PKV_WAIT_VMCNT(0); consume(j + 1, 1, true_type{});
-            } else {
-              PKV_WAIT_VMCNT(0); consume(j, 0, true_type{});
-            }
+        {
+          using std::false_type;
+          using std::true_type;
+          int j = j0;
+          while (j + 2 < j1) {
+            issue(j + 1, 1); PKV_WAIT_VMCNT(8); consume(j, 0, false_type{});
+            issue(j + 2, 0); PKV_WAIT_VMCNT(8); consume(j + 1, 1, false_type{});
+            j += 2;
           }
+          if (j + 2 == j1) {
+            issue(j + 1, 1); PKV_WAIT_VMCNT(8); consume(j, 0, false_type{});
+            PKV_WAIT_VMCNT(0); consume(j + 1, 1, true_type{});
+          } else {
+            PKV_WAIT_VMCNT(0); consume(j, 0, true_type{});
+          }
+        }
 
           const bool last = (info1 >> 6) & 1;
           const bool flush = last || (j1 == nt && chunk_ends_here);
-          // the next segment's first tile and query go in flight before this one is flushed
+          // the next tile of this wavefront (next segment, next group or next chunk) and, if a
+          // new segment starts there, its query go in flight before anything is flushed
           if (j1 < nt) {
             sp = __builtin_amdgcn_readlane(d_sp, j1);
-            load_q(sp);
             issue(j1, 0);
+            load_q(sp);
+          } else {
+            const u32x4* nx = nullptr;
+            if (r0 + kWaveSize < ntb) nx = dtab + r0 + kWaveSize;
+            else if (chunk_ends_here && has_next) nx = dtabs + (tab ^ 1) * kDescBatch;
+            if (nx != nullptr) {
+              const u32x4 pd = *nx;
+              issue_at((uint32_t)rfl((int)pd[0]), (uint32_t)rfl((int)pd[1]), 0);
+              if (flush) {
+                sp = rfl((int)pd[2]);
+                load_q(sp);
+              }
+              inflight = true;
+            }
           }
 
           if (flush) {
-            // ---- flush the open segment ----------------------------------------------------------
-            const int seq = seg_sp >> 8, pp = seg_sp & 255;
-            const int kvh = pp / p.group_tiles, gtile = pp - kvh * p.group_tiles;
-            const int h0 = kvh * p.group + gtile * GH;
-            const int nheads = min(GH, p.group - gtile * GH);
-            const bool first = (seg_info0 >> 5) & 1;
-            const int prank = seq * NP + pp;
+          // ---- flush the open segment ----------------------------------------------------------
+          const int seq = seg_sp >> 8, pp = seg_sp & 255;
+          const int kvh = pp / p.group_tiles, gtile = pp - kvh * p.group_tiles;
+          const int h0 = kvh * p.group + gtile * GH;
+          const int nheads = min(GH, p.group - gtile * GH);
+          const bool first = (seg_info0 >> 5) & 1;
+          const int prank = seq * NP + pp;
 
 #pragma unroll
-            for (int r = 0; r < 4; ++r) l[r] = row16_sum(l[r]);
-            // (m, l) of every head slot to every lane
-            *reinterpret_cast<f32x4*>(pbuf + 4 * q4) = f32x4{m[0], m[1], m[2], m[3]};
-            *reinterpret_cast<f32x4*>(pbuf + 16 + 4 * q4) = f32x4{l[0], l[1], l[2], l[3]};
-            float mg[GH], lg[GH];
+          for (int r = 0; r < 4; ++r) l[r] = row16_sum(l[r]);
+          // (m, l) of every head slot to every lane
+          *reinterpret_cast<f32x4*>(pbuf + 4 * q4) = f32x4{m[0], m[1], m[2], m[3]};
+          *reinterpret_cast<f32x4*>(pbuf + 16 + 4 * q4) = f32x4{l[0], l[1], l[2], l[3]};
+          float mg[GH], lg[GH];
 #pragma unroll
-            for (int g = 0; g < GH; ++g) { mg[g] = pbuf[g]; lg[g] = pbuf[16 + g]; }
+          for (int g = 0; g < GH; ++g) { mg[g] = pbuf[g]; lg[g] = pbuf[16 + g]; }
+          // Sum the accumulators of the four row groups.  Row group q only writes heads g with
+          // g % 4 == q, so this is a reduce-scatter: every lane parks its 8 values of head g in
+          // LDS (K ring stage 1 is idle during a flush: the tile in flight goes to stage 0) and
+          // the lanes of row group g % 4 add the other three groups' values, in fixed order.
+          {
+            float* red = reinterpret_cast<float*>(wlds + kTileBytes);   // 2 x 2 KiB, alternating
 #pragma unroll
-            for (int g = 0; g < GH; ++g)
+            for (int g = 0; g < GH; ++g) {
+              float* mine = red + (g & 1) * 512 + (q4 * 16 + t16) * 8;
+              *reinterpret_cast<f32x4*>(mine) = f32x4{acc[g][0], acc[g][1], acc[g][2], acc[g][3]};
+              *reinterpret_cast<f32x4*>(mine + 4) = f32x4{acc[g][4], acc[g][5], acc[g][6], acc[g][7]};
+              if ((g & 3) == q4) {
 #pragma unroll
-              for (int e = 0; e < 8; ++e) {
-                float v = acc[g][e];
-                v += __shfl_xor(v, 16, kWaveSize);
-                v += __shfl_xor(v, 32, kWaveSize);
-                acc[g][e] = v;
-              }
-
-            if (first && last) {
-              // the whole (sequence, pair) was in this segment: finished rows
-#pragma unroll
-              for (int g = 0; g < GH; ++g) {
-                if ((g & 3) == q4 && g < nheads) {
-                  const float inv = 1.0f / lg[g];
-                  const int64_t o = ((int64_t)seq * p.num_q_heads + h0 + g) * D + t16 * 8;
-                  if (p.out_is_bf16) {
-                    u32x4 w;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                      w[e] = pack_bf16x2_rne(acc[g][2 * e] * inv, acc[g][2 * e + 1] * inv);
-                    *reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(p.out) + o) = w;
-                  } else {
-                    float* op = reinterpret_cast<float*>(p.out) + o;
-                    *reinterpret_cast<f32x4*>(op) =
-                        f32x4{acc[g][0] * inv, acc[g][1] * inv, acc[g][2] * inv, acc[g][3] * inv};
-                    *reinterpret_cast<f32x4*>(op + 4) =
-                        f32x4{acc[g][4] * inv, acc[g][5] * inv, acc[g][6] * inv, acc[g][7] * inv};
-                  }
+                for (int r = 1; r < 4; ++r) {
+                  const float* theirs = red + (g & 1) * 512 + (((q4 + r) & 3) * 16 + t16) * 8;
+                  const f32x4 a = *reinterpret_cast<const f32x4*>(theirs);
+                  const f32x4 b = *reinterpret_cast<const f32x4*>(theirs + 4);
+                  acc[g][0] += a[0]; acc[g][1] += a[1]; acc[g][2] += a[2]; acc[g][3] += a[3];
+                  acc[g][4] += b[0]; acc[g][5] += b[1]; acc[g][6] += b[2]; acc[g][7] += b[3];
                 }
-              }
-              if (lane == 0) *reinterpret_cast<i32x2*>(p.ws_dir + 2 * (int64_t)prank) = i32x2{0, 1};
-            } else {
-              const int64_t slot = (int64_t)prank + c;   // unique: both terms grow along the axis
-#pragma unroll
-              for (int g = 0; g < GH; ++g) {
-                if ((g & 3) == q4 && g < nheads) {
-                  float* op = p.ws_o + (slot * GH + g) * D + t16 * 8;
-                  *reinterpret_cast<f32x4*>(op) = f32x4{acc[g][0], acc[g][1], acc[g][2], acc[g][3]};
-                  *reinterpret_cast<f32x4*>(op + 4) = f32x4{acc[g][4], acc[g][5], acc[g][6], acc[g][7]};
-                  if (t16 == 0)
-                    *reinterpret_cast<f32x2*>(p.ws_ml + (slot * GH + g) * 2) = f32x2{mg[g], lg[g]};
-                }
-              }
-              if (first && lane == 0) {
-                // directory entry of the pair: its partials sit in consecutive slots
-                const int tiles = seg_info0 >> 8;
-                const int c_last = plan.chunk_of(seg_x + tiles - 1);
-                *reinterpret_cast<i32x2*>(p.ws_dir + 2 * (int64_t)prank) = i32x2{(int)slot, c_last - c + 1};
               }
             }
-            open = false;
+          }
+
+          if (first && last) {
+            // the whole (sequence, pair) was in this segment: finished rows
+#pragma unroll
+            for (int g = 0; g < GH; ++g) {
+              if ((g & 3) == q4 && g < nheads) {
+                const float inv = 1.0f / lg[g];
+                const int64_t o = ((int64_t)seq * p.num_q_heads + h0 + g) * D + t16 * 8;
+                if (p.out_is_bf16) {
+                  u32x4 w;
+#pragma unroll
+                  for (int e = 0; e < 4; ++e)
+                    w[e] = pack_bf16x2_rne(acc[g][2 * e] * inv, acc[g][2 * e + 1] * inv);
+                  *reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(p.out) + o) = w;
+                } else {
+                  float* op = reinterpret_cast<float*>(p.out) + o;
+                  *reinterpret_cast<f32x4*>(op) =
+                      f32x4{acc[g][0] * inv, acc[g][1] * inv, acc[g][2] * inv, acc[g][3] * inv};
+                  *reinterpret_cast<f32x4*>(op + 4) =
+                      f32x4{acc[g][4] * inv, acc[g][5] * inv, acc[g][6] * inv, acc[g][7] * inv};
+                }
+              }
+            }
+            if (lane == 0) *reinterpret_cast<i32x2*>(p.ws_dir + 2 * (int64_t)prank) = i32x2{0, 1};
+          } else {
+            const int64_t slot = (int64_t)prank + c;   // unique: both terms grow along the axis
+#pragma unroll
+            for (int g = 0; g < GH; ++g) {
+              if ((g & 3) == q4 && g < nheads) {
+                float* op = p.ws_o + (slot * GH + g) * D + t16 * 8;
+                *reinterpret_cast<f32x4*>(op) = f32x4{acc[g][0], acc[g][1], acc[g][2], acc[g][3]};
+                *reinterpret_cast<f32x4*>(op + 4) = f32x4{acc[g][4], acc[g][5], acc[g][6], acc[g][7]};
+                if (t16 == 0)
+                  *reinterpret_cast<f32x2*>(p.ws_ml + (slot * GH + g) * 2) = f32x2{mg[g], lg[g]};
+              }
+            }
+            if (first && lane == 0) {
+              // directory entry of the pair: its partials sit in consecutive slots
+              const int tiles = seg_info0 >> 8;
+              const int c_last = plan.chunk_of(seg_x + tiles - 1);
+              *reinterpret_cast<i32x2*>(p.ws_dir + 2 * (int64_t)prank) = i32x2{(int)slot, c_last - c + 1};
+            }
+          }
+          open = false;
           }
           j0 = j1;
         }
       }
     }
+    tab ^= 1;
   }
 }
 
-// Merge of the partials of one (sequence, query head); also writes the zero rows of
-// empty contexts.  M = max m_p, L = sum l_p 2^(m_p-M), out = sum O_p 2^(m_p-M) / L, partials
-// taken in ascending order along the tile axis.
 constexpr int kMergeThreads = 256, kMW = kMergeThreads / kWaveSize;
 
 template <int GH>
