@@ -155,6 +155,22 @@ int32_t paged_decode_attention(const pkv_attn_desc* desc, const void* q,
                                size_t workspace_bytes, void* hip_stream);
 
 /*
+ * The same call with two optional hipEvent_t handles (passed as void*, either
+ * may be NULL) that are recorded on hip_stream immediately before and after the
+ * kernel that streams K and V (Sec. 4.2: the part of the step whose time grows
+ * with the KV volume), i.e. excluding the small kernel that merges the split-K
+ * partials.  For profiling: the elapsed time between the two events is that
+ * kernel's duration.  The events are the caller's; nothing waits on them.
+ */
+int32_t paged_decode_attention_timed(const pkv_attn_desc* desc, const void* q,
+                                     const void* k_pool, const void* v_pool,
+                                     const int32_t* block_tables,
+                                     const int32_t* context_lens, float scale,
+                                     void* out, void* workspace,
+                                     size_t workspace_bytes, void* hip_stream,
+                                     void* ev_kernel_begin, void* ev_kernel_end);
+
+/*
  * Block gather/scatter of the preemption swap path (Sec. 5.1.2 "Swapping":
  * the victim's KV blocks leave the pool and are later migrated back, in
  * general to different physical blocks).  For every plane p and every pair

@@ -19,7 +19,7 @@ FLAG_VECTOR_ALU = 1
 
 EXPORTS = [
     "pkv_version", "pkv_status_string", "pkv_attn_partition_tokens", "pkv_attn_workspace_bytes",
-    "paged_decode_attention", "kv_block_swap", "pkv_validate_tables_host",
+    "paged_decode_attention", "paged_decode_attention_timed", "kv_block_swap", "pkv_validate_tables_host",
     "pkv_validate_mapping_host", "pkv_validate_tables", "pkv_validate_mapping",
     "pkv_probe_copy", "pkv_probe_read",
 ]
@@ -70,6 +70,9 @@ def lib() -> ctypes.CDLL:
         L.paged_decode_attention.restype = i32
         L.paged_decode_attention.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp,
                                              ctypes.c_float, vp, vp, sz, vp]
+        L.paged_decode_attention_timed.restype = i32
+        L.paged_decode_attention_timed.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp,
+                                                   ctypes.c_float, vp, vp, sz, vp, vp, vp]
         L.kv_block_swap.restype = i32
         L.kv_block_swap.argtypes = [ctypes.POINTER(SwapDesc), vp, vp, vp, i32, vp]
         L.pkv_validate_tables_host.restype = i32
@@ -149,7 +152,8 @@ def new_workspace(nbytes: int, device, *, stream=None):
 
 def paged_decode_attention(q, k_pool, v_pool, block_tables, context_lens, scale, out, *,
                            max_context_len: int, partition_tokens: int = 0, workspace=None,
-                           desc: Optional[AttnDesc] = None, stream=None, flags: int = 0):
+                           desc: Optional[AttnDesc] = None, stream=None, flags: int = 0,
+                           kernel_events=None):
     """out[i,h,:] = softmax_t(scale * q[i,h] . K_t) V_t over the paged pool (device tensors).
     Returns the workspace tensor used (reusable by the caller)."""
     import torch
@@ -164,10 +168,14 @@ def paged_decode_attention(q, k_pool, v_pool, block_tables, context_lens, scale,
         workspace = new_workspace(need, q.device, stream=stream)
     ws_ptr = workspace.data_ptr() if workspace is not None else None
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
-    st = L.paged_decode_attention(ctypes.byref(desc), q.data_ptr(), k_pool.data_ptr(),
-                                  v_pool.data_ptr(), block_tables.data_ptr(),
-                                  context_lens.data_ptr(), float(scale), out.data_ptr(),
-                                  ws_ptr, ws_bytes, _stream_ptr(stream))
+    args = (ctypes.byref(desc), q.data_ptr(), k_pool.data_ptr(), v_pool.data_ptr(),
+            block_tables.data_ptr(), context_lens.data_ptr(), float(scale), out.data_ptr(),
+            ws_ptr, ws_bytes, _stream_ptr(stream))
+    if kernel_events is None:
+        st = L.paged_decode_attention(*args)
+    else:   # two torch.cuda.Event(enable_timing=True) that have been recorded once (so they exist)
+        st = L.paged_decode_attention_timed(*args, ctypes.c_void_p(kernel_events[0].cuda_event),
+                                            ctypes.c_void_p(kernel_events[1].cuda_event))
     _check(st, "paged_decode_attention")
     return workspace
 

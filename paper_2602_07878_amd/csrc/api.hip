@@ -105,10 +105,10 @@ size_t pkv_attn_workspace_bytes(const pkv_attn_desc* desc) {
   return (size_t)(ml + (o + 255) / 256 * 256);
 }
 
-int32_t paged_decode_attention(const pkv_attn_desc* desc, const void* q, const void* k_pool,
-                               const void* v_pool, const int32_t* block_tables,
-                               const int32_t* context_lens, float scale, void* out,
-                               void* workspace, size_t workspace_bytes, void* hip_stream) {
+static int32_t attention_impl(const pkv_attn_desc* desc, const void* q, const void* k_pool,
+                              const void* v_pool, const int32_t* block_tables,
+                              const int32_t* context_lens, float scale, void* out, void* workspace,
+                              size_t workspace_bytes, void* hip_stream, void* ev_begin, void* ev_end) {
   const int32_t st = check_attn_desc(desc);
   if (st != PKV_OK) return st;
   if (desc->batch == 0) return PKV_OK;
@@ -142,6 +142,8 @@ int32_t paged_decode_attention(const pkv_attn_desc* desc, const void* q, const v
   p.out_is_bf16 = desc->out_dtype == PKV_BF16;
   p.no_mfma = (desc->flags & PKV_ATTN_FLAG_VECTOR_ALU) != 0;
   p.scale_log2e = scale * 1.4426950408889634f;
+  p.ev_begin = static_cast<hipEvent_t>(ev_begin);
+  p.ev_end = static_cast<hipEvent_t>(ev_end);
   if (attn_stream_supported(*desc)) {
     const StreamWorkspace w = stream_workspace(*desc);
     uint8_t* base = reinterpret_cast<uint8_t*>(workspace);
@@ -160,6 +162,23 @@ int32_t paged_decode_attention(const pkv_attn_desc* desc, const void* q, const v
   }
   const hipError_t e = launch_attn_decode(p, desc->kv_dtype, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? PKV_OK : PKV_ERR_HIP;
+}
+
+int32_t paged_decode_attention(const pkv_attn_desc* desc, const void* q, const void* k_pool,
+                               const void* v_pool, const int32_t* block_tables,
+                               const int32_t* context_lens, float scale, void* out,
+                               void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return attention_impl(desc, q, k_pool, v_pool, block_tables, context_lens, scale, out, workspace,
+                        workspace_bytes, hip_stream, nullptr, nullptr);
+}
+
+int32_t paged_decode_attention_timed(const pkv_attn_desc* desc, const void* q, const void* k_pool,
+                                     const void* v_pool, const int32_t* block_tables,
+                                     const int32_t* context_lens, float scale, void* out,
+                                     void* workspace, size_t workspace_bytes, void* hip_stream,
+                                     void* ev_kernel_begin, void* ev_kernel_end) {
+  return attention_impl(desc, q, k_pool, v_pool, block_tables, context_lens, scale, out, workspace,
+                        workspace_bytes, hip_stream, ev_kernel_begin, ev_kernel_end);
 }
 
 int32_t kv_block_swap(const pkv_swap_desc* desc, const void* src_pool, void* dst,

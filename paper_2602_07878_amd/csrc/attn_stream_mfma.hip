@@ -614,9 +614,11 @@ hipError_t launch(const AttnParams& p, hipStream_t s) {
     if (e != hipSuccess) return e;
     prepared = true;
   }
+  if (p.ev_begin && hipEventRecord(p.ev_begin, s) != hipSuccess) return hipErrorInvalidValue;
   hipLaunchKernelGGL((attn_stream_mfma_d128<GH>), dim3(num_cus()), dim3(kStreamThreads), lds, s, p);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  if (p.ev_end && hipEventRecord(p.ev_end, s) != hipSuccess) return hipErrorInvalidValue;
   hipLaunchKernelGGL((attn_stream_merge<GH>), dim3(p.num_q_heads, p.batch), dim3(kMergeThreads), 0, s, p);
   return hipGetLastError();
 }

@@ -38,6 +38,8 @@ struct AttnParams {
   int32_t chunk_tiles_max;  // stream kernel: most tiles one wavefront takes per chunk (<= 64)
   int32_t prefix_bytes;     // stream kernel: LDS bytes of the tile prefix table
   float scale_log2e;        // scale * log2(e)
+  // host side only: optional events recorded right before / after the partial kernel
+  hipEvent_t ev_begin, ev_end;
 };
 
 struct SwapParams {
