@@ -16,19 +16,24 @@
 // issue priority so that neither falls behind (the older one would otherwise win every
 // arbitration tie and finish a third earlier, leaving the CU half empty at the end).
 //
-// Per tile:
-//  * K goes HBM -> LDS with direct-to-LDS 16-byte loads (no VGPR staging) into a 2-deep
-//    ring per wavefront.  The LDS image is XOR-swizzled by choosing which 16-byte piece
-//    of its token row each lane fetches, so the row-per-lane reads that feed the matrix
+// Per tile (the vector ALU, not HBM, limits this kernel as soon as the per-token work is
+// done with ordinary FMAs, so everything that is a contraction runs on the matrix cores):
+//  * K and V go HBM -> LDS with direct-to-LDS 16-byte loads (no VGPR staging) into a
+//    2-deep ring per wavefront.  Both LDS images are XOR-swizzled by choosing which
+//    16-byte piece of its token row each lane fetches, so the reads that feed the matrix
 //    cores are bank-conflict free while every wave-wide global load still covers whole
 //    contiguous 256-byte rows.
-//  * scores S[head slot][token] = Q_g K^T come from v_mfma_f32_16x16x32_bf16 (both
-//    operands exact bf16; the query group is replicated to the 16 rows of the tile).
-//  * softmax weights stay fp32 and move from the score layout (lane = token) to the V
-//    layout (lane = 16-byte piece of a V row) through a 1 KiB LDS tile; P.V is fp32 FMA
-//    on V rows loaded straight into registers with coalesced 16-byte loads.
+//  * scores S^T[token][head] = K Q_g^T come from v_mfma_f32_16x16x32_bf16 (both operands
+//    exact bf16; column c of the tile is query head c of the group).  In the result a lane
+//    holds four tokens of one head: exactly the A-operand layout of the second product.
 //  * the running maximum is only a reference point for exp2(): it is raised (and the
-//    accumulators rescaled) only when a score exceeds it by more than kSlack.
+//    accumulators rescaled) only when a score exceeds it by more than kSlack, so the
+//    common tile needs no cross-lane reduction at all; row sums stay per lane until the
+//    flush.
+//  * the fp32 weights are split into a bf16 head and a bf16 remainder (relative error
+//    2^-17) and O[head][dim] += P V runs as two v_mfma_f32_16x16x16_bf16 per 16 output
+//    dims; the B operand (four tokens of one dim per lane) comes out of the row-major V
+//    tile with the transposing LDS read ds_read_b64_tr_b16.
 // The loads of tile j+1 are in flight while tile j is consumed; the first tile of the
 // next segment is issued before the current segment is flushed.
 
@@ -40,9 +45,12 @@ namespace pkv {
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 typedef __attribute__((ext_vector_type(2))) int32_t i32x2;
 
 constexpr float kNegBig = -1.0e30f;
@@ -51,28 +59,17 @@ constexpr int kStreamThreads = 512;        // one workgroup of 8 wavefronts per 
 constexpr int kNW = kStreamThreads / kWaveSize;
 constexpr int kTileBytes = 4096;           // 16 tokens x 256-byte rows
 constexpr int kStages = 2;
-constexpr int kDescBatch = 128;            // tile descriptors per table
-constexpr int kWaveLds = kStages * kTileBytes + 1024 + 2 * kDescBatch * 16;   // K ring + P tile + 2 descriptor tables
+constexpr int kDescBatch = 64;             // tile descriptors per table
+constexpr int kStageBytes = 2 * kTileBytes; // K tile, then V tile
+constexpr int kXchgBytes = 512;            // per-head values passed between lanes
+// per wavefront: ring of (K, V) stages, exchange area, two descriptor tables
+constexpr int kWaveLds = kStages * kStageBytes + kXchgBytes + 2 * kDescBatch * 16;
+constexpr int kStageRow = 132;             // floats per head row when a flush stages O in LDS
 constexpr int kMinGroupTiles = 32;         // tiles per workgroup range below which fewer workgroups work
 constexpr int D = 128;
 
 #define PKV_WAIT_VMCNT(n) \
   __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (((n) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
-
-template <int CTRL>
-__device__ __forceinline__ float dpp(float v) {
-  return __builtin_bit_cast(
-      float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
-}
-__device__ __forceinline__ float row16_max(float v) {
-  v = fmaxf(v, dpp<0xB1>(v)); v = fmaxf(v, dpp<0x4E>(v));
-  v = fmaxf(v, dpp<0x141>(v)); v = fmaxf(v, dpp<0x140>(v));
-  return v;
-}
-__device__ __forceinline__ float row16_sum(float v) {
-  v += dpp<0xB1>(v); v += dpp<0x4E>(v); v += dpp<0x141>(v); v += dpp<0x140>(v);
-  return v;
-}
 
 __device__ __forceinline__ uint32_t pack_bf16x2_rne(float lo, float hi) {
   auto cv = [](float f) -> uint32_t {
@@ -113,8 +110,6 @@ __device__ __forceinline__ ChunkPlan plan_chunks(int T, int nwg, int cap) {
 // GH = query heads accumulated per lane (1, 2, 4 or 8).
 template <int GH>
 __global__ __launch_bounds__(kStreamThreads, 2) void attn_stream_mfma_d128(const AttnParams p) {
-  constexpr int HS = GH >= 8 ? 8 : 4;   // distinct head slots among the 16 MFMA rows
-
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
   __shared__ int wave_total[kNW];
   __shared__ int progress[kNW];   // tiles consumed so far, per wavefront
@@ -161,39 +156,56 @@ __global__ __launch_bounds__(kStreamThreads, 2) void attn_stream_mfma_d128(const
   const int rs = plan.rs;                                  // tiles per chunk
   if (glen <= 0) return;
   // ---- per-lane, loop-invariant offsets -------------------------------------------------------
-  uint32_t koff[4], voff[4], krd[4];
+  // Load j of a tile brings token rows 4j..4j+3; this lane fetches one 16-byte piece of row
+  // 4j+q4 and the hardware puts it at LDS slot (j, lane).  Which piece it fetches fixes the swizzle:
+  // K row t keeps piece c at slot c ^ t, V row t keeps piece c at slot c ^ 2(t mod 8).
+  uint32_t koff[4], voff[4], krd[4], vrd[8];
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    const int tok = 4 * j + q4;                        // token row this lane fetches in load j
+    const int tok = 4 * j + q4;
     koff[j] = (uint32_t)(tok * p.k_stride_token) + (uint32_t)((t16 ^ tok) * 16);
-    voff[j] = (uint32_t)(tok * p.v_stride_token) + (uint32_t)(t16 * 16);
-    // MFMA step j: this lane (token t16) needs piece 4j+q4 of its row, stored at slot piece^t16
-    krd[j] = (uint32_t)((t16 >> 2) * 1024 + (t16 & 3) * 256 + (((4 * j + q4) ^ t16) * 16));
+    voff[j] = (uint32_t)(tok * p.v_stride_token) + (uint32_t)((t16 ^ (2 * (tok & 7))) * 16);
+    // first product, step j: this lane (token t16) needs dims 32j+8q4..+7 of its K row
+    krd[j] = (uint32_t)(t16 * 256 + (((4 * j + q4) ^ t16) * 16));
+  }
+  {
+    // second product, output dims 16nb..16nb+15: the transposing read hands lane i of a 16-lane
+    // group element (i mod 4) of the 8-byte pieces addressed by lanes i/4, 4+i/4, 8+i/4, 12+i/4.
+    // Lane s of group q4 therefore points at token 4q4 + s/4, dims 16nb + 4(s mod 4)..+3, and
+    // every lane receives tokens 4q4..4q4+3 of dim 16nb + t16: the B operand.
+    const int tv = 4 * q4 + (t16 >> 2);
+    const uint32_t vbase = (uint32_t)(tv * 256 + ((tv & 7) << 5) + (t16 & 3) * 8);
+#pragma unroll
+    for (int nb = 0; nb < 8; ++nb) vrd[nb] = vbase ^ (uint32_t)(nb << 5);
   }
   uint8_t* wlds = lds + p.prefix_bytes + wave * kWaveLds;
-  float* pbuf = reinterpret_cast<float*>(wlds + kStages * kTileBytes);   // [16 tokens][16 slots]
+  {
+    // as LDS byte addresses (a common shift of all addresses leaves the bank pattern conflict free)
+    const uint32_t wbase = (uint32_t)(uintptr_t)(lptr_t)wlds;
+#pragma unroll
+    for (int nb = 0; nb < 8; ++nb) vrd[nb] += wbase;
+  }
+  float* xchg = reinterpret_cast<float*>(wlds + kStages * kStageBytes);   // 128 floats
   const uint8_t* kpool = reinterpret_cast<const uint8_t*>(p.k_pool);
   const uint8_t* vpool = reinterpret_cast<const uint8_t*>(p.v_pool);
   const int tile_mask = (1 << p.tpb_shift) - 1;
 
   int tiles_done = 0;
-  float m[4], l[4];
-  float acc[GH][8];
+  // Softmax state of head column t16 (the same value in the four lanes that share a column):
+  // reference maximum, and this lane's share of the row sum (tokens 4q4..4q4+3 of every tile).
+  float m_ref = kNegBig, l_part = 0.f;
+  f32x4 acc[8];          // O[head 4q4+r][dim 16nb+t16] in acc[nb][r]
   bf16x8 qfrag[4];
-  u32x4 vreg[kStages][4];
 
-  // two descriptor tables per wavefront: the one in use and the one filled ahead for the next chunk
-  u32x4* dtabs = reinterpret_cast<u32x4*>(wlds + kStages * kTileBytes + 1024);   // [2][kDescBatch]
+  // two descriptor tables per wavefront: the one in use and the one filled ahead for the next batch
+  u32x4* dtabs = reinterpret_cast<u32x4*>(wlds + kStages * kStageBytes + kXchgBytes);   // [2][kDescBatch]
 
-  // Tile descriptors of `count` (<= kDescBatch) tiles from axis position xb, built by the lanes:
+  // Tile descriptors of `count` (<= kDescBatch) tiles from axis position xb, one per lane:
   //   x: byte offset / 16 of the tile's first K row      y: same for V
   //   z: sequence << 8 | pair
   //   w: valid tokens (1..16) | first-of-pair << 5 | last-of-pair << 6 | tiles of the pair << 8
   auto build_desc = [&](int xb, int count, u32x4* tab) {
-#pragma unroll 1
-    for (int pass = 0; pass * kWaveSize < count; ++pass) {
-    const int idx = pass * kWaveSize + lane;
-    const int x = xb + min(idx, count - 1);
+    const int x = xb + min(lane, count - 1);
     const int xq = x / NP;
     int lo = 0, hi = B;                            // prefix[lo] <= xq < prefix[hi]
     while (hi - lo > 1) {
@@ -216,33 +228,34 @@ __global__ __launch_bounds__(kStreamThreads, 2) void attn_stream_mfma_d128(const
     d[2] = (uint32_t)((seq << 8) | pp);
     const int ntok = min(kTileTokens, n - t * kTileTokens);
     d[3] = (uint32_t)(ntok | ((t == 0) << 5) | ((t == tiles - 1) << 6) | (tiles << 8));
-    tab[idx] = d;
-    }
+    tab[lane] = d;
   };
 
-  int d_k = 0, d_v = 0, d_sp = 0, d_info = 0;   // descriptors of the current group, one tile per lane
+  int d_k = 0, d_v = 0, d_sp = 0, d_info = 0;   // descriptors of the current batch, one tile per lane
 
   auto issue_at = [&](uint32_t sk, uint32_t sv, int stage) {
     const uint8_t* kb = kpool + ((uint64_t)sk << 4);
     const uint8_t* vb = vpool + ((uint64_t)sv << 4);
-    uint8_t* kl = wlds + stage * kTileBytes;
+    uint8_t* kl = wlds + stage * kStageBytes;
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj)
-      __builtin_amdgcn_global_load_lds((gptr_t)(kb + koff[jj]), (lptr_t)(kl + jj * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t)(kb + koff[jj]), (lptr_t)(kl + jj * 1024), 16, 0, 2);
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj)
-      vreg[stage][jj] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vb + voff[jj]));
+      __builtin_amdgcn_global_load_lds((gptr_t)(vb + voff[jj]), (lptr_t)(kl + kTileBytes + jj * 1024), 16, 0, 2);
   };
   auto issue = [&](int j, int stage) {
     issue_at((uint32_t)__builtin_amdgcn_readlane(d_k, j), (uint32_t)__builtin_amdgcn_readlane(d_v, j), stage);
   };
 
+  // Query rows as the B operand of the first product: column t16 is head min(t16, nheads-1)
+  // of the group (columns past the group repeat its last head and are never written out).
   auto load_q = [&](int sp) {
     const int seq = sp >> 8, pp = sp & 255;
     const int kvh = pp / p.group_tiles, gtile = pp - kvh * p.group_tiles;
     const int h0 = kvh * p.group + gtile * GH;
     const int nheads = min(GH, p.group - gtile * GH);
-    const int hs = min(t16 % HS, nheads - 1);
+    const int hs = min(t16, nheads - 1);
     const uint8_t* qp = reinterpret_cast<const uint8_t*>(p.q) +
                         ((int64_t)seq * p.num_q_heads + h0 + hs) * (D * 2) + q4 * 16;
 #pragma unroll
@@ -251,81 +264,104 @@ __global__ __launch_bounds__(kStreamThreads, 2) void attn_stream_mfma_d128(const
   };
 
   // TAIL: the tile may hold fewer than 16 valid tokens (only the last tile of a pair can)
-  auto consume = [&](int j, int stage, auto tail_tag) {
+  auto consume = [&](int j, auto stage_tag, auto tail_tag) {
+    constexpr int STAGE = decltype(stage_tag)::value;
     constexpr bool TAIL = decltype(tail_tag)::value;
     const int ntok = TAIL ? (__builtin_amdgcn_readlane(d_info, j) & 31) : kTileTokens;
-    const uint8_t* kl = wlds + stage * kTileBytes;
+    const uint8_t* kl = wlds + STAGE * kStageBytes;
     f32x4 cfr = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj) {
       const bf16x8 kf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(kl + krd[jj]));
-      cfr = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qfrag[jj], kf, cfr, 0, 0, 0);
+      cfr = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qfrag[jj], cfr, 0, 0, 0);
     }
-    const bool dead = TAIL && (t16 >= ntok);
-    float s[4];
-#pragma unroll
-    for (int r = 0; r < 4; ++r) s[r] = dead ? -INFINITY : cfr[r] * p.scale_log2e;
-
-    bool grow = false;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) grow |= s[r] > m[r] + kSlack;
-    if (__builtin_amdgcn_ballot_w64(grow) != 0) {      // wave-uniform, rare after a first tile
-      f32x4 alpha;
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const float mn = fmaxf(m[r], row16_max(s[r]));
-        alpha[r] = __builtin_amdgcn_exp2f(m[r] - mn);
-        m[r] = mn;
-        l[r] *= alpha[r];
-      }
-      // the rescale factors of all head slots are needed by every lane's accumulators
-      *reinterpret_cast<f32x4*>(pbuf + 4 * q4) = alpha;
-      float a[GH];
-#pragma unroll
-      for (int g = 0; g < GH; ++g) a[g] = pbuf[g];
-#pragma unroll
-      for (int g = 0; g < GH; ++g)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc[g][e] *= a[g];
-    }
-
-    f32x4 pw;
+    // cfr[r] = q_head(t16) . k_token(4q4+r); d = score - reference, in log2 units
+    float d[4];
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      pw[r] = __builtin_amdgcn_exp2f(s[r] - m[r]);
-      l[r] += pw[r];
+      d[r] = fmaf(cfr[r], p.scale_log2e, -m_ref);
+      if (TAIL && 4 * q4 + r >= ntok) d[r] = -INFINITY;   // stale slot: may hold NaN bits
     }
-    *reinterpret_cast<f32x4*>(pbuf + t16 * 16 + 4 * q4) = pw;
+    const float dmax = fmaxf(fmaxf(d[0], d[1]), fmaxf(d[2], d[3]));
+    if (__builtin_amdgcn_ballot_w64(dmax > kSlack) != 0) {   // wave-uniform, rare after a first tile
+      float s[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        s[r] = cfr[r] * p.scale_log2e;
+        if (TAIL && 4 * q4 + r >= ntok) s[r] = -INFINITY;
+      }
+      xchg[q4 * 16 + t16] = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
+      const float tm = fmaxf(fmaxf(xchg[t16], xchg[16 + t16]), fmaxf(xchg[32 + t16], xchg[48 + t16]));
+      const float mn = fmaxf(m_ref, tm);
+      const float alpha = __builtin_amdgcn_exp2f(m_ref - mn);
+      m_ref = mn;
+      l_part *= alpha;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) d[r] = s[r] - mn;
+      // the accumulators of this lane belong to heads 4q4..4q4+3
+      xchg[64 + t16] = alpha;   // the four lanes of a column write the same value
+      const f32x4 a = *reinterpret_cast<const f32x4*>(xchg + 64 + 4 * q4);
+#pragma unroll
+      for (int nb = 0; nb < 8; ++nb)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc[nb][r] *= a[r];
+    }
 
+    // weights, and their split into a bf16 head and a rounded bf16 remainder
+    uint32_t hi[4], lo[4];
+    float psum = 0.f;
 #pragma unroll
-    for (int jj = 0; jj < 4; ++jj) {
-      const int tok = 4 * jj + q4;                      // V row held by this lane for load jj
-      float pv[GH];
-      if constexpr (GH >= 4) {
-#pragma unroll
-        for (int g4 = 0; g4 < GH / 4; ++g4) {
-          const f32x4 t = *reinterpret_cast<const f32x4*>(pbuf + tok * 16 + 4 * g4);
-          pv[4 * g4] = t[0]; pv[4 * g4 + 1] = t[1]; pv[4 * g4 + 2] = t[2]; pv[4 * g4 + 3] = t[3];
-        }
-      } else if constexpr (GH == 2) {
-        const f32x2 t = *reinterpret_cast<const f32x2*>(pbuf + tok * 16);
-        pv[0] = t[0]; pv[1] = t[1];
-      } else {
-        pv[0] = pbuf[tok * 16];
-      }
-      u32x4 vv = vreg[stage][jj];
-      if (TAIL && tok >= ntok) vv = u32x4{0, 0, 0, 0};   // stale slot: may hold NaN bits
-      float vf[8];
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        vf[2 * e] = __builtin_bit_cast(float, vv[e] << 16);
-        vf[2 * e + 1] = __builtin_bit_cast(float, vv[e] & 0xFFFF0000u);
-      }
-#pragma unroll
-      for (int g = 0; g < GH; ++g)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc[g][e] = fmaf(pv[g], vf[e], acc[g][e]);
+    for (int r = 0; r < 4; ++r) {
+      const float pw = __builtin_amdgcn_exp2f(d[r]);
+      psum += pw;
+      hi[r] = __builtin_bit_cast(uint32_t, pw);
+      const float rest = pw - __builtin_bit_cast(float, hi[r] & 0xFFFF0000u);   // exact, >= 0
+      lo[r] = __builtin_bit_cast(uint32_t, rest) + 0x8000u;
     }
+    l_part += psum;
+    const s16x4 p_hi = __builtin_bit_cast(s16x4, u32x2{__builtin_amdgcn_perm(hi[1], hi[0], 0x07060302u),
+                                                       __builtin_amdgcn_perm(hi[3], hi[2], 0x07060302u)});
+    const s16x4 p_lo = __builtin_bit_cast(s16x4, u32x2{__builtin_amdgcn_perm(lo[1], lo[0], 0x07060302u),
+                                                       __builtin_amdgcn_perm(lo[3], lo[2], 0x07060302u)});
+
+    uint32_t keep0 = 0xFFFFFFFFu, keep1 = 0xFFFFFFFFu;   // V rows past the context: zero, not NaN
+    if (TAIL) {
+      keep0 = (4 * q4 + 0 < ntok ? 0x0000FFFFu : 0u) | (4 * q4 + 1 < ntok ? 0xFFFF0000u : 0u);
+      keep1 = (4 * q4 + 2 < ntok ? 0x0000FFFFu : 0u) | (4 * q4 + 3 < ntok ? 0xFFFF0000u : 0u);
+    }
+    // The transposing reads are written out by hand: through the compiler's builtin each of
+    // them would be preceded by a wait for every outstanding direct-to-LDS load, i.e. for the
+    // whole next tile, which would undo the prefetch.  The data they read is complete (the
+    // wait before this call covered the tile's eight loads).
+    u32x2 vt[8];
+    asm volatile(
+        "ds_read_b64_tr_b16 %0, %8 offset:%16\n\t"
+        "ds_read_b64_tr_b16 %1, %9 offset:%16\n\t"
+        "ds_read_b64_tr_b16 %2, %10 offset:%16\n\t"
+        "ds_read_b64_tr_b16 %3, %11 offset:%16\n\t"
+        "ds_read_b64_tr_b16 %4, %12 offset:%16\n\t"
+        "ds_read_b64_tr_b16 %5, %13 offset:%16\n\t"
+        "ds_read_b64_tr_b16 %6, %14 offset:%16\n\t"
+        "ds_read_b64_tr_b16 %7, %15 offset:%16\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&v"(vt[0]), "=&v"(vt[1]), "=&v"(vt[2]), "=&v"(vt[3]), "=&v"(vt[4]), "=&v"(vt[5]),
+          "=&v"(vt[6]), "=&v"(vt[7])
+        : "v"(vrd[0]), "v"(vrd[1]), "v"(vrd[2]), "v"(vrd[3]), "v"(vrd[4]), "v"(vrd[5]), "v"(vrd[6]),
+          "v"(vrd[7]), "n"(STAGE * kStageBytes + kTileBytes)
+        : "memory");
+    s16x4 vf[8];
+#pragma unroll
+    for (int nb = 0; nb < 8; ++nb) {
+      if (TAIL) { vt[nb][0] &= keep0; vt[nb][1] &= keep1; }
+      vf[nb] = __builtin_bit_cast(s16x4, vt[nb]);
+    }
+#pragma unroll
+    for (int nb = 0; nb < 8; ++nb)
+      acc[nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_hi, vf[nb], acc[nb], 0, 0, 0);
+#pragma unroll
+    for (int nb = 0; nb < 8; ++nb)
+      acc[nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_lo, vf[nb], acc[nb], 0, 0, 0);
+
     // The two wavefronts that share a SIMD (w and w+4) do not get equal issue slots: the
     // older one wins every tie.  Whoever is behind raises its priority until it catches up.
     ++tiles_done;
@@ -334,200 +370,167 @@ __global__ __launch_bounds__(kStreamThreads, 2) void attn_stream_mfma_d128(const
     else __builtin_amdgcn_s_setprio(0);
   };
 
-
-  // state of the segment being accumulated (may span groups of one chunk) and of the pipeline
+  // state of the segment being accumulated (may span batches of one chunk) and of the pipeline
   bool open = false;        // a segment is being accumulated
-  bool inflight = false;    // the first tile of the coming group is already issued, its query loaded
+  bool inflight = false;    // the first tile of the coming batch is already issued, its query loaded
   int seg_sp = 0, seg_info0 = 0, seg_x = 0, sp = 0, tab = 0;
 
   auto chunk_valid = [&](int ci) { return ci < plan.ns && ci * rs < glen; };
   auto chunk_tiles = [&](int ci) { return min(glen, (ci + 1) * rs) - ci * rs; };
 
-  if (chunk_valid(wave)) build_desc(g0 + wave * rs, min(kDescBatch, chunk_tiles(wave)), dtabs);
-  for (int ci = wave; chunk_valid(ci); ci += kNW) {   // local chunk id
+  // A wavefront's work is a sequence of batches of up to kDescBatch tiles: the batches of its
+  // first chunk, then those of its next chunk (local ids wave, wave+8, ...), and so on.
+  int ci = wave, b0 = 0;
+  bool have = chunk_valid(ci);
+  if (have) build_desc(g0 + ci * rs, min(kDescBatch, chunk_tiles(ci)), dtabs);
+  while (have) {
     const int c = blockIdx.x * plan.ns + ci;         // chunk id on the whole axis
     const int x0 = g0 + ci * rs;
     const int ntc = chunk_tiles(ci);                 // tiles of this chunk
-    const bool has_next = chunk_valid(ci + kNW);
+    const int nt = min(kDescBatch, ntc - b0);        // tiles of this batch, one descriptor per lane
+    const bool chunk_ends_here = b0 + nt == ntc;
+    int nci = ci, nb0 = b0 + kDescBatch;             // the batch after this one
+    bool has_next = true;
+    if (chunk_ends_here) { nci = ci + kNW; nb0 = 0; has_next = chunk_valid(nci); }
+    const u32x4* dtab = dtabs + tab * kDescBatch;
+    u32x4* dnext = dtabs + (tab ^ 1) * kDescBatch;
+    {
+      const u32x4 dreg = dtab[min(lane, nt - 1)];
+      d_k = (int)dreg[0]; d_v = (int)dreg[1]; d_sp = (int)dreg[2]; d_info = (int)dreg[3];
+    }
 
-    for (int b0 = 0; b0 < ntc; b0 += kDescBatch) {
-      const int ntb = min(kDescBatch, ntc - b0);
-      u32x4* dtab = dtabs + tab * kDescBatch;
-      if (b0 > 0) build_desc(x0 + b0, ntb, dtab);   // a chunk's first batch was built ahead
-      const bool last_batch = b0 + ntb == ntc;
+    int j0 = 0;
+    if (!inflight) {
+      sp = __builtin_amdgcn_readlane(d_sp, 0);
+      issue(0, 0);
+      if (!open) load_q(sp);                    // an open segment continues with its query
+    }
+    inflight = false;
+    // describe the next batch now: its index loads ride along with the tile that is in flight
+    if (has_next) build_desc(g0 + nci * rs + nb0, min(kDescBatch, chunk_tiles(nci) - nb0), dnext);
 
-      for (int r0 = 0; r0 < ntb; r0 += kWaveSize) {
-        const int nt = min(kWaveSize, ntb - r0);    // tiles of this group, one descriptor per lane
-        {
-          const u32x4 dreg = dtab[r0 + min(lane, nt - 1)];
-          d_k = (int)dreg[0]; d_v = (int)dreg[1]; d_sp = (int)dreg[2]; d_info = (int)dreg[3];
+    while (j0 < nt) {
+      // tiles j0 .. j1-1 belong to (sequence, pair) sp; the first one is already in flight
+      const uint64_t same = __builtin_amdgcn_ballot_w64(d_sp == sp && lane >= j0 && lane < nt);
+      const int j1 = j0 + __builtin_popcountll(same);
+      const int info1 = __builtin_amdgcn_readlane(d_info, j1 - 1);
+
+      if (!open) {
+        open = true;
+        seg_sp = sp;
+        seg_info0 = __builtin_amdgcn_readlane(d_info, j0);
+        seg_x = x0 + b0 + j0;
+        m_ref = kNegBig;
+        l_part = 0.f;
+#pragma unroll
+        for (int nb = 0; nb < 8; ++nb) acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+      }
+
+      {
+        using std::false_type;
+        using std::true_type;
+        using stage0 = std::integral_constant<int, 0>;
+        using stage1 = std::integral_constant<int, 1>;
+        int j = j0;
+        while (j + 2 < j1) {
+          issue(j + 1, 1); PKV_WAIT_VMCNT(8); consume(j, stage0{}, false_type{});
+          issue(j + 2, 0); PKV_WAIT_VMCNT(8); consume(j + 1, stage1{}, false_type{});
+          j += 2;
         }
-        const bool chunk_ends_here = b0 + r0 + nt == ntc;
-
-        int j0 = 0;
-        if (!inflight) {
-          // tile first, query second: the compiler drains the load queue before a
-          // direct-to-LDS load, so anything issued ahead of it would be waited for in full
-          sp = __builtin_amdgcn_readlane(d_sp, 0);
-          issue(0, 0);
-          if (!open) load_q(sp);                    // an open segment continues with its query
-        }
-        inflight = false;
-        // with this chunk's last stretch under way, describe the next chunk: its index loads ride
-        // along with the tile that is in flight
-        if (r0 == 0 && last_batch && has_next)
-          build_desc(g0 + (ci + kNW) * rs, min(kDescBatch, chunk_tiles(ci + kNW)),
-                     dtabs + (tab ^ 1) * kDescBatch);
-
-        while (j0 < nt) {
-          // tiles j0 .. j1-1 belong to (sequence, pair) sp; the first one is already in flight
-          const uint64_t same = __builtin_amdgcn_ballot_w64(d_sp == sp && lane >= j0 && lane < nt);
-          const int j1 = j0 + __builtin_popcountll(same);
-          const int info1 = __builtin_amdgcn_readlane(d_info, j1 - 1);
-
-        if (!open) {
-          open = true;
-          seg_sp = sp;
-          seg_info0 = __builtin_amdgcn_readlane(d_info, j0);
-          seg_x = x0 + b0 + r0 + j0;
-#pragma unroll
-          for (int r = 0; r < 4; ++r) { m[r] = kNegBig; l[r] = 0.f; }
-#pragma unroll
-          for (int g = 0; g < GH; ++g)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
-        }
-
-        {
-          using std::false_type;
-          using std::true_type;
-          int j = j0;
-          while (j + 2 < j1) {
-            issue(j + 1, 1); PKV_WAIT_VMCNT(8); consume(j, 0, false_type{});
-            issue(j + 2, 0); PKV_WAIT_VMCNT(8); consume(j + 1, 1, false_type{});
-            j += 2;
-          }
-          if (j + 2 == j1) {
-            issue(j + 1, 1); PKV_WAIT_VMCNT(8); consume(j, 0, false_type{});
-            PKV_WAIT_VMCNT(0); consume(j + 1, 1, true_type{});
-          } else {
-            PKV_WAIT_VMCNT(0); consume(j, 0, true_type{});
-          }
-        }
-
-          const bool last = (info1 >> 6) & 1;
-          const bool flush = last || (j1 == nt && chunk_ends_here);
-          // the next tile of this wavefront (next segment, next group or next chunk) and, if a
-          // new segment starts there, its query go in flight before anything is flushed
-          if (j1 < nt) {
-            sp = __builtin_amdgcn_readlane(d_sp, j1);
-            issue(j1, 0);
-            load_q(sp);
-          } else {
-            const u32x4* nx = nullptr;
-            if (r0 + kWaveSize < ntb) nx = dtab + r0 + kWaveSize;
-            else if (chunk_ends_here && has_next) nx = dtabs + (tab ^ 1) * kDescBatch;
-            if (nx != nullptr) {
-              const u32x4 pd = *nx;
-              issue_at((uint32_t)rfl((int)pd[0]), (uint32_t)rfl((int)pd[1]), 0);
-              if (flush) {
-                sp = rfl((int)pd[2]);
-                load_q(sp);
-              }
-              inflight = true;
-            }
-          }
-
-          if (flush) {
-          // ---- flush the open segment ----------------------------------------------------------
-          const int seq = seg_sp >> 8, pp = seg_sp & 255;
-          const int kvh = pp / p.group_tiles, gtile = pp - kvh * p.group_tiles;
-          const int h0 = kvh * p.group + gtile * GH;
-          const int nheads = min(GH, p.group - gtile * GH);
-          const bool first = (seg_info0 >> 5) & 1;
-          const int prank = seq * NP + pp;
-
-#pragma unroll
-          for (int r = 0; r < 4; ++r) l[r] = row16_sum(l[r]);
-          // (m, l) of every head slot to every lane
-          *reinterpret_cast<f32x4*>(pbuf + 4 * q4) = f32x4{m[0], m[1], m[2], m[3]};
-          *reinterpret_cast<f32x4*>(pbuf + 16 + 4 * q4) = f32x4{l[0], l[1], l[2], l[3]};
-          float mg[GH], lg[GH];
-#pragma unroll
-          for (int g = 0; g < GH; ++g) { mg[g] = pbuf[g]; lg[g] = pbuf[16 + g]; }
-          // Sum the accumulators of the four row groups.  Row group q only writes heads g with
-          // g % 4 == q, so this is a reduce-scatter: every lane parks its 8 values of head g in
-          // LDS (K ring stage 1 is idle during a flush: the tile in flight goes to stage 0) and
-          // the lanes of row group g % 4 add the other three groups' values, in fixed order.
-          {
-            float* red = reinterpret_cast<float*>(wlds + kTileBytes);   // 2 x 2 KiB, alternating
-#pragma unroll
-            for (int g = 0; g < GH; ++g) {
-              float* mine = red + (g & 1) * 512 + (q4 * 16 + t16) * 8;
-              *reinterpret_cast<f32x4*>(mine) = f32x4{acc[g][0], acc[g][1], acc[g][2], acc[g][3]};
-              *reinterpret_cast<f32x4*>(mine + 4) = f32x4{acc[g][4], acc[g][5], acc[g][6], acc[g][7]};
-              if ((g & 3) == q4) {
-#pragma unroll
-                for (int r = 1; r < 4; ++r) {
-                  const float* theirs = red + (g & 1) * 512 + (((q4 + r) & 3) * 16 + t16) * 8;
-                  const f32x4 a = *reinterpret_cast<const f32x4*>(theirs);
-                  const f32x4 b = *reinterpret_cast<const f32x4*>(theirs + 4);
-                  acc[g][0] += a[0]; acc[g][1] += a[1]; acc[g][2] += a[2]; acc[g][3] += a[3];
-                  acc[g][4] += b[0]; acc[g][5] += b[1]; acc[g][6] += b[2]; acc[g][7] += b[3];
-                }
-              }
-            }
-          }
-
-          if (first && last) {
-            // the whole (sequence, pair) was in this segment: finished rows
-#pragma unroll
-            for (int g = 0; g < GH; ++g) {
-              if ((g & 3) == q4 && g < nheads) {
-                const float inv = 1.0f / lg[g];
-                const int64_t o = ((int64_t)seq * p.num_q_heads + h0 + g) * D + t16 * 8;
-                if (p.out_is_bf16) {
-                  u32x4 w;
-#pragma unroll
-                  for (int e = 0; e < 4; ++e)
-                    w[e] = pack_bf16x2_rne(acc[g][2 * e] * inv, acc[g][2 * e + 1] * inv);
-                  *reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(p.out) + o) = w;
-                } else {
-                  float* op = reinterpret_cast<float*>(p.out) + o;
-                  *reinterpret_cast<f32x4*>(op) =
-                      f32x4{acc[g][0] * inv, acc[g][1] * inv, acc[g][2] * inv, acc[g][3] * inv};
-                  *reinterpret_cast<f32x4*>(op + 4) =
-                      f32x4{acc[g][4] * inv, acc[g][5] * inv, acc[g][6] * inv, acc[g][7] * inv};
-                }
-              }
-            }
-            if (lane == 0) *reinterpret_cast<i32x2*>(p.ws_dir + 2 * (int64_t)prank) = i32x2{0, 1};
-          } else {
-            const int64_t slot = (int64_t)prank + c;   // unique: both terms grow along the axis
-#pragma unroll
-            for (int g = 0; g < GH; ++g) {
-              if ((g & 3) == q4 && g < nheads) {
-                float* op = p.ws_o + (slot * GH + g) * D + t16 * 8;
-                *reinterpret_cast<f32x4*>(op) = f32x4{acc[g][0], acc[g][1], acc[g][2], acc[g][3]};
-                *reinterpret_cast<f32x4*>(op + 4) = f32x4{acc[g][4], acc[g][5], acc[g][6], acc[g][7]};
-                if (t16 == 0)
-                  *reinterpret_cast<f32x2*>(p.ws_ml + (slot * GH + g) * 2) = f32x2{mg[g], lg[g]};
-              }
-            }
-            if (first && lane == 0) {
-              // directory entry of the pair: its partials sit in consecutive slots
-              const int tiles = seg_info0 >> 8;
-              const int c_last = plan.chunk_of(seg_x + tiles - 1);
-              *reinterpret_cast<i32x2*>(p.ws_dir + 2 * (int64_t)prank) = i32x2{(int)slot, c_last - c + 1};
-            }
-          }
-          open = false;
-          }
-          j0 = j1;
+        if (j + 2 == j1) {
+          issue(j + 1, 1); PKV_WAIT_VMCNT(8); consume(j, stage0{}, false_type{});
+          PKV_WAIT_VMCNT(0); consume(j + 1, stage1{}, true_type{});
+        } else {
+          PKV_WAIT_VMCNT(0); consume(j, stage0{}, true_type{});
         }
       }
+
+      const bool last = (info1 >> 6) & 1;
+      const bool flush = last || (j1 == nt && chunk_ends_here);
+      // the next tile of this wavefront (next segment, next batch or next chunk) and, if a
+      // new segment starts there, its query go in flight before anything is flushed
+      if (j1 < nt) {
+        sp = __builtin_amdgcn_readlane(d_sp, j1);
+        issue(j1, 0);
+        load_q(sp);
+      } else if (has_next) {
+        const u32x4 pd = dnext[0];
+        issue_at((uint32_t)rfl((int)pd[0]), (uint32_t)rfl((int)pd[1]), 0);
+        if (flush) {
+          sp = rfl((int)pd[2]);
+          load_q(sp);
+        }
+        inflight = true;
+      }
+
+      if (flush) {
+        // ---- flush the open segment ------------------------------------------------------------
+        const int seq = seg_sp >> 8, pp = seg_sp & 255;
+        const int kvh = pp / p.group_tiles, gtile = pp - kvh * p.group_tiles;
+        const int h0 = kvh * p.group + gtile * GH;
+        const int nheads = min(GH, p.group - gtile * GH);
+        const bool first = (seg_info0 >> 5) & 1;
+        const int prank = seq * NP + pp;
+
+        // row-sum shares and reference maxima of all head columns, for every lane to read
+        xchg[q4 * 16 + t16] = l_part;
+        xchg[64 + t16] = m_ref;
+        // O goes through LDS to turn the accumulator layout (lane = one dim of four heads) into
+        // whole rows: stage 1 of the ring is idle during a flush, the tile in flight uses stage 0
+        float* st = reinterpret_cast<float*>(wlds + kStageBytes);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          if (4 * q4 + r < GH) {
+#pragma unroll
+            for (int nb = 0; nb < 8; ++nb) st[(4 * q4 + r) * kStageRow + nb * 16 + t16] = acc[nb][r];
+          }
+        }
+        const int64_t slot = (int64_t)prank + c;   // unique: both terms grow along the axis
+        const int hh = lane >> 5, piece = lane & 31;   // two head rows per pass, 32 x 16 bytes each
+#pragma unroll
+        for (int g2 = 0; g2 < GH; g2 += 2) {
+          const int g = g2 + hh;
+          if (g < nheads) {
+            const f32x4 o4 = *reinterpret_cast<const f32x4*>(st + g * kStageRow + piece * 4);
+            const float lsum = (xchg[g] + xchg[16 + g]) + (xchg[32 + g] + xchg[48 + g]);
+            if (first && last) {
+              // the whole (sequence, pair) was in this segment: finished rows
+              const float inv = 1.0f / lsum;
+              const int64_t o = ((int64_t)seq * p.num_q_heads + h0 + g) * D + piece * 4;
+              if (p.out_is_bf16) {
+                i32x2 w;
+                w[0] = (int)pack_bf16x2_rne(o4[0] * inv, o4[1] * inv);
+                w[1] = (int)pack_bf16x2_rne(o4[2] * inv, o4[3] * inv);
+                *reinterpret_cast<i32x2*>(reinterpret_cast<uint16_t*>(p.out) + o) = w;
+              } else {
+                *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(p.out) + o) =
+                    f32x4{o4[0] * inv, o4[1] * inv, o4[2] * inv, o4[3] * inv};
+              }
+            } else {
+              *reinterpret_cast<f32x4*>(p.ws_o + (slot * GH + g) * D + piece * 4) = o4;
+              if (piece == 0)
+                *reinterpret_cast<f32x2*>(p.ws_ml + (slot * GH + g) * 2) = f32x2{xchg[64 + g], lsum};
+            }
+          }
+        }
+        if (lane == 0) {
+          if (first && last) {
+            *reinterpret_cast<i32x2*>(p.ws_dir + 2 * (int64_t)prank) = i32x2{0, 1};
+          } else if (first) {
+            // directory entry of the pair: its partials sit in consecutive slots
+            const int tiles = seg_info0 >> 8;
+            const int c_last = plan.chunk_of(seg_x + tiles - 1);
+            *reinterpret_cast<i32x2*>(p.ws_dir + 2 * (int64_t)prank) = i32x2{(int)slot, c_last - c + 1};
+          }
+        }
+        open = false;
+      }
+      j0 = j1;
     }
     tab ^= 1;
+    ci = nci;
+    b0 = nb0;
+    have = has_next;
   }
 }
 

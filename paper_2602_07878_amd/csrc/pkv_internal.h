@@ -11,7 +11,7 @@ constexpr int kWaveSize = 64;
 constexpr int kTileTokens = 16;          // tokens handled per inner tile
 constexpr int kDefaultPartition = 512;   // split-K partition length in tokens
 constexpr int kAttnThreads = 256;        // 4 wavefronts per workgroup
-constexpr int kStreamMaxPrefixBytes = 16384;  // LDS for per-sequence tile prefix sums
+constexpr int kStreamMaxPrefixBytes = 8192;   // LDS for per-sequence tile prefix sums
 
 // Launch geometry and pointers of one attention call, passed by value.
 struct AttnParams {
