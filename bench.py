@@ -24,6 +24,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+STREAM_KERNEL = "attn_stream_mfma_d128<4>"   # the kernel that streams K and V for the timed workload
 
 
 def log(*a):
@@ -47,7 +48,7 @@ def upload_attn(w, layers, torch):
 
 
 def time_attention(w, d, steps, warmup, torch, binding, kernel_events=False):
-    """Returns (out, ms per call, wall ms per call, ms per launch of the K/V-streaming kernel).
+    """Returns (out, ms per call, wall ms per call, sorted ms of every launch of the K/V-streaming kernel).
     With kernel_events, every call also records an event right before and right after that
     kernel (paged_decode_attention_timed), on the stream the kernels run on."""
     out = torch.empty(w.B, w.Hq, w.D, dtype=torch.float32, device="cuda:0")
@@ -82,8 +83,8 @@ def time_attention(w, d, steps, warmup, torch, binding, kernel_events=False):
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
     ev_ms = e0.elapsed_time(e1)
-    kern_ms = sum(a.elapsed_time(b) for a, b in evs) / steps if evs else None
-    return out, ev_ms / steps, wall_ms / steps, kern_ms
+    kern = sorted(a.elapsed_time(b) for a, b in evs) if evs else None
+    return out, ev_ms / steps, wall_ms / steps, kern
 
 
 def source_fingerprint():
@@ -97,14 +98,21 @@ def source_fingerprint():
     return h.hexdigest()[:16]
 
 
-def recorded_traffic(workload):
-    """HBM bytes per launch from the committed rocprofv3 --pmc summary, or None if stale/missing."""
-    path = os.path.join(ROOT, "profiles", "attn_stream_traffic.json")
+def recorded_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary (its
+    `key = value` header lines), or None if that summary is missing or was taken from other
+    sources than the ones now in the tree."""
+    path = os.path.join(ROOT, "profiles", "attn_stream_cfg2_hbm_traffic.txt")
+    rec = {}
     try:
-        rec = json.load(open(path))
-        if rec.get("source_fingerprint") == source_fingerprint() and rec.get("workload") == workload:
-            return rec.get("hbm_bytes_per_launch")
-    except (OSError, ValueError):
+        for line in open(path):
+            if line.startswith("# ") and " = " in line:
+                k, v = line[2:].split(" = ", 1)
+                rec[k.strip()] = v.strip()
+        if (rec.get("source_fingerprint") == source_fingerprint() and rec.get("workload") == workload
+                and rec.get("kernel") == kernel):
+            return float(rec["hbm_bytes_per_launch"])
+    except (OSError, ValueError, KeyError):
         pass
     return None
 
@@ -197,8 +205,9 @@ def main():
     ap.add_argument("--extra", action="store_true", help="also time the Fill and long-context configs")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only; --gpus must be 1 (no multi-GPU path "
-              "exists: the kernels need no collective, see DESIGN.md)", file=sys.stderr)
+        print("bench.py: this library runs on one GPU only; --gpus must be 1 (the kernels need no "
+              "collective: every GPU of a tensor-parallel group would run them on its own KV heads)",
+              file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
@@ -216,7 +225,9 @@ def main():
     # an event before and after every launch of the streaming kernel; the two extra stream
     # markers per call cost a few microseconds, which is why `value` does not come from it.
     out, ms, wall_ms, _ = time_attention(w, d, args.steps, args.warmup, torch, binding)
-    _, ms_ev, _, kern_ms = time_attention(w, d, args.steps, 4, torch, binding, kernel_events=True)
+    _, ms_ev, _, kern = time_attention(w, d, args.steps, 4, torch, binding, kernel_events=True)
+    kern_ms = sum(kern) / len(kern)
+    pct = lambda q: kern[min(len(kern) - 1, int(q * len(kern)))] * 1e3
     gbps = w.kv_bytes / ms / 1e6
     kern_gbps = w.kv_bytes / kern_ms / 1e6
     log(f"[bench] attention: {ms*1e3:.1f} us/call, {gbps:.0f} KV GB/s = {gbps/HBM_PEAK_GBS:.1%} of HBM peak; "
@@ -235,8 +246,9 @@ def main():
         "kv_tokens_per_s": w.total_tokens / (ms * 1e-3),
         "wall_ms_per_step": wall_ms,
         "roofline": {"bound": "hbm", "achieved": kern_gbps, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": kern_gbps / HBM_PEAK_GBS, "traffic": recorded_traffic(w.name),
-                     "kernel": "attn_stream_mfma_d128<4>", "us_per_launch": kern_ms * 1e3,
+                     "frac": kern_gbps / HBM_PEAK_GBS, "traffic": recorded_traffic(w.name, STREAM_KERNEL),
+                     "kernel": STREAM_KERNEL, "us_per_launch": kern_ms * 1e3,
+                     "us_per_launch_p10_p50_p90": [pct(0.1), pct(0.5), pct(0.9)],
                      "algorithmic_bytes_per_launch": w.kv_bytes,
                      "timed_region": f"second pass of {args.steps} steps with an event before and after "
                                      f"each launch ({ms_ev * 1e3:.1f} us per call in that pass)"},
@@ -271,7 +283,8 @@ def main():
             # library's own split
             for pt in sorted({wx.partition_tokens, 0}, reverse=True):
                 wx.partition_tokens = pt
-                _, msx, _, kx = time_attention(wx, dx, 40, 8, torch, binding, kernel_events=True)
+                _, msx, _, kxs = time_attention(wx, dx, 40, 8, torch, binding, kernel_events=True)
+                kx = sum(kxs) / len(kxs)
                 g = wx.kv_bytes / msx / 1e6
                 key = wx.name + (f"_partition{pt}" if pt else "")
                 extra[key] = {"ms": msx, "kv_GBps": g, "frac_hbm_peak": g / HBM_PEAK_GBS,

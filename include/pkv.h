@@ -156,11 +156,13 @@ int32_t paged_decode_attention(const pkv_attn_desc* desc, const void* q,
 
 /*
  * The same call with two optional hipEvent_t handles (passed as void*, either
- * may be NULL) that are recorded on hip_stream immediately before and after the
- * kernel that streams K and V (Sec. 4.2: the part of the step whose time grows
- * with the KV volume), i.e. excluding the small kernel that merges the split-K
- * partials.  For profiling: the elapsed time between the two events is that
- * kernel's duration.  The events are the caller's; nothing waits on them.
+ * may be NULL) that are attached to the launch of the kernel that streams K and
+ * V (Sec. 4.2: the part of the step whose time grows with the KV volume) and
+ * receive that kernel's own begin and end on hip_stream, i.e. excluding the
+ * small kernel that merges the split-K partials.  For profiling: the elapsed
+ * time between the two events is that kernel's duration.  The events are the
+ * caller's and must have been created with timing enabled; nothing waits on
+ * them.
  */
 int32_t paged_decode_attention_timed(const pkv_attn_desc* desc, const void* q,
                                      const void* k_pool, const void* v_pool,

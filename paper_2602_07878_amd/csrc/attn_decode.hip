@@ -16,6 +16,8 @@
 // softmax state over the tokens of row group r: no cross-lane traffic in the
 // main loop except the LPR-lane sum that finishes each dot product.
 
+#include <hip/hip_ext.h>
+
 #include "pkv_internal.h"
 
 namespace pkv {
@@ -314,10 +316,12 @@ template <int EB, int LPR, int GT>
 hipError_t launch_valu(const AttnParams& p, hipStream_t s) {
   dim3 grid(p.max_partitions, p.num_kv_heads * p.group_tiles, p.batch);
   const size_t lds = sizeof(float) * (kAttnThreads / kWaveSize) * GT * (p.head_dim + 2);
-  if (p.ev_begin && hipEventRecord(p.ev_begin, s) != hipSuccess) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((attn_partial_valu<EB, LPR, GT>), grid, dim3(kAttnThreads), lds, s, p);
+  if (p.ev_begin || p.ev_end)
+    hipExtLaunchKernelGGL((attn_partial_valu<EB, LPR, GT>), grid, dim3(kAttnThreads), lds, s,
+                          p.ev_begin, p.ev_end, 0, p);
+  else
+    hipLaunchKernelGGL((attn_partial_valu<EB, LPR, GT>), grid, dim3(kAttnThreads), lds, s, p);
   const hipError_t e = hipGetLastError();
-  if (e == hipSuccess && p.ev_end && hipEventRecord(p.ev_end, s) != hipSuccess) return hipErrorInvalidValue;
   return e;
 }
 
