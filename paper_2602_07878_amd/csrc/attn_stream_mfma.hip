@@ -88,68 +88,25 @@ __device__ __forceinline__ int rfl(int v) { return __builtin_amdgcn_readfirstlan
 typedef const void __attribute__((address_space(1)))* gptr_t;
 typedef void __attribute__((address_space(3)))* lptr_t;
 
-// Chunk schedule.  The tile axis is cut into contiguous ranges, one per workgroup, and each
-// range into chunks of equal length: one per wavefront, or k per wavefront when the caller caps
-// the tokens per partial (wavefront w then takes chunks w, w+8, ...).  Chunk ids grow along the
-// axis: id = workgroup * ns + local id, with ns = 8k ids set aside per workgroup.
-//
-// Workgroups are dealt to the eight XCDs round-robin, and the XCDs do not finish equal ranges
-// at the same time (measured: up to 15 % apart, odd XCDs later than their even neighbours).
-// The ranges of every round of eight consecutive workgroups can therefore be sized by a table
-// of shares (256 = a fair share).  The XCDs compete for one HBM, so their speeds depend on
-// each other and on the workload, and no fixed table gained more than 2 %: the default is the
-// equal split, and the table is a build-time knob.
-#ifndef PKV_XCD_SHARES
-#define PKV_XCD_SHARES 256, 256, 256, 256, 256, 256, 256, 256
-#endif
-constexpr int kXcdShare[8] = {PKV_XCD_SHARES};
-constexpr int xcd_share_max() {
-  int m = 0;
-  for (int i = 0; i < 8; ++i) m = kXcdShare[i] > m ? kXcdShare[i] : m;
-  return m;
-}
-static_assert(kXcdShare[0] + kXcdShare[1] + kXcdShare[2] + kXcdShare[3] + kXcdShare[4] +
-              kXcdShare[5] + kXcdShare[6] + kXcdShare[7] == 8 * 256, "shares of a round sum to 8");
-static_assert(xcd_share_max() <= 320, "the workspace bound allows for ranges up to 5/4 of a fair share");
-
-__device__ __forceinline__ int xcd_cum(int x) {   // summed shares of the first x workgroups of a round
-  int c = 0;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) c += i < x ? kXcdShare[i] : 0;
-  return c;
-}
-
+// Chunk schedule.  The tile axis is cut into equal contiguous ranges, one per workgroup, and
+// each range into `ns` chunks of `rs` tiles: one per wavefront, or k per wavefront when the
+// caller caps the tokens per partial (wavefront w then takes chunks w, w+8, ...; all chunks
+// have the same length so that the eight wavefronts carry equal loads).  Chunk ids grow along
+// the axis without gaps: id = workgroup * ns + local id.
 struct ChunkPlan {
-  int lg;      // fair share of a workgroup, in tiles
-  int k, ns;   // chunks per wavefront, chunk ids per workgroup
-  bool skew;   // shares apply (the grid is a whole number of rounds)
-  __device__ __forceinline__ int bound(int g) const {   // first tile of workgroup g's range
-    return skew ? (g >> 3) * 8 * lg + ((xcd_cum(g & 7) * lg) >> 8) : g * lg;
-  }
-  __device__ __forceinline__ int chunk_len(int glen) const { return max(1, (glen + kNW * k - 1) / (kNW * k)); }
+  int lg, rs, ns;
   __device__ __forceinline__ int chunk_of(int x) const {
-    int g;
-    if (skew) {
-      const int r = x / (8 * lg), rem = x - r * 8 * lg;
-      int xi = 0;
-#pragma unroll
-      for (int i = 1; i < 8; ++i) xi += rem >= ((xcd_cum(i) * lg) >> 8);
-      g = 8 * r + xi;
-    } else {
-      g = x / lg;
-    }
-    const int b0 = bound(g);
-    return g * ns + (x - b0) / chunk_len(bound(g + 1) - b0);
+    const int g = x / lg;
+    return g * ns + (x - g * lg) / rs;
   }
 };
 
 __device__ __forceinline__ ChunkPlan plan_chunks(int T, int nwg, int cap) {
   ChunkPlan pl;
   pl.lg = max(kMinGroupTiles, (T + nwg - 1) / nwg);
-  pl.skew = (nwg & 7) == 0 && xcd_share_max() != 256;
-  const int longest = pl.skew ? ((xcd_share_max() * pl.lg) >> 8) + 1 : pl.lg;
-  pl.k = cap > 0 ? (longest + kNW * cap - 1) / (kNW * cap) : 1;
-  pl.ns = kNW * pl.k;
+  const int k = cap > 0 ? (pl.lg + kNW * cap - 1) / (kNW * cap) : 1;
+  pl.rs = (pl.lg + kNW * k - 1) / (kNW * k);
+  pl.ns = (pl.lg + pl.rs - 1) / pl.rs;
   return pl;
 }
 
@@ -197,10 +154,9 @@ __global__ __launch_bounds__(kStreamThreads, 2) void attn_stream_mfma_d128(const
   if (T == 0) return;
 
   const ChunkPlan plan = plan_chunks(T, gridDim.x, p.chunk_tiles_max);
-  const int g0 = plan.bound(blockIdx.x);                   // first tile of this workgroup's range
-  const int gfull = plan.bound(blockIdx.x + 1) - g0;
-  const int glen = min(gfull, T - g0);                     // its length (<= 0: nothing to do)
-  const int rs = plan.chunk_len(gfull);                    // tiles per chunk
+  const int g0 = blockIdx.x * plan.lg;                     // first tile of this workgroup's range
+  const int glen = min(plan.lg, T - g0);                   // its length (<= 0: nothing to do)
+  const int rs = plan.rs;                                  // tiles per chunk
   if (glen <= 0) return;
   // ---- per-lane, loop-invariant offsets -------------------------------------------------------
   // Load j of a tile brings token rows 4j..4j+3; this lane fetches one 16-byte piece of row
@@ -713,8 +669,8 @@ StreamWorkspace stream_workspace(const pkv_attn_desc& d) {
   // chunk ids stay below workgroups * chunks-per-workgroup, see plan_chunks()
   const int64_t ncu = num_cus();
   const int64_t cap = w.chunk_tiles_max;
-  // ns = 8k with k < longest range / (8 cap) + 1, and the longest range is at most 5/4 of a fair share
-  w.slots = pairs + (cap ? (tiles_ub + kMinGroupTiles * ncu) * 5 / 4 / cap + 2 * ncu : 0) + ncu * (kNW + 1) + 2;
+  // ns <= 8k with k < lg / (8 cap) + 1 chunks per wavefront
+  w.slots = pairs + (cap ? (tiles_ub + kMinGroupTiles * ncu) / cap + ncu : 0) + ncu * (kNW + 1) + 2;
   auto up = [](int64_t b) { return (b + 255) / 256 * 256; };
   w.dir_bytes = up(pairs * 2 * 4);
   w.ml_bytes = up(w.slots * gh * 2 * 4);
