@@ -50,6 +50,8 @@ def _load():
             [i32] * 8 + [i64] * 6 + [vp] * 5 + [ctypes.c_float, vp, vp, i32])
         lib.orc_kv_block_swap.restype = ctypes.c_int
         lib.orc_kv_block_swap.argtypes = [i32, i64, i64, i64, i32, i32, vp, vp, vp, i32]
+        lib.orc_kv_append.restype = ctypes.c_int
+        lib.orc_kv_append.argtypes = [i32] * 7 + [i64] * 6 + [vp] * 6
         lib.orc_num_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -138,3 +140,34 @@ def kv_block_swap(src, dst, mapping, *, num_planes, block_bytes,
     if rc != 0:
         raise IndexError("oracle: mapping entry outside its plane")
     return dst
+
+
+def kv_append(k_pool, v_pool, k_new, v_new, block_tables, context_lens, *, block_size,
+              k_strides=None, v_strides=None):
+    """Write row k_new[i], v_new[i] ([B,Hkv,D]) at token position context_lens[i]-1 of
+    every sequence (pools modified in place; same layout rules as the attention oracle)."""
+    lib = _load()
+    assert k_pool.flags.c_contiguous and v_pool.flags.c_contiguous
+    assert k_pool.flags.writeable and v_pool.flags.writeable
+    k_new = np.ascontiguousarray(k_new)
+    v_new = np.ascontiguousarray(v_new)
+    bt = np.ascontiguousarray(block_tables, dtype=np.int32)
+    cl = np.ascontiguousarray(context_lens, dtype=np.int32)
+    code = _dtype_code(k_pool)
+    if {_dtype_code(v_pool), _dtype_code(k_new), _dtype_code(v_new)} != {code}:
+        raise TypeError("pools and new rows must share one dtype")
+    B, Hkv, D = k_new.shape
+    nblk = k_pool.shape[0]
+    if k_strides is None:
+        assert k_pool.shape == (nblk, Hkv, block_size, D), k_pool.shape
+        k_strides = (Hkv * block_size * D, block_size * D, D)
+    if v_strides is None:
+        assert v_pool.shape == (nblk, Hkv, block_size, D), v_pool.shape
+        v_strides = (Hkv * block_size * D, block_size * D, D)
+    assert bt.ndim == 2 and bt.shape[0] == B and cl.shape == (B,)
+    rc = lib.orc_kv_append(B, Hkv, D, block_size, nblk, bt.shape[1], k_pool.itemsize,
+                           *[int(x) for x in k_strides], *[int(x) for x in v_strides],
+                           _ptr(k_new), _ptr(v_new), _ptr(k_pool), _ptr(v_pool), _ptr(bt), _ptr(cl))
+    if rc != 0:
+        raise IndexError(f"oracle: append outside pool/table (code {rc})")
+    return k_pool, v_pool

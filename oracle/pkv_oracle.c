@@ -166,6 +166,41 @@ int orc_kv_block_swap(int num_planes, int64_t block_bytes,
   return 0;
 }
 
+/*
+ * KV append (arXiv 2602.07878, Sec. 2.2 "KV-Cache": the K and V vectors of the
+ * token generated in a step are added to the request's cache).  context_lens
+ * already counts the new token, so for every sequence i with n_i >= 1 the rows
+ * k_new[i][g][:] and v_new[i][g][:] go to token position n_i - 1:
+ * block block_tables[i][(n_i-1)/bs], slot (n_i-1)%bs, every KV head g.
+ * Sequences with n_i == 0 are skipped.  Strides are in elements, eb = bytes
+ * per element.  Returns 0, or negative for an index outside table or pool.
+ */
+int orc_kv_append(int B, int Hkv, int D, int bs, int nblk, int maxb, int eb,
+                  int64_t ksb, int64_t ksh, int64_t kst,
+                  int64_t vsb, int64_t vsh, int64_t vst,
+                  const uint8_t* k_new, const uint8_t* v_new,
+                  uint8_t* k_pool, uint8_t* v_pool,
+                  const int32_t* bt, const int32_t* cl) {
+  for (int i = 0; i < B; ++i) {
+    const int n = cl[i];
+    if (n < 0) return -1;
+    if (n == 0) continue;
+    const int pos = n - 1;
+    if (pos / bs >= maxb) return -2;
+    const int64_t blk = bt[(int64_t)i * maxb + pos / bs];
+    if (blk < 0 || blk >= nblk) return -3;
+    const int slot = pos % bs;
+    for (int g = 0; g < Hkv; ++g) {
+      const size_t row = (size_t)D * eb;
+      memcpy(k_pool + (blk * ksb + g * ksh + slot * kst) * eb,
+             k_new + ((int64_t)i * Hkv + g) * row, row);
+      memcpy(v_pool + (blk * vsb + g * vsh + slot * vst) * eb,
+             v_new + ((int64_t)i * Hkv + g) * row, row);
+    }
+  }
+  return 0;
+}
+
 int orc_num_threads(void) {
   int n = 1;
 #ifdef _OPENMP

@@ -383,3 +383,70 @@ def test_swap_rejects_out_of_range_pair():
     dst = np.zeros(64, np.uint8)
     with pytest.raises(IndexError):
         oracle.kv_block_swap(src, dst, [[0, 4]], num_planes=1, block_bytes=16)
+
+
+# Append oracle (Sec. 2.2: the new token's K/V rows join the cache) -----------------
+def _new_rows(w, seed):
+    rng = np.random.default_rng(seed)
+    shape = (w.B, w.Hkv, w.D)
+    k = rng.standard_normal(shape).astype(np.float32)
+    v = rng.standard_normal(shape).astype(np.float32)
+    if w.k_pool.dtype == np.uint16:
+        return W.f32_to_bf16_bits(k), W.f32_to_bf16_bits(v)
+    return k, v
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_append_writes_exactly_the_last_token_rows(dtype):
+    lens = (1, 5, 8, 16, 0, 7)            # last slot of a block, first slot, empty sequence
+    w = small(21, dtype=dtype, Hq=4, Hkv=2, lens=lens, pool_factor=2.0)
+    kn, vn = _new_rows(w, 5)
+    k0, v0 = w.k_pool.copy(), w.v_pool.copy()
+    oracle.kv_append(w.k_pool, w.v_pool, kn, vn, w.block_tables, w.context_lens, block_size=w.block_size)
+    # expected image built here with the test's own index arithmetic
+    ke, ve = k0.copy(), v0.copy()
+    for i, n in enumerate(lens):
+        if n == 0:
+            continue
+        blk, slot = w.block_tables[i, (n - 1) // w.block_size], (n - 1) % w.block_size
+        ke[blk, :, slot, :] = kn[i]
+        ve[blk, :, slot, :] = vn[i]
+    assert np.array_equal(w.k_pool.view(np.uint8), ke.view(np.uint8))   # bytewise: NaN poison stays put
+    assert np.array_equal(w.v_pool.view(np.uint8), ve.view(np.uint8))
+    assert not np.array_equal(ke.view(np.uint8), k0.view(np.uint8))
+
+
+def test_append_then_attention_equals_attention_over_the_longer_contiguous_history():
+    # grow every sequence by one token with append, then compare with softmax attention
+    # written out here over explicitly concatenated K/V (no paging at all)
+    lens0 = (3, 4, 7, 12)
+    w = small(22, dtype="f32", Hq=4, Hkv=2, D=8, bs=4, lens=tuple(n + 1 for n in lens0), pool_factor=1.5)
+    kn, vn = _new_rows(w, 6)
+    hist_k = [[gather_rows(w.k_pool, w.block_tables[i], lens0[i], g, 4) for g in range(2)] for i in range(4)]
+    hist_v = [[gather_rows(w.v_pool, w.block_tables[i], lens0[i], g, 4) for g in range(2)] for i in range(4)]
+    oracle.kv_append(w.k_pool, w.v_pool, kn, vn, w.block_tables, w.context_lens, block_size=4)
+    out = run(w)
+    for i in range(4):
+        for h in range(4):
+            g = h // 2
+            K = np.concatenate([hist_k[i][g], kn[i, g][None]]).astype(np.float64)
+            V = np.concatenate([hist_v[i][g], vn[i, g][None]]).astype(np.float64)
+            s = float(np.float32(w.scale)) * (K @ w.q[i, h].astype(np.float64))
+            p = np.exp(s - s.max())
+            assert np.abs(out[i, h] - (p / p.sum()) @ V).max() < 1e-12
+
+
+def test_append_respects_strided_token_major_layout_and_reports_bad_table():
+    w = small(23, dtype="bf16", Hq=4, Hkv=2, D=8, bs=4, lens=(6, 9), pool_factor=1.5)
+    kn, vn = _new_rows(w, 7)
+    # token-major copy of the pools: [block][slot][head][D]
+    kt = np.ascontiguousarray(w.k_pool.transpose(0, 2, 1, 3))
+    vt = np.ascontiguousarray(w.v_pool.transpose(0, 2, 1, 3))
+    st = (4 * 2 * 8, 8, 2 * 8)            # block, head, token strides in elements
+    oracle.kv_append(kt, vt, kn, vn, w.block_tables, w.context_lens, block_size=4, k_strides=st, v_strides=st)
+    oracle.kv_append(w.k_pool, w.v_pool, kn, vn, w.block_tables, w.context_lens, block_size=4)
+    assert np.array_equal(kt.transpose(0, 2, 1, 3), w.k_pool)
+    assert np.array_equal(vt.transpose(0, 2, 1, 3), w.v_pool)
+    w.block_tables[1, 2] = -1
+    with pytest.raises(IndexError):
+        oracle.kv_append(w.k_pool, w.v_pool, kn, vn, w.block_tables, w.context_lens, block_size=4)
