@@ -117,6 +117,35 @@ def recorded_traffic(workload, kernel):
     return None
 
 
+def time_append(w, d, torch, binding, reps=200):
+    """The new token's K/V rows of every sequence written into the pools (the step right before
+    attention in a decode iteration): time of the append alone and of append + attention."""
+    desc = binding.attn_desc_for(d["q"], d["ks"][0], d["vs"][0], d["bt"], max_context_len=w.max_context_len,
+                                 partition_tokens=w.partition_tokens)
+    ws = binding.new_workspace(binding.attn_workspace_bytes(desc), "cuda:0")
+    out = torch.empty(w.B, w.Hq, w.D, dtype=torch.float32, device="cuda:0")
+    kn = torch.randn(w.B, w.Hkv, w.D, device="cuda:0").to(d["ks"][0].dtype)
+    vn = torch.randn(w.B, w.Hkv, w.D, device="cuda:0").to(d["ks"][0].dtype)
+    L = len(d["ks"])
+
+    def run(with_attention):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(reps):
+            binding.kv_append(desc, kn, vn, d["ks"][i % L], d["vs"][i % L], d["bt"], d["cl"])
+            if with_attention:
+                binding.paged_decode_attention(d["q"], d["ks"][i % L], d["vs"][i % L], d["bt"], d["cl"],
+                                               w.scale, out, max_context_len=w.max_context_len,
+                                               workspace=ws, desc=desc)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e3
+    run(True)
+    return {"append_us": run(False), "append_plus_attention_us": run(True),
+            "bytes_written": 2 * w.B * w.Hkv * w.D * 2}
+
+
 def time_swap(sw, reps, torch, binding):
     """Gather the victims' blocks to contiguous staging, then scatter to fresh blocks."""
     g = torch.Generator(device="cuda:0")
@@ -253,6 +282,8 @@ def main():
                      "timed_region": f"second pass of {args.steps} steps with an event before and after "
                                      f"each launch ({ms_ev * 1e3:.1f} us per call in that pass)"},
     }
+    result["kv_append"] = time_append(w, d, torch, binding)
+    log(f"[bench] append ahead of attention: {result['kv_append']}")
     result["ceilings"] = probe_ceilings(torch, binding)
     log(f"[bench] ceilings: {result['ceilings']}")
 

@@ -106,6 +106,12 @@ int32_t pkv_version(void);
 const char* pkv_status_string(int32_t status);
 
 /*
+ * Text of the HIP runtime error behind the most recent PKV_ERR_HIP returned to
+ * the calling thread ("no error" if there was none).  Diagnostics only.
+ */
+const char* pkv_last_hip_error_string(void);
+
+/*
  * Split-K partition length in tokens the library will use for `desc`
  * (desc->partition_tokens, or the default when that is 0).  Returns 0 if
  * desc is NULL or the value is unsupported.
@@ -171,6 +177,26 @@ int32_t paged_decode_attention_timed(const pkv_attn_desc* desc, const void* q,
                                      void* out, void* workspace,
                                      size_t workspace_bytes, void* hip_stream,
                                      void* ev_kernel_begin, void* ev_kernel_end);
+
+/*
+ * KV append (Sec. 2.2 "KV-Cache": the K and V vectors of the token generated
+ * in a step join the request's cache before the step's attention reads it).
+ * desc is the descriptor of the attention call that follows; context_lens
+ * already counts the new token.  For every sequence i with
+ * n_i = context_lens[i] >= 1 and every KV head g, the rows k_new[i][g][:] and
+ * v_new[i][g][:] (device, [batch][num_kv_heads][head_dim] contiguous, dtype
+ * desc->kv_dtype) are copied bit-exactly to token position n_i - 1 of the
+ * pools: block block_tables[i][(n_i-1)/block_size], slot (n_i-1)%block_size,
+ * at the strides of desc.  Sequences with n_i = 0 are skipped; nothing else
+ * in the pools is touched.  Two sequences whose last token maps to the same
+ * (block, slot) race (undefined).  Table entries are trusted as in the
+ * attention call (pkv_validate_tables checks them).  Enqueued on hip_stream
+ * ahead of the attention call that reads the pools; batch = 0 enqueues
+ * nothing.  Errors as for paged_decode_attention (no workspace is used).
+ */
+int32_t kv_append(const pkv_attn_desc* desc, const void* k_new, const void* v_new,
+                  void* k_pool, void* v_pool, const int32_t* block_tables,
+                  const int32_t* context_lens, void* hip_stream);
 
 /*
  * Block gather/scatter of the preemption swap path (Sec. 5.1.2 "Swapping":

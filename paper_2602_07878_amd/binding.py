@@ -18,8 +18,9 @@ PKV_OK = 0
 FLAG_VECTOR_ALU = 1
 
 EXPORTS = [
-    "pkv_version", "pkv_status_string", "pkv_attn_partition_tokens", "pkv_attn_workspace_bytes",
-    "paged_decode_attention", "paged_decode_attention_timed", "kv_block_swap", "pkv_validate_tables_host",
+    "pkv_version", "pkv_status_string", "pkv_last_hip_error_string", "pkv_attn_partition_tokens", "pkv_attn_workspace_bytes",
+    "paged_decode_attention", "paged_decode_attention_timed", "kv_append", "kv_block_swap",
+    "pkv_validate_tables_host",
     "pkv_validate_mapping_host", "pkv_validate_tables", "pkv_validate_mapping",
     "pkv_probe_copy", "pkv_probe_read",
 ]
@@ -57,12 +58,18 @@ def lib() -> ctypes.CDLL:
         if not os.path.exists(LIB_PATH):
             raise FileNotFoundError(
                 f"{LIB_PATH} is not built; run `python -m paper_2602_07878_amd.build`")
+        # The callers' tensors and streams come from PyTorch, which ships its own copy of the
+        # HIP runtime: load it first, so that the library binds to that same runtime instead
+        # of bringing a second one into the process (whose streams would be foreign to it).
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
         L.pkv_version.restype = i32
         L.pkv_version.argtypes = []
         L.pkv_status_string.restype = ctypes.c_char_p
         L.pkv_status_string.argtypes = [i32]
+        L.pkv_last_hip_error_string.restype = ctypes.c_char_p
+        L.pkv_last_hip_error_string.argtypes = []
         L.pkv_attn_partition_tokens.restype = i32
         L.pkv_attn_partition_tokens.argtypes = [ctypes.POINTER(AttnDesc)]
         L.pkv_attn_workspace_bytes.restype = sz
@@ -73,6 +80,8 @@ def lib() -> ctypes.CDLL:
         L.paged_decode_attention_timed.restype = i32
         L.paged_decode_attention_timed.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp,
                                                    ctypes.c_float, vp, vp, sz, vp, vp, vp]
+        L.kv_append.restype = i32
+        L.kv_append.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, vp]
         L.kv_block_swap.restype = i32
         L.kv_block_swap.argtypes = [ctypes.POINTER(SwapDesc), vp, vp, vp, i32, vp]
         L.pkv_validate_tables_host.restype = i32
@@ -97,6 +106,8 @@ def status_string(status: int) -> str:
 
 def _check(status: int, where: str):
     if status != PKV_OK:
+        if status == PKV_ERR_HIP:
+            where += " (" + lib().pkv_last_hip_error_string().decode() + ")"
         raise PkvError(status, where)
 
 
@@ -192,6 +203,15 @@ def swap_desc(num_planes: int, block_bytes: int, src_num_blocks: int, dst_num_bl
     d.dst_plane_stride_bytes = (dst_num_blocks * block_bytes if dst_plane_stride_bytes is None
                                 else dst_plane_stride_bytes)
     return d
+
+
+def kv_append(desc: AttnDesc, k_new, v_new, k_pool, v_pool, block_tables, context_lens, *, stream=None):
+    """Write rows k_new[i], v_new[i] ([B,Hkv,D], device) at token position context_lens[i]-1."""
+    assert k_new.is_contiguous() and v_new.is_contiguous()
+    st = lib().kv_append(ctypes.byref(desc), k_new.data_ptr(), v_new.data_ptr(), k_pool.data_ptr(),
+                         v_pool.data_ptr(), block_tables.data_ptr(), context_lens.data_ptr(),
+                         _stream_ptr(stream))
+    _check(st, "kv_append")
 
 
 def kv_block_swap(desc: SwapDesc, src_pool, dst, block_mapping, *, stream=None):

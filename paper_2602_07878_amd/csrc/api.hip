@@ -12,6 +12,15 @@ namespace {
 
 using namespace pkv;
 
+// Runtime error behind the most recent PKV_ERR_HIP of this thread (diagnostics only).
+thread_local hipError_t g_last_hip_error = hipSuccess;
+
+inline int32_t hip_status(hipError_t e) {
+  if (e == hipSuccess) return PKV_OK;
+  g_last_hip_error = e;
+  return PKV_ERR_HIP;
+}
+
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 inline int elem_bytes(int dtype) { return dtype == PKV_BF16 ? 2 : dtype == PKV_F32 ? 4 : 0; }
@@ -91,6 +100,8 @@ const char* pkv_status_string(int32_t status) {
   }
 }
 
+const char* pkv_last_hip_error_string(void) { return hipGetErrorString(g_last_hip_error); }
+
 int32_t pkv_attn_partition_tokens(const pkv_attn_desc* desc) { return partition_tokens_of(desc); }
 
 size_t pkv_attn_workspace_bytes(const pkv_attn_desc* desc) {
@@ -152,7 +163,7 @@ static int32_t attention_impl(const pkv_attn_desc* desc, const void* q, const vo
     p.ws_o = reinterpret_cast<float*>(base + w.dir_bytes + w.ml_bytes);
     p.chunk_tiles_max = w.chunk_tiles_max;
     const hipError_t e = launch_attn_stream(p, static_cast<hipStream_t>(hip_stream));
-    return e == hipSuccess ? PKV_OK : PKV_ERR_HIP;
+    return hip_status(e);
   }
   if (need > 0) {
     const int64_t rows = (int64_t)desc->batch * desc->num_q_heads * p.max_partitions;
@@ -161,7 +172,7 @@ static int32_t attention_impl(const pkv_attn_desc* desc, const void* q, const vo
     p.ws_o = reinterpret_cast<float*>(reinterpret_cast<uint8_t*>(workspace) + ml);
   }
   const hipError_t e = launch_attn_decode(p, desc->kv_dtype, static_cast<hipStream_t>(hip_stream));
-  return e == hipSuccess ? PKV_OK : PKV_ERR_HIP;
+  return hip_status(e);
 }
 
 int32_t paged_decode_attention(const pkv_attn_desc* desc, const void* q, const void* k_pool,
@@ -179,6 +190,35 @@ int32_t paged_decode_attention_timed(const pkv_attn_desc* desc, const void* q, c
                                      void* ev_kernel_begin, void* ev_kernel_end) {
   return attention_impl(desc, q, k_pool, v_pool, block_tables, context_lens, scale, out, workspace,
                         workspace_bytes, hip_stream, ev_kernel_begin, ev_kernel_end);
+}
+
+int32_t kv_append(const pkv_attn_desc* desc, const void* k_new, const void* v_new, void* k_pool,
+                  void* v_pool, const int32_t* block_tables, const int32_t* context_lens,
+                  void* hip_stream) {
+  const int32_t st = check_attn_desc(desc);
+  if (st != PKV_OK) return st;
+  if (desc->batch == 0) return PKV_OK;
+  if (!k_new || !v_new || !k_pool || !v_pool || !block_tables || !context_lens) return PKV_ERR_NULL;
+  if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k_pool) || !aligned16(v_pool) ||
+      (reinterpret_cast<uintptr_t>(block_tables) & 3u) ||
+      (reinterpret_cast<uintptr_t>(context_lens) & 3u))
+    return PKV_ERR_ALIGN;
+  const int eb = elem_bytes(desc->kv_dtype);
+  AttnParams p;
+  std::memset(&p, 0, sizeof p);
+  p.k_pool = k_pool; p.v_pool = v_pool;
+  p.block_tables = block_tables; p.context_lens = context_lens;
+  p.k_stride_block = desc->k_stride_block * eb;
+  p.k_stride_head = desc->k_stride_head * eb;
+  p.k_stride_token = desc->k_stride_token * eb;
+  p.v_stride_block = desc->v_stride_block * eb;
+  p.v_stride_head = desc->v_stride_head * eb;
+  p.v_stride_token = desc->v_stride_token * eb;
+  p.batch = desc->batch; p.num_kv_heads = desc->num_kv_heads;
+  p.head_dim = desc->head_dim; p.block_size = desc->block_size;
+  p.max_blocks_per_seq = desc->max_blocks_per_seq;
+  const hipError_t e = launch_kv_append(p, k_new, v_new, eb, static_cast<hipStream_t>(hip_stream));
+  return hip_status(e);
 }
 
 int32_t kv_block_swap(const pkv_swap_desc* desc, const void* src_pool, void* dst,
@@ -200,7 +240,7 @@ int32_t kv_block_swap(const pkv_swap_desc* desc, const void* src_pool, void* dst
   p.num_planes = desc->num_planes;
   p.n_pairs = n_pairs;
   const hipError_t e = launch_swap(p, static_cast<hipStream_t>(hip_stream));
-  return e == hipSuccess ? PKV_OK : PKV_ERR_HIP;
+  return hip_status(e);
 }
 
 int32_t pkv_validate_tables_host(const pkv_attn_desc* desc, const int32_t* block_tables_host,
@@ -277,16 +317,14 @@ int32_t pkv_probe_copy(const void* src, void* dst, size_t bytes, void* hip_strea
   if (!src || !dst) return PKV_ERR_NULL;
   if (!aligned16(src) || !aligned16(dst) || bytes % 16 != 0) return PKV_ERR_ALIGN;
   if (bytes == 0) return PKV_OK;
-  return launch_probe_copy(src, dst, bytes, static_cast<hipStream_t>(hip_stream)) == hipSuccess
-             ? PKV_OK : PKV_ERR_HIP;
+  return hip_status(launch_probe_copy(src, dst, bytes, static_cast<hipStream_t>(hip_stream)));
 }
 
 int32_t pkv_probe_read(const void* src, void* sink, size_t bytes, void* hip_stream) {
   if (!src || !sink) return PKV_ERR_NULL;
   if (!aligned16(src) || !aligned16(sink) || bytes % 16 != 0) return PKV_ERR_ALIGN;
   if (bytes == 0) return PKV_OK;
-  return launch_probe_read(src, sink, bytes, static_cast<hipStream_t>(hip_stream)) == hipSuccess
-             ? PKV_OK : PKV_ERR_HIP;
+  return hip_status(launch_probe_read(src, sink, bytes, static_cast<hipStream_t>(hip_stream)));
 }
 
 }  // extern "C"

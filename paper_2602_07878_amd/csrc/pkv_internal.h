@@ -63,6 +63,9 @@ StreamWorkspace stream_workspace(const pkv_attn_desc& d);
 hipError_t launch_attn_stream(AttnParams& p, hipStream_t s);
 // swap.hip
 hipError_t launch_swap(const SwapParams& p, hipStream_t s);
+// append.hip (uses the pointers, strides and shapes of AttnParams; q/out unused)
+hipError_t launch_kv_append(const AttnParams& p, const void* k_new, const void* v_new, int elem_bytes,
+                            hipStream_t s);
 hipError_t launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t s);
 hipError_t launch_probe_read(const void* src, void* sink, size_t bytes, hipStream_t s);
 

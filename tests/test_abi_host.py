@@ -18,7 +18,7 @@ ST = dict(OK=0, NULL=1, SHAPE=2, DTYPE=3, ALIGN=4, WORKSPACE=5, INDEX=6, HIP=7)
 def header_functions():
     src = open(os.path.join(ROOT, "include", "pkv.h")).read()
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
-    return sorted(set(re.findall(r"\b(pkv_[a-z_]+|paged_decode_attention[a-z_]*|kv_block_swap)\s*\(", src)))
+    return sorted(set(re.findall(r"\b(pkv_[a-z_]+|paged_decode_attention[a-z_]*|kv_block_swap|kv_append)\s*\(", src)))
 
 
 def test_library_exports_every_declared_symbol():
@@ -122,6 +122,19 @@ def test_swap_rejects_bad_arguments_on_host():
     assert f(swap_desc(), t=0x2004) == ST["ALIGN"]
     assert f(swap_desc(), n=-1) == ST["SHAPE"]
     assert f(swap_desc(), s=0, t=0, m=0, n=0) == ST["OK"]
+
+
+def test_append_rejects_bad_arguments_on_host():
+    L = binding.lib()
+    f = lambda d, kn=0x1000, vn=0x2000, kp=0x3000, vp=0x4000, bt=0x5000, cl=0x6000: L.kv_append(
+        ctypes.byref(d), kn, vn, kp, vp, bt, cl, None)
+    assert L.kv_append(None, 1, 1, 1, 1, 1, 1, None) == ST["NULL"]
+    assert f(good_desc(head_dim=96)) == ST["SHAPE"]
+    assert f(good_desc(kv_dtype=7)) == ST["DTYPE"]
+    assert f(good_desc(), kn=0) == ST["NULL"]
+    assert f(good_desc(), vp=0x4008) == ST["ALIGN"]
+    assert f(good_desc(), cl=0x6002) == ST["ALIGN"]
+    assert f(good_desc(batch=0), kn=0, vn=0, kp=0, vp=0, bt=0, cl=0) == ST["OK"]
 
 
 def test_host_validators():

@@ -447,6 +447,12 @@ def test_append_respects_strided_token_major_layout_and_reports_bad_table():
     oracle.kv_append(w.k_pool, w.v_pool, kn, vn, w.block_tables, w.context_lens, block_size=4)
     assert np.array_equal(kt.transpose(0, 2, 1, 3), w.k_pool)
     assert np.array_equal(vt.transpose(0, 2, 1, 3), w.v_pool)
+    # K head-major and V token-major in one call (their strides are independent)
+    w2 = small(23, dtype="bf16", Hq=4, Hkv=2, D=8, bs=4, lens=(6, 9), pool_factor=1.5)
+    vt2 = np.ascontiguousarray(w2.v_pool.transpose(0, 2, 1, 3))
+    oracle.kv_append(w2.k_pool, vt2, kn, vn, w2.block_tables, w2.context_lens, block_size=4,
+                     k_strides=(2 * 4 * 8, 4 * 8, 8), v_strides=st)
+    assert np.array_equal(w2.k_pool, w.k_pool) and np.array_equal(vt2.transpose(0, 2, 1, 3), w.v_pool)
     w.block_tables[1, 2] = -1
     with pytest.raises(IndexError):
         oracle.kv_append(w.k_pool, w.v_pool, kn, vn, w.block_tables, w.context_lens, block_size=4)
