@@ -1,0 +1,148 @@
+"""Reference model of the scheduler / block manager -- TEST INFRASTRUCTURE ONLY.
+
+A plain, slow transcription of the engine iteration that arXiv 2602.07878 describes in
+Sec. 5.1 ("Revisiting vLLM Scheduler"): FIFO free-block queue and persistent blocks
+(Sec. 5.1.1), strict first-come-first-served admission that stops at the first request
+that does not fit (Sec. 5.1.1, head-of-line blocking), last-in-first-out preemption with
+the victim put at the front of the waiting queue and recovery by swapping or by
+recomputation (Sec. 5.1.2).  Python lists only; no code shared with the C++ model.
+"""
+from __future__ import annotations
+
+SWAP, RECOMPUTE = 0, 1
+
+
+class Request:
+    def __init__(self, rid, prompt, max_new):
+        self.rid, self.prompt, self.max_new = rid, prompt, max_new
+        self.generated = 0       # output tokens produced so far
+        self.computed = 0        # tokens whose K/V sit in GPU blocks
+        self.blocks = []         # physical GPU blocks, in logical order
+        self.cpu_blocks = []     # host blocks while swapped out
+        self.swapped = False
+
+
+class RefScheduler:
+    def __init__(self, num_gpu_blocks, num_cpu_blocks, block_size, max_num_seqs,
+                 max_num_batched_tokens, max_blocks_per_seq, watermark_blocks=0, mode=SWAP):
+        self.bs = block_size
+        self.max_seqs, self.budget = max_num_seqs, max_num_batched_tokens
+        self.max_blocks, self.watermark, self.mode = max_blocks_per_seq, watermark_blocks, mode
+        self.num_gpu_blocks = num_gpu_blocks
+        self.free_gpu = list(range(num_gpu_blocks))     # FIFO: take from the front, return to the back
+        self.free_cpu = list(range(num_cpu_blocks))
+        self.waiting, self.running, self.known = [], [], set()
+        self.totals = dict(steps=0, preemptions=0, swap_out=0, swap_in=0, recomputed=0,
+                           finished=0, blocked=0, decoded=0)
+
+    def add_request(self, rid, prompt, max_new):
+        full = -(-(prompt + max_new - 1) // self.bs)      # blocks at full length
+        if prompt < 1 or max_new < 1 or prompt > self.budget or full > self.max_blocks \
+                or full > self.num_gpu_blocks:
+            raise ValueError("request can never run")
+        if rid in self.known:
+            raise KeyError(rid)
+        self.known.add(rid)
+        self.waiting.append(Request(rid, prompt, max_new))
+
+    def _preempt(self, r, out):
+        self.totals["preemptions"] += 1
+        out["preempted"].append(r.rid)
+        if self.mode == SWAP and len(self.free_cpu) >= len(r.blocks):
+            for b in r.blocks:
+                c = self.free_cpu.pop(0)
+                out["swap_out"].append((b, c))
+                r.cpu_blocks.append(c)
+                self.free_gpu.append(b)
+            self.totals["swap_out"] += len(r.blocks)
+            r.swapped = True
+        else:                                            # recomputation: the cache is dropped
+            self.free_gpu.extend(r.blocks)
+            r.computed = 0
+        r.blocks = []
+        self.waiting.insert(0, r)                        # front of the queue
+
+    def _finish(self, r, out):
+        self.free_gpu.extend(r.blocks)
+        r.blocks = []
+        out["finished"].append(r.rid)
+        self.totals["finished"] += 1
+
+    def step(self):
+        out = dict(decode=[], prefill=[], preempted=[], swap_out=[], swap_in=[], finished=[],
+                   head_blocked=False)
+        self.totals["steps"] += 1
+        # 1. a slot for the next token of every running request, in scheduling order
+        i = 0
+        while i < len(self.running):
+            r = self.running[i]
+            need = 1 if r.computed % self.bs == 0 else 0
+            evicted_self = False
+            while len(self.free_gpu) < need:
+                victim = self.running.pop()              # most recently scheduled
+                self._preempt(victim, out)
+                if victim is r:
+                    evicted_self = True
+                    break
+            if evicted_self:
+                break
+            if need:
+                r.blocks.append(self.free_gpu.pop(0))
+            i += 1
+        # 2. first-come-first-served admission, unless this iteration had to preempt
+        admitted = []
+        if not out["preempted"]:
+            budget = self.budget
+            while self.waiting and len(self.running) + len(admitted) < self.max_seqs:
+                r = self.waiting[0]
+                if r.swapped:
+                    nb = len(r.cpu_blocks)
+                    if len(self.free_gpu) < nb + self.watermark:
+                        out["head_blocked"] = True
+                        break
+                    for c in r.cpu_blocks:
+                        g = self.free_gpu.pop(0)
+                        out["swap_in"].append((c, g))
+                        r.blocks.append(g)
+                        self.free_cpu.append(c)
+                    self.totals["swap_in"] += nb
+                    r.cpu_blocks, r.swapped = [], False
+                    self.waiting.pop(0)
+                    admitted.append(r)
+                    continue
+                tokens = r.prompt if r.generated == 0 else r.prompt + r.generated - 1
+                nb = -(-tokens // self.bs)
+                if tokens > budget or len(self.free_gpu) < nb + self.watermark:
+                    out["head_blocked"] = True
+                    break
+                r.blocks = [self.free_gpu.pop(0) for _ in range(nb)]
+                r.computed = tokens
+                budget -= tokens
+                if r.generated == 0:
+                    r.generated = 1                      # the prefill yields the first token
+                else:
+                    self.totals["recomputed"] += tokens
+                out["prefill"].append((r.rid, tokens))
+                self.waiting.pop(0)
+                if r.generated >= r.max_new:
+                    self._finish(r, out)
+                else:
+                    admitted.append(r)
+        if out["head_blocked"]:
+            self.totals["blocked"] += 1
+        # 3. one decode token for everything that was running before the admissions
+        still = []
+        for r in self.running:
+            r.computed += 1
+            out["decode"].append((r.rid, r.computed, list(r.blocks)))
+            r.generated += 1
+            self.totals["decoded"] += 1
+            if r.generated >= r.max_new:
+                self._finish(r, out)
+            else:
+                still.append(r)
+        self.running = still + admitted
+        out["free_blocks"] = len(self.free_gpu)
+        out["running"], out["waiting"] = len(self.running), len(self.waiting)
+        out["swapped"] = sum(1 for r in self.waiting if r.swapped)
+        return out

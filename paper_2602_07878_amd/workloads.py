@@ -313,3 +313,24 @@ def random_bytes(nbytes: int, seed: int) -> np.ndarray:
         with ThreadPoolExecutor(_FILL_THREADS) as ex:
             list(ex.map(work, range(nchunks)))
     return out.view(np.uint8)
+
+
+# --------------------------------------------------------------------------- request streams
+def poisson_request_stream(seed: int, steps: int, rate: float, *, prompt_median: int = 256,
+                           prompt_sigma: float = 0.8, out_median: int = 128, out_sigma: float = 0.7,
+                           max_prompt: int = 2048, max_new: int = 1024):
+    """Benign open-loop load for the scheduler model: per engine iteration a Poisson(rate)
+    number of requests arrives, with lognormal prompt and output lengths (clamped).  Returns a
+    list, one entry per iteration, of lists of (request id, prompt_len, max_new_tokens).
+    Stands in for the chat traces the paper replays (Sec. 6.1); no dataset record is used."""
+    rng = np.random.default_rng(seed)
+    out, rid = [], 0
+    for _ in range(steps):
+        arrivals = []
+        for _ in range(int(rng.poisson(rate))):
+            p = int(np.clip(round(float(rng.lognormal(math.log(prompt_median), prompt_sigma))), 1, max_prompt))
+            n = int(np.clip(round(float(rng.lognormal(math.log(out_median), out_sigma))), 1, max_new))
+            arrivals.append((rid, p, n))
+            rid += 1
+        out.append(arrivals)
+    return out

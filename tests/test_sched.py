@@ -1,0 +1,217 @@
+"""Scheduler / block-manager model: the Python reference (oracle/sched_ref.py) pinned to what
+the paper fixes (Sec. 5.1.1: FIFO free queue, persistent blocks, strict FCFS admission with
+head-of-line blocking; Sec. 5.1.2: LIFO victim, victim to the front of the queue, swap or
+recompute recovery) by hand-worked traces and invariants, then the C++ library held to the
+reference, iteration by iteration and bit for bit.  CPU only."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle.sched_ref import RefScheduler, SWAP, RECOMPUTE
+from paper_2602_07878_amd import binding, sched, workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def ref(**kw):
+    d = dict(num_gpu_blocks=4, num_cpu_blocks=4, block_size=2, max_num_seqs=8,
+             max_num_batched_tokens=64, max_blocks_per_seq=8, watermark_blocks=0, mode=RECOMPUTE)
+    d.update(kw)
+    return RefScheduler(**d)
+
+
+# ---- pins of the reference ------------------------------------------------------------------
+def test_head_of_line_blocking_small_request_waits_behind_a_big_one():
+    s = ref(block_size=4)
+    s.add_request(1, 8, 100 - 91)      # 2 blocks
+    s.add_request(2, 12, 4)            # 3 blocks: does not fit beside request 1
+    s.add_request(3, 4, 4)             # 1 block: would fit, but is behind request 2
+    o = s.step()
+    assert o["prefill"] == [(1, 8)] and o["head_blocked"] and o["waiting"] == 2
+    assert o["free_blocks"] == 2       # capacity for request 3 is there, and stays unused
+    o = s.step()
+    assert [d[0] for d in o["decode"]] == [1] and o["prefill"] == [] and o["head_blocked"]
+
+
+def test_hand_worked_trace_lifo_victim_goes_to_the_front_and_is_recomputed():
+    s = ref()                          # 4 blocks of 2 tokens, recompute mode
+    for rid in (1, 2, 3):
+        s.add_request(rid, 2, 6)       # 7 tokens at full length: the whole pool
+    o = s.step()                       # all three prefilled: blocks 0, 1, 2; block 3 free
+    assert o["prefill"] == [(1, 2), (2, 2), (3, 2)] and o["decode"] == [] and o["free_blocks"] == 1
+    s.add_request(4, 2, 6)             # arrives before the victim is preempted
+    o = s.step()
+    # every request needs a second block: 1 takes block 3; for 2 the pool is empty, so the most
+    # recently scheduled request (3) is evicted and its block 2 serves request 2
+    assert o["preempted"] == [3]
+    assert o["decode"] == [(1, 3, [0, 3]), (2, 3, [1, 2])]
+    assert o["prefill"] == [] and o["free_blocks"] == 0          # no admission while preempting
+    assert [r.rid for r in s.waiting] == [3, 4]                   # victim ahead of the newcomer
+    o = s.step()                       # nobody needs a block; request 3 cannot come back yet
+    assert o["decode"] == [(1, 4, [0, 3]), (2, 4, [1, 2])] and o["head_blocked"] and not o["preempted"]
+    o = s.step()                       # request 1 needs a third block: victim is request 2
+    assert o["preempted"] == [2] and o["decode"] == [(1, 5, [0, 3, 1])] and o["free_blocks"] == 1
+    assert [r.rid for r in s.waiting] == [2, 3, 4]
+    o = s.step()                       # request 2 (3 generated tokens) needs prompt + 2 = 4 tokens = 2 blocks
+    assert o["head_blocked"] and o["decode"] == [(1, 6, [0, 3, 1])]
+    assert s.totals["recomputed"] == 0
+
+
+def test_recompute_prefills_prompt_plus_generated_minus_one_and_resumes_decoding():
+    s = ref(num_gpu_blocks=3)
+    s.add_request(1, 2, 3)
+    s.add_request(2, 2, 4)
+    s.step()                           # both prefilled (blocks 0, 1), block 2 free, generated = 1 each
+    o = s.step()                       # 1 takes block 2; 2 finds none and is evicted itself
+    assert o["preempted"] == [2] and o["decode"] == [(1, 3, [0, 2])]
+    o = s.step()                       # request 2 returns into its old block: it had produced 1 token,
+    assert o["prefill"] == [(2, 2)]    # so prompt + 1 - 1 tokens are prefilled again;
+    assert o["finished"] == [1] and o["decode"] == [(1, 4, [0, 2])]   # request 1 ends with its third token
+    o = s.step()
+    assert o["decode"] == [(2, 3, [1, 0])]   # request 2 goes on where it stopped: context 3
+    assert s.totals["recomputed"] == 2 and s.totals["preemptions"] == 1
+
+
+def test_swap_moves_blocks_out_and_back_to_other_physical_blocks():
+    s = ref(mode=SWAP)
+    for rid in (1, 2, 3):
+        s.add_request(rid, 2, 6)
+    s.step()
+    o = s.step()
+    assert o["preempted"] == [3] and o["swap_out"] == [(2, 0)]    # pool block 2 -> host block 0
+    assert s.waiting[0].rid == 3 and s.waiting[0].swapped and s.waiting[0].computed == 2
+    for _ in range(2):
+        o = s.step()
+    assert o["preempted"] == [2] and o["swap_out"] == [(1, 1), (2, 2)]
+    # request 1 runs to its end (6 tokens), then the victims return in queue order: 2, then 3
+    seen_in = []
+    for _ in range(12):
+        o = s.step()
+        seen_in += o["swap_in"]
+    host_blocks = [c for c, _ in seen_in]
+    assert seen_in[:3] == [(1, 0), (2, 3), (0, 1)]                # request 2's blocks first, into
+    assert host_blocks[:3] == [1, 2, 0]                           # the blocks request 1 gave back
+    assert s.totals["swap_in"] == s.totals["swap_out"] and s.totals["recomputed"] == 0
+
+
+def test_swap_without_host_space_falls_back_to_recomputation():
+    s = ref(mode=SWAP, num_cpu_blocks=0)
+    for rid in (1, 2, 3):
+        s.add_request(rid, 2, 6)
+    s.step()
+    o = s.step()
+    assert o["preempted"] == [3] and o["swap_out"] == [] and s.waiting[0].computed == 0
+
+
+def test_requests_that_can_never_run_are_refused():
+    s = ref()
+    with pytest.raises(ValueError):
+        s.add_request(1, 9, 1)         # 5 blocks at full length > pool of 4
+    with pytest.raises(ValueError):
+        s.add_request(1, 65, 1)        # prompt above the token budget
+    s.add_request(1, 2, 2)
+    with pytest.raises(KeyError):
+        s.add_request(1, 2, 2)
+
+
+def drive(s, stream, extra_steps, on_step):
+    for arrivals in stream:
+        for rid, p, n in arrivals:
+            s.add_request(rid, p, n)
+        on_step(s.step())
+    for _ in range(extra_steps):
+        on_step(s.step())
+
+
+@pytest.mark.parametrize("mode", [SWAP, RECOMPUTE])
+def test_invariants_under_overload(mode):
+    total = 64
+    s = ref(num_gpu_blocks=total, num_cpu_blocks=48, block_size=16, max_num_seqs=16,
+            max_num_batched_tokens=2048, max_blocks_per_seq=32, mode=mode)
+    stream = W.poisson_request_stream(5, 400, 0.25, prompt_median=96, out_median=96, max_prompt=256, max_new=200)
+    submitted = sum(len(a) for a in stream)
+    order_admitted, first_seen = [], set()
+
+    def check(o):
+        owned = [b for r in s.running for b in r.blocks]
+        assert len(owned) == len(set(owned))                          # no block has two owners
+        assert sorted(owned + s.free_gpu) == list(range(total))       # none lost, none invented
+        host = [c for r in s.waiting for c in r.cpu_blocks]
+        assert sorted(host + s.free_cpu) == list(range(48))
+        for r in s.running:
+            assert len(r.blocks) == -(-r.computed // 16) and r.computed == r.prompt + r.generated - 1
+        for rid, ctx, blocks in o["decode"]:
+            assert len(blocks) == -(-ctx // 16)
+        assert not (o["preempted"] and (o["prefill"] or o["swap_in"]))
+        for rid, _ in o["prefill"]:
+            if rid not in first_seen:
+                first_seen.add(rid)
+                order_admitted.append(rid)
+
+    drive(s, stream, 3000, check)
+    assert order_admitted == sorted(order_admitted)                   # first admissions in arrival order
+    assert s.totals["finished"] == submitted and not s.running and not s.waiting
+    assert s.totals["preemptions"] > 0 and s.totals["blocked"] > 0    # the load did saturate the pool
+    assert s.totals["decoded"] == sum(n - 1 for a in stream for _, _, n in a)   # every token exactly once
+    if mode == SWAP:
+        assert s.totals["swap_in"] == s.totals["swap_out"] > 0
+
+
+# ---- the C++ library against the reference -------------------------------------------------
+def test_header_and_library_agree_on_the_exported_names():
+    src = open(os.path.join(ROOT, "include", "pkv_sched.h")).read()
+    names = sorted(set(re.findall(r"\b(pkv_sched_[a-z_]+)\s*\(", src)))
+    assert names == sorted(sched.SCHED_EXPORTS)
+    L = binding.lib()
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_create_rejects_bad_configurations_and_getters_check_capacity():
+    L = sched._lib()
+    assert not L.pkv_sched_create(None)
+    bad = sched.SchedConfig(0, 0, 16, 4, 64, 8, 0, 0)
+    assert not L.pkv_sched_create(ctypes.byref(bad))
+    bad = sched.SchedConfig(8, 0, 16, 4, 64, 8, 0, 2)
+    assert not L.pkv_sched_create(ctypes.byref(bad))
+    s = sched.Scheduler(num_gpu_blocks=4, num_cpu_blocks=4, block_size=2, max_num_seqs=8,
+                        max_num_batched_tokens=64, max_blocks_per_seq=8, mode=sched.RECOMPUTE)
+    with pytest.raises(binding.PkvError):
+        s.add_request(1, 9, 1)
+    s.add_request(1, 2, 5)
+    with pytest.raises(binding.PkvError):
+        s.add_request(1, 2, 5)
+    s.step(); s.step()
+    assert L.pkv_sched_decode_batch(s._h, None, None, None, 0) == -2
+    assert L.pkv_sched_decode_batch(s._h, None, None, None, 1) == 1
+    assert L.pkv_sched_step(None, None) == 1
+
+
+@pytest.mark.parametrize("mode,seed,cpu_blocks", [(SWAP, 11, 64), (RECOMPUTE, 12, 0), (SWAP, 13, 6)])
+def test_library_reproduces_the_reference_trace_exactly(mode, seed, cpu_blocks):
+    kw = dict(num_gpu_blocks=96, num_cpu_blocks=cpu_blocks, block_size=16, max_num_seqs=24,
+              max_num_batched_tokens=1024, max_blocks_per_seq=40, watermark_blocks=1)
+    r = RefScheduler(mode=mode, **kw)
+    s = sched.Scheduler(mode=mode, **kw)
+    stream = W.poisson_request_stream(seed, 300, 0.3, prompt_median=120, out_median=100, max_prompt=400, max_new=200)
+    stream += [[] for _ in range(2500)]
+    for arrivals in stream:
+        for rid, p, n in arrivals:
+            r.add_request(rid, p, n)
+            s.add_request(rid, p, n)
+        o, info = r.step(), s.step()
+        ids, lens, tabs = s.decode_batch()
+        assert [d[0] for d in o["decode"]] == ids.tolist() and [d[1] for d in o["decode"]] == lens.tolist()
+        for row, (_, _, blocks) in zip(tabs, o["decode"]):
+            assert row[:len(blocks)].tolist() == blocks and np.all(row[len(blocks):] == -1)
+        assert [tuple(p) for p in s.swap_out().tolist()] == o["swap_out"]
+        assert [tuple(p) for p in s.swap_in().tolist()] == o["swap_in"]
+        pid, ptok = s.prefills()
+        assert list(zip(pid.tolist(), ptok.tolist())) == o["prefill"]
+        assert s.finished().tolist() == o["finished"]
+        assert (info.free_blocks, info.running, info.waiting, info.swapped, info.head_blocked, info.num_preempted) == \
+               (o["free_blocks"], o["running"], o["waiting"], o["swapped"], int(o["head_blocked"]), len(o["preempted"]))
+    assert s.totals() == r.totals and r.totals["preemptions"] > 0 and r.totals["finished"] > 0
