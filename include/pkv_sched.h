@@ -126,6 +126,15 @@ int32_t pkv_sched_prefills(const pkv_sched* s, int64_t* request_ids, int32_t* to
 /* Requests that finished in the last iteration.  Returns the count. */
 int32_t pkv_sched_finished(const pkv_sched* s, int64_t* request_ids, int32_t capacity);
 
+/*
+ * Pool blocks a live request holds right now, in logical order (what a prefill
+ * writes its K/V into before the request's first decode).  Returns their
+ * number (0 for a request that is waiting or swapped out), -PKV_ERR_INDEX for
+ * an unknown or finished request, -PKV_ERR_SHAPE if capacity is too small.
+ */
+int32_t pkv_sched_request_blocks(const pkv_sched* s, int64_t request_id, int32_t* blocks,
+                                 int32_t capacity);
+
 /* Totals since creation: [0] iterations, [1] preemptions, [2] swapped-out blocks,
  * [3] swapped-in blocks, [4] recomputed tokens, [5] finished requests,
  * [6] iterations in which the head of the waiting queue was blocked,

@@ -265,6 +265,14 @@ int32_t pkv_sched_finished(const pkv_sched* s, int64_t* request_ids, int32_t cap
   return s ? copy_out(s->finished_ids, request_ids, capacity) : -PKV_ERR_NULL;
 }
 
+int32_t pkv_sched_request_blocks(const pkv_sched* s, int64_t request_id, int32_t* blocks,
+                                 int32_t capacity) {
+  if (!s) return -PKV_ERR_NULL;
+  const auto it = s->requests.find(request_id);
+  if (it == s->requests.end()) return -PKV_ERR_INDEX;
+  return copy_out(it->second->blocks, blocks, capacity);
+}
+
 int32_t pkv_sched_totals(const pkv_sched* s, int64_t totals[8]) {
   if (!s || !totals) return PKV_ERR_NULL;
   for (int i = 0; i < 8; ++i) totals[i] = s->totals[i];

@@ -13,7 +13,7 @@ SWAP, RECOMPUTE = 0, 1
 SCHED_EXPORTS = [
     "pkv_sched_create", "pkv_sched_destroy", "pkv_sched_add_request", "pkv_sched_step",
     "pkv_sched_decode_batch", "pkv_sched_swap_out", "pkv_sched_swap_in", "pkv_sched_prefills",
-    "pkv_sched_finished", "pkv_sched_totals",
+    "pkv_sched_finished", "pkv_sched_request_blocks", "pkv_sched_totals",
 ]
 
 TOTALS = ("steps", "preemptions", "swap_out", "swap_in", "recomputed", "finished", "blocked", "decoded")
@@ -55,6 +55,8 @@ def _lib():
             getattr(L, name).argtypes = [vp, vp, i32]
         L.pkv_sched_prefills.restype = i32
         L.pkv_sched_prefills.argtypes = [vp, vp, vp, i32]
+        L.pkv_sched_request_blocks.restype = i32
+        L.pkv_sched_request_blocks.argtypes = [vp, i64, vp, i32]
         L.pkv_sched_totals.restype = i32
         L.pkv_sched_totals.argtypes = [vp, vp]
         _ready = True
@@ -131,6 +133,14 @@ class Scheduler:
         got = _lib().pkv_sched_finished(self._h, ids.ctypes.data, n)
         assert got == n, got
         return ids
+
+    def request_blocks(self, rid: int):
+        """Pool blocks of a live request in logical order (int32 array)."""
+        b = np.empty(self.cfg.max_blocks_per_seq, np.int32)
+        n = _lib().pkv_sched_request_blocks(self._h, rid, b.ctypes.data, b.size)
+        if n < 0:
+            raise binding.PkvError(-n, "pkv_sched_request_blocks")
+        return b[:n].copy()
 
     def totals(self) -> dict:
         t = np.zeros(8, np.int64)

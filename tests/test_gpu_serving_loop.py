@@ -1,0 +1,109 @@
+"""The scheduler model driving the GPU calls over time (Sec. 5.1 dynamics -> the data movement
+of Sec. 2.2, 4.2 and 5.1.2): every engine iteration moves preempted requests' blocks out to a
+swap area and returning ones back with kv_block_swap, appends the new tokens' K/V with
+kv_append and runs paged_decode_attention on the scheduler's block tables.  The same sequence
+is replayed on numpy pools with the oracle: pools must agree bit for bit after every swap, and
+attention within tolerance."""
+import numpy as np
+import pytest
+
+from paper_2602_07878_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+HKV, HQ, D, BS = 2, 8, 128, 16
+
+
+def rows_of(rid, n):
+    """All K and V rows request `rid` will ever cache (stand-in for what a model computes)."""
+    rng = np.random.default_rng([7, rid])
+    k = W.f32_to_bf16_bits(rng.standard_normal((n, HKV, D)).astype(np.float32))
+    v = W.f32_to_bf16_bits(rng.standard_normal((n, HKV, D)).astype(np.float32))
+    return k, v
+
+
+@pytest.mark.parametrize("mode", ["swap", "recompute"])
+def test_scheduler_driven_decode_with_preemption(mode):
+    import oracle
+    import torch
+    from paper_2602_07878_amd import binding, sched
+    n_gpu, n_cpu = 80, 64
+    s = sched.Scheduler(num_gpu_blocks=n_gpu, num_cpu_blocks=n_cpu, block_size=BS, max_num_seqs=16,
+                        max_num_batched_tokens=1024, max_blocks_per_seq=24,
+                        mode=sched.SWAP if mode == "swap" else sched.RECOMPUTE)
+    stream = W.poisson_request_stream(31, 120, 0.35, prompt_median=100, out_median=90, max_prompt=250, max_new=130)
+    stream += [[] for _ in range(500)]
+    rows = {}
+    up = lambda a: torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+    bits = lambda t: t.view(torch.int16).cpu().numpy().view(np.uint16)
+    # pools [blocks][Hkv][bs][D] as bf16 bits (NaN wherever nothing was written yet); the swap
+    # area has the same block shape (a device buffer stands in for host memory)
+    hk = np.full((n_gpu, HKV, BS, D), 0x7FC0, np.uint16)
+    hv = hk.copy()
+    sk, sv = np.zeros((n_cpu, HKV, BS, D), np.uint16), np.zeros((n_cpu, HKV, BS, D), np.uint16)
+    dk, dv, dsk, dsv = up(hk), up(hv), up(sk), up(sv)
+    block_bytes = HKV * BS * D * 2
+    out_desc = binding.swap_desc(1, block_bytes, n_gpu, n_cpu)
+    in_desc = binding.swap_desc(1, block_bytes, n_cpu, n_gpu)
+    scale = float(D) ** -0.5
+    checked = swaps = 0
+    rng = np.random.default_rng(99)
+    for it, arrivals in enumerate(stream):
+        for rid, p, n in arrivals:
+            s.add_request(rid, p, n)
+            rows[rid] = rows_of(rid, p + n)
+        info = s.step()
+        # 1. swaps: victims leave before anything is written into the blocks they gave up
+        for count, getter, desc, src, dst, hsrc, hdst in (
+                (info.num_swap_out_blocks, s.swap_out, out_desc, (dk, dv), (dsk, dsv), (hk, hv), (sk, sv)),
+                (info.num_swap_in_blocks, s.swap_in, in_desc, (dsk, dsv), (dk, dv), (sk, sv), (hk, hv))):
+            if count:
+                m = getter()
+                dm = torch.from_numpy(m).cuda()
+                for a, b, ha, hb in zip(src, dst, hsrc, hdst):
+                    binding.kv_block_swap(desc, a, b, dm)
+                    oracle.kv_block_swap(ha, hb, m, num_planes=1, block_bytes=block_bytes)
+                swaps += 1
+        # 2. prefills (new and recomputed requests): the model's rows land in the request's blocks
+        pid, ptok = s.prefills()
+        for rid, tokens in zip(pid.tolist(), ptok.tolist()):
+            try:
+                blocks = s.request_blocks(rid)
+            except binding.PkvError:
+                continue                                    # finished within its prefill
+            tok = np.arange(tokens)
+            b, slot = blocks[tok // BS], tok % BS
+            k_all, v_all = rows[rid]
+            hk[b, :, slot, :], hv[b, :, slot, :] = k_all[:tokens], v_all[:tokens]
+            tb, ts = torch.from_numpy(b.astype(np.int64)).cuda(), torch.from_numpy(slot).cuda()
+            dk[tb, :, ts, :], dv[tb, :, ts, :] = up(k_all[:tokens]), up(v_all[:tokens])
+        # 3. decode: append the new tokens' rows, then attention over the grown contexts
+        if info.num_decode:
+            ids, lens, tabs = s.decode_batch()
+            kn = np.stack([rows[r][0][c - 1] for r, c in zip(ids.tolist(), lens.tolist())])
+            vn = np.stack([rows[r][1][c - 1] for r, c in zip(ids.tolist(), lens.tolist())])
+            bt, cl = torch.from_numpy(tabs).cuda(), torch.from_numpy(lens).cuda()
+            q = W.f32_to_bf16_bits(rng.standard_normal((info.num_decode, HQ, D)).astype(np.float32))
+            dq = up(q)
+            desc = binding.attn_desc_for(dq, dk, dv, bt, max_context_len=int(lens.max()))
+            binding.kv_append(desc, up(kn), up(vn), dk, dv, bt, cl)
+            oracle.kv_append(hk, hv, kn, vn, tabs, lens, block_size=BS)
+            if it % 9 == 0 or info.num_swap_in_blocks or info.num_preempted:
+                out = torch.empty(info.num_decode, HQ, D, dtype=torch.float32, device="cuda")
+                binding.paged_decode_attention(dq, dk, dv, bt, cl, scale, out, max_context_len=int(lens.max()))
+                ref = oracle.paged_decode_attention(q, hk, hv, tabs, lens, scale, block_size=BS)
+                torch.cuda.synchronize()
+                got = out.cpu().numpy().astype(np.float64)
+                assert np.all(np.isfinite(got)) and np.abs(got - ref).max() <= 2e-3, (it, mode)
+                checked += 1
+        if info.num_swap_out_blocks or info.num_swap_in_blocks or it % 50 == 0:
+            torch.cuda.synchronize()
+            assert np.array_equal(bits(dk), hk) and np.array_equal(bits(dv), hv), it
+            assert np.array_equal(bits(dsk), sk) and np.array_equal(bits(dsv), sv), it
+    t = s.totals()
+    print(mode, t, "attention checks", checked, flush=True)
+    assert t["finished"] == sum(len(a) for a in stream) and t["preemptions"] > 0 and checked > 20
+    if mode == "swap":
+        assert swaps > 0 and t["swap_in"] == t["swap_out"] > 0
+    else:
+        assert t["recomputed"] > 0

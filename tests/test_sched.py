@@ -188,6 +188,8 @@ def test_create_rejects_bad_configurations_and_getters_check_capacity():
     assert L.pkv_sched_decode_batch(s._h, None, None, None, 0) == -2
     assert L.pkv_sched_decode_batch(s._h, None, None, None, 1) == 1
     assert L.pkv_sched_step(None, None) == 1
+    with pytest.raises(binding.PkvError):
+        s.request_blocks(12345)
 
 
 @pytest.mark.parametrize("mode,seed,cpu_blocks", [(SWAP, 11, 64), (RECOMPUTE, 12, 0), (SWAP, 13, 6)])
@@ -211,6 +213,10 @@ def test_library_reproduces_the_reference_trace_exactly(mode, seed, cpu_blocks):
         assert [tuple(p) for p in s.swap_in().tolist()] == o["swap_in"]
         pid, ptok = s.prefills()
         assert list(zip(pid.tolist(), ptok.tolist())) == o["prefill"]
+        for q in r.running:
+            assert s.request_blocks(q.rid).tolist() == q.blocks
+        for q in r.waiting[:3]:
+            assert s.request_blocks(q.rid).size == 0
         assert s.finished().tolist() == o["finished"]
         assert (info.free_blocks, info.running, info.waiting, info.swapped, info.head_blocked, info.num_preempted) == \
                (o["free_blocks"], o["running"], o["waiting"], o["swapped"], int(o["head_blocked"]), len(o["preempted"]))
