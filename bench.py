@@ -186,6 +186,37 @@ def time_swap(sw, reps, torch, binding):
     return res
 
 
+def time_swap_host(sw, torch, binding, staging_mib=256, reps=2):
+    """The same victims' blocks out to pinned host memory and back in (PCIe-bound), in pieces
+    through a device staging buffer with kernel and copy on two streams."""
+    g = torch.Generator(device="cuda:0")
+    g.manual_seed(sw.seed)
+    pool = torch.randint(-2**31, 2**31 - 1, (sw.pool_bytes // 4,), dtype=torch.int32, device="cuda:0", generator=g)
+    host = torch.empty(sw.staging_bytes, dtype=torch.uint8).pin_memory()
+    staging = torch.empty(staging_mib << 20, dtype=torch.uint8, device="cuda:0")
+    copy_stream = torch.cuda.Stream()
+    gm = torch.from_numpy(sw.gather_mapping).cuda()
+    sm = torch.from_numpy(sw.scatter_mapping).cuda()
+    d_out = binding.swap_desc(sw.num_planes, sw.block_bytes, sw.num_pool_blocks, sw.n_blocks)
+    d_in = binding.swap_desc(sw.num_planes, sw.block_bytes, sw.n_blocks, sw.num_pool_blocks)
+    res = {}
+    for name, fn in (("out", lambda: binding.kv_swap_out_host(d_out, pool, host, gm, staging, copy_stream=copy_stream)),
+                     ("in", lambda: binding.kv_swap_in_host(d_in, host, pool, sm, staging, copy_stream=copy_stream))):
+        fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / reps * 1e3
+        res[name] = {"ms": ms, "payload_GBps": sw.payload_bytes / ms / 1e6}
+    res["payload_GB"] = sw.payload_bytes / 1e9
+    res["staging_MiB"] = staging_mib
+    del pool, host, staging
+    torch.cuda.empty_cache()
+    return res
+
+
 def probe_ceilings(torch, binding, nbytes=4 << 30, reps=5):
     a = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0").random_(0, 255)
     b = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
@@ -303,6 +334,9 @@ def main():
             swap[sw.name] = time_swap(sw, 5, torch, binding)
             log(f"[bench] swap {sw.name}: {swap[sw.name]}")
         result["swap"] = swap
+        swh = W.config4_squeeze(victims=16)
+        result["swap_host_leg"] = time_swap_host(swh, torch, binding)
+        log(f"[bench] swap host leg {swh.name} ({int(swh.victim_lens.size)} victims): {result['swap_host_leg']}")
 
     if args.extra:
         extra = {}

@@ -216,6 +216,43 @@ int32_t kv_block_swap(const pkv_swap_desc* desc, const void* src_pool,
                       int32_t n_pairs, void* hip_stream);
 
 /*
+ * Host leg of the swap path (Sec. 5.1.2 "Swapping": a victim's KV blocks are
+ * offloaded from GPU memory to CPU host memory, and recovery migrates them
+ * back over PCIe).
+ *
+ * kv_swap_out_host: for every plane p and pair j < n_pairs, pool block
+ * s_j = block_mapping[2j] goes to host slot j:
+ *   host_dst + p*desc->dst_plane_stride_bytes + j*block_bytes
+ * (block_mapping[2j+1] must equal j: the victims' blocks are stored back to
+ * back in swap order; desc->src_* describe the pool, desc->dst_* the host
+ * buffer, dst_num_blocks >= n_pairs).
+ * kv_swap_in_host: the reverse: host slot j (block_mapping[2j] must equal j) of
+ * host_src goes to pool block block_mapping[2j+1] (desc->src_* describe the host
+ * buffer, desc->dst_* the pool).
+ *
+ * host_dst / host_src is page-locked HOST memory, everything else is device
+ * memory.  The swap moves in pieces through `staging`, a device buffer of
+ * staging_bytes >= 2*num_planes*block_bytes (PKV_ERR_WORKSPACE otherwise; bigger
+ * pieces make longer PCIe transfers): the kv_block_swap kernel gathers or
+ * scatters one piece on stream_compute while the neighbouring piece crosses
+ * PCIe as a strided copy on stream_copy (the two may be the same stream: the
+ * pieces then go one after the other).  Both calls only enqueue work.  After
+ * kv_swap_out_host, completion of stream_compute implies that all of host_dst
+ * is written; after kv_swap_in_host, completion of stream_compute implies that
+ * the pool blocks are.  The copy stream is made to wait for work enqueued on
+ * stream_compute before the call.  The library keeps one set of events per
+ * device for these two calls: do not issue them for one device from several
+ * host threads at once.  The bytes arrive exactly; same mapping rules as
+ * kv_block_swap.
+ */
+int32_t kv_swap_out_host(const pkv_swap_desc* desc, const void* src_pool, void* host_dst,
+                         const int32_t* block_mapping, int32_t n_pairs, void* staging,
+                         size_t staging_bytes, void* stream_compute, void* stream_copy);
+int32_t kv_swap_in_host(const pkv_swap_desc* desc, const void* host_src, void* dst_pool,
+                        const int32_t* block_mapping, int32_t n_pairs, void* staging,
+                        size_t staging_bytes, void* stream_compute, void* stream_copy);
+
+/*
  * Host-side range checks of the index arrays the fast path trusts.
  * *_host variants take HOST pointers and touch no GPU; the others take device
  * pointers, copy them to the host on `hip_stream` and wait for that copy.

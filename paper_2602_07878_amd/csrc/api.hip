@@ -239,8 +239,51 @@ int32_t kv_block_swap(const pkv_swap_desc* desc, const void* src_pool, void* dst
   p.dst_plane_stride = desc->dst_plane_stride_bytes;
   p.num_planes = desc->num_planes;
   p.n_pairs = n_pairs;
+  p.src_index_offset = 0;
+  p.dst_index_offset = 0;
   const hipError_t e = launch_swap(p, static_cast<hipStream_t>(hip_stream));
   return hip_status(e);
+}
+
+static int32_t swap_host_impl(bool out, const pkv_swap_desc* desc, const void* src, void* dst,
+                              const int32_t* block_mapping, int32_t n_pairs, void* staging,
+                              size_t staging_bytes, void* stream_compute, void* stream_copy) {
+  const int32_t st = check_swap_desc(desc);
+  if (st != PKV_OK) return st;
+  if (n_pairs < 0) return PKV_ERR_SHAPE;
+  if (n_pairs == 0) return PKV_OK;
+  if (!src || !dst || !block_mapping || !staging) return PKV_ERR_NULL;
+  if (!aligned16(src) || !aligned16(dst) || !aligned16(staging) ||
+      (reinterpret_cast<uintptr_t>(block_mapping) & 3u))
+    return PKV_ERR_ALIGN;
+  // the host side holds one slot per pair
+  if ((out ? desc->dst_num_blocks : desc->src_num_blocks) < n_pairs) return PKV_ERR_SHAPE;
+  bool too_small = false;
+  const hipError_t e =
+      out ? swap_out_host(*desc, static_cast<const uint8_t*>(src), static_cast<uint8_t*>(dst),
+                          block_mapping, n_pairs, static_cast<uint8_t*>(staging), staging_bytes,
+                          static_cast<hipStream_t>(stream_compute), static_cast<hipStream_t>(stream_copy),
+                          &too_small)
+          : swap_in_host(*desc, static_cast<const uint8_t*>(src), static_cast<uint8_t*>(dst),
+                         block_mapping, n_pairs, static_cast<uint8_t*>(staging), staging_bytes,
+                         static_cast<hipStream_t>(stream_compute), static_cast<hipStream_t>(stream_copy),
+                         &too_small);
+  if (too_small) return PKV_ERR_WORKSPACE;
+  return hip_status(e);
+}
+
+int32_t kv_swap_out_host(const pkv_swap_desc* desc, const void* src_pool, void* host_dst,
+                         const int32_t* block_mapping, int32_t n_pairs, void* staging,
+                         size_t staging_bytes, void* stream_compute, void* stream_copy) {
+  return swap_host_impl(true, desc, src_pool, host_dst, block_mapping, n_pairs, staging,
+                        staging_bytes, stream_compute, stream_copy);
+}
+
+int32_t kv_swap_in_host(const pkv_swap_desc* desc, const void* host_src, void* dst_pool,
+                        const int32_t* block_mapping, int32_t n_pairs, void* staging,
+                        size_t staging_bytes, void* stream_compute, void* stream_copy) {
+  return swap_host_impl(false, desc, host_src, dst_pool, block_mapping, n_pairs, staging,
+                        staging_bytes, stream_compute, stream_copy);
 }
 
 int32_t pkv_validate_tables_host(const pkv_attn_desc* desc, const int32_t* block_tables_host,

@@ -48,6 +48,9 @@ struct SwapParams {
   const int32_t* mapping;  // [n_pairs][2]
   int64_t block_bytes, src_plane_stride, dst_plane_stride;
   int32_t num_planes, n_pairs;
+  // subtracted from the mapping's block ids: lets a window of a longer mapping address a
+  // buffer that holds only that window (the host leg moves a swap in pieces)
+  int32_t src_index_offset, dst_index_offset;
 };
 
 // attn_decode.hip
@@ -66,6 +69,13 @@ hipError_t launch_swap(const SwapParams& p, hipStream_t s);
 // append.hip (uses the pointers, strides and shapes of AttnParams; q/out unused)
 hipError_t launch_kv_append(const AttnParams& p, const void* k_new, const void* v_new, int elem_bytes,
                             hipStream_t s);
+// swap_host.hip
+hipError_t swap_out_host(const pkv_swap_desc& d, const uint8_t* pool, uint8_t* host_dst, const int32_t* mapping,
+                         int32_t n_pairs, uint8_t* staging, size_t staging_bytes, hipStream_t compute,
+                         hipStream_t copy, bool* too_small);
+hipError_t swap_in_host(const pkv_swap_desc& d, const uint8_t* host_src, uint8_t* pool, const int32_t* mapping,
+                        int32_t n_pairs, uint8_t* staging, size_t staging_bytes, hipStream_t compute,
+                        hipStream_t copy, bool* too_small);
 hipError_t launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t s);
 hipError_t launch_probe_read(const void* src, void* sink, size_t bytes, hipStream_t s);
 

@@ -18,7 +18,7 @@ ST = dict(OK=0, NULL=1, SHAPE=2, DTYPE=3, ALIGN=4, WORKSPACE=5, INDEX=6, HIP=7)
 def header_functions():
     src = open(os.path.join(ROOT, "include", "pkv.h")).read()
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
-    return sorted(set(re.findall(r"\b(pkv_[a-z_]+|paged_decode_attention[a-z_]*|kv_block_swap|kv_append)\s*\(", src)))
+    return sorted(set(re.findall(r"\b(pkv_[a-z_]+|paged_decode_attention[a-z_]*|kv_block_swap|kv_append|kv_swap_[a-z_]+)\s*\(", src)))
 
 
 def test_library_exports_every_declared_symbol():
@@ -135,6 +135,23 @@ def test_append_rejects_bad_arguments_on_host():
     assert f(good_desc(), vp=0x4008) == ST["ALIGN"]
     assert f(good_desc(), cl=0x6002) == ST["ALIGN"]
     assert f(good_desc(batch=0), kn=0, vn=0, kp=0, vp=0, bt=0, cl=0) == ST["OK"]
+
+
+def test_swap_host_leg_rejects_bad_arguments_on_host():
+    L = binding.lib()
+    for fn in (L.kv_swap_out_host, L.kv_swap_in_host):
+        f = lambda d, a=0x1000, b=0x2000, m=0x3000, n=5, st=0x4000, sb=1 << 22: fn(
+            ctypes.byref(d), a, b, m, n, st, sb, None, None)
+        assert fn(None, 1, 1, 1, 1, 1, 1, None, None) == ST["NULL"]
+        assert f(swap_desc(block_bytes=24)) == ST["ALIGN"]
+        assert f(swap_desc(), st=0) == ST["NULL"]
+        assert f(swap_desc(), a=0x1008) == ST["ALIGN"]
+        assert f(swap_desc(), n=-1) == ST["SHAPE"]
+        assert f(swap_desc(), n=0, a=0, b=0, m=0, st=0) == ST["OK"]
+        assert f(swap_desc(), sb=2 * 4 * 32768 - 16) == ST["WORKSPACE"]   # not even one pair per half
+    # the host side needs a slot per pair: 50 slots in the 100 -> 50 descriptor, 100 the other way round
+    assert L.kv_swap_out_host(ctypes.byref(swap_desc()), 0x1000, 0x2000, 0x3000, 51, 0x4000, 1 << 22, None, None) == ST["SHAPE"]
+    assert L.kv_swap_in_host(ctypes.byref(swap_desc()), 0x1000, 0x2000, 0x3000, 101, 0x4000, 1 << 22, None, None) == ST["SHAPE"]
 
 
 def test_host_validators():

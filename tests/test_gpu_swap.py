@@ -94,3 +94,37 @@ def test_swap_is_transparent_to_attention():
                 block_tables=torch.from_numpy(w.block_tables).cuda())
     after = run_hip(w, dev2)
     assert np.array_equal(before, after)
+
+
+# ---- host leg (Sec. 5.1.2: the victims' blocks go to CPU host memory and come back) ---------
+@pytest.mark.parametrize("staging_pairs,two_streams", [(1, False), (7, True), (64, True), (1000, False)])
+def test_swap_out_to_pinned_host_and_back_is_bit_exact(staging_pairs, two_streams):
+    import oracle
+    import torch
+    from paper_2602_07878_amd import binding
+    planes, bb = 6, 4096
+    sw = W.make_swap_workload("hostleg", 71, victim_lens=(700, 33, 1200, 16, 90), num_planes=planes,
+                              block_bytes=bb)
+    n = sw.n_blocks
+    pool = W.random_bytes(sw.pool_bytes, 72)
+    d_pool = torch.from_numpy(pool).cuda()
+    host = torch.zeros(planes * n * bb + 64, dtype=torch.uint8).pin_memory()
+    host[-64:] = 0xA5                                                   # canary behind the slots
+    staging = torch.empty(2 * staging_pairs * planes * bb, dtype=torch.uint8, device="cuda")
+    copy_stream = torch.cuda.Stream() if two_streams else None
+    out_desc = binding.swap_desc(planes, bb, sw.num_pool_blocks, n)
+    gm = torch.from_numpy(sw.gather_mapping).cuda()
+    binding.kv_swap_out_host(out_desc, d_pool, host, gm, staging, copy_stream=copy_stream)
+    torch.cuda.current_stream().synchronize()                           # compute stream alone
+    ref = np.zeros(planes * n * bb, np.uint8)
+    oracle.kv_block_swap(pool, ref, sw.gather_mapping, num_planes=planes, block_bytes=bb)
+    assert np.array_equal(host[:-64].numpy(), ref) and bool((host[-64:] == 0xA5).all())
+    # back into fresh blocks of a poisoned pool
+    d_new = torch.full_like(d_pool, 0x5A)
+    in_desc = binding.swap_desc(planes, bb, n, sw.num_pool_blocks)
+    sm = torch.from_numpy(sw.scatter_mapping).cuda()
+    binding.kv_swap_in_host(in_desc, host, d_new, sm, staging, copy_stream=copy_stream)
+    torch.cuda.current_stream().synchronize()
+    ref_pool = np.full(sw.pool_bytes, 0x5A, np.uint8)
+    oracle.kv_block_swap(ref, ref_pool, sw.scatter_mapping, num_planes=planes, block_bytes=bb)
+    assert np.array_equal(d_new.cpu().numpy(), ref_pool)                # blocks in place, nothing else touched
