@@ -209,7 +209,8 @@ int32_t kv_append(const pkv_attn_desc* desc, const void* k_new, const void* v_ne
  * are this same call with the roles of pool and staging exchanged.  The copy
  * is bytewise exact.  src and dst must not overlap; a destination block named
  * twice is a data race (undefined); a source block may repeat.  n_pairs = 0
- * enqueues nothing.
+ * enqueues nothing.  The order of the pairs does not change the result; pairs
+ * listed by ascending destination block copy fastest (sequential writes).
  */
 int32_t kv_block_swap(const pkv_swap_desc* desc, const void* src_pool,
                       void* dst, const int32_t* block_mapping,

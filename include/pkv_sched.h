@@ -115,7 +115,8 @@ int32_t pkv_sched_decode_batch(const pkv_sched* s, int64_t* request_ids, int32_t
 /*
  * Swap mappings of the last iteration as [n][2] int32 pairs, the
  * block_mapping argument of kv_block_swap: swap-out pairs are (pool block,
- * host block), swap-in pairs (host block, pool block).  Returns n, or
+ * host block) in eviction order, swap-in pairs (host block, pool block) by
+ * ascending pool block (sequential writes for the scatter).  Returns n, or
  * -PKV_ERR_SHAPE if capacity_pairs is too small.
  */
 int32_t pkv_sched_swap_out(const pkv_sched* s, int32_t* mapping, int32_t capacity_pairs);

@@ -128,6 +128,7 @@ class RefScheduler:
                     self._finish(r, out)
                 else:
                     admitted.append(r)
+        out["swap_in"].sort(key=lambda pair: pair[1])   # reported by ascending pool block
         if out["head_blocked"]:
             self.totals["blocked"] += 1
         # 3. one decode token for everything that was running before the admissions

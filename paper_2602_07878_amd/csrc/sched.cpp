@@ -4,10 +4,12 @@
 // block tables, context lengths and swap mappings that the GPU calls of this library take.
 // Plain C++ on the host; see pkv_sched.h for the iteration it implements.
 
+#include <algorithm>
 #include <cstdint>
 #include <deque>
 #include <memory>
 #include <unordered_map>
+#include <utility>
 #include <vector>
 
 #include "pkv.h"
@@ -143,6 +145,16 @@ struct pkv_sched {
       }
     }
     if (head_blocked) ++totals[6];
+    // the order of the pairs is free; ascending pool blocks make the scatter's writes sequential
+    {
+      std::vector<std::pair<int32_t, int32_t>> pairs;   // (pool block, host block)
+      for (size_t k = 0; k + 1 < swap_in.size(); k += 2) pairs.emplace_back(swap_in[k + 1], swap_in[k]);
+      std::sort(pairs.begin(), pairs.end());
+      for (size_t k = 0; k < pairs.size(); ++k) {
+        swap_in[2 * k] = pairs[k].second;
+        swap_in[2 * k + 1] = pairs[k].first;
+      }
+    }
 
     // 3. one decode token for everything that was running before the admissions
     std::vector<Request*> still;
