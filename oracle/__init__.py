@@ -171,3 +171,31 @@ def kv_append(k_pool, v_pool, k_new, v_new, block_tables, context_lens, *, block
     if rc != 0:
         raise IndexError(f"oracle: append outside pool/table (code {rc})")
     return k_pool, v_pool
+
+
+def paged_prefill_attention(q, k_pool, v_pool, block_tables, context_lens, query_lens, scale,
+                            *, block_size, k_strides=None, v_strides=None):
+    """Causal attention of the last query_lens[i] tokens of every sequence over the paged cache
+    (the prefill / re-prefill of the recompute recovery path, arXiv 2602.07878 Sec. 2.1 and
+    Sec. 5.1.2: a token attends to itself and to everything before it).
+
+    q is packed [sum(query_lens), Hq, D] in sequence order; context_lens[i] counts all cached
+    tokens of sequence i INCLUDING those query_lens[i] tokens, whose K/V are already in the pool.
+    Query token j of sequence i sits at position context_lens[i] - query_lens[i] + j and sees
+    positions 0..that, which is exactly the decode definition with that many tokens: the
+    function is written as one decode-oracle row per query token.  Returns float64 [sum, Hq, D].
+    """
+    cl = np.ascontiguousarray(context_lens, dtype=np.int64)
+    ql = np.ascontiguousarray(query_lens, dtype=np.int64)
+    bt = np.ascontiguousarray(block_tables, dtype=np.int32)
+    assert cl.shape == ql.shape and np.all(ql >= 0) and np.all(ql <= cl)
+    q = np.ascontiguousarray(q)
+    assert q.shape[0] == int(ql.sum())
+    rows_seq = np.repeat(np.arange(len(ql)), ql)                       # sequence of every query row
+    first = np.cumsum(ql) - ql                                         # first packed row of a sequence
+    j = np.arange(int(ql.sum())) - first[rows_seq]                     # index inside its sequence
+    ctx = (cl[rows_seq] - ql[rows_seq] + j + 1).astype(np.int32)       # tokens that row may see
+    if q.shape[0] == 0:
+        return np.zeros(q.shape, np.float64)
+    return paged_decode_attention(q, k_pool, v_pool, bt[rows_seq], ctx, scale, block_size=block_size,
+                                  k_strides=k_strides, v_strides=v_strides)

@@ -456,3 +456,57 @@ def test_append_respects_strided_token_major_layout_and_reports_bad_table():
     w.block_tables[1, 2] = -1
     with pytest.raises(IndexError):
         oracle.kv_append(w.k_pool, w.v_pool, kn, vn, w.block_tables, w.context_lens, block_size=4)
+
+
+# Prefill oracle (causal attention of a chunk over the paged cache) ---------------------------
+def _contiguous(w, i, g):
+    n = int(w.context_lens[i])
+    return (as_f64(gather_rows(w.k_pool, w.block_tables[i], n, g, w.block_size)),
+            as_f64(gather_rows(w.v_pool, w.block_tables[i], n, g, w.block_size)))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_prefill_of_whole_sequences_matches_library_causal_sdpa(dtype):
+    import torch
+    lens = (1, 5, 9, 16)
+    w = small(31, dtype=dtype, Hq=4, Hkv=2, D=8, bs=4, lens=lens)
+    rng = np.random.default_rng(3)
+    q = rng.standard_normal((sum(lens), 4, 8)).astype(np.float32)
+    if dtype == "bf16":
+        q = W.f32_to_bf16_bits(q)
+    out = oracle.paged_prefill_attention(q, w.k_pool, w.v_pool, w.block_tables, w.context_lens, lens,
+                                         w.scale, block_size=4)
+    row = 0
+    for i, n in enumerate(lens):
+        qi = torch.from_numpy(as_f64(q[row:row + n])).permute(1, 0, 2)              # [Hq, n, D]
+        K = torch.stack([torch.from_numpy(_contiguous(w, i, h // 2)[0]) for h in range(4)])
+        V = torch.stack([torch.from_numpy(_contiguous(w, i, h // 2)[1]) for h in range(4)])
+        ref = torch.nn.functional.scaled_dot_product_attention(qi, K, V, is_causal=True,
+                                                               scale=float(np.float32(w.scale)))
+        assert np.abs(out[row:row + n] - ref.permute(1, 0, 2).numpy()).max() < 1e-12
+        row += n
+
+
+def test_prefill_chunk_is_the_tail_of_the_full_causal_result_and_one_token_is_decode():
+    lens = (7, 12, 16)
+    w = small(32, dtype="f32", Hq=4, Hkv=2, D=8, bs=4, lens=lens)
+    rng = np.random.default_rng(4)
+    q_full = rng.standard_normal((sum(lens), 4, 8)).astype(np.float32)
+    full = oracle.paged_prefill_attention(q_full, w.k_pool, w.v_pool, w.block_tables, w.context_lens,
+                                          lens, w.scale, block_size=4)
+    chunk = (3, 12, 1)                  # a tail, the whole sequence, a single token
+    starts = np.cumsum(lens) - np.array(lens)
+    q_chunk = np.concatenate([q_full[s + n - c:s + n] for s, n, c in zip(starts, lens, chunk)])
+    part = oracle.paged_prefill_attention(q_chunk, w.k_pool, w.v_pool, w.block_tables, w.context_lens,
+                                          chunk, w.scale, block_size=4)
+    want = np.concatenate([full[s + n - c:s + n] for s, n, c in zip(starts, lens, chunk)])
+    assert np.array_equal(part, want)
+    # the last token of every sequence sees everything: the decode result
+    q_last = np.stack([q_full[s + n - 1] for s, n in zip(starts, lens)])
+    dec = oracle.paged_decode_attention(q_last, w.k_pool, w.v_pool, w.block_tables, w.context_lens,
+                                        w.scale, block_size=4)
+    assert np.array_equal(np.stack([full[s + n - 1] for s, n in zip(starts, lens)]), dec)
+    # the first token of a sequence sees only itself
+    for i, s in enumerate(starts):
+        for h in range(4):
+            assert np.array_equal(full[s, h], _contiguous(w, i, h // 2)[1][0])
