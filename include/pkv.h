@@ -179,6 +179,31 @@ int32_t paged_decode_attention_timed(const pkv_attn_desc* desc, const void* q,
                                      void* ev_kernel_begin, void* ev_kernel_end);
 
 /*
+ * Causal prefill attention of a chunk over the paged cache (Sec. 2.1: masked
+ * self-attention, a token attends to itself and to what precedes it; this is
+ * the prefill phase and, after a preemption, the re-prefill of Sec. 5.1.2
+ * "Recomputation").  Sequence i contributes its LAST query_lens[i] tokens as
+ * queries; context_lens[i] counts all its cached tokens including those, whose
+ * K/V are already in the pool.  q and out are packed [total_query_tokens][Hq][D]
+ * in sequence order, cu_query_lens [batch+1] holds the first packed row of every
+ * sequence (device, int32).  Query token j of sequence i has position
+ * context_lens[i] - query_lens[i] + j and sees positions 0..that:
+ *   out[row,h,:] = softmax_{s <= pos}(scale * q[row,h,:] . K_s) V_s.
+ * desc as for paged_decode_attention (max_context_len, partition_tokens and
+ * flags are not used); max_query_len is a host-known upper bound of all
+ * query_lens (it sizes the grid).  Supported: bf16 K/V/q, head_dim 128,
+ * block_size a power-of-two multiple of 16 (PKV_ERR_SHAPE / PKV_ERR_DTYPE
+ * otherwise); out is fp32 or bf16 per desc->out_dtype.  No workspace.  Rows of
+ * sequences with query_lens[i] = 0 do not exist; query_lens[i] > context_lens[i]
+ * is clipped.  batch = 0 or max_query_len = 0 enqueues nothing.
+ */
+int32_t paged_prefill_attention(const pkv_attn_desc* desc, const void* q, const void* k_pool,
+                                const void* v_pool, const int32_t* block_tables,
+                                const int32_t* context_lens, const int32_t* query_lens,
+                                const int32_t* cu_query_lens, int32_t max_query_len,
+                                float scale, void* out, void* hip_stream);
+
+/*
  * KV append (Sec. 2.2 "KV-Cache": the K and V vectors of the token generated
  * in a step join the request's cache before the step's attention reads it).
  * desc is the descriptor of the attention call that follows; context_lens

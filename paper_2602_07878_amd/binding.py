@@ -15,11 +15,12 @@ LIB_PATH = os.path.join(_HERE, "libpkv.so")
 
 PKV_F32, PKV_BF16 = 0, 1
 PKV_OK = 0
+PKV_ERR_HIP = 7
 FLAG_VECTOR_ALU = 1
 
 EXPORTS = [
     "pkv_version", "pkv_status_string", "pkv_last_hip_error_string", "pkv_attn_partition_tokens", "pkv_attn_workspace_bytes",
-    "paged_decode_attention", "paged_decode_attention_timed", "kv_append", "kv_block_swap",
+    "paged_decode_attention", "paged_decode_attention_timed", "paged_prefill_attention", "kv_append", "kv_block_swap",
     "kv_swap_out_host", "kv_swap_in_host",
     "pkv_validate_tables_host",
     "pkv_validate_mapping_host", "pkv_validate_tables", "pkv_validate_mapping",
@@ -81,6 +82,9 @@ def lib() -> ctypes.CDLL:
         L.paged_decode_attention_timed.restype = i32
         L.paged_decode_attention_timed.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp,
                                                    ctypes.c_float, vp, vp, sz, vp, vp, vp]
+        L.paged_prefill_attention.restype = i32
+        L.paged_prefill_attention.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, vp, i32,
+                                              ctypes.c_float, vp, vp]
         L.kv_append.restype = i32
         L.kv_append.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, vp]
         for name in ("kv_swap_out_host", "kv_swap_in_host"):
@@ -207,6 +211,18 @@ def swap_desc(num_planes: int, block_bytes: int, src_num_blocks: int, dst_num_bl
     d.dst_plane_stride_bytes = (dst_num_blocks * block_bytes if dst_plane_stride_bytes is None
                                 else dst_plane_stride_bytes)
     return d
+
+
+def paged_prefill_attention(desc: AttnDesc, q, k_pool, v_pool, block_tables, context_lens, query_lens,
+                            cu_query_lens, max_query_len: int, scale: float, out, *, stream=None):
+    """Causal attention of the last query_lens[i] tokens of every sequence (q, out packed
+    [total, Hq, D]; all tensors on the device)."""
+    assert q.is_contiguous() and out.is_contiguous() and out.shape == q.shape
+    st = lib().paged_prefill_attention(ctypes.byref(desc), q.data_ptr(), k_pool.data_ptr(), v_pool.data_ptr(),
+                                       block_tables.data_ptr(), context_lens.data_ptr(), query_lens.data_ptr(),
+                                       cu_query_lens.data_ptr(), int(max_query_len), float(scale),
+                                       out.data_ptr(), _stream_ptr(stream))
+    _check(st, "paged_prefill_attention")
 
 
 def kv_append(desc: AttnDesc, k_new, v_new, k_pool, v_pool, block_tables, context_lens, *, stream=None):

@@ -192,6 +192,44 @@ int32_t paged_decode_attention_timed(const pkv_attn_desc* desc, const void* q, c
                         workspace_bytes, hip_stream, ev_kernel_begin, ev_kernel_end);
 }
 
+int32_t paged_prefill_attention(const pkv_attn_desc* desc, const void* q, const void* k_pool,
+                                const void* v_pool, const int32_t* block_tables,
+                                const int32_t* context_lens, const int32_t* query_lens,
+                                const int32_t* cu_query_lens, int32_t max_query_len, float scale,
+                                void* out, void* hip_stream) {
+  const int32_t st = check_attn_desc(desc);
+  if (st != PKV_OK) return st;
+  if (max_query_len < 0) return PKV_ERR_SHAPE;
+  if (desc->batch == 0 || max_query_len == 0) return PKV_OK;
+  if (desc->kv_dtype != PKV_BF16) return PKV_ERR_DTYPE;
+  if (!attn_prefill_supported(*desc)) return PKV_ERR_SHAPE;
+  if (!q || !k_pool || !v_pool || !block_tables || !context_lens || !query_lens || !cu_query_lens || !out)
+    return PKV_ERR_NULL;
+  if (!aligned16(q) || !aligned16(k_pool) || !aligned16(v_pool) || !aligned16(out) ||
+      (reinterpret_cast<uintptr_t>(block_tables) & 3u) || (reinterpret_cast<uintptr_t>(context_lens) & 3u) ||
+      (reinterpret_cast<uintptr_t>(query_lens) & 3u) || (reinterpret_cast<uintptr_t>(cu_query_lens) & 3u))
+    return PKV_ERR_ALIGN;
+  if (!std::isfinite(scale)) return PKV_ERR_SHAPE;
+  AttnParams p;
+  std::memset(&p, 0, sizeof p);
+  p.q = q; p.k_pool = k_pool; p.v_pool = v_pool;
+  p.block_tables = block_tables; p.context_lens = context_lens;
+  p.query_lens = query_lens; p.cu_query_lens = cu_query_lens; p.out = out;
+  p.k_stride_block = desc->k_stride_block * 2;
+  p.k_stride_head = desc->k_stride_head * 2;
+  p.k_stride_token = desc->k_stride_token * 2;
+  p.v_stride_block = desc->v_stride_block * 2;
+  p.v_stride_head = desc->v_stride_head * 2;
+  p.v_stride_token = desc->v_stride_token * 2;
+  p.batch = desc->batch; p.num_q_heads = desc->num_q_heads; p.num_kv_heads = desc->num_kv_heads;
+  p.head_dim = desc->head_dim; p.block_size = desc->block_size;
+  p.max_blocks_per_seq = desc->max_blocks_per_seq;
+  p.group = desc->num_q_heads / desc->num_kv_heads;
+  p.out_is_bf16 = desc->out_dtype == PKV_BF16;
+  p.scale_log2e = scale * 1.4426950408889634f;
+  return hip_status(launch_attn_prefill(p, max_query_len, static_cast<hipStream_t>(hip_stream)));
+}
+
 int32_t kv_append(const pkv_attn_desc* desc, const void* k_new, const void* v_new, void* k_pool,
                   void* v_pool, const int32_t* block_tables, const int32_t* context_lens,
                   void* hip_stream) {

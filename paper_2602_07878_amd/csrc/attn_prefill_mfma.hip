@@ -1,0 +1,328 @@
+// Causal prefill attention of a chunk of query tokens over the paged KV cache, bf16 /
+// head_dim 128, for gfx950.
+//
+// Operation (arXiv 2602.07878, Sec. 2.1: masked self-attention, a token attends to itself
+// and to everything before it; Sec. 5.1.2 "Recomputation": a preempted request's prompt and
+// generated tokens are prefilled again): for the last query_lens[i] tokens of sequence i,
+// out[row] = softmax over positions s <= pos(row) of (scale q_row . K_s) V_s, with K and V
+// found through the block table.  The chunk's own K/V are already in the pool.
+//
+// Unlike decode this is a dense contraction with reuse: a 16-token K/V tile serves every
+// query row that may see it, so the matrix cores, not HBM, bound it.
+//
+// Work split.  A workgroup of 8 wavefronts takes 128 consecutive query tokens of one
+// sequence and up to two query heads of one KV head; each wavefront owns 16 of those
+// tokens.  The workgroup walks the K/V tiles 0 .. (its last position)/16 once: the eight
+// wavefronts fetch one tile together with direct-to-LDS loads (four fetch K rows, four V
+// rows) into a 2-deep ring, and all of them consume it from LDS.  A wavefront skips the
+// tiles that lie entirely in its future.
+//
+// Per tile and head (same tile code as the decode kernel, with the 16 MFMA columns now
+// holding 16 query tokens of one head instead of the heads of one token):
+//   S^T[token][query] = K Q^T   4 x v_mfma_f32_16x16x32_bf16
+//   causal mask, lazy-max base-2 softmax in fp32 (no cross-lane traffic unless the
+//   reference maximum has to be raised)
+//   O[query][dim] += P V        2 x 8 x v_mfma_f32_16x16x16_bf16, P split into a bf16 head
+//   and a bf16 remainder, V through the transposing LDS read.
+
+#include <type_traits>
+
+#include "pkv_internal.h"
+
+namespace pkv {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef const void __attribute__((address_space(1)))* gptr_t;
+typedef void __attribute__((address_space(3)))* lptr_t;
+
+constexpr int D = 128;
+constexpr int kThreads = 512, kWaves = kThreads / kWaveSize;
+constexpr int kQueryPerWave = 16, kQueryPerGroup = kWaves * kQueryPerWave;
+constexpr int kTileBytes = 4096, kStageBytes = 2 * kTileBytes;
+constexpr float kNegBig = -1.0e30f;
+constexpr float kSlack = 8.0f;
+
+#define PKV_PF_WAIT_VMCNT(n) \
+  __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (((n) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
+
+__device__ __forceinline__ uint32_t bf16x2_rne(float lo, float hi) {
+  auto cv = [](float f) -> uint32_t {
+    uint32_t u = __builtin_bit_cast(uint32_t, f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x40u;
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return u >> 16;
+  };
+  return cv(lo) | (cv(hi) << 16);
+}
+
+// NG = query heads per workgroup (1 or 2).
+template <int NG>
+__global__ __launch_bounds__(kThreads, 2) void attn_prefill_mfma_d128(const AttnParams p) {
+  __shared__ __attribute__((aligned(256))) uint8_t ring[2 * kStageBytes];
+  __shared__ __attribute__((aligned(16))) float xchg_all[kWaves][128];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & (kWaveSize - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(tid / kWaveSize);
+  const int t16 = lane & 15;   // score layout: query token of the wavefront's 16; V layout: dim
+  const int q4 = lane >> 4;    // score layout: K tokens 4*q4..+3 of the tile
+
+  const int seq = blockIdx.z;
+  const int n = p.context_lens[seq];
+  const int ql = min(p.query_lens[seq], n);
+  const int q0 = blockIdx.x * kQueryPerGroup;          // first query token of this workgroup
+  if (ql <= 0 || q0 >= ql) return;                     // uniform over the workgroup
+  const int pos0 = n - ql;                             // position of the chunk's first token
+  const int kvh = blockIdx.y / p.group_tiles, gtile = blockIdx.y - kvh * p.group_tiles;
+  const int h0 = kvh * p.group + gtile * NG;
+  const int nheads = min(NG, p.group - gtile * NG);
+
+  const int qw = q0 + kQueryPerWave * wave;            // first query token of this wavefront
+  const bool wave_live = qw < ql;
+  const int qi = qw + t16;                             // query token of this lane's column
+  const bool col_live = qi < ql;
+  const int qpos = pos0 + qi;
+  const int ntiles = (pos0 + min(ql, q0 + kQueryPerGroup) - 1) / kTileTokens + 1;
+  const int wave_last_tile = wave_live ? (pos0 + min(ql, qw + kQueryPerWave) - 1) / kTileTokens : -1;
+
+  // ---- per-lane offsets: same swizzled LDS images as the decode kernel -------------------------
+  // fetch: wavefront w < 4 brings K rows 4w..4w+3, wavefront w >= 4 brings V rows 4(w-4)..+3
+  const int frow = 4 * (wave & 3) + q4;
+  const bool fetch_v = wave >= 4;
+  const uint32_t foff = fetch_v ? (uint32_t)(frow * p.v_stride_token) + (uint32_t)((t16 ^ (2 * (frow & 7))) * 16)
+                                : (uint32_t)(frow * p.k_stride_token) + (uint32_t)((t16 ^ frow) * 16);
+  const uint32_t fdst = (uint32_t)((fetch_v ? kTileBytes : 0) + (wave & 3) * 1024);
+  uint32_t krd[4], vrd[8];
+  const uint32_t rbase = (uint32_t)(uintptr_t)(lptr_t)ring;   // LDS byte address of the ring
+#pragma unroll
+  for (int j = 0; j < 4; ++j) krd[j] = (uint32_t)(t16 * 256 + (((4 * j + q4) ^ t16) * 16)) + rbase;
+  {
+    const int tv = 4 * q4 + (t16 >> 2);
+    const uint32_t vbase = (uint32_t)(tv * 256 + ((tv & 7) << 5) + (t16 & 3) * 8);
+#pragma unroll
+    for (int nb = 0; nb < 8; ++nb) vrd[nb] = (vbase ^ (uint32_t)(nb << 5)) + rbase;
+  }
+  float* xchg = xchg_all[wave];
+  const uint8_t* kpool = reinterpret_cast<const uint8_t*>(p.k_pool);
+  const uint8_t* vpool = reinterpret_cast<const uint8_t*>(p.v_pool);
+  const int tile_mask = (1 << p.tpb_shift) - 1;
+  const int32_t* table = p.block_tables + (int64_t)seq * p.max_blocks_per_seq;
+
+  // block ids of up to 64 tiles at a time, one per lane
+  int ids = 0;
+  auto load_ids = [&](int t0) { ids = table[min(t0 + lane, ntiles - 1) >> p.tpb_shift]; };
+
+  auto issue = [&](int j, int stage) {
+    const int64_t blk = __builtin_amdgcn_readlane(ids, j & 63);
+    const int slot0 = (j & tile_mask) * kTileTokens;
+    const uint8_t* base = fetch_v ? vpool + blk * p.v_stride_block + kvh * p.v_stride_head + slot0 * p.v_stride_token
+                                  : kpool + blk * p.k_stride_block + kvh * p.k_stride_head + slot0 * p.k_stride_token;
+    __builtin_amdgcn_global_load_lds((gptr_t)(base + foff), (lptr_t)(ring + stage * kStageBytes + fdst), 16, 0, 2);
+  };
+
+  // ---- query rows as B operands: column t16 = query token qi, one fragment set per head -------
+  bf16x8 qfrag[NG][4];
+  {
+    const int64_t qrow = (int64_t)p.cu_query_lens[seq] + (col_live ? qi : q0);
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      const uint8_t* qp = reinterpret_cast<const uint8_t*>(p.q) +
+                          (qrow * p.num_q_heads + h0 + min(g, nheads - 1)) * (D * 2) + q4 * 16;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        u32x4 v = *reinterpret_cast<const u32x4*>(qp + c * 64);
+        if (!col_live) v = u32x4{0, 0, 0, 0};
+        qfrag[g][c] = __builtin_bit_cast(bf16x8, v);
+      }
+    }
+  }
+
+  float m_ref[NG], l_part[NG];
+  f32x4 acc[NG][8];
+#pragma unroll
+  for (int g = 0; g < NG; ++g) {
+    m_ref[g] = kNegBig;
+    l_part[g] = 0.f;
+#pragma unroll
+    for (int nb = 0; nb < 8; ++nb) acc[g][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  auto consume = [&](int j, auto stage_tag) {
+    constexpr int STAGE = decltype(stage_tag)::value;
+    // K as A operand (row-per-lane 16-byte reads) and V as B operand (transposing reads).  All
+    // twelve LDS reads are issued by hand: the compiler would put a wait for every outstanding
+    // direct-to-LDS load, i.e. for the tile in flight, in front of reads it cannot tell apart
+    // from the ring.  The data is complete: the barrier before this call covered the tile.
+    u32x4 kraw[4];
+    u32x2 vt[8];
+    asm volatile(
+        "ds_read_b128 %0, %12 offset:%24\n\t"
+        "ds_read_b128 %1, %13 offset:%24\n\t"
+        "ds_read_b128 %2, %14 offset:%24\n\t"
+        "ds_read_b128 %3, %15 offset:%24\n\t"
+        "ds_read_b64_tr_b16 %4, %16 offset:%25\n\t"
+        "ds_read_b64_tr_b16 %5, %17 offset:%25\n\t"
+        "ds_read_b64_tr_b16 %6, %18 offset:%25\n\t"
+        "ds_read_b64_tr_b16 %7, %19 offset:%25\n\t"
+        "ds_read_b64_tr_b16 %8, %20 offset:%25\n\t"
+        "ds_read_b64_tr_b16 %9, %21 offset:%25\n\t"
+        "ds_read_b64_tr_b16 %10, %22 offset:%25\n\t"
+        "ds_read_b64_tr_b16 %11, %23 offset:%25\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&v"(kraw[0]), "=&v"(kraw[1]), "=&v"(kraw[2]), "=&v"(kraw[3]), "=&v"(vt[0]), "=&v"(vt[1]),
+          "=&v"(vt[2]), "=&v"(vt[3]), "=&v"(vt[4]), "=&v"(vt[5]), "=&v"(vt[6]), "=&v"(vt[7])
+        : "v"(krd[0]), "v"(krd[1]), "v"(krd[2]), "v"(krd[3]), "v"(vrd[0]), "v"(vrd[1]), "v"(vrd[2]),
+          "v"(vrd[3]), "v"(vrd[4]), "v"(vrd[5]), "v"(vrd[6]), "v"(vrd[7]), "n"(STAGE * kStageBytes),
+          "n"(STAGE * kStageBytes + kTileBytes)
+        : "memory");
+    bf16x8 kf[4];
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) kf[jj] = __builtin_bit_cast(bf16x8, kraw[jj]);
+    const int kpos0 = j * kTileTokens + 4 * q4;          // position of this lane's first K token
+    if (j * kTileTokens + kTileTokens > n) {             // last tile: rows past the context may be NaN
+      const uint32_t keep0 = (kpos0 + 0 < n ? 0x0000FFFFu : 0u) | (kpos0 + 1 < n ? 0xFFFF0000u : 0u);
+      const uint32_t keep1 = (kpos0 + 2 < n ? 0x0000FFFFu : 0u) | (kpos0 + 3 < n ? 0xFFFF0000u : 0u);
+#pragma unroll
+      for (int nb = 0; nb < 8; ++nb) { vt[nb][0] &= keep0; vt[nb][1] &= keep1; }
+    }
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      if (g < nheads) {
+        f32x4 cfr = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj)
+          cfr = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[jj], qfrag[g][jj], cfr, 0, 0, 0);
+        // cfr[r] = q(query t16) . k(token kpos0 + r); causal: a query sees positions <= its own
+        float d[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          d[r] = fmaf(cfr[r], p.scale_log2e, -m_ref[g]);
+          if (kpos0 + r > qpos) d[r] = -INFINITY;
+        }
+        const float dmax = fmaxf(fmaxf(d[0], d[1]), fmaxf(d[2], d[3]));
+        if (__builtin_amdgcn_ballot_w64(dmax > kSlack) != 0) {
+          float s[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            s[r] = cfr[r] * p.scale_log2e;
+            if (kpos0 + r > qpos) s[r] = -INFINITY;
+          }
+          xchg[q4 * 16 + t16] = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
+          const float tm = fmaxf(fmaxf(xchg[t16], xchg[16 + t16]), fmaxf(xchg[32 + t16], xchg[48 + t16]));
+          const float mn = fmaxf(m_ref[g], tm);
+          const float alpha = __builtin_amdgcn_exp2f(m_ref[g] - mn);
+          m_ref[g] = mn;
+          l_part[g] *= alpha;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) d[r] = s[r] - mn;
+          xchg[64 + t16] = alpha;   // accumulator rows of this lane are queries 4q4..4q4+3
+          const f32x4 a = *reinterpret_cast<const f32x4*>(xchg + 64 + 4 * q4);
+#pragma unroll
+          for (int nb = 0; nb < 8; ++nb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[g][nb][r] *= a[r];
+        }
+        uint32_t hi[4], lo[4];
+        float psum = 0.f;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float pw = __builtin_amdgcn_exp2f(d[r]);
+          psum += pw;
+          hi[r] = __builtin_bit_cast(uint32_t, pw);
+          const float rest = pw - __builtin_bit_cast(float, hi[r] & 0xFFFF0000u);
+          lo[r] = __builtin_bit_cast(uint32_t, rest) + 0x8000u;
+        }
+        l_part[g] += psum;
+        const s16x4 p_hi = __builtin_bit_cast(s16x4, u32x2{__builtin_amdgcn_perm(hi[1], hi[0], 0x07060302u),
+                                                           __builtin_amdgcn_perm(hi[3], hi[2], 0x07060302u)});
+        const s16x4 p_lo = __builtin_bit_cast(s16x4, u32x2{__builtin_amdgcn_perm(lo[1], lo[0], 0x07060302u),
+                                                           __builtin_amdgcn_perm(lo[3], lo[2], 0x07060302u)});
+#pragma unroll
+        for (int nb = 0; nb < 8; ++nb)
+          acc[g][nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_hi, __builtin_bit_cast(s16x4, vt[nb]), acc[g][nb], 0, 0, 0);
+#pragma unroll
+        for (int nb = 0; nb < 8; ++nb)
+          acc[g][nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_lo, __builtin_bit_cast(s16x4, vt[nb]), acc[g][nb], 0, 0, 0);
+      }
+    }
+  };
+
+  // ---- walk the tiles: fetch j+1 while j is consumed ------------------------------------------
+  using stage0 = std::integral_constant<int, 0>;
+  using stage1 = std::integral_constant<int, 1>;
+  load_ids(0);
+  issue(0, 0);
+  for (int j = 0; j < ntiles; ++j) {
+    if (j + 1 < ntiles) {
+      if (((j + 1) & 63) == 0) load_ids(j + 1);
+      issue(j + 1, (j + 1) & 1);
+      PKV_PF_WAIT_VMCNT(1);
+    } else {
+      PKV_PF_WAIT_VMCNT(0);
+    }
+    // Bare barriers: the data they order is in LDS and is complete by the waits above (own
+    // share of the tile) and by data dependence (LDS reads feed the matrix cores before the
+    // second barrier); a full __syncthreads() would also wait for the tile in flight.
+    asm volatile("s_barrier" ::: "memory");   // every wavefront's share of tile j has landed
+    if (j <= wave_last_tile) {
+      if (j & 1) consume(j, stage1{});
+      else consume(j, stage0{});
+    }
+    asm volatile("s_barrier" ::: "memory");   // tile j is consumed: its stage may be refilled
+  }
+
+  // ---- normalise and store ------------------------------------------------------------------------
+  if (!wave_live) return;
+#pragma unroll
+  for (int g = 0; g < NG; ++g) {
+    if (g < nheads) {
+      xchg[q4 * 16 + t16] = l_part[g];
+      float inv[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int c = 4 * q4 + r;
+        inv[r] = 1.0f / ((xchg[c] + xchg[16 + c]) + (xchg[32 + c] + xchg[48 + c]));
+      }
+      const int64_t row0 = (int64_t)p.cu_query_lens[seq] + qw + 4 * q4;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        if (qw + 4 * q4 + r < ql) {
+          const int64_t o = ((row0 + r) * p.num_q_heads + h0 + g) * D + t16;
+#pragma unroll
+          for (int nb = 0; nb < 8; ++nb) {
+            const float v = acc[g][nb][r] * inv[r];
+            if (p.out_is_bf16) reinterpret_cast<uint16_t*>(p.out)[o + nb * 16] = (uint16_t)(bf16x2_rne(v, 0.f) & 0xFFFFu);
+            else reinterpret_cast<float*>(p.out)[o + nb * 16] = v;
+          }
+        }
+      }
+    }
+  }
+}
+
+}  // namespace
+
+// bf16, head_dim 128, power-of-two block size / 16
+bool attn_prefill_supported(const pkv_attn_desc& d) {
+  const int tpb = d.block_size / kTileTokens;
+  return d.kv_dtype == PKV_BF16 && d.head_dim == 128 && tpb >= 1 && (tpb & (tpb - 1)) == 0;
+}
+
+hipError_t launch_attn_prefill(AttnParams& p, int max_query_len, hipStream_t s) {
+  p.tpb_shift = 0;
+  while ((kTileTokens << p.tpb_shift) < p.block_size) ++p.tpb_shift;
+  const int ng = p.group == 1 ? 1 : 2;
+  p.group_tiles = (p.group + ng - 1) / ng;
+  const dim3 grid((unsigned)((max_query_len + kQueryPerGroup - 1) / kQueryPerGroup),
+                  (unsigned)(p.num_kv_heads * p.group_tiles), (unsigned)p.batch);
+  if (ng == 1) hipLaunchKernelGGL((attn_prefill_mfma_d128<1>), grid, dim3(kThreads), 0, s, p);
+  else hipLaunchKernelGGL((attn_prefill_mfma_d128<2>), grid, dim3(kThreads), 0, s, p);
+  return hipGetLastError();
+}
+
+}  // namespace pkv

@@ -20,6 +20,8 @@ struct AttnParams {
   const void* v_pool;
   const int32_t* block_tables;
   const int32_t* context_lens;
+  const int32_t* query_lens;      // prefill only: query tokens per sequence
+  const int32_t* cu_query_lens;   // prefill only: [B+1] first packed query row of each sequence
   void* out;
   float* ws_ml;   // [B][Hq][P][2]  (running max in log2 units, normaliser)
   float* ws_o;    // [B][Hq][P][D]  un-normalised partial output rows
@@ -66,6 +68,9 @@ StreamWorkspace stream_workspace(const pkv_attn_desc& d);
 hipError_t launch_attn_stream(AttnParams& p, hipStream_t s);
 // swap.hip
 hipError_t launch_swap(const SwapParams& p, hipStream_t s);
+// attn_prefill_mfma.hip
+bool attn_prefill_supported(const pkv_attn_desc& d);
+hipError_t launch_attn_prefill(AttnParams& p, int max_query_len, hipStream_t s);
 // append.hip (uses the pointers, strides and shapes of AttnParams; q/out unused)
 hipError_t launch_kv_append(const AttnParams& p, const void* k_new, const void* v_new, int elem_bytes,
                             hipStream_t s);

@@ -1,0 +1,122 @@
+"""GPU parity of paged_prefill_attention (through the C ABI) against the fp64 oracle.
+Tolerance: max abs error 2e-3 (bf16 inputs, fp32 accumulation), outputs read as fp32."""
+import numpy as np
+import pytest
+
+from paper_2602_07878_amd import workloads as W
+from helpers import to_device
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-3
+
+
+def run_prefill(w, query_lens, seed, out_dtype=None, token_major=False):
+    """Returns (GPU out as float64 [total, Hq, D], oracle out)."""
+    import oracle
+    import torch
+    from paper_2602_07878_amd import binding
+    ql = np.asarray(query_lens, np.int32)
+    total = int(ql.sum())
+    rng = np.random.default_rng(seed)
+    q = W.f32_to_bf16_bits(rng.standard_normal((total, w.Hq, w.D)).astype(np.float32))
+    ref = oracle.paged_prefill_attention(q, w.k_pool, w.v_pool, w.block_tables, w.context_lens, ql,
+                                         w.scale, block_size=w.block_size)
+    dev = to_device(w)
+    kp, vp = dev["k_pool"], dev["v_pool"]
+    if token_major:
+        kp = kp.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+        vp = vp.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    dq = torch.from_numpy(q.view(np.int16)).cuda().view(torch.bfloat16)
+    cu = torch.from_numpy(np.concatenate([[0], np.cumsum(ql)]).astype(np.int32)).cuda()
+    odt = out_dtype or torch.float32
+    pad = 256
+    buf = torch.full((total * w.Hq * w.D + 2 * pad,), 777.0, dtype=odt, device="cuda")
+    out = buf[pad:pad + total * w.Hq * w.D].view(total, w.Hq, w.D)
+    desc = binding.attn_desc_for(dq[:max(total, 1)] if total else torch.empty(1, w.Hq, w.D, dtype=torch.bfloat16, device="cuda"),
+                                 kp, vp, dev["block_tables"], max_context_len=w.max_context_len, out_dtype=odt)
+    desc.batch = w.B
+    binding.paged_prefill_attention(desc, dq, kp, vp, dev["block_tables"], dev["context_lens"],
+                                    torch.from_numpy(ql).cuda(), cu, int(ql.max()) if ql.size else 0, w.scale, out)
+    torch.cuda.synchronize()
+    assert torch.all(buf[:pad] == 777.0) and torch.all(buf[pad + total * w.Hq * w.D:] == 777.0)
+    return out.float().cpu().numpy().astype(np.float64), ref
+
+
+def check(w, query_lens, seed=5, **kw):
+    got, ref = run_prefill(w, query_lens, seed, **kw)
+    assert np.all(np.isfinite(got)), "non-finite output (poison leaked?)"
+    err = np.abs(got - ref).max() if got.size else 0.0
+    print(f"{w.name}: Hq={w.Hq} Hkv={w.Hkv} bs={w.block_size} ctx={list(w.context_lens)[:6]} q={list(query_lens)[:6]} "
+          f"max_abs_err={err:.3e}", flush=True)
+    assert err <= TOL, err
+    return got, ref
+
+
+def mk(seed, lens, Hq=8, Hkv=2, bs=16):
+    return W.make_attn_workload("prefill", seed, dtype="bf16", Hq=Hq, Hkv=Hkv, D=128, block_size=bs,
+                                context_lens=list(lens), pool_factor=1.2)
+
+
+def test_whole_sequences_small_and_ragged():
+    lens = (1, 5, 16, 17, 100, 129, 300)
+    check(mk(81, lens), lens)
+
+
+def test_chunks_tails_single_tokens_and_absent_sequences():
+    lens = (400, 64, 33, 257, 90, 16)
+    check(mk(82, lens), (128, 1, 0, 257, 17, 16))
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(4, 4), (4, 2), (6, 2), (16, 2), (32, 8)])
+def test_group_sizes(Hq, Hkv):
+    lens = (70, 200, 31)
+    check(mk(83, lens, Hq=Hq, Hkv=Hkv), (70, 130, 5))
+
+
+@pytest.mark.parametrize("bs", [16, 32, 64, 128])
+def test_block_sizes(bs):
+    lens = (bs + 3, 3 * bs, 500)
+    check(mk(84, lens, bs=bs), (bs + 3, bs, 260))
+
+
+def test_long_context_short_chunk_and_chunk_of_512():
+    lens = (5000, 2048, 700)
+    check(mk(85, lens), (512, 512, 512))
+
+
+def test_last_query_token_equals_decode_kernel():
+    """Row of the last token of a chunk against the decode call on the same pools."""
+    import torch
+    from helpers import run_hip
+    lens = (333, 48, 1000)
+    w = mk(86, lens, Hq=32, Hkv=8)
+    got, _ = run_prefill(w, lens, 9)
+    last = np.cumsum(lens) - 1
+    rng = np.random.default_rng(9)
+    q = W.f32_to_bf16_bits(rng.standard_normal((sum(lens), 32, 128)).astype(np.float32))
+    w.q = q[last]
+    dec = run_hip(w)
+    assert np.abs(got[last] - dec).max() <= 1e-5
+
+
+def test_bf16_output_and_token_major_layout():
+    import torch
+    lens = (150, 40)
+    w = mk(87, lens)
+    got, ref = run_prefill(w, (150, 40), 3, out_dtype=torch.bfloat16)
+    ulp = np.maximum(np.abs(ref), 2.0 ** -126) * 2.0 ** -8
+    assert np.all(np.abs(got - ref) <= TOL + ulp)
+    check(w, (100, 40), token_major=True)
+
+
+def test_rejects_unsupported_shapes():
+    import torch
+    from paper_2602_07878_amd import binding
+    w = W.config1_tiny()                                   # fp32, D = 64
+    dev = to_device(w)
+    desc = binding.attn_desc_for(dev["q"], dev["k_pool"], dev["v_pool"], dev["block_tables"], max_context_len=256)
+    z = torch.zeros(8, dtype=torch.int32, device="cuda")
+    with pytest.raises(binding.PkvError):
+        binding.paged_prefill_attention(desc, dev["q"], dev["k_pool"], dev["v_pool"], dev["block_tables"],
+                                        dev["context_lens"], z, z, 4, 0.1, torch.empty_like(dev["q"]))
