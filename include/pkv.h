@@ -189,9 +189,10 @@ int32_t paged_decode_attention_timed(const pkv_attn_desc* desc, const void* q,
  * sequence (device, int32).  Query token j of sequence i has position
  * context_lens[i] - query_lens[i] + j and sees positions 0..that:
  *   out[row,h,:] = softmax_{s <= pos}(scale * q[row,h,:] . K_s) V_s.
- * desc as for paged_decode_attention (max_context_len, partition_tokens and
- * flags are not used); max_query_len is a host-known upper bound of all
- * query_lens (it sizes the grid).  Supported: bf16 K/V/q, head_dim 128,
+ * desc as for paged_decode_attention (partition_tokens and flags are not
+ * used; max_context_len bounds every context_lens[i] and sizes an on-chip copy
+ * of a block table row: at most 16 Ki blocks per sequence); max_query_len is a
+ * host-known upper bound of all query_lens (it sizes the grid).  Supported: bf16 K/V/q, head_dim 128,
  * block_size a power-of-two multiple of 16 (PKV_ERR_SHAPE / PKV_ERR_DTYPE
  * otherwise); out is fp32 or bf16 per desc->out_dtype.  No workspace.  Rows of
  * sequences with query_lens[i] = 0 do not exist; query_lens[i] > context_lens[i]

@@ -227,7 +227,8 @@ int32_t paged_prefill_attention(const pkv_attn_desc* desc, const void* q, const 
   p.group = desc->num_q_heads / desc->num_kv_heads;
   p.out_is_bf16 = desc->out_dtype == PKV_BF16;
   p.scale_log2e = scale * 1.4426950408889634f;
-  return hip_status(launch_attn_prefill(p, max_query_len, static_cast<hipStream_t>(hip_stream)));
+  return hip_status(launch_attn_prefill(p, max_query_len, desc->max_context_len,
+                                        static_cast<hipStream_t>(hip_stream)));
 }
 
 int32_t kv_append(const pkv_attn_desc* desc, const void* k_new, const void* v_new, void* k_pool,

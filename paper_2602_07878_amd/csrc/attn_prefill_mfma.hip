@@ -14,8 +14,9 @@
 // sequence and up to two query heads of one KV head; each wavefront owns 16 of those
 // tokens.  The workgroup walks the K/V tiles 0 .. (its last position)/16 once: the eight
 // wavefronts fetch one tile together with direct-to-LDS loads (four fetch K rows, four V
-// rows) into a 2-deep ring, and all of them consume it from LDS.  A wavefront skips the
-// tiles that lie entirely in its future.
+// rows) into a 4-deep ring, three tiles ahead of the one in use, and all of them consume it
+// from LDS; one barrier per tile orders the ring.  A wavefront skips the tiles that lie
+// entirely in its future.
 //
 // Per tile and head (same tile code as the decode kernel, with the 16 MFMA columns now
 // holding 16 query tokens of one head instead of the heads of one token):
@@ -44,8 +45,10 @@ constexpr int D = 128;
 constexpr int kThreads = 512, kWaves = kThreads / kWaveSize;
 constexpr int kQueryPerWave = 16, kQueryPerGroup = kWaves * kQueryPerWave;
 constexpr int kTileBytes = 4096, kStageBytes = 2 * kTileBytes;
+constexpr int kStages = 4;                 // K/V ring depth: three tiles in flight behind the one in use
 constexpr float kNegBig = -1.0e30f;
 constexpr float kSlack = 8.0f;
+constexpr int kMaxIdsBytes = 64 * 1024;     // LDS for one sequence's block table row: 16 Ki blocks
 
 #define PKV_PF_WAIT_VMCNT(n) \
   __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (((n) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
@@ -63,8 +66,9 @@ __device__ __forceinline__ uint32_t bf16x2_rne(float lo, float hi) {
 // NG = query heads per workgroup (1 or 2).
 template <int NG>
 __global__ __launch_bounds__(kThreads, 2) void attn_prefill_mfma_d128(const AttnParams p) {
-  __shared__ __attribute__((aligned(256))) uint8_t ring[2 * kStageBytes];
+  __shared__ __attribute__((aligned(256))) uint8_t ring[kStages * kStageBytes];
   __shared__ __attribute__((aligned(16))) float xchg_all[kWaves][128];
+  extern __shared__ int32_t ids_lds[];   // block table row of this sequence: ceil(max context / block size) entries
 
   const int tid = threadIdx.x;
   const int lane = tid & (kWaveSize - 1);
@@ -72,13 +76,21 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_mfma_d128(const Attn
   const int t16 = lane & 15;   // score layout: query token of the wavefront's 16; V layout: dim
   const int q4 = lane >> 4;    // score layout: K tokens 4*q4..+3 of the tile
 
-  const int seq = blockIdx.z;
+  // Workgroups are numbered so that the 128-query groups with the most K/V tiles to walk (the
+  // latest queries) are dispatched first, across all sequences and heads, and the short ones
+  // fill the gaps at the end; in launch order of (group, head, sequence) triples every round
+  // of workgroups would last as long as its longest member.
+  const int per_group = p.num_kv_heads * p.group_tiles * p.batch;
+  const int qgroup = (int)(gridDim.x / per_group) - 1 - (int)(blockIdx.x / per_group);
+  const int rest = blockIdx.x % per_group;
+  const int pair = rest % (p.num_kv_heads * p.group_tiles);
+  const int seq = rest / (p.num_kv_heads * p.group_tiles);
   const int n = p.context_lens[seq];
   const int ql = min(p.query_lens[seq], n);
-  const int q0 = blockIdx.x * kQueryPerGroup;          // first query token of this workgroup
+  const int q0 = qgroup * kQueryPerGroup;              // first query token of this workgroup
   if (ql <= 0 || q0 >= ql) return;                     // uniform over the workgroup
   const int pos0 = n - ql;                             // position of the chunk's first token
-  const int kvh = blockIdx.y / p.group_tiles, gtile = blockIdx.y - kvh * p.group_tiles;
+  const int kvh = pair / p.group_tiles, gtile = pair - kvh * p.group_tiles;
   const int h0 = kvh * p.group + gtile * NG;
   const int nheads = min(NG, p.group - gtile * NG);
 
@@ -113,16 +125,25 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_mfma_d128(const Attn
   const int tile_mask = (1 << p.tpb_shift) - 1;
   const int32_t* table = p.block_tables + (int64_t)seq * p.max_blocks_per_seq;
 
-  // block ids of up to 64 tiles at a time, one per lane
-  int ids = 0;
-  auto load_ids = [&](int t0) { ids = table[min(t0 + lane, ntiles - 1) >> p.tpb_shift]; };
+  // The sequence's block ids go to LDS once (a vector load inside the tile loop would make the
+  // compiler wait for every fetch in flight before its value is used).
+  {
+    const int nblk = ((ntiles - 1) >> p.tpb_shift) + 1;
+    for (int i = tid; i < nblk; i += kThreads) ids_lds[i] = table[i];
+    __syncthreads();
+  }
+  const uint32_t ids_base = (uint32_t)(uintptr_t)(lptr_t)ids_lds;
 
-  auto issue = [&](int j, int stage) {
-    const int64_t blk = __builtin_amdgcn_readlane(ids, j & 63);
+  auto issue = [&](int j) {
+    int blk_v;
+    asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)"
+                 : "=v"(blk_v) : "v"(ids_base + 4u * (uint32_t)(j >> p.tpb_shift)) : "memory");
+    const int64_t blk = __builtin_amdgcn_readfirstlane(blk_v);
     const int slot0 = (j & tile_mask) * kTileTokens;
     const uint8_t* base = fetch_v ? vpool + blk * p.v_stride_block + kvh * p.v_stride_head + slot0 * p.v_stride_token
                                   : kpool + blk * p.k_stride_block + kvh * p.k_stride_head + slot0 * p.k_stride_token;
-    __builtin_amdgcn_global_load_lds((gptr_t)(base + foff), (lptr_t)(ring + stage * kStageBytes + fdst), 16, 0, 2);
+    __builtin_amdgcn_global_load_lds((gptr_t)(base + foff),
+                                     (lptr_t)(ring + (j & (kStages - 1)) * kStageBytes + fdst), 16, 0, 2);
   };
 
   // ---- query rows as B operands: column t16 = query token qi, one fragment set per head -------
@@ -152,8 +173,13 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_mfma_d128(const Attn
     for (int nb = 0; nb < 8; ++nb) acc[g][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
-  auto consume = [&](int j, auto stage_tag) {
-    constexpr int STAGE = decltype(stage_tag)::value;
+  auto consume = [&](int j) {
+    const uint32_t soff = (uint32_t)((j & (kStages - 1)) * kStageBytes);
+    uint32_t ka[4], va[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) ka[i] = krd[i] + soff;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) va[i] = vrd[i] + soff;
     // K as A operand (row-per-lane 16-byte reads) and V as B operand (transposing reads).  All
     // twelve LDS reads are issued by hand: the compiler would put a wait for every outstanding
     // direct-to-LDS load, i.e. for the tile in flight, in front of reads it cannot tell apart
@@ -176,9 +202,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_mfma_d128(const Attn
         "s_waitcnt lgkmcnt(0)"
         : "=&v"(kraw[0]), "=&v"(kraw[1]), "=&v"(kraw[2]), "=&v"(kraw[3]), "=&v"(vt[0]), "=&v"(vt[1]),
           "=&v"(vt[2]), "=&v"(vt[3]), "=&v"(vt[4]), "=&v"(vt[5]), "=&v"(vt[6]), "=&v"(vt[7])
-        : "v"(krd[0]), "v"(krd[1]), "v"(krd[2]), "v"(krd[3]), "v"(vrd[0]), "v"(vrd[1]), "v"(vrd[2]),
-          "v"(vrd[3]), "v"(vrd[4]), "v"(vrd[5]), "v"(vrd[6]), "v"(vrd[7]), "n"(STAGE * kStageBytes),
-          "n"(STAGE * kStageBytes + kTileBytes)
+        : "v"(ka[0]), "v"(ka[1]), "v"(ka[2]), "v"(ka[3]), "v"(va[0]), "v"(va[1]), "v"(va[2]),
+          "v"(va[3]), "v"(va[4]), "v"(va[5]), "v"(va[6]), "v"(va[7]), "n"(0), "n"(kTileBytes)
         : "memory");
     bf16x8 kf[4];
 #pragma unroll
@@ -252,28 +277,22 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_mfma_d128(const Attn
     }
   };
 
-  // ---- walk the tiles: fetch j+1 while j is consumed ------------------------------------------
-  using stage0 = std::integral_constant<int, 0>;
-  using stage1 = std::integral_constant<int, 1>;
-  load_ids(0);
-  issue(0, 0);
+  // ---- walk the tiles: three fetches in flight behind the tile in use ----------------------------
+  for (int j = 0; j < min(kStages - 1, ntiles); ++j) issue(j);
   for (int j = 0; j < ntiles; ++j) {
-    if (j + 1 < ntiles) {
-      if (((j + 1) & 63) == 0) load_ids(j + 1);
-      issue(j + 1, (j + 1) & 1);
-      PKV_PF_WAIT_VMCNT(1);
-    } else {
-      PKV_PF_WAIT_VMCNT(0);
-    }
-    // Bare barriers: the data they order is in LDS and is complete by the waits above (own
-    // share of the tile) and by data dependence (LDS reads feed the matrix cores before the
-    // second barrier); a full __syncthreads() would also wait for the tile in flight.
-    asm volatile("s_barrier" ::: "memory");   // every wavefront's share of tile j has landed
-    if (j <= wave_last_tile) {
-      if (j & 1) consume(j, stage1{});
-      else consume(j, stage0{});
-    }
-    asm volatile("s_barrier" ::: "memory");   // tile j is consumed: its stage may be refilled
+    // this wavefront's share of tile j has landed once at most the younger fetches are pending
+    // (loads complete in order)
+    const int younger = min(kStages - 2, ntiles - 1 - j);
+    if (younger >= 2) PKV_PF_WAIT_VMCNT(2);
+    else if (younger == 1) PKV_PF_WAIT_VMCNT(1);
+    else PKV_PF_WAIT_VMCNT(0);
+    // A bare barrier: what it orders is in LDS and complete by the wait above and by data
+    // dependence (the LDS reads of the previous tile fed the matrix cores before this point);
+    // __syncthreads() would also wait for the fetches in flight.  After it every wavefront's
+    // share of tile j is there, and everybody is done with tile j-1, whose stage is refilled.
+    asm volatile("s_barrier" ::: "memory");
+    if (j + kStages - 1 < ntiles) issue(j + kStages - 1);
+    if (j <= wave_last_tile) consume(j);
   }
 
   // ---- normalise and store ------------------------------------------------------------------------
@@ -307,21 +326,35 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_mfma_d128(const Attn
 
 }  // namespace
 
-// bf16, head_dim 128, power-of-two block size / 16
+// bf16, head_dim 128, power-of-two block size / 16, block table row of the longest context in LDS
 bool attn_prefill_supported(const pkv_attn_desc& d) {
   const int tpb = d.block_size / kTileTokens;
-  return d.kv_dtype == PKV_BF16 && d.head_dim == 128 && tpb >= 1 && (tpb & (tpb - 1)) == 0;
+  const int64_t ids_bytes = ((int64_t)d.max_context_len + d.block_size - 1) / d.block_size * 4 + 16;
+  return d.kv_dtype == PKV_BF16 && d.head_dim == 128 && tpb >= 1 && (tpb & (tpb - 1)) == 0 &&
+         ids_bytes <= kMaxIdsBytes;
 }
 
-hipError_t launch_attn_prefill(AttnParams& p, int max_query_len, hipStream_t s) {
+hipError_t launch_attn_prefill(AttnParams& p, int max_query_len, int max_context_len, hipStream_t s) {
   p.tpb_shift = 0;
   while ((kTileTokens << p.tpb_shift) < p.block_size) ++p.tpb_shift;
   const int ng = p.group == 1 ? 1 : 2;
   p.group_tiles = (p.group + ng - 1) / ng;
-  const dim3 grid((unsigned)((max_query_len + kQueryPerGroup - 1) / kQueryPerGroup),
-                  (unsigned)(p.num_kv_heads * p.group_tiles), (unsigned)p.batch);
-  if (ng == 1) hipLaunchKernelGGL((attn_prefill_mfma_d128<1>), grid, dim3(kThreads), 0, s, p);
-  else hipLaunchKernelGGL((attn_prefill_mfma_d128<2>), grid, dim3(kThreads), 0, s, p);
+  const int64_t nwg = (int64_t)((max_query_len + kQueryPerGroup - 1) / kQueryPerGroup) * p.num_kv_heads *
+                      p.group_tiles * p.batch;
+  if (nwg > 0x7FFFFFFF) return hipErrorInvalidValue;
+  const dim3 grid((unsigned)nwg);
+  const size_t ids_bytes = (size_t)((max_context_len + p.block_size - 1) / p.block_size) * 4 + 16;
+  static bool prepared = false;   // static + dynamic LDS may exceed 64 KiB: ask once
+  if (!prepared) {
+    for (const void* f : {reinterpret_cast<const void*>(&attn_prefill_mfma_d128<1>),
+                          reinterpret_cast<const void*>(&attn_prefill_mfma_d128<2>)}) {
+      const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxIdsBytes);
+      if (e != hipSuccess) return e;
+    }
+    prepared = true;
+  }
+  if (ng == 1) hipLaunchKernelGGL((attn_prefill_mfma_d128<1>), grid, dim3(kThreads), ids_bytes, s, p);
+  else hipLaunchKernelGGL((attn_prefill_mfma_d128<2>), grid, dim3(kThreads), ids_bytes, s, p);
   return hipGetLastError();
 }
 

@@ -70,7 +70,7 @@ hipError_t launch_attn_stream(AttnParams& p, hipStream_t s);
 hipError_t launch_swap(const SwapParams& p, hipStream_t s);
 // attn_prefill_mfma.hip
 bool attn_prefill_supported(const pkv_attn_desc& d);
-hipError_t launch_attn_prefill(AttnParams& p, int max_query_len, hipStream_t s);
+hipError_t launch_attn_prefill(AttnParams& p, int max_query_len, int max_context_len, hipStream_t s);
 // append.hip (uses the pointers, strides and shapes of AttnParams; q/out unused)
 hipError_t launch_kv_append(const AttnParams& p, const void* k_new, const void* v_new, int elem_bytes,
                             hipStream_t s);
