@@ -222,6 +222,42 @@ def time_swap_host(sw, torch, binding, staging_mib=256, reps=2):
     return res
 
 
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 matrix-core rate
+
+
+def time_prefill(torch, binding, B=16, n=4096, Hq=32, Hkv=8, reps=5):
+    """Re-prefill of B preempted requests of n tokens each (the recompute recovery path): causal
+    attention of all n tokens over the paged cache, 8B-shaped heads.  Flops counted: 4*D per
+    (query, visible key) pair and query head, i.e. the causal half only."""
+    D, bs = 128, 16
+    nblk = B * ((n + bs - 1) // bs)
+    g = torch.Generator(device="cuda:0")
+    g.manual_seed(1006)
+    kp = torch.randn(nblk, Hkv, bs, D, device="cuda:0", generator=g).bfloat16()
+    vp = torch.randn(nblk, Hkv, bs, D, device="cuda:0", generator=g).bfloat16()
+    bt = torch.randperm(nblk, device="cuda:0", generator=g).int().view(B, -1)
+    cl = torch.full((B,), n, dtype=torch.int32, device="cuda:0")
+    cu = torch.arange(0, (B + 1) * n, n, dtype=torch.int32, device="cuda:0")
+    q = torch.randn(B * n, Hq, D, device="cuda:0", generator=g).bfloat16()
+    out = torch.empty(B * n, Hq, D, device="cuda:0")
+    desc = binding.attn_desc_for(q, kp, vp, bt, max_context_len=n)
+    desc.batch = B
+    f = lambda: binding.paged_prefill_attention(desc, q, kp, vp, bt, cl, cl, cu, n, D ** -0.5, out)
+    f()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        f()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    flops = 4.0 * D * (n * (n + 1) // 2) * Hq * B
+    return {"workload": f"causal re-prefill, {B} sequences x {n} tokens, {Hq}/{Hkv} heads, bf16", "ms": ms,
+            "tflops": flops / ms / 1e9, "bound": "mfma", "peak_tflops": MFMA_BF16_PEAK_TFLOPS,
+            "frac": flops / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS}
+
+
 def probe_ceilings(torch, binding, nbytes=4 << 30, reps=5):
     a = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0").random_(0, 255)
     b = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
@@ -321,6 +357,8 @@ def main():
     result["kv_append"] = time_append(w, d, torch, binding)
     log(f"[bench] append ahead of attention: {result['kv_append']}")
     result["ceilings"] = probe_ceilings(torch, binding)
+    result["prefill"] = time_prefill(torch, binding)
+    log(f"[bench] prefill: {result['prefill']}")
     log(f"[bench] ceilings: {result['ceilings']}")
 
     if not args.no_cpu:
