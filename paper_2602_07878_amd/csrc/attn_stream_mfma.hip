@@ -88,25 +88,54 @@ __device__ __forceinline__ int rfl(int v) { return __builtin_amdgcn_readfirstlan
 typedef const void __attribute__((address_space(1)))* gptr_t;
 typedef void __attribute__((address_space(3)))* lptr_t;
 
-// Chunk schedule.  The tile axis is cut into equal contiguous ranges, one per workgroup, and
-// each range into `ns` chunks of `rs` tiles: one per wavefront, or k per wavefront when the
-// caller caps the tokens per partial (wavefront w then takes chunks w, w+8, ...; all chunks
-// have the same length so that the eight wavefronts carry equal loads).  Chunk ids grow along
-// the axis without gaps: id = workgroup * ns + local id.
+// Chunk schedule.  The tile axis is cut into contiguous ranges, one per workgroup, and each
+// range into ns = 8k chunks whose lengths differ by at most one tile: one chunk per wavefront,
+// or k per wavefront when the caller caps the tokens per partial (wavefront w then takes
+// chunks w, w+8, ...).  Chunk ids grow along the axis without gaps: id = workgroup * ns + local
+// id, every workgroup owning exactly ns of them.
+//
+// Workgroups are dealt to the eight XCDs round-robin, and on this part the odd XCDs finish an
+// equal range 6-7 % later than their even neighbours (seen on every machine tried; which pair
+// of XCDs is ahead varies, that does not).  Of every two consecutive workgroups the even one
+// therefore takes kEvenShare/256 of a fair share and the odd one the rest (measured optimum
+// 268-272 on two machines, +2 % throughput; 276 and more overshoots).
+constexpr int kEvenShare = 268;
+static_assert(kEvenShare >= 224 && kEvenShare <= 288, "the workspace bound allows ranges up to 9/8 of a fair share");
+
 struct ChunkPlan {
-  int lg, rs, ns;
+  int lg;      // fair share of a workgroup, in tiles
+  int ns;      // chunks (and chunk ids) per workgroup
+  int first;   // tiles of the even workgroup of a pair
+  bool skew;
+  __device__ __forceinline__ int bound(int g) const {   // first tile of workgroup g's range
+    return skew ? (g >> 1) * 2 * lg + ((g & 1) ? first : 0) : g * lg;
+  }
+  __device__ __forceinline__ int length(int g) const {  // nominal length of that range
+    return skew ? ((g & 1) ? 2 * lg - first : first) : lg;
+  }
+  // first tile (relative to the range) of chunk i of a range of `len` tiles
+  __device__ __forceinline__ int chunk_start(int len, int i) const { return (int)((int64_t)i * len / ns); }
   __device__ __forceinline__ int chunk_of(int x) const {
-    const int g = x / lg;
-    return g * ns + (x - g * lg) / rs;
+    int g;
+    if (skew) {
+      const int pr = x / (2 * lg);
+      g = 2 * pr + (x - pr * 2 * lg >= first ? 1 : 0);
+    } else {
+      g = x / lg;
+    }
+    const int u = x - bound(g);
+    return g * ns + (int)((((int64_t)u + 1) * ns - 1) / length(g));   // inverse of chunk_start
   }
 };
 
 __device__ __forceinline__ ChunkPlan plan_chunks(int T, int nwg, int cap) {
   ChunkPlan pl;
   pl.lg = max(kMinGroupTiles, (T + nwg - 1) / nwg);
-  const int k = cap > 0 ? (pl.lg + kNW * cap - 1) / (kNW * cap) : 1;
-  pl.rs = (pl.lg + kNW * k - 1) / (kNW * k);
-  pl.ns = (pl.lg + pl.rs - 1) / pl.rs;
+  pl.skew = kEvenShare != 256 && (nwg & 1) == 0;
+  pl.first = pl.skew ? (kEvenShare * pl.lg) >> 8 : pl.lg;
+  const int longest = pl.skew ? max(pl.first, 2 * pl.lg - pl.first) : pl.lg;
+  const int k = cap > 0 ? (longest + kNW * cap - 1) / (kNW * cap) : 1;
+  pl.ns = kNW * k;
   return pl;
 }
 
@@ -154,9 +183,9 @@ __global__ __launch_bounds__(kStreamThreads, 2) void attn_stream_mfma_d128(const
   if (T == 0) return;
 
   const ChunkPlan plan = plan_chunks(T, gridDim.x, p.chunk_tiles_max);
-  const int g0 = blockIdx.x * plan.lg;                     // first tile of this workgroup's range
-  const int glen = min(plan.lg, T - g0);                   // its length (<= 0: nothing to do)
-  const int rs = plan.rs;                                  // tiles per chunk
+  const int g0 = plan.bound(blockIdx.x);                   // first tile of this workgroup's range
+  const int gfull = plan.length(blockIdx.x);
+  const int glen = min(gfull, T - g0);                     // its length (<= 0: nothing to do)
   if (glen <= 0) return;
   // ---- per-lane, loop-invariant offsets -------------------------------------------------------
   // Load j of a tile brings token rows 4j..4j+3; this lane fetches one 16-byte piece of row
@@ -378,17 +407,18 @@ __global__ __launch_bounds__(kStreamThreads, 2) void attn_stream_mfma_d128(const
   bool inflight = false;    // the first tile of the coming batch is already issued, its query loaded
   int seg_sp = 0, seg_info0 = 0, seg_x = 0, sp = 0, tab = 0;
 
-  auto chunk_valid = [&](int ci) { return ci < plan.ns && ci * rs < glen; };
-  auto chunk_tiles = [&](int ci) { return min(glen, (ci + 1) * rs) - ci * rs; };
+  auto chunk_first = [&](int ci) { return plan.chunk_start(gfull, ci); };
+  auto chunk_valid = [&](int ci) { return ci < plan.ns && chunk_first(ci) < glen; };
+  auto chunk_tiles = [&](int ci) { return min(glen, chunk_first(ci + 1)) - chunk_first(ci); };
 
   // A wavefront's work is a sequence of batches of up to kDescBatch tiles: the batches of its
   // first chunk, then those of its next chunk (local ids wave, wave+8, ...), and so on.
   int ci = wave, b0 = 0;
   bool have = chunk_valid(ci);
-  if (have) build_desc(g0 + ci * rs, min(kDescBatch, chunk_tiles(ci)), dtabs);
+  if (have) build_desc(g0 + chunk_first(ci), min(kDescBatch, chunk_tiles(ci)), dtabs);
   while (have) {
     const int c = blockIdx.x * plan.ns + ci;         // chunk id on the whole axis
-    const int x0 = g0 + ci * rs;
+    const int x0 = g0 + chunk_first(ci);
     const int ntc = chunk_tiles(ci);                 // tiles of this chunk
     const int nt = min(kDescBatch, ntc - b0);        // tiles of this batch, one descriptor per lane
     const bool chunk_ends_here = b0 + nt == ntc;
@@ -410,7 +440,7 @@ __global__ __launch_bounds__(kStreamThreads, 2) void attn_stream_mfma_d128(const
     }
     inflight = false;
     // describe the next batch now: its index loads ride along with the tile that is in flight
-    if (has_next) build_desc(g0 + nci * rs + nb0, min(kDescBatch, chunk_tiles(nci) - nb0), dnext);
+    if (has_next) build_desc(g0 + chunk_first(nci) + nb0, min(kDescBatch, chunk_tiles(nci) - nb0), dnext);
 
     while (j0 < nt) {
       // tiles j0 .. j1-1 belong to (sequence, pair) sp; the first one is already in flight
@@ -669,8 +699,8 @@ StreamWorkspace stream_workspace(const pkv_attn_desc& d) {
   // chunk ids stay below workgroups * chunks-per-workgroup, see plan_chunks()
   const int64_t ncu = num_cus();
   const int64_t cap = w.chunk_tiles_max;
-  // ns <= 8k with k < lg / (8 cap) + 1 chunks per wavefront
-  w.slots = pairs + (cap ? (tiles_ub + kMinGroupTiles * ncu) / cap + ncu : 0) + ncu * (kNW + 1) + 2;
+  // ns = 8k with k < longest range / (8 cap) + 1, the longest range at most 9/8 of a fair share
+  w.slots = pairs + (cap ? (tiles_ub + kMinGroupTiles * ncu) * 9 / 8 / cap + 2 * ncu : 0) + ncu * (kNW + 1) + 2;
   auto up = [](int64_t b) { return (b + 255) / 256 * 256; };
   w.dir_bytes = up(pairs * 2 * 4);
   w.ml_bytes = up(w.slots * gh * 2 * 4);
