@@ -14,17 +14,17 @@
 // sequence and up to two query heads of one KV head; each wavefront owns 16 of those
 // tokens.  The workgroup walks the K/V tiles 0 .. (its last position)/16 once: the eight
 // wavefronts fetch one tile together with direct-to-LDS loads (four fetch K rows, four V
-// rows) into a 4-deep ring, three tiles ahead of the one in use, and all of them consume it
-// from LDS; one barrier per tile orders the ring.  A wavefront skips the tiles that lie
-// entirely in its future.
+// rows) into a ring of four tiles: the pair in use and the pair in flight, and all of them
+// consume it from LDS; one barrier per pair orders the ring.  A wavefront skips the pairs
+// that lie entirely in its future.
 //
-// Per tile and head (same tile code as the decode kernel, with the 16 MFMA columns now
+// Per pair of tiles and head (the decode kernel's tile code, with the 16 MFMA columns now
 // holding 16 query tokens of one head instead of the heads of one token):
-//   S^T[token][query] = K Q^T   4 x v_mfma_f32_16x16x32_bf16
+//   S^T[token][query] = K Q^T   2 x 4 x v_mfma_f32_16x16x32_bf16
 //   causal mask, lazy-max base-2 softmax in fp32 (no cross-lane traffic unless the
 //   reference maximum has to be raised)
-//   O[query][dim] += P V        2 x 8 x v_mfma_f32_16x16x16_bf16, P split into a bf16 head
-//   and a bf16 remainder, V through the transposing LDS read.
+//   O[query][dim] += P V        2 x 8 x v_mfma_f32_16x16x32_bf16 over the 32 tokens of the
+//   pair, P split into a bf16 head and a bf16 remainder, V through the transposing LDS read.
 
 #include <type_traits>
 
@@ -173,78 +173,132 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_mfma_d128(const Attn
     for (int nb = 0; nb < 8; ++nb) acc[g][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
-  auto consume = [&](int j) {
-    const uint32_t soff = (uint32_t)((j & (kStages - 1)) * kStageBytes);
-    uint32_t ka[4], va[8];
+  // Two tiles (32 tokens) per step, so that P.V can use the 16x16x32 shape: of the eight
+  // k-values a lane feeds, four are its tokens of tile A and four its tokens of tile B, for
+  // the weights and for V alike.  have_b is false for the odd tile at the end of the walk.
+  auto consume = [&](int j, bool have_b) {
+    const uint32_t soff_a = (uint32_t)((j & (kStages - 1)) * kStageBytes);
+    const uint32_t soff_b = (uint32_t)(((j + 1) & (kStages - 1)) * kStageBytes);
+    const int kpos_a = j * kTileTokens + 4 * q4;         // position of this lane's first token of tile A
+    const int kpos_b = kpos_a + kTileTokens;
+
+    // All LDS reads are issued by hand: the compiler would put a wait for every outstanding
+    // direct-to-LDS load, i.e. for the tiles in flight, in front of reads it cannot tell apart
+    // from the ring.  The data is complete: the barrier before this call covered both tiles.
+    auto read_k = [&](uint32_t soff, bf16x8* kf) {
+      u32x4 raw[4];
+      asm volatile(
+          "ds_read_b128 %0, %4\n\t"
+          "ds_read_b128 %1, %5\n\t"
+          "ds_read_b128 %2, %6\n\t"
+          "ds_read_b128 %3, %7\n\t"
+          "s_waitcnt lgkmcnt(0)"
+          : "=&v"(raw[0]), "=&v"(raw[1]), "=&v"(raw[2]), "=&v"(raw[3])
+          : "v"(krd[0] + soff), "v"(krd[1] + soff), "v"(krd[2] + soff), "v"(krd[3] + soff)
+          : "memory");
 #pragma unroll
-    for (int i = 0; i < 4; ++i) ka[i] = krd[i] + soff;
+      for (int i = 0; i < 4; ++i) kf[i] = __builtin_bit_cast(bf16x8, raw[i]);
+    };
+    auto read_v = [&](uint32_t soff, u32x2* vt) {
+      asm volatile(
+          "ds_read_b64_tr_b16 %0, %8 offset:%16\n\t"
+          "ds_read_b64_tr_b16 %1, %9 offset:%16\n\t"
+          "ds_read_b64_tr_b16 %2, %10 offset:%16\n\t"
+          "ds_read_b64_tr_b16 %3, %11 offset:%16\n\t"
+          "ds_read_b64_tr_b16 %4, %12 offset:%16\n\t"
+          "ds_read_b64_tr_b16 %5, %13 offset:%16\n\t"
+          "ds_read_b64_tr_b16 %6, %14 offset:%16\n\t"
+          "ds_read_b64_tr_b16 %7, %15 offset:%16\n\t"
+          "s_waitcnt lgkmcnt(0)"
+          : "=&v"(vt[0]), "=&v"(vt[1]), "=&v"(vt[2]), "=&v"(vt[3]), "=&v"(vt[4]), "=&v"(vt[5]),
+            "=&v"(vt[6]), "=&v"(vt[7])
+          : "v"(vrd[0] + soff), "v"(vrd[1] + soff), "v"(vrd[2] + soff), "v"(vrd[3] + soff),
+            "v"(vrd[4] + soff), "v"(vrd[5] + soff), "v"(vrd[6] + soff), "v"(vrd[7] + soff), "n"(kTileBytes)
+          : "memory");
+    };
+
+    // scores of both tiles, all heads: cfr[g][0] = tile A, cfr[g][1] = tile B
+    f32x4 cfr[NG][2];
+    {
+      bf16x8 kf[4];
+      read_k(soff_a, kf);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) va[i] = vrd[i] + soff;
-    // K as A operand (row-per-lane 16-byte reads) and V as B operand (transposing reads).  All
-    // twelve LDS reads are issued by hand: the compiler would put a wait for every outstanding
-    // direct-to-LDS load, i.e. for the tile in flight, in front of reads it cannot tell apart
-    // from the ring.  The data is complete: the barrier before this call covered the tile.
-    u32x4 kraw[4];
-    u32x2 vt[8];
-    asm volatile(
-        "ds_read_b128 %0, %12 offset:%24\n\t"
-        "ds_read_b128 %1, %13 offset:%24\n\t"
-        "ds_read_b128 %2, %14 offset:%24\n\t"
-        "ds_read_b128 %3, %15 offset:%24\n\t"
-        "ds_read_b64_tr_b16 %4, %16 offset:%25\n\t"
-        "ds_read_b64_tr_b16 %5, %17 offset:%25\n\t"
-        "ds_read_b64_tr_b16 %6, %18 offset:%25\n\t"
-        "ds_read_b64_tr_b16 %7, %19 offset:%25\n\t"
-        "ds_read_b64_tr_b16 %8, %20 offset:%25\n\t"
-        "ds_read_b64_tr_b16 %9, %21 offset:%25\n\t"
-        "ds_read_b64_tr_b16 %10, %22 offset:%25\n\t"
-        "ds_read_b64_tr_b16 %11, %23 offset:%25\n\t"
-        "s_waitcnt lgkmcnt(0)"
-        : "=&v"(kraw[0]), "=&v"(kraw[1]), "=&v"(kraw[2]), "=&v"(kraw[3]), "=&v"(vt[0]), "=&v"(vt[1]),
-          "=&v"(vt[2]), "=&v"(vt[3]), "=&v"(vt[4]), "=&v"(vt[5]), "=&v"(vt[6]), "=&v"(vt[7])
-        : "v"(ka[0]), "v"(ka[1]), "v"(ka[2]), "v"(ka[3]), "v"(va[0]), "v"(va[1]), "v"(va[2]),
-          "v"(va[3]), "v"(va[4]), "v"(va[5]), "v"(va[6]), "v"(va[7]), "n"(0), "n"(kTileBytes)
-        : "memory");
-    bf16x8 kf[4];
+      for (int g = 0; g < NG; ++g) {
+        cfr[g][0] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int jj = 0; jj < 4; ++jj) kf[jj] = __builtin_bit_cast(bf16x8, kraw[jj]);
-    const int kpos0 = j * kTileTokens + 4 * q4;          // position of this lane's first K token
-    if (j * kTileTokens + kTileTokens > n) {             // last tile: rows past the context may be NaN
-      const uint32_t keep0 = (kpos0 + 0 < n ? 0x0000FFFFu : 0u) | (kpos0 + 1 < n ? 0xFFFF0000u : 0u);
-      const uint32_t keep1 = (kpos0 + 2 < n ? 0x0000FFFFu : 0u) | (kpos0 + 3 < n ? 0xFFFF0000u : 0u);
+        for (int jj = 0; jj < 4; ++jj)
+          cfr[g][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[jj], qfrag[g][jj], cfr[g][0], 0, 0, 0);
+      }
+      if (have_b) {
+        read_k(soff_b, kf);
 #pragma unroll
-      for (int nb = 0; nb < 8; ++nb) { vt[nb][0] &= keep0; vt[nb][1] &= keep1; }
+        for (int g = 0; g < NG; ++g) {
+          cfr[g][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int jj = 0; jj < 4; ++jj)
+            cfr[g][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[jj], qfrag[g][jj], cfr[g][1], 0, 0, 0);
+        }
+      } else {
+#pragma unroll
+        for (int g = 0; g < NG; ++g) cfr[g][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+      }
     }
+
+    // V of both tiles as one B operand per 16 output dims; rows past the context (they may
+    // hold NaN) and the absent tile B are zero
+    bf16x8 vop[8];
+    {
+      u32x2 va[8], vb[8];
+      read_v(soff_a, va);
+      if (have_b) {
+        read_v(soff_b, vb);
+      } else {
+#pragma unroll
+        for (int nb = 0; nb < 8; ++nb) vb[nb] = u32x2{0u, 0u};
+      }
+      if ((j + 2) * kTileTokens > n) {   // some row of the pair is past the context (wave-uniform)
+        const uint32_t a0 = (kpos_a + 0 < n ? 0x0000FFFFu : 0u) | (kpos_a + 1 < n ? 0xFFFF0000u : 0u);
+        const uint32_t a1 = (kpos_a + 2 < n ? 0x0000FFFFu : 0u) | (kpos_a + 3 < n ? 0xFFFF0000u : 0u);
+        const uint32_t b0 = (kpos_b + 0 < n ? 0x0000FFFFu : 0u) | (kpos_b + 1 < n ? 0xFFFF0000u : 0u);
+        const uint32_t b1 = (kpos_b + 2 < n ? 0x0000FFFFu : 0u) | (kpos_b + 3 < n ? 0xFFFF0000u : 0u);
+#pragma unroll
+        for (int nb = 0; nb < 8; ++nb) { va[nb][0] &= a0; va[nb][1] &= a1; vb[nb][0] &= b0; vb[nb][1] &= b1; }
+      }
+#pragma unroll
+      for (int nb = 0; nb < 8; ++nb)
+        vop[nb] = __builtin_bit_cast(bf16x8, u32x4{va[nb][0], va[nb][1], vb[nb][0], vb[nb][1]});
+    }
+
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
       if (g < nheads) {
-        f32x4 cfr = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int jj = 0; jj < 4; ++jj)
-          cfr = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[jj], qfrag[g][jj], cfr, 0, 0, 0);
-        // cfr[r] = q(query t16) . k(token kpos0 + r); causal: a query sees positions <= its own
-        float d[4];
+        // d = score - reference in log2 units; causal: a query sees positions <= its own
+        float d[8];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          d[r] = fmaf(cfr[r], p.scale_log2e, -m_ref[g]);
-          if (kpos0 + r > qpos) d[r] = -INFINITY;
+          d[r] = fmaf(cfr[g][0][r], p.scale_log2e, -m_ref[g]);
+          if (kpos_a + r > qpos) d[r] = -INFINITY;
+          d[4 + r] = fmaf(cfr[g][1][r], p.scale_log2e, -m_ref[g]);
+          if (kpos_b + r > qpos || !have_b) d[4 + r] = -INFINITY;
         }
-        const float dmax = fmaxf(fmaxf(d[0], d[1]), fmaxf(d[2], d[3]));
-        if (__builtin_amdgcn_ballot_w64(dmax > kSlack) != 0) {
-          float s[4];
+        const float dmax = fmaxf(fmaxf(fmaxf(d[0], d[1]), fmaxf(d[2], d[3])), fmaxf(fmaxf(d[4], d[5]), fmaxf(d[6], d[7])));
+        if (__builtin_amdgcn_ballot_w64(dmax > kSlack) != 0) {   // wave-uniform, rare after the first tiles
+          float s[8];
 #pragma unroll
           for (int r = 0; r < 4; ++r) {
-            s[r] = cfr[r] * p.scale_log2e;
-            if (kpos0 + r > qpos) s[r] = -INFINITY;
+            s[r] = cfr[g][0][r] * p.scale_log2e;
+            if (kpos_a + r > qpos) s[r] = -INFINITY;
+            s[4 + r] = cfr[g][1][r] * p.scale_log2e;
+            if (kpos_b + r > qpos || !have_b) s[4 + r] = -INFINITY;
           }
-          xchg[q4 * 16 + t16] = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
+          xchg[q4 * 16 + t16] = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
           const float tm = fmaxf(fmaxf(xchg[t16], xchg[16 + t16]), fmaxf(xchg[32 + t16], xchg[48 + t16]));
           const float mn = fmaxf(m_ref[g], tm);
           const float alpha = __builtin_amdgcn_exp2f(m_ref[g] - mn);
           m_ref[g] = mn;
           l_part[g] *= alpha;
 #pragma unroll
-          for (int r = 0; r < 4; ++r) d[r] = s[r] - mn;
+          for (int r = 0; r < 8; ++r) d[r] = s[r] - mn;
           xchg[64 + t16] = alpha;   // accumulator rows of this lane are queries 4q4..4q4+3
           const f32x4 a = *reinterpret_cast<const f32x4*>(xchg + 64 + 4 * q4);
 #pragma unroll
@@ -252,10 +306,11 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_mfma_d128(const Attn
 #pragma unroll
             for (int r = 0; r < 4; ++r) acc[g][nb][r] *= a[r];
         }
-        uint32_t hi[4], lo[4];
+        // weights, split into a bf16 head and a rounded bf16 remainder
+        uint32_t hi[8], lo[8];
         float psum = 0.f;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
+        for (int r = 0; r < 8; ++r) {
           const float pw = __builtin_amdgcn_exp2f(d[r]);
           psum += pw;
           hi[r] = __builtin_bit_cast(uint32_t, pw);
@@ -263,36 +318,36 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_mfma_d128(const Attn
           lo[r] = __builtin_bit_cast(uint32_t, rest) + 0x8000u;
         }
         l_part[g] += psum;
-        const s16x4 p_hi = __builtin_bit_cast(s16x4, u32x2{__builtin_amdgcn_perm(hi[1], hi[0], 0x07060302u),
-                                                           __builtin_amdgcn_perm(hi[3], hi[2], 0x07060302u)});
-        const s16x4 p_lo = __builtin_bit_cast(s16x4, u32x2{__builtin_amdgcn_perm(lo[1], lo[0], 0x07060302u),
-                                                           __builtin_amdgcn_perm(lo[3], lo[2], 0x07060302u)});
+        const bf16x8 p_hi = __builtin_bit_cast(bf16x8, u32x4{
+            __builtin_amdgcn_perm(hi[1], hi[0], 0x07060302u), __builtin_amdgcn_perm(hi[3], hi[2], 0x07060302u),
+            __builtin_amdgcn_perm(hi[5], hi[4], 0x07060302u), __builtin_amdgcn_perm(hi[7], hi[6], 0x07060302u)});
+        const bf16x8 p_lo = __builtin_bit_cast(bf16x8, u32x4{
+            __builtin_amdgcn_perm(lo[1], lo[0], 0x07060302u), __builtin_amdgcn_perm(lo[3], lo[2], 0x07060302u),
+            __builtin_amdgcn_perm(lo[5], lo[4], 0x07060302u), __builtin_amdgcn_perm(lo[7], lo[6], 0x07060302u)});
 #pragma unroll
         for (int nb = 0; nb < 8; ++nb)
-          acc[g][nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_hi, __builtin_bit_cast(s16x4, vt[nb]), acc[g][nb], 0, 0, 0);
+          acc[g][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(p_hi, vop[nb], acc[g][nb], 0, 0, 0);
 #pragma unroll
         for (int nb = 0; nb < 8; ++nb)
-          acc[g][nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_lo, __builtin_bit_cast(s16x4, vt[nb]), acc[g][nb], 0, 0, 0);
+          acc[g][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(p_lo, vop[nb], acc[g][nb], 0, 0, 0);
       }
     }
   };
 
-  // ---- walk the tiles: three fetches in flight behind the tile in use ----------------------------
-  for (int j = 0; j < min(kStages - 1, ntiles); ++j) issue(j);
-  for (int j = 0; j < ntiles; ++j) {
-    // this wavefront's share of tile j has landed once at most the younger fetches are pending
-    // (loads complete in order)
-    const int younger = min(kStages - 2, ntiles - 1 - j);
-    if (younger >= 2) PKV_PF_WAIT_VMCNT(2);
-    else if (younger == 1) PKV_PF_WAIT_VMCNT(1);
-    else PKV_PF_WAIT_VMCNT(0);
+  // ---- walk the tiles in pairs: the next pair is fetched while this one is consumed --------------
+  issue(0);
+  if (ntiles > 1) issue(1);
+  for (int j = 0; j < ntiles; j += 2) {
+    PKV_PF_WAIT_VMCNT(0);   // this wavefront's shares of tiles j and j+1 have landed
     // A bare barrier: what it orders is in LDS and complete by the wait above and by data
-    // dependence (the LDS reads of the previous tile fed the matrix cores before this point);
-    // __syncthreads() would also wait for the fetches in flight.  After it every wavefront's
-    // share of tile j is there, and everybody is done with tile j-1, whose stage is refilled.
+    // dependence (the LDS reads of the previous pair fed the matrix cores before this point);
+    // __syncthreads() could not be told apart from it here, but says more than is meant.  After
+    // it every wavefront's share of the pair is there, and everybody is done with the previous
+    // pair, whose two stages are refilled now.
     asm volatile("s_barrier" ::: "memory");
-    if (j + kStages - 1 < ntiles) issue(j + kStages - 1);
-    if (j <= wave_last_tile) consume(j);
+    if (j + 2 < ntiles) issue(j + 2);
+    if (j + 3 < ntiles) issue(j + 3);
+    if (j <= wave_last_tile) consume(j, j + 1 < ntiles);
   }
 
   // ---- normalise and store ------------------------------------------------------------------------
