@@ -626,6 +626,60 @@ __global__ __launch_bounds__(kMergeThreads) void attn_stream_merge(const AttnPar
   }
 }
 
+// Merge for the library's own split, where a pair has a handful of partials: one workgroup per
+// (sequence, pair), one wavefront per query head, no LDS and no barrier.  A wavefront walks its
+// head's partials in ascending order, eight loads in flight, rescaling the running sums when
+// the reference maximum rises; lane covers output dims 2*lane and 2*lane+1.
+template <int GH>
+__global__ __launch_bounds__(GH * kWaveSize) void attn_stream_merge_lean(const AttnParams p) {
+  const int NP = p.num_kv_heads * p.group_tiles;
+  const int prank = blockIdx.x;
+  const int seq = prank / NP, pp = prank - seq * NP;
+  const int kvh = pp / p.group_tiles, gtile = pp - kvh * p.group_tiles;
+  const int lane = threadIdx.x & (kWaveSize - 1), g = threadIdx.x / kWaveSize;
+  if (gtile * GH + g >= p.group) return;               // wave-uniform
+  const int h = kvh * p.group + gtile * GH + g;
+  const int64_t o = ((int64_t)seq * p.num_q_heads + h) * D + 2 * lane;
+  auto store = [&](float a, float b) {
+    if (p.out_is_bf16) reinterpret_cast<uint32_t*>(p.out)[o / 2] = pack_bf16x2_rne(a, b);
+    else *reinterpret_cast<f32x2*>(reinterpret_cast<float*>(p.out) + o) = f32x2{a, b};
+  };
+  if (p.context_lens[seq] <= 0) { store(0.f, 0.f); return; }
+  const i32x2 de = *reinterpret_cast<const i32x2*>(p.ws_dir + 2 * (int64_t)prank);
+  const int count = de[1];
+  if (count <= 1) return;                               // finished by the stream kernel
+  const int64_t s0 = de[0];
+  const float* ml = p.ws_ml + (s0 * GH + g) * 2;            // partial q at ml[q*GH*2]
+  const float* ov = p.ws_o + (s0 * GH + g) * D + 2 * lane;  // partial q at ov[q*GH*D]
+  float M = kNegBig, L = 0.f, O0 = 0.f, O1 = 0.f;
+  for (int q0 = 0; q0 < count; q0 += 8) {
+    f32x2 mlq[8], oq[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const bool live = q0 + i < count;
+      const int64_t q = live ? q0 + i : q0;
+      mlq[i] = *reinterpret_cast<const f32x2*>(ml + q * GH * 2);
+      oq[i] = *reinterpret_cast<const f32x2*>(ov + q * GH * D);
+      if (!live) { mlq[i] = f32x2{kNegBig, 0.f}; oq[i] = f32x2{0.f, 0.f}; }
+    }
+    float Mb = M;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) Mb = fmaxf(Mb, mlq[i][0]);
+    const float fo = __builtin_amdgcn_exp2f(M - Mb);
+    L *= fo; O0 *= fo; O1 *= fo;
+    M = Mb;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float f = __builtin_amdgcn_exp2f(mlq[i][0] - M);
+      L = fmaf(mlq[i][1], f, L);
+      O0 = fmaf(oq[i][0], f, O0);
+      O1 = fmaf(oq[i][1], f, O1);
+    }
+  }
+  const float inv = 1.0f / L;
+  store(O0 * inv, O1 * inv);
+}
+
 int num_cus() {
   static int cached = 0;
   if (cached == 0) {
@@ -658,7 +712,11 @@ hipError_t launch(const AttnParams& p, hipStream_t s) {
     hipLaunchKernelGGL((attn_stream_mfma_d128<GH>), dim3(num_cus()), dim3(kStreamThreads), lds, s, p);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((attn_stream_merge<GH>), dim3(p.num_q_heads, p.batch), dim3(kMergeThreads), 0, s, p);
+  if (p.chunk_tiles_max == 0)   // the library's own split: few partials per pair
+    hipLaunchKernelGGL((attn_stream_merge_lean<GH>), dim3(p.batch * p.num_kv_heads * p.group_tiles),
+                       dim3(GH * kWaveSize), 0, s, p);
+  else
+    hipLaunchKernelGGL((attn_stream_merge<GH>), dim3(p.num_q_heads, p.batch), dim3(kMergeThreads), 0, s, p);
   return hipGetLastError();
 }
 
