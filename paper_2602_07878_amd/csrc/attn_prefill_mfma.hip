@@ -142,8 +142,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_mfma_d128(const Attn
     const int slot0 = (j & tile_mask) * kTileTokens;
     const uint8_t* base = fetch_v ? vpool + blk * p.v_stride_block + kvh * p.v_stride_head + slot0 * p.v_stride_token
                                   : kpool + blk * p.k_stride_block + kvh * p.k_stride_head + slot0 * p.k_stride_token;
+    // default cache policy: other workgroups (other query groups, the other head pair) read the
+    // same tile again, so unlike in the decode kernel it should stay in L2
     __builtin_amdgcn_global_load_lds((gptr_t)(base + foff),
-                                     (lptr_t)(ring + (j & (kStages - 1)) * kStageBytes + fdst), 16, 0, 2);
+                                     (lptr_t)(ring + (j & (kStages - 1)) * kStageBytes + fdst), 16, 0, 0);
   };
 
   // ---- query rows as B operands: column t16 = query token qi, one fragment set per head -------
