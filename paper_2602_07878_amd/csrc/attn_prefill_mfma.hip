@@ -10,11 +10,11 @@
 // Unlike decode this is a dense contraction with reuse: a 16-token K/V tile serves every
 // query row that may see it, so the matrix cores, not HBM, bound it.
 //
-// Work split.  A workgroup of 8 wavefronts takes 128 consecutive query tokens of one
-// sequence and up to two query heads of one KV head; each wavefront owns 16 of those
-// tokens.  The workgroup walks the K/V tiles 0 .. (its last position)/16 once: the eight
-// wavefronts fetch one tile together with direct-to-LDS loads (four fetch K rows, four V
-// rows) into a ring of four tiles: the pair in use and the pair in flight, and all of them
+// Work split.  A workgroup of 4 wavefronts takes 64 consecutive query tokens of one sequence
+// and up to two query heads of one KV head; each wavefront owns 16 of those tokens.  Two such
+// workgroups share a CU (8 wavefronts in one workgroup of 128 queries measured the same).  The workgroup walks the K/V tiles 0 .. (its last position)/16 once: the wavefronts
+// fetch one tile together with direct-to-LDS loads (a quarter of K and a quarter of V
+// each) into a ring of four tiles: the pair in use and the pair in flight, and all of them
 // consume it from LDS; one barrier per pair orders the ring.  A wavefront skips the pairs
 // that lie entirely in its future.
 //
@@ -42,7 +42,12 @@ typedef const void __attribute__((address_space(1)))* gptr_t;
 typedef void __attribute__((address_space(3)))* lptr_t;
 
 constexpr int D = 128;
-constexpr int kThreads = 512, kWaves = kThreads / kWaveSize;
+#ifndef PKV_PREFILL_THREADS
+#define PKV_PREFILL_THREADS 256
+#endif
+constexpr int kThreads = PKV_PREFILL_THREADS, kWaves = kThreads / kWaveSize;
+constexpr int kFetches = 8 / kWaves;       // quarter tiles (1 KiB) a wavefront fetches per tile: K has 4, V has 4
+static_assert(kWaves == 4 || kWaves == 8, "the eight quarter tiles are dealt to 4 or 8 wavefronts");
 constexpr int kQueryPerWave = 16, kQueryPerGroup = kWaves * kQueryPerWave;
 constexpr int kTileBytes = 4096, kStageBytes = 2 * kTileBytes;
 constexpr int kStages = 4;                 // K/V ring depth: three tiles in flight behind the one in use
@@ -103,12 +108,17 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_mfma_d128(const Attn
   const int wave_last_tile = wave_live ? (pos0 + min(ql, qw + kQueryPerWave) - 1) / kTileTokens : -1;
 
   // ---- per-lane offsets: same swizzled LDS images as the decode kernel -------------------------
-  // fetch: wavefront w < 4 brings K rows 4w..4w+3, wavefront w >= 4 brings V rows 4(w-4)..+3
-  const int frow = 4 * (wave & 3) + q4;
-  const bool fetch_v = wave >= 4;
-  const uint32_t foff = fetch_v ? (uint32_t)(frow * p.v_stride_token) + (uint32_t)((t16 ^ (2 * (frow & 7))) * 16)
-                                : (uint32_t)(frow * p.k_stride_token) + (uint32_t)((t16 ^ frow) * 16);
-  const uint32_t fdst = (uint32_t)((fetch_v ? kTileBytes : 0) + (wave & 3) * 1024);
+  // fetch: quarter tile f (rows 4f..4f+3) of K for f < 4, of V (rows 4(f-4)..) for f >= 4; the
+  // wavefronts share the eight quarters evenly
+  uint32_t foff[kFetches], fdst[kFetches];
+#pragma unroll
+  for (int i = 0; i < kFetches; ++i) {
+    const int f = wave * kFetches + i;
+    const int frow = 4 * (f & 3) + q4;
+    foff[i] = f >= 4 ? (uint32_t)(frow * p.v_stride_token) + (uint32_t)((t16 ^ (2 * (frow & 7))) * 16)
+                     : (uint32_t)(frow * p.k_stride_token) + (uint32_t)((t16 ^ frow) * 16);
+    fdst[i] = (uint32_t)((f >= 4 ? kTileBytes : 0) + (f & 3) * 1024);
+  }
   uint32_t krd[4], vrd[8];
   const uint32_t rbase = (uint32_t)(uintptr_t)(lptr_t)ring;   // LDS byte address of the ring
 #pragma unroll
@@ -140,12 +150,16 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_mfma_d128(const Attn
                  : "=v"(blk_v) : "v"(ids_base + 4u * (uint32_t)(j >> p.tpb_shift)) : "memory");
     const int64_t blk = __builtin_amdgcn_readfirstlane(blk_v);
     const int slot0 = (j & tile_mask) * kTileTokens;
-    const uint8_t* base = fetch_v ? vpool + blk * p.v_stride_block + kvh * p.v_stride_head + slot0 * p.v_stride_token
-                                  : kpool + blk * p.k_stride_block + kvh * p.k_stride_head + slot0 * p.k_stride_token;
+    const uint8_t* kbase = kpool + blk * p.k_stride_block + kvh * p.k_stride_head + slot0 * p.k_stride_token;
+    const uint8_t* vbase = vpool + blk * p.v_stride_block + kvh * p.v_stride_head + slot0 * p.v_stride_token;
     // default cache policy: other workgroups (other query groups, the other head pair) read the
     // same tile again, so unlike in the decode kernel it should stay in L2
-    __builtin_amdgcn_global_load_lds((gptr_t)(base + foff),
-                                     (lptr_t)(ring + (j & (kStages - 1)) * kStageBytes + fdst), 16, 0, 0);
+#pragma unroll
+    for (int i = 0; i < kFetches; ++i) {
+      const bool is_v = wave * kFetches + i >= 4;   // wave-uniform
+      __builtin_amdgcn_global_load_lds((gptr_t)((is_v ? vbase : kbase) + foff[i]),
+                                       (lptr_t)(ring + (j & (kStages - 1)) * kStageBytes + fdst[i]), 16, 0, 0);
+    }
   };
 
   // ---- query rows as B operands: column t16 = query token qi, one fragment set per head -------
