@@ -258,6 +258,107 @@ def time_prefill(torch, binding, B=16, n=4096, Hq=32, Hkv=8, reps=5):
             "frac": flops / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS}
 
 
+def serve_loop(torch, binding, steps, mode="recompute", seed=1007):
+    """The scheduler model driving the GPU calls for `steps` engine iterations under a benign
+    Poisson load that saturates the pool (the Fill state, with preemptions): per iteration the
+    swaps, the prefills (new and recomputed requests), the KV append and the decode attention
+    of one layer, 8B-shaped heads.  K/V contents are random; only shapes and tables matter here."""
+    import numpy as np
+    from paper_2602_07878_amd import sched, workloads as W
+    Hq, Hkv, D, bs = 32, 8, 128, 16
+    n_gpu, n_cpu, max_blocks = 12288, 12288, 384
+    s = sched.Scheduler(num_gpu_blocks=n_gpu, num_cpu_blocks=n_cpu, block_size=bs, max_num_seqs=256,
+                        max_num_batched_tokens=8192, max_blocks_per_seq=max_blocks, watermark_blocks=n_gpu // 100,
+                        mode=sched.SWAP if mode == "swap" else sched.RECOMPUTE)
+    stream = W.poisson_request_stream(seed, steps, 0.45, prompt_median=700, prompt_sigma=0.9, out_median=400,
+                                      out_sigma=0.7, max_prompt=4096, max_new=1500)
+    g = torch.Generator(device="cuda:0")
+    g.manual_seed(seed)
+    kp = torch.randn(n_gpu, Hkv, bs, D, device="cuda:0", generator=g).bfloat16()
+    vp = torch.randn(n_gpu, Hkv, bs, D, device="cuda:0", generator=g).bfloat16()
+    sk, sv = torch.empty(n_cpu, Hkv, bs, D, device="cuda:0", dtype=torch.bfloat16), \
+        torch.empty(n_cpu, Hkv, bs, D, device="cuda:0", dtype=torch.bfloat16)
+    bb = Hkv * bs * D * 2
+    d_out, d_in = binding.swap_desc(1, bb, n_gpu, n_cpu), binding.swap_desc(1, bb, n_cpu, n_gpu)
+    q_all = torch.randn(8192, Hq, D, device="cuda:0", generator=g).bfloat16()
+    kn, vn = torch.randn(256, Hkv, D, device="cuda:0", generator=g).bfloat16(), \
+        torch.randn(256, Hkv, D, device="cuda:0", generator=g).bfloat16()
+    out = torch.empty(8192, Hq, D, device="cuda:0")
+    scale = D ** -0.5
+    rec = []
+    occ = []
+    for arrivals in stream:
+        for rid, pl, nn in arrivals:
+            s.add_request(rid, pl, nn)
+        info = s.step()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        if info.num_swap_out_blocks:
+            m = torch.from_numpy(s.swap_out()).cuda()
+            binding.kv_block_swap(d_out, kp, sk, m)
+            binding.kv_block_swap(d_out, vp, sv, m)
+        if info.num_swap_in_blocks:
+            m = torch.from_numpy(s.swap_in()).cuda()
+            binding.kv_block_swap(d_in, sk, kp, m)
+            binding.kv_block_swap(d_in, sv, vp, m)
+        pf_tokens = 0
+        if info.num_prefill:
+            pid, ptok = s.prefills()
+            rows = [(rid, t) for rid, t in zip(pid.tolist(), ptok.tolist())]
+            tabs = np.full((len(rows), max_blocks), -1, np.int32)
+            keep = []
+            for i, (rid, t) in enumerate(rows):
+                try:
+                    b = s.request_blocks(rid)
+                except binding.PkvError:
+                    continue                      # finished within its prefill
+                tabs[i, :b.size] = b
+                keep.append(i)
+            if keep:
+                tabs = tabs[keep]
+                lens = np.array([rows[i][1] for i in keep], np.int32)
+                pf_tokens = int(lens.sum())
+                cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+                qv = q_all[:pf_tokens]
+                desc = binding.attn_desc_for(qv, kp, vp, torch.from_numpy(tabs).cuda(), max_context_len=int(lens.max()))
+                desc.batch = len(keep)
+                dl = torch.from_numpy(lens).cuda()
+                binding.paged_prefill_attention(desc, qv, kp, vp, torch.from_numpy(tabs).cuda(), dl, dl,
+                                                torch.from_numpy(cu).cuda(), int(lens.max()), scale, out[:pf_tokens])
+        kv_tokens = 0
+        if info.num_decode:
+            ids, lens, tabs = s.decode_batch()
+            B = len(ids)
+            kv_tokens = int(lens.sum())
+            bt, cl = torch.from_numpy(tabs).cuda(), torch.from_numpy(lens).cuda()
+            desc = binding.attn_desc_for(q_all[:B], kp, vp, bt, max_context_len=int(lens.max()))
+            binding.kv_append(desc, kn[:B], vn[:B], kp, vp, bt, cl)
+            binding.paged_decode_attention(q_all[:B], kp, vp, bt, cl, scale, out[:B], max_context_len=int(lens.max()),
+                                           desc=desc)
+        e1.record()
+        rec.append((e0, e1, info.num_decode, kv_tokens, pf_tokens, info.num_preempted,
+                    info.num_swap_out_blocks + info.num_swap_in_blocks))
+        occ.append(1.0 - info.free_blocks / n_gpu)
+    torch.cuda.synchronize()
+    us = np.array([a.elapsed_time(b) * 1e3 for a, b, *_ in rec])
+    dec = np.array([r[2] for r in rec]); kvt = np.array([r[3] for r in rec]); pft = np.array([r[4] for r in rec])
+    pre = np.array([r[5] for r in rec])
+    steady = np.arange(len(rec)) >= len(rec) // 4          # after the pool has filled
+    quiet = steady & (pft == 0) & (pre == 0) & (dec > 0)     # iterations that only decode
+    t = s.totals()
+    q = lambda a, f: float(np.percentile(a, f)) if a.size else None
+    return {"iterations": len(rec), "mode": mode, "finished": t["finished"], "preemptions": t["preemptions"],
+            "head_blocked_iterations": t["blocked"], "recomputed_tokens": t["recomputed"],
+            "swapped_blocks": t["swap_out"] + t["swap_in"],
+            "pool_occupancy_min_max_after_fill": [float(np.min(np.array(occ)[steady])), float(np.max(np.array(occ)[steady]))],
+            "decode_batch_mean": float(dec[steady].mean()), "kv_tokens_per_iteration_mean": float(kvt[steady].mean()),
+            "iteration_us_decode_only_p50_p90": [q(us[quiet], 50), q(us[quiet], 90)],
+            "iteration_us_with_prefill_or_preemption_p50_p90": [q(us[steady & ~quiet & (dec > 0)], 50),
+                                                                q(us[steady & ~quiet & (dec > 0)], 90)],
+            "decode_only_kv_GBps_mean": float((kvt[quiet] * 4096 / us[quiet] / 1e3).mean()) if quiet.any() else None,
+            "note": "one layer; an iteration's GPU time includes the Python-side launches of this script"}
+
+
 def probe_ceilings(torch, binding, nbytes=4 << 30, reps=5):
     a = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0").random_(0, 255)
     b = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
@@ -304,6 +405,8 @@ def main():
     ap.add_argument("--no-swap", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--extra", action="store_true", help="also time the Fill and long-context configs")
+    ap.add_argument("--serve", type=int, default=0, metavar="ITERATIONS",
+                    help="also run the scheduler-driven serving loop for this many engine iterations")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this library runs on one GPU only; --gpus must be 1 (the kernels need no "
@@ -381,6 +484,18 @@ def main():
         result["swap_host_leg"] = time_swap_host(swh, torch, binding)
         log(f"[bench] swap host leg {swh.name} ({int(swh.victim_lens.size)} victims): {result['swap_host_leg']}")
 
+    # every kernel family against the roofline that bounds it (the headline one is `roofline`)
+    rl = {"paged_prefill_attention": {"bound": "mfma", "achieved": result["prefill"]["tflops"],
+                                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                      "frac": result["prefill"]["frac"], "workload": result["prefill"]["workload"]}}
+    for name, sres in result.get("swap", {}).items():
+        for leg in ("gather", "scatter"):
+            rl[f"kv_block_swap_{leg}_{name}"] = {"bound": "hbm", "achieved": sres[leg]["traffic_GBps"],
+                                                 "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                                 "frac": sres[leg]["frac_hbm_peak"],
+                                                 "algorithmic_bytes": 2 * int(sres["payload_GB"] * 1e9)}
+    result["other_rooflines"] = rl
+
     if args.extra:
         extra = {}
         for mk, layers in ((W.config3_fill, 4), (W.config5_long70b, 2)):
@@ -402,6 +517,10 @@ def main():
             del dx
             torch.cuda.empty_cache()
         result["other_configs"] = extra
+
+    if args.serve > 0:
+        result["serving_loop"] = {m: serve_loop(torch, binding, args.serve, mode=m) for m in ("recompute", "swap")}
+        log(f"[bench] serving loop: {result['serving_loop']}")
 
     print(json.dumps(result), flush=True)
 
