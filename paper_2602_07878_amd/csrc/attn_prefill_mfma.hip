@@ -85,21 +85,24 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_mfma_d128(const Attn
   const int c32 = lane & 31;   // score layout: query token of the wavefront's 32; output layout: dim of a 32-block
   const int hl = lane >> 5;    // k-group of the operands; rows 4*hl + ... of the results
 
-  // Workgroups are numbered so that the query groups with the most K/V tiles to walk (the
-  // latest queries) are dispatched first, across all sequences and heads, and the short ones
-  // fill the gaps at the end; in launch order of (group, head, sequence) triples every round
-  // of workgroups would last as long as its longest member.
-  const int per_group = p.num_kv_heads * p.group_tiles * p.batch;
-  const int qgroup = (int)(gridDim.x / per_group) - 1 - (int)(blockIdx.x / per_group);
-  const int rest = blockIdx.x % per_group;
-  const int pair = rest % (p.num_kv_heads * p.group_tiles);
-  const int seq = rest / (p.num_kv_heads * p.group_tiles);
+  // Workgroup numbering.  (1) The workgroups that walk the same K/V stream (sequence, KV head)
+  // sit on one XCD, next to each other in launch order, so that the stream is fetched from HBM
+  // about once and re-read from that XCD's L2: workgroups are dealt to the XCDs round-robin,
+  // so stream st gets the ids congruent to st mod 8.  (2) Within a stream the query groups with
+  // the most tiles to walk (the latest queries) come first and the short ones fill the gaps at
+  // the end; in ascending order every round of workgroups lasts as long as its longest member.
+  const int nq = (int)(gridDim.x / 8) / (p.group_tiles * p.streams_per_xcd);   // query groups per stream
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int gtile = slot % p.group_tiles;
+  const int qgroup = nq - 1 - (slot / p.group_tiles) % nq;
+  const int stream = (slot / (p.group_tiles * nq)) * 8 + xcd;
+  if (stream >= p.batch * p.num_kv_heads) return;      // padding of the last round of streams
+  const int seq = stream / p.num_kv_heads, kvh = stream - seq * p.num_kv_heads;
   const int n = p.context_lens[seq];
   const int ql = min(p.query_lens[seq], n);
   const int q0 = qgroup * kQueryPerGroup;              // first query token of this workgroup
   if (ql <= 0 || q0 >= ql) return;                     // uniform over the workgroup
   const int pos0 = n - ql;                             // position of the chunk's first token
-  const int kvh = pair / p.group_tiles, gtile = pair - kvh * p.group_tiles;
   const int hslot = wave / kGroupsPerHead;             // which of the workgroup's heads
   const int head = kvh * p.group + gtile * HW + hslot;
   const bool head_live = gtile * HW + hslot < p.group;
@@ -388,7 +391,8 @@ hipError_t launch_attn_prefill(AttnParams& p, int max_query_len, int max_context
   const int hw = p.group == 1 ? 1 : 2;                       // heads per workgroup
   p.group_tiles = (p.group + hw - 1) / hw;
   const int qpg = kWaves / hw * kQueryPerWave;               // query tokens per workgroup
-  const int64_t nwg = (int64_t)((max_query_len + qpg - 1) / qpg) * p.num_kv_heads * p.group_tiles * p.batch;
+  p.streams_per_xcd = (p.num_kv_heads * p.batch + 7) / 8;
+  const int64_t nwg = (int64_t)((max_query_len + qpg - 1) / qpg) * p.group_tiles * p.streams_per_xcd * 8;
   if (nwg > 0x7FFFFFFF) return hipErrorInvalidValue;
   const dim3 grid((unsigned)nwg);
   const size_t ids_bytes = (size_t)((max_context_len + p.block_size - 1) / p.block_size) * 4 + 16;

@@ -39,6 +39,7 @@ struct AttnParams {
   int32_t tpb_shift;        // log2(block_size / 16) (matrix-core kernel only)
   int32_t chunk_tiles_max;  // stream kernel: most tiles one wavefront takes per chunk (<= 64)
   int32_t prefix_bytes;     // stream kernel: LDS bytes of the tile prefix table
+  int32_t streams_per_xcd;  // prefill kernel: (sequence, KV head) streams dealt to one XCD
   float scale_log2e;        // scale * log2(e)
   // host side only: optional events recorded right before / after the partial kernel
   hipEvent_t ev_begin, ev_end;
