@@ -195,3 +195,14 @@ def test_workspace_shared_between_descriptors_and_repeatable():
             if rep == 0:
                 first[w.name] = a
             assert np.array_equal(a, first[w.name])
+
+
+@pytest.mark.parametrize("B", [2047, 2048, 2500])
+def test_batch_sizes_around_the_streaming_kernel_limit(B):
+    """Up to 2047 sequences the tile prefix table of the streaming kernel fits its LDS budget;
+    beyond that the call falls back to the grid kernel.  Same answer either way."""
+    rng = np.random.default_rng(B)
+    lens = [int(x) for x in rng.integers(0, 70, B)]
+    w = W.make_attn_workload(f"batch{B}", 90 + B, dtype="bf16", Hq=8, Hkv=2, D=128, block_size=16,
+                             context_lens=lens, pool_factor=1.1)
+    check(w)
