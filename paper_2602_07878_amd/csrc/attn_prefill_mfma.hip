@@ -29,6 +29,7 @@
 //   O[query][dim] += P V        2 x 2 x 4 x v_mfma_f32_32x32x16_bf16, P split into a bf16 head
 //   and a bf16 remainder (exact to 2^-17), V through the transposing LDS read.
 
+#include <atomic>
 #include <type_traits>
 
 #include "pkv_internal.h"
@@ -396,14 +397,15 @@ hipError_t launch_attn_prefill(AttnParams& p, int max_query_len, int max_context
   if (nwg > 0x7FFFFFFF) return hipErrorInvalidValue;
   const dim3 grid((unsigned)nwg);
   const size_t ids_bytes = (size_t)((max_context_len + p.block_size - 1) / p.block_size) * 4 + 16;
-  static bool prepared = false;   // static + dynamic LDS may exceed 64 KiB: ask once
-  if (!prepared) {
+  static std::atomic<bool> prepared[kMaxDevices];   // static + dynamic LDS may exceed 64 KiB: ask once per device
+  const int slot = current_device_slot();
+  if (!prepared[slot].load(std::memory_order_acquire)) {
     for (const void* f : {reinterpret_cast<const void*>(&attn_prefill_mfma_d128<1>),
                           reinterpret_cast<const void*>(&attn_prefill_mfma_d128<2>)}) {
       const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxIdsBytes);
       if (e != hipSuccess) return e;
     }
-    prepared = true;
+    prepared[slot].store(true, std::memory_order_release);
   }
   if (hw == 1) hipLaunchKernelGGL((attn_prefill_mfma_d128<1>), grid, dim3(kThreads), ids_bytes, s, p);
   else hipLaunchKernelGGL((attn_prefill_mfma_d128<2>), grid, dim3(kThreads), ids_bytes, s, p);

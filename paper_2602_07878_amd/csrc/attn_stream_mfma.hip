@@ -37,6 +37,7 @@
 // The loads of tile j+1 are in flight while tile j is consumed; the first tile of the
 // next segment is issued before the current segment is flushed.
 
+#include <atomic>
 #include <type_traits>
 
 #include <hip/hip_ext.h>
@@ -681,28 +682,30 @@ __global__ __launch_bounds__(GH * kWaveSize) void attn_stream_merge_lean(const A
 }
 
 int num_cus() {
-  static int cached = 0;
-  if (cached == 0) {
-    int dev = 0, v = 0;
-    if (hipGetDevice(&dev) == hipSuccess &&
-        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
-      cached = v;
-    else
-      cached = 256;
+  static std::atomic<int> cached[kMaxDevices];   // zero-initialised: not asked yet
+  const int slot = current_device_slot();
+  int v = cached[slot].load(std::memory_order_relaxed);
+  if (v == 0) {
+    int dev = 0;
+    if (!(hipGetDevice(&dev) == hipSuccess &&
+          hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0))
+      v = 256;   // no device (sizing a workspace on a host without one): the MI355X count
+    cached[slot].store(v, std::memory_order_relaxed);
   }
-  return cached;
+  return v;
 }
 
 template <int GH>
 hipError_t launch(const AttnParams& p, hipStream_t s) {
   const size_t lds = (size_t)p.prefix_bytes + (size_t)kNW * kWaveLds;
-  static bool prepared = false;   // more than 64 KiB of dynamic LDS has to be asked for once
-  if (!prepared) {
+  static std::atomic<bool> prepared[kMaxDevices];   // more than 64 KiB of dynamic LDS: ask once per device
+  const int slot = current_device_slot();
+  if (!prepared[slot].load(std::memory_order_acquire)) {
     const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_stream_mfma_d128<GH>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize,
                                              kStreamMaxPrefixBytes + kNW * kWaveLds);
     if (e != hipSuccess) return e;
-    prepared = true;
+    prepared[slot].store(true, std::memory_order_release);
   }
   // with events: attached to the dispatch itself, so they carry the kernel's own begin and end
   if (p.ev_begin || p.ev_end)

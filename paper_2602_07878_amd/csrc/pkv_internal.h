@@ -13,6 +13,15 @@ constexpr int kDefaultPartition = 512;   // split-K partition length in tokens
 constexpr int kAttnThreads = 256;        // 4 wavefronts per workgroup
 constexpr int kStreamMaxPrefixBytes = 8192;   // LDS for per-sequence tile prefix sums
 
+// Per-device bookkeeping (kernel attributes set, CU counts) is kept in small tables indexed by
+// the HIP device id; ids outside the table share slot 0.
+constexpr int kMaxDevices = 16;
+inline int current_device_slot() {
+  int d = 0;
+  if (hipGetDevice(&d) != hipSuccess || d < 0 || d >= kMaxDevices) d = 0;
+  return d;
+}
+
 // Launch geometry and pointers of one attention call, passed by value.
 struct AttnParams {
   const void* q;

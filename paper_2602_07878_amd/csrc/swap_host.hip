@@ -14,8 +14,6 @@
 namespace pkv {
 namespace {
 
-constexpr int kMaxDevices = 16;
-
 struct DeviceEvents {
   hipEvent_t kernel_done[2], copy_done[2], start;
   bool ready = false;
