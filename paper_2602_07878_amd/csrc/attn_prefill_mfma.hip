@@ -13,14 +13,13 @@
 // Work split.  A workgroup of 8 wavefronts takes up to two query heads of one KV head and 128
 // consecutive query tokens of one sequence per head (256 when the KV head has a single query
 // head): each wavefront owns 32 tokens of one head.  The workgroup walks the K/V tiles
-// 0 .. (its last position)/16 once, two tiles (32 tokens) per step: the wavefronts fetch the
-// tiles together with direct-to-LDS loads (a quarter of K or of V each) into a ring of four
-// tiles, the pair in use and the pair in flight, and all of them consume the pair from LDS; one
-// barrier per pair orders the ring.  A wavefront skips the pairs that lie entirely in its
-// future.
+// 0 .. (its last position)/16 once, two tiles (32 tokens, a "pair") per step: the wavefronts
+// fetch the tiles together with direct-to-LDS loads (a quarter of K or of V each) into a ring
+// of four pairs, and all of them consume the pairs from LDS; one barrier per pair orders the
+// ring.  A wavefront skips the pairs that lie entirely in its future.
 //
-// Per pair of tiles, in the 32x32x16 shape (on this part the 16x16 shapes run at half the
-// rate: 1.3 against 2.3 PFLOP/s measured for back-to-back bf16 MFMAs):
+// Per pair, in the 32x32x16 shape (on this part the 16x16 shapes run at half the rate: 1.3
+// against 2.3 PFLOP/s measured for back-to-back bf16 MFMAs):
 //   S^T[token][query] = K Q^T   8 x v_mfma_f32_32x32x16_bf16 (32 tokens x 32 queries x 128 dims)
 //   causal mask, lazy-max base-2 softmax in fp32: a lane holds 16 tokens of one query, and that
 //   is already the A-operand layout of the second product (k-step u = tile u of the pair), so
@@ -28,6 +27,20 @@
 //   has to be raised
 //   O[query][dim] += P V        2 x 2 x 4 x v_mfma_f32_32x32x16_bf16, P split into a bf16 head
 //   and a bf16 remainder (exact to 2^-17), V through the transposing LDS read.
+//
+// Schedule.  Run one after the other, the three steps leave the matrix cores idle during the
+// softmax, the vector ALU idle during the products, and both idle while LDS answers.  So the
+// walk is software-pipelined inside a wavefront, in two phases per pair i:
+//   phase 1: the exponentials and the bf16 split of pair i, two weights per slice, with one
+//            MFMA of the first product of pair i+1 issued in front of each slice; the K rows
+//            of pair i+1 and the V rows of pair i are read from LDS meanwhile
+//   phase 2: the second product of pair i, interleaved with the scaling of the new scores
+//            (and their causal mask and running maximum)
+// and the two wavefronts that share a SIMD run in opposite phases: the workgroup's barrier
+// falls before phase 1 in wavefronts 0..3 and before phase 2 in wavefronts 4..7, so that one
+// of the two is in its ALU-heavy phase while the other is in its MFMA-heavy one.  The ring
+// holds four pairs for this: at barrier k the pairs up to k+2 are complete, pair k+3 is
+// requested into the place of pair k-1, and the pairs k .. k+2 are being read.
 
 #include <atomic>
 #include <type_traits>
@@ -52,9 +65,9 @@ constexpr int D = 128;
 constexpr int kThreads = 512, kWaves = kThreads / kWaveSize;   // one quarter tile (1 KiB) of K or V per wavefront
 constexpr int kQueryPerWave = 32;
 constexpr int kTileBytes = 4096, kStageBytes = 2 * kTileBytes;
-constexpr int kStages = 4;                 // K/V ring depth: three tiles in flight behind the one in use
-constexpr float kNegBig = -1.0e30f;
-constexpr float kSlack = 8.0f;
+constexpr int kStages = 8;                 // K/V ring depth in tiles: four pairs
+constexpr int kRingBytes = kStages * kStageBytes;
+constexpr float kGrowLimit = 0x1p40f;       // a pair's weights relative to a stale reference maximum may sum to this
 constexpr int kMaxIdsBytes = 64 * 1024;     // LDS for one sequence's block table row: 16 Ki blocks
 
 #define PKV_PF_WAIT_VMCNT(n) \
@@ -76,9 +89,12 @@ template <int HW>
 __global__ __launch_bounds__(kThreads, 2) void attn_prefill_mfma_d128(const AttnParams p) {
   constexpr int kGroupsPerHead = kWaves / HW;                       // 32-query groups per head
   constexpr int kQueryPerGroup = kGroupsPerHead * kQueryPerWave;    // query tokens per workgroup
-  __shared__ __attribute__((aligned(256))) uint8_t ring[kStages * kStageBytes];
   __shared__ __attribute__((aligned(16))) float xchg_all[kWaves][128];
-  extern __shared__ int32_t ids_lds[];   // block table row of this sequence: ceil(max context / block size) entries
+  // dynamic LDS: the K/V ring, then the block table row of this sequence (ceil(max context /
+  // block size) entries)
+  extern __shared__ __attribute__((aligned(256))) uint8_t dyn_lds[];
+  uint8_t* const ring = dyn_lds;
+  int32_t* const ids_lds = reinterpret_cast<int32_t*>(dyn_lds + kRingBytes);
 
   const int tid = threadIdx.x;
   const int lane = tid & (kWaveSize - 1);
@@ -133,7 +149,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_mfma_d128(const Attn
   const int krow = c32 & 15;
   uint32_t krd[8];
 #pragma unroll
-  for (int s8 = 0; s8 < 8; ++s8) krd[s8] = (uint32_t)(krow * 256 + (((2 * s8 + hl) ^ krow) * 16)) + rbase;
+  for (int s8 = 0; s8 < 8; ++s8)
+    krd[s8] = (uint32_t)(krow * 256 + (((2 * s8 + hl) ^ krow) * 16)) + rbase + (c32 < 16 ? 0u : (uint32_t)kStageBytes);
   // second product, output dims 32nb .. 32nb+31: a 16-lane group g reads, for k-group hl = g/2
   // and dim half g%2, the tokens 4hl + s/4 (first read) and 8 + 4hl + s/4 (second read) at dims
   // 32nb + 16(g%2) + 4(s%4)..+3, s = lane within the group; the transposing read then leaves
@@ -163,14 +180,16 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_mfma_d128(const Attn
   }
   const uint32_t ids_base = (uint32_t)(uintptr_t)(lptr_t)ids_lds;
 
-  auto issue = [&](int j) {
-    int blk_v;
-    asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)"
-                 : "=v"(blk_v) : "v"(ids_base + 4u * (uint32_t)(j >> p.tpb_shift)) : "memory");
-    const int64_t blk = __builtin_amdgcn_readfirstlane(blk_v);
+  // A tile's fetch in two steps, so that the first can be done ahead of the barrier that frees
+  // the tile's place in the ring: locate() forms the address of this wavefront's quarter
+  // from the block id (wave-uniform, in scalar registers), request() starts the load.
+  auto locate = [&](int j, int blk_id) -> const uint8_t* {
+    const int64_t blk = blk_id;
     const int slot0 = (j & tile_mask) * kTileTokens;
-    const uint8_t* base = wave >= 4 ? vpool + blk * p.v_stride_block + kvh * p.v_stride_head + slot0 * p.v_stride_token
-                                    : kpool + blk * p.k_stride_block + kvh * p.k_stride_head + slot0 * p.k_stride_token;
+    return wave >= 4 ? vpool + blk * p.v_stride_block + kvh * p.v_stride_head + slot0 * p.v_stride_token
+                     : kpool + blk * p.k_stride_block + kvh * p.k_stride_head + slot0 * p.k_stride_token;
+  };
+  auto request = [&](int j, const uint8_t* base) {
     // default cache policy: other workgroups (other query groups, other heads) read the same
     // tile again, so unlike in the decode kernel it should stay in L2
     __builtin_amdgcn_global_load_lds((gptr_t)(base + foff),
@@ -193,66 +212,158 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_mfma_d128(const Attn
 
   // softmax state of query column c32 (same value in the two lanes that share a column), and
   // O[query 8(r/4) + 4hl + r%4][dim 32nb + c32] in acc[nb][r]
-  float m_ref = kNegBig, l_part = 0.f;
+  float m_ref = 0.f, l_part = 0.f;
   f32x16 acc[4];
 #pragma unroll
   for (int nb = 0; nb < 4; ++nb)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[nb][r] = 0.f;
 
-  // Tiles j (A) and j+1 (B) of the ring; have_b is false for the odd tile at the end of the walk
-  // (its tokens lie past every query of the workgroup, so the causal test masks them).
-  auto consume = [&](int j, bool have_b) {
-    const uint32_t soff_a = (uint32_t)((j & (kStages - 1)) * kStageBytes);
-    const uint32_t soff_b = (uint32_t)(((j + 1) & (kStages - 1)) * kStageBytes);
-    const uint32_t soff_k = c32 < 16 ? soff_a : soff_b;        // the tile of this lane's K row
+  // All LDS reads are issued by hand.  The compiler would put a wait for every outstanding
+  // direct-to-LDS load, i.e. for the pairs in flight, in front of reads it cannot tell apart
+  // from the ring; and a read issued here is waited for later, by a counted s_waitcnt that
+  // names the registers it completes (as in/out operands), so that nothing that uses them can
+  // be moved in front of it.  LDS answers in order, which is what the counts rely on; scalar
+  // loads the compiler may have in flight only make a counted wait longer.
+#define PKV_PF_READ_K4(k0, k1, k2, k3, a0, a1, a2, a3)                                           \
+  asm volatile("ds_read_b128 %0, %4\n\tds_read_b128 %1, %5\n\tds_read_b128 %2, %6\n\tds_read_b128 %3, %7" \
+               : "=&v"(k0), "=&v"(k1), "=&v"(k2), "=&v"(k3)                                      \
+               : "v"(a0), "v"(a1), "v"(a2), "v"(a3)                                              \
+               : "memory")
+#define PKV_PF_WAIT_K4(cnt, k0, k1, k2, k3) \
+  asm volatile("s_waitcnt lgkmcnt(" #cnt ")" : "+v"(k0), "+v"(k1), "+v"(k2), "+v"(k3) : : "memory")
+#define PKV_PF_READ_V8(vt, b0, b1)                                                               \
+  do {                                                                                           \
+    const uint32_t a0_ = (b0), a1_ = (b1), a2_ = a0_ ^ 64u, a3_ = a1_ ^ 64u, a4_ = a0_ ^ 128u,     \
+                   a5_ = a1_ ^ 128u, a6_ = a0_ ^ 192u, a7_ = a1_ ^ 192u;                          \
+    asm volatile(                                                                                \
+        "ds_read_b64_tr_b16 %0, %8\n\tds_read_b64_tr_b16 %1, %9\n\t"                              \
+        "ds_read_b64_tr_b16 %2, %10\n\tds_read_b64_tr_b16 %3, %11\n\t"                            \
+        "ds_read_b64_tr_b16 %4, %12\n\tds_read_b64_tr_b16 %5, %13\n\t"                            \
+        "ds_read_b64_tr_b16 %6, %14\n\tds_read_b64_tr_b16 %7, %15"                                \
+        : "=&v"(vt[0]), "=&v"(vt[1]), "=&v"(vt[2]), "=&v"(vt[3]), "=&v"(vt[4]), "=&v"(vt[5]),     \
+          "=&v"(vt[6]), "=&v"(vt[7])                                                             \
+        : "v"(a0_), "v"(a1_), "v"(a2_), "v"(a3_), "v"(a4_), "v"(a5_), "v"(a6_), "v"(a7_)          \
+        : "memory");                                                                             \
+  } while (0)
+#define PKV_PF_WAIT_V8(cnt, vt)                                                                  \
+  asm volatile("s_waitcnt lgkmcnt(" #cnt ")"                                                     \
+               : "+v"(vt[0]), "+v"(vt[1]), "+v"(vt[2]), "+v"(vt[3]), "+v"(vt[4]), "+v"(vt[5]),    \
+                 "+v"(vt[6]), "+v"(vt[7])                                                        \
+               : : "memory")
 
-    // All LDS reads are issued by hand: the compiler would put a wait for every outstanding
-    // direct-to-LDS load, i.e. for the tiles in flight, in front of reads it cannot tell apart
-    // from the ring.  The data is complete: the barrier before this call covered both tiles.
-    f32x16 cfr;
+  // State carried from one pair to the next: the raw scores of the coming pair (q . k;
+  // register r = token 8(r/4) + 4hl + r%4 of the pair, query c32) from phase 1 to phase 2, and
+  // from phase 2 to the next phase 1 the same scaled, masked and taken relative to the reference
+  // maximum (log2 units).
+  f32x16 s_next;
+  float d[16];
+  uint32_t hi[8], lo[8];   // bf16 pairs (2i, 2i+1) of the weights: head and remainder
+  u32x2 vta[8];            // V of the pair's first tile, B operands (read in phase 1, used in phase 2)
+
+  // The first pair, not pipelined: its scores, and the reference maximum set to their true
+  // maximum (position 0 is visible to every query, so it is finite).
+  auto first_scores = [&]() {
+    f32x16 sc;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) cfr[r] = 0.f;
+    for (int r = 0; r < 16; ++r) sc[r] = 0.f;
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
-      u32x4 raw[4];
-      const uint32_t a0 = krd[4 * half + 0] + soff_k, a1 = krd[4 * half + 1] + soff_k;
-      const uint32_t a2 = krd[4 * half + 2] + soff_k, a3 = krd[4 * half + 3] + soff_k;
-      asm volatile(
-          "ds_read_b128 %0, %4\n\t"
-          "ds_read_b128 %1, %5\n\t"
-          "ds_read_b128 %2, %6\n\t"
-          "ds_read_b128 %3, %7\n\t"
-          "s_waitcnt lgkmcnt(0)"
-          : "=&v"(raw[0]), "=&v"(raw[1]), "=&v"(raw[2]), "=&v"(raw[3])
-          : "v"(a0), "v"(a1), "v"(a2), "v"(a3)
-          : "memory");
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        cfr = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, raw[i]), qfrag[4 * half + i], cfr, 0, 0, 0);
+      u32x4 f0, f1, f2, f3;
+      const uint32_t a0 = krd[4 * half + 0], a1 = krd[4 * half + 1], a2 = krd[4 * half + 2], a3 = krd[4 * half + 3];
+      PKV_PF_READ_K4(f0, f1, f2, f3, a0, a1, a2, a3);
+      PKV_PF_WAIT_K4(0, f0, f1, f2, f3);
+      sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f0), qfrag[4 * half + 0], sc, 0, 0, 0);
+      sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f1), qfrag[4 * half + 1], sc, 0, 0, 0);
+      sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f2), qfrag[4 * half + 2], sc, 0, 0, 0);
+      sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f3), qfrag[4 * half + 3], sc, 0, 0, 0);
     }
-    // cfr[r] = q(query c32) . k(token tk(r) of the pair), tk(r) = 8(r/4) + 4hl + r%4;
-    // d = score - reference in log2 units; causal: a query sees positions <= its own
-    const int kpos0 = j * kTileTokens + 4 * hl;
-    // (only a pair that reaches past the wavefront's first query needs the test: wave-uniform)
-    const bool diagonal = (j + 2) * kTileTokens - 1 > pos0 + qw;
-    float d[16];
+    // causal: a query sees positions <= its own (this also removes an absent second tile)
+    const int kpos0 = 4 * hl;
+    float smax = -INFINITY;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) d[r] = fmaf(cfr[r], p.scale_log2e, -m_ref);
-    if (diagonal) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r)
-        if (kpos0 + 8 * (r / 4) + (r % 4) > qpos) d[r] = -INFINITY;
+    for (int r = 0; r < 16; ++r) {
+      d[r] = kpos0 + 8 * (r / 4) + (r % 4) > qpos ? -INFINITY : sc[r] * p.scale_log2e;
+      smax = fmaxf(smax, d[r]);
     }
-    float dmax = d[0];
+    xchg[hl * 32 + c32] = smax;
+    m_ref = fmaxf(xchg[c32], xchg[32 + c32]);
 #pragma unroll
-    for (int r = 1; r < 16; ++r) dmax = fmaxf(dmax, d[r]);
-    if (__builtin_amdgcn_ballot_w64(dmax > kSlack) != 0) {   // wave-uniform, rare after the first tiles
+    for (int r = 0; r < 16; ++r) d[r] -= m_ref;
+  };
+
+  // Phase 1 of pair i: weights of pair i from d[], raw scores of pair i+1 into s_next.  (The
+  // scores of a pair that does not exist, or that this wavefront will not use, are computed
+  // from whatever the ring holds and never looked at.)
+  //
+  // The reference maximum is lazy in the extreme: the weights are taken relative to m_ref as
+  // it stands, without looking at the scores first, and only if their sum shows that a score
+  // lies far above m_ref (or is not a number) is m_ref raised to the true maximum and the
+  // pair's weights taken again.  A weight of 2^30 is as exact as one of 1 in fp32 and in
+  // the bf16 split, so nothing is lost; with the first pair's true maximum as the start, the
+  // second path is taken when a later score exceeds everything before it by some 2^35.
+  uint32_t sel0 = 0x0000BF80u, sel1 = 0xBF800000u;       // bf16 pairs (-1, 0) and (0, -1)
+  asm volatile("" : "+s"(sel0), "+s"(sel1));             // kept out of the instruction's constant field
+  const bf16x2 minus_first = __builtin_bit_cast(bf16x2, sel0), minus_second = __builtin_bit_cast(bf16x2, sel1);
+  // two weights p0, p1: bf16 head by a packed round-to-nearest conversion, bf16 remainder
+  // p - head, exactly, by a dot product of the packed heads with (-1, 0) or (0, -1) added to p
+  // (finite weights only: an infinite neighbour would turn 0 x inf into NaN)
+#define PKV_PF_SPLIT(c, p0, p1)                                                                    \
+    {                                                                                              \
+      psum += (p0) + (p1);                                                                         \
+      const bf16x2 h = __builtin_convertvector(f32x2{(p0), (p1)}, bf16x2);                         \
+      const float r0 = __builtin_amdgcn_fdot2_f32_bf16(h, minus_first, (p0), false);               \
+      const float r1 = __builtin_amdgcn_fdot2_f32_bf16(h, minus_second, (p1), false);              \
+      hi[c] = __builtin_bit_cast(uint32_t, h);                                                     \
+      lo[c] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{r0, r1}, bf16x2));         \
+    }
+  // The K rows of pair i+1, as A operands, are read one phase ahead of phase 1 of pair i: at
+  // the end of the previous pair's phase 2 (pair i+1 is complete in the ring by then).
+  u32x4 k0, k1, k2, k3, k4, k5, k6, k7;
+  auto read_next_k = [&](int i) {
+    const uint32_t soff_n = (uint32_t)(((2 * i + 2) & (kStages - 1)) * kStageBytes);
+    const uint32_t a0 = krd[0] + soff_n, a1 = krd[1] + soff_n, a2 = krd[2] + soff_n, a3 = krd[3] + soff_n;
+    PKV_PF_READ_K4(k0, k1, k2, k3, a0, a1, a2, a3);
+    const uint32_t a4 = krd[4] + soff_n, a5 = krd[5] + soff_n, a6 = krd[6] + soff_n, a7 = krd[7] + soff_n;
+    PKV_PF_READ_K4(k4, k5, k6, k7, a4, a5, a6, a7);
+  };
+  auto phase1 = [&](int i) {
+    const uint32_t soff_a = (uint32_t)(((2 * i) & (kStages - 1)) * kStageBytes);
+    PKV_PF_WAIT_K4(4, k0, k1, k2, k3);   // K reads 4..7 may still be under way
+    PKV_PF_READ_V8(vta, vrd[0] + soff_a, vrd[1] + soff_a);   // (never more than 15 reads under way: the counter's range)
+    __builtin_amdgcn_sched_barrier(0);
+
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s_next[r] = 0.f;
+    float psum = 0.f;
+    // one slice: an MFMA of the next scores, the exponentials of the following slice's two
+    // weights and the split of this slice's two (two independent chains for the ALU to
+    // alternate between); the scheduling barriers keep the slices apart
+    float e0 = __builtin_amdgcn_exp2f(d[0]), e1 = __builtin_amdgcn_exp2f(d[1]);
+#define PKV_PF_SLICE(c, kreg)                                                                      \
+    {                                                                                              \
+      s_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kreg), qfrag[c], s_next, 0, 0, 0); \
+      const float n0 = (c) < 7 ? __builtin_amdgcn_exp2f(d[((c) < 7 ? 2 * (c) + 2 : 0)]) : 0.f;      \
+      const float n1 = (c) < 7 ? __builtin_amdgcn_exp2f(d[((c) < 7 ? 2 * (c) + 3 : 0)]) : 0.f;      \
+      PKV_PF_SPLIT(c, e0, e1)                                                                      \
+      e0 = n0; e1 = n1;                                                                            \
+    }                                                                                              \
+    __builtin_amdgcn_sched_barrier(0)
+    PKV_PF_SLICE(0, k0);
+    PKV_PF_SLICE(1, k1);
+    PKV_PF_SLICE(2, k2);
+    PKV_PF_SLICE(3, k3);
+    PKV_PF_WAIT_K4(8, k4, k5, k6, k7);   // the eight V reads behind them may still be under way
+    PKV_PF_SLICE(4, k4);
+    PKV_PF_SLICE(5, k5);
+    PKV_PF_SLICE(6, k6);
+    PKV_PF_SLICE(7, k7);
+#undef PKV_PF_SLICE
+    if (__builtin_amdgcn_ballot_w64(!(psum < kGrowLimit)) != 0) {   // wave-uniform, rare after the first pair
       float smax = -INFINITY;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        float sv = cfr[r] * p.scale_log2e;
-        if (diagonal && kpos0 + 8 * (r / 4) + (r % 4) > qpos) sv = -INFINITY;
+        const float sv = d[r] + m_ref;                     // the scaled score again; masked stays -inf
         d[r] = sv;
         smax = fmaxf(smax, sv);
       }
@@ -273,52 +384,27 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_mfma_d128(const Attn
 #pragma unroll
           for (int e = 0; e < 4; ++e) acc[nb][4 * k + e] *= a[e];
       }
-    }
-    // weights, split into a bf16 head (round to nearest) and a bf16 remainder, two values per
-    // packed conversion; k-step u of the second product takes registers 8u .. 8u+7, which are
-    // exactly this lane's tokens of tile u
-    uint32_t hi[8], lo[8];   // pairs (2i, 2i+1)
-    float psum = 0.f;
+      psum = 0.f;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const float p0 = __builtin_amdgcn_exp2f(d[2 * i]), p1 = __builtin_amdgcn_exp2f(d[2 * i + 1]);
-      psum += p0 + p1;
-      hi[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{p0, p1}, bf16x2));
-      const float r0 = p0 - __builtin_bit_cast(float, hi[i] << 16);
-      const float r1 = p1 - __builtin_bit_cast(float, hi[i] & 0xFFFF0000u);
-      lo[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{r0, r1}, bf16x2));
+      for (int c = 0; c < 8; ++c) {
+        const float p0 = __builtin_amdgcn_exp2f(d[2 * c]), p1 = __builtin_amdgcn_exp2f(d[2 * c + 1]);
+        PKV_PF_SPLIT(c, p0, p1)
+      }
     }
     l_part += psum;
+  };
+#undef PKV_PF_SPLIT
 
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      if (u == 1 && !have_b) break;                       // weights of the absent tile are zero
-      const uint32_t soff = u == 0 ? soff_a : soff_b;
-      const bf16x8 p_hi = __builtin_bit_cast(bf16x8, u32x4{hi[4 * u], hi[4 * u + 1], hi[4 * u + 2], hi[4 * u + 3]});
-      const bf16x8 p_lo = __builtin_bit_cast(bf16x8, u32x4{lo[4 * u], lo[4 * u + 1], lo[4 * u + 2], lo[4 * u + 3]});
-      // V of tile u as B operands: four tokens per read, two reads per 32 output dims
-      u32x2 vt[8];
-      {
-        const uint32_t b0 = vrd[0] + soff, b1 = vrd[1] + soff;
-        const uint32_t a0 = b0, a1 = b1, a2 = b0 ^ 64u, a3 = b1 ^ 64u, a4 = b0 ^ 128u, a5 = b1 ^ 128u,
-                       a6 = b0 ^ 192u, a7 = b1 ^ 192u;
-        asm volatile(
-            "ds_read_b64_tr_b16 %0, %8\n\t"
-            "ds_read_b64_tr_b16 %1, %9\n\t"
-            "ds_read_b64_tr_b16 %2, %10\n\t"
-            "ds_read_b64_tr_b16 %3, %11\n\t"
-            "ds_read_b64_tr_b16 %4, %12\n\t"
-            "ds_read_b64_tr_b16 %5, %13\n\t"
-            "ds_read_b64_tr_b16 %6, %14\n\t"
-            "ds_read_b64_tr_b16 %7, %15\n\t"
-            "s_waitcnt lgkmcnt(0)"
-            : "=&v"(vt[0]), "=&v"(vt[1]), "=&v"(vt[2]), "=&v"(vt[3]), "=&v"(vt[4]), "=&v"(vt[5]),
-              "=&v"(vt[6]), "=&v"(vt[7])
-            : "v"(a0), "v"(a1), "v"(a2), "v"(a3), "v"(a4), "v"(a5), "v"(a6), "v"(a7)
-            : "memory");
-      }
-      const int tpos = (j + u) * kTileTokens + 4 * hl;    // position of the first token of read 0
-      if ((j + u + 1) * kTileTokens > n) {                // rows past the context may hold NaN: zero them
+  // Phase 2 of pair i: O += P V for its one or two tiles, and d[] of pair i+1.
+  auto phase2 = [&](int i, bool have_b) {
+    const uint32_t soff_b = (uint32_t)(((2 * i + 1) & (kStages - 1)) * kStageBytes);
+    u32x2 vtb[8];
+    PKV_PF_WAIT_V8(0, vta);
+    if (have_b) PKV_PF_READ_V8(vtb, vrd[0] + soff_b, vrd[1] + soff_b);
+    // rows past the context may hold NaN: zero them (only in the sequence's last tile)
+    auto clear_rows_past_context = [&](u32x2* vt, int tile) {
+      const int tpos = tile * kTileTokens + 4 * hl;       // position of the first token of read 0
+      if ((tile + 1) * kTileTokens > n) {
         const uint32_t f0 = (tpos + 0 < n ? 0x0000FFFFu : 0u) | (tpos + 1 < n ? 0xFFFF0000u : 0u);
         const uint32_t f1 = (tpos + 2 < n ? 0x0000FFFFu : 0u) | (tpos + 3 < n ? 0xFFFF0000u : 0u);
         const uint32_t g0 = (tpos + 8 < n ? 0x0000FFFFu : 0u) | (tpos + 9 < n ? 0xFFFF0000u : 0u);
@@ -329,29 +415,106 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_mfma_d128(const Attn
           vt[2 * nb + 1][0] &= g0; vt[2 * nb + 1][1] &= g1;
         }
       }
+    };
+    clear_rows_past_context(vta, 2 * i);
+    __builtin_amdgcn_sched_barrier(0);
+    {
+      // k-step u of the second product takes weight registers 8u .. 8u+7, which are exactly
+      // this lane's tokens of tile u; the scaling of the next scores rides along
+      const bf16x8 p_hi = __builtin_bit_cast(bf16x8, u32x4{hi[0], hi[1], hi[2], hi[3]});
+      const bf16x8 p_lo = __builtin_bit_cast(bf16x8, u32x4{lo[0], lo[1], lo[2], lo[3]});
 #pragma unroll
       for (int nb = 0; nb < 4; ++nb) {
-        const bf16x8 vop = __builtin_bit_cast(bf16x8, u32x4{vt[2 * nb][0], vt[2 * nb][1], vt[2 * nb + 1][0], vt[2 * nb + 1][1]});
+        const bf16x8 vop = __builtin_bit_cast(bf16x8, u32x4{vta[2 * nb][0], vta[2 * nb][1], vta[2 * nb + 1][0], vta[2 * nb + 1][1]});
+        acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p_hi, vop, acc[nb], 0, 0, 0);
+#pragma unroll
+        for (int r = 4 * nb; r < 4 * nb + 2; ++r) d[r] = fmaf(s_next[r], p.scale_log2e, -m_ref);
+        __builtin_amdgcn_sched_barrier(0);
+        acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p_lo, vop, acc[nb], 0, 0, 0);
+#pragma unroll
+        for (int r = 4 * nb + 2; r < 4 * nb + 4; ++r) d[r] = fmaf(s_next[r], p.scale_log2e, -m_ref);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    if (have_b) {
+      PKV_PF_WAIT_V8(0, vtb);
+      clear_rows_past_context(vtb, 2 * i + 1);
+      const bf16x8 p_hi = __builtin_bit_cast(bf16x8, u32x4{hi[4], hi[5], hi[6], hi[7]});
+      const bf16x8 p_lo = __builtin_bit_cast(bf16x8, u32x4{lo[4], lo[5], lo[6], lo[7]});
+#pragma unroll
+      for (int nb = 0; nb < 4; ++nb) {
+        const bf16x8 vop = __builtin_bit_cast(bf16x8, u32x4{vtb[2 * nb][0], vtb[2 * nb][1], vtb[2 * nb + 1][0], vtb[2 * nb + 1][1]});
         acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p_hi, vop, acc[nb], 0, 0, 0);
         acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p_lo, vop, acc[nb], 0, 0, 0);
       }
     }
+    // causal mask of the next pair (its scaling was done above)
+    const int pr = i + 1;
+    const int kpos0 = 2 * pr * kTileTokens + 4 * hl;
+    if ((2 * pr + 2) * kTileTokens - 1 > pos0 + qw) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (kpos0 + 8 * (r / 4) + (r % 4) > qpos) d[r] = -INFINITY;
+    }
   };
 
-  // ---- walk the tiles in pairs: the next pair is fetched while this one is consumed --------------
-  issue(0);
-  if (ntiles > 1) issue(1);
-  for (int j = 0; j < ntiles; j += 2) {
-    PKV_PF_WAIT_VMCNT(0);   // this wavefront's shares of tiles j and j+1 have landed
-    // A bare barrier: what it orders is in LDS and complete by the wait above and by data
-    // dependence (the LDS reads of the previous pair fed the matrix cores before this point).
-    // After it every wavefront's share of the pair is there, and everybody is done with the
-    // previous pair, whose two stages are refilled now.
+  // ---- walk the pairs ------------------------------------------------------------------------------
+  const int npairs = (ntiles + 1) / 2;
+  const int np_wave = wave_live ? wave_last_tile / 2 + 1 : 0;   // pairs this wavefront weighs
+  // Barrier k.  Before it every wavefront waits for its own shares of the pairs requested so
+  // far, so after it the pairs up to k+2 are complete; and every wavefront has finished
+  // phase 2 of pair k-1, whose place pair k+3 takes: its two tiles were located ahead of the
+  // barrier and are requested right behind it.  A bare s_barrier: what it orders is in LDS,
+  // complete by the wait above (writes) and by data dependence (reads fed the matrix cores
+  // before this point).
+  const uint8_t* next_a = nullptr;
+  const uint8_t* next_b = nullptr;
+  auto locate_pair = [&](int pr) {
+    if (2 * pr >= ntiles) return;
+    // the block ids of both tiles with one LDS read: an aligned pair of table entries holds them
+    // (tile 2pr is even, so with one tile per block they are entries 2pr and 2pr+1, else one entry)
+    const int ia = (2 * pr) >> p.tpb_shift, ib = (2 * pr + 1) >> p.tpb_shift;
+    u32x2 two;
+    asm volatile("ds_read_b64 %0, %1\n\ts_waitcnt lgkmcnt(0)"
+                 : "=v"(two) : "v"(ids_base + 4u * (uint32_t)(ia & ~1)) : "memory");
+    const int e0 = __builtin_amdgcn_readfirstlane((int)two[0]), e1 = __builtin_amdgcn_readfirstlane((int)two[1]);
+    next_a = locate(2 * pr, (ia & 1) ? e1 : e0);
+    if (2 * pr + 1 < ntiles) next_b = locate(2 * pr + 1, (ib & 1) ? e1 : e0);
+  };
+  auto request_pair = [&](int pr) {
+    if (2 * pr < ntiles) request(2 * pr, next_a);
+    if (2 * pr + 1 < ntiles) request(2 * pr + 1, next_b);
+  };
+  auto barrier_and_fetch = [&](int k) {
+    PKV_PF_WAIT_VMCNT(0);
     asm volatile("s_barrier" ::: "memory");
-    if (j + 2 < ntiles) issue(j + 2);
-    if (j + 3 < ntiles) issue(j + 3);
-    if (j <= wave_last_tile) consume(j, j + 1 < ntiles);
+    request_pair(k + 3);
+  };
+  const bool shifted = wave >= kWaves / 2;               // the wavefront's phase against the barrier
+
+  for (int pr = 0; pr < 3; ++pr) {
+    locate_pair(pr);
+    request_pair(pr);
   }
+  locate_pair(3);
+  PKV_PF_WAIT_VMCNT(0);
+  asm volatile("s_barrier" ::: "memory");
+  if (np_wave > 0) {
+    first_scores();
+    read_next_k(0);
+  }
+  for (int i = 0; i < npairs; ++i) {
+    if (!shifted) barrier_and_fetch(i);
+    if (i < np_wave) phase1(i);
+    if (shifted) barrier_and_fetch(i);
+    if (i < np_wave) phase2(i, 2 * i + 1 < ntiles);
+    locate_pair(i + 4);                       // (its wait also ends the reads of a last phase 2)
+    if (i + 1 < np_wave) read_next_k(i + 1);
+  }
+#undef PKV_PF_READ_K4
+#undef PKV_PF_WAIT_K4
+#undef PKV_PF_READ_V8
+#undef PKV_PF_WAIT_V8
 
   // ---- normalise and store ------------------------------------------------------------------------
   if (!wave_live) return;
@@ -396,19 +559,19 @@ hipError_t launch_attn_prefill(AttnParams& p, int max_query_len, int max_context
   const int64_t nwg = (int64_t)((max_query_len + qpg - 1) / qpg) * p.group_tiles * p.streams_per_xcd * 8;
   if (nwg > 0x7FFFFFFF) return hipErrorInvalidValue;
   const dim3 grid((unsigned)nwg);
-  const size_t ids_bytes = (size_t)((max_context_len + p.block_size - 1) / p.block_size) * 4 + 16;
-  static std::atomic<bool> prepared[kMaxDevices];   // static + dynamic LDS may exceed 64 KiB: ask once per device
+  const size_t lds_bytes = (size_t)kRingBytes + (size_t)((max_context_len + p.block_size - 1) / p.block_size) * 4 + 16;
+  static std::atomic<bool> prepared[kMaxDevices];   // more than 64 KiB of dynamic LDS: ask once per device
   const int slot = current_device_slot();
   if (!prepared[slot].load(std::memory_order_acquire)) {
     for (const void* f : {reinterpret_cast<const void*>(&attn_prefill_mfma_d128<1>),
                           reinterpret_cast<const void*>(&attn_prefill_mfma_d128<2>)}) {
-      const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxIdsBytes);
+      const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, kRingBytes + kMaxIdsBytes);
       if (e != hipSuccess) return e;
     }
     prepared[slot].store(true, std::memory_order_release);
   }
-  if (hw == 1) hipLaunchKernelGGL((attn_prefill_mfma_d128<1>), grid, dim3(kThreads), ids_bytes, s, p);
-  else hipLaunchKernelGGL((attn_prefill_mfma_d128<2>), grid, dim3(kThreads), ids_bytes, s, p);
+  if (hw == 1) hipLaunchKernelGGL((attn_prefill_mfma_d128<1>), grid, dim3(kThreads), lds_bytes, s, p);
+  else hipLaunchKernelGGL((attn_prefill_mfma_d128<2>), grid, dim3(kThreads), lds_bytes, s, p);
   return hipGetLastError();
 }
 
