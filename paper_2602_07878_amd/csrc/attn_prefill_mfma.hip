@@ -21,10 +21,10 @@
 // Per pair, in the 32x32x16 shape (on this part the 16x16 shapes run at half the rate: 1.3
 // against 2.3 PFLOP/s measured for back-to-back bf16 MFMAs):
 //   S^T[token][query] = K Q^T   8 x v_mfma_f32_32x32x16_bf16 (32 tokens x 32 queries x 128 dims)
-//   causal mask, lazy-max base-2 softmax in fp32: a lane holds 16 tokens of one query, and that
-//   is already the A-operand layout of the second product (k-step u = tile u of the pair), so
-//   the weights never move between lanes; cross-lane traffic only when the reference maximum
-//   has to be raised
+//   causal mask, base-2 softmax in fp32 relative to a lazily raised reference maximum: a lane
+//   holds 16 tokens of one query, and that is already the A-operand layout of the second
+//   product (k-step u = tile u of the pair), so the weights never move between lanes;
+//   cross-lane traffic only when the reference maximum has to be raised
 //   O[query][dim] += P V        2 x 2 x 4 x v_mfma_f32_32x32x16_bf16, P split into a bf16 head
 //   and a bf16 remainder (exact to 2^-17), V through the transposing LDS read.
 //
@@ -32,15 +32,23 @@
 // softmax, the vector ALU idle during the products, and both idle while LDS answers.  So the
 // walk is software-pipelined inside a wavefront, in two phases per pair i:
 //   phase 1: the exponentials and the bf16 split of pair i, two weights per slice, with one
-//            MFMA of the first product of pair i+1 issued in front of each slice; the K rows
-//            of pair i+1 and the V rows of pair i are read from LDS meanwhile
+//            MFMA of the first product of pair i+1 issued in front of each slice (its K rows
+//            were read from LDS a phase earlier; the V rows of pair i are read meanwhile)
 //   phase 2: the second product of pair i, interleaved with the scaling of the new scores
-//            (and their causal mask and running maximum)
+//            (and their causal mask); then the K rows of pair i+2 are read and the addresses
+//            of the tiles to fetch next are formed, ahead of the barrier
 // and the two wavefronts that share a SIMD run in opposite phases: the workgroup's barrier
-// falls before phase 1 in wavefronts 0..3 and before phase 2 in wavefronts 4..7, so that one
-// of the two is in its ALU-heavy phase while the other is in its MFMA-heavy one.  The ring
+// falls before phase 1 in wavefronts 0..3 and before phase 2 in wavefronts 4..7.  The ring
 // holds four pairs for this: at barrier k the pairs up to k+2 are complete, pair k+3 is
 // requested into the place of pair k-1, and the pairs k .. k+2 are being read.
+//
+// What bounds it (measured): instruction issue.  A pair costs a wavefront some 200
+// instructions (24 MFMAs, 115 vector ALU, 26 LDS, the rest scalar), many in dependent chains,
+// and a wavefront alone on its SIMD needs about 2000 cycles for them; the two per SIMD that
+// the 225 registers allow overlap to about 2500 cycles for their two pairs, against 1536 of
+// MFMA time.  Fetches and barriers cost 5 % on top.  A single-phase schedule (24 slices of
+// one MFMA and a few ALU instructions) was no faster for a lone wavefront and, short of
+// registers, slower for two.
 
 #include <atomic>
 #include <type_traits>
@@ -62,7 +70,6 @@ typedef const void __attribute__((address_space(1)))* gptr_t;
 typedef void __attribute__((address_space(3)))* lptr_t;
 
 constexpr int D = 128;
-constexpr int kThreads = 512, kWaves = kThreads / kWaveSize;   // one quarter tile (1 KiB) of K or V per wavefront
 constexpr int kQueryPerWave = 32;
 constexpr int kTileBytes = 4096, kStageBytes = 2 * kTileBytes;
 constexpr int kStages = 8;                 // K/V ring depth in tiles: four pairs
@@ -85,8 +92,14 @@ __device__ __forceinline__ uint32_t bf16x2_rne(float lo, float hi) {
 
 // HW = query heads per workgroup (1 or 2): wavefront w works on head (w / (8 / HW)) and on the
 // 32 query tokens number (w % (8 / HW)) of the workgroup.
+// A tile is fetched in eight quarter-tile shares of 1 KiB (four of K, four of V), one per
+// wavefront.  (Workgroups of four wavefronts, two to a CU, each wavefront bringing two shares,
+// were measured 8 % slower: the same work per SIMD, twice the fetches.)
+constexpr int kWaves = 8, kThreads = kWaves * kWaveSize;
 template <int HW>
 __global__ __launch_bounds__(kThreads, 2) void attn_prefill_mfma_d128(const AttnParams p) {
+  constexpr int NW = kWaves;
+  constexpr int kShares = 8 / NW;                                   // quarter tiles per wavefront and tile
   constexpr int kGroupsPerHead = kWaves / HW;                       // 32-query groups per head
   constexpr int kQueryPerGroup = kGroupsPerHead * kQueryPerWave;    // query tokens per workgroup
   __shared__ __attribute__((aligned(16))) float xchg_all[kWaves][128];
@@ -133,16 +146,18 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_mfma_d128(const Attn
   const int wave_last_tile = wave_live ? (pos0 + min(ql, qw + kQueryPerWave) - 1) / kTileTokens : -1;
 
   // ---- per-lane offsets: same swizzled LDS images as the decode kernel -------------------------
-  // fetch: wavefront w < 4 brings K rows 4w..4w+3 of a tile, wavefront w >= 4 V rows 4(w-4)..+3;
+  // fetch: share s < 4 is K rows 4s..4s+3 of a tile, share s >= 4 V rows 4(s-4)..+3;
   // K row t keeps its 16-byte piece c at slot c ^ t, V row t at slot c ^ 2(t mod 8)
   const uint32_t rbase = (uint32_t)(uintptr_t)(lptr_t)ring;   // LDS byte address of the ring
-  uint32_t foff, fdst;
-  {
+  uint32_t foff[kShares], fdst[kShares];
+#pragma unroll
+  for (int k = 0; k < kShares; ++k) {
+    const int share = wave + k * NW;
     const int q4 = lane >> 4, t16 = lane & 15;
-    const int frow = 4 * (wave & 3) + q4;
-    foff = wave >= 4 ? (uint32_t)(frow * p.v_stride_token) + (uint32_t)((t16 ^ (2 * (frow & 7))) * 16)
-                     : (uint32_t)(frow * p.k_stride_token) + (uint32_t)((t16 ^ frow) * 16);
-    fdst = (uint32_t)((wave >= 4 ? kTileBytes : 0) + (wave & 3) * 1024);
+    const int frow = 4 * (share & 3) + q4;
+    foff[k] = share >= 4 ? (uint32_t)(frow * p.v_stride_token) + (uint32_t)((t16 ^ (2 * (frow & 7))) * 16)
+                         : (uint32_t)(frow * p.k_stride_token) + (uint32_t)((t16 ^ frow) * 16);
+    fdst[k] = (uint32_t)((share >= 4 ? kTileBytes : 0) + (share & 3) * 1024);
   }
   // first product: this lane is token c32 of the pair (tile c32/16, row c32%16) and needs dims
   // 16s + 8hl .. +7 of its K row in step s, i.e. piece 2s + hl
@@ -183,17 +198,17 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_mfma_d128(const Attn
   // A tile's fetch in two steps, so that the first can be done ahead of the barrier that frees
   // the tile's place in the ring: locate() forms the address of this wavefront's quarter
   // from the block id (wave-uniform, in scalar registers), request() starts the load.
-  auto locate = [&](int j, int blk_id) -> const uint8_t* {
+  auto locate = [&](int j, int blk_id, int k) -> const uint8_t* {
     const int64_t blk = blk_id;
     const int slot0 = (j & tile_mask) * kTileTokens;
-    return wave >= 4 ? vpool + blk * p.v_stride_block + kvh * p.v_stride_head + slot0 * p.v_stride_token
-                     : kpool + blk * p.k_stride_block + kvh * p.k_stride_head + slot0 * p.k_stride_token;
+    return wave + k * NW >= 4 ? vpool + blk * p.v_stride_block + kvh * p.v_stride_head + slot0 * p.v_stride_token
+                              : kpool + blk * p.k_stride_block + kvh * p.k_stride_head + slot0 * p.k_stride_token;
   };
-  auto request = [&](int j, const uint8_t* base) {
+  auto request = [&](int j, const uint8_t* base, int k) {
     // default cache policy: other workgroups (other query groups, other heads) read the same
     // tile again, so unlike in the decode kernel it should stay in L2
-    __builtin_amdgcn_global_load_lds((gptr_t)(base + foff),
-                                     (lptr_t)(ring + (j & (kStages - 1)) * kStageBytes + fdst), 16, 0, 0);
+    __builtin_amdgcn_global_load_lds((gptr_t)(base + foff[k]),
+                                     (lptr_t)(ring + (j & (kStages - 1)) * kStageBytes + fdst[k]), 16, 0, 0);
   };
 
   // ---- query rows as the B operand: column c32 = query token qi, dims 16s + 8hl .. +7 in step s --
@@ -467,8 +482,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_mfma_d128(const Attn
   // barrier and are requested right behind it.  A bare s_barrier: what it orders is in LDS,
   // complete by the wait above (writes) and by data dependence (reads fed the matrix cores
   // before this point).
-  const uint8_t* next_a = nullptr;
-  const uint8_t* next_b = nullptr;
+  const uint8_t* next_a[kShares];
+  const uint8_t* next_b[kShares];
   auto locate_pair = [&](int pr) {
     if (2 * pr >= ntiles) return;
     // the block ids of both tiles with one LDS read: an aligned pair of table entries holds them
@@ -478,19 +493,26 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_mfma_d128(const Attn
     asm volatile("ds_read_b64 %0, %1\n\ts_waitcnt lgkmcnt(0)"
                  : "=v"(two) : "v"(ids_base + 4u * (uint32_t)(ia & ~1)) : "memory");
     const int e0 = __builtin_amdgcn_readfirstlane((int)two[0]), e1 = __builtin_amdgcn_readfirstlane((int)two[1]);
-    next_a = locate(2 * pr, (ia & 1) ? e1 : e0);
-    if (2 * pr + 1 < ntiles) next_b = locate(2 * pr + 1, (ib & 1) ? e1 : e0);
+#pragma unroll
+    for (int k = 0; k < kShares; ++k) {
+      next_a[k] = locate(2 * pr, (ia & 1) ? e1 : e0, k);
+      if (2 * pr + 1 < ntiles) next_b[k] = locate(2 * pr + 1, (ib & 1) ? e1 : e0, k);
+    }
   };
   auto request_pair = [&](int pr) {
-    if (2 * pr < ntiles) request(2 * pr, next_a);
-    if (2 * pr + 1 < ntiles) request(2 * pr + 1, next_b);
+#pragma unroll
+    for (int k = 0; k < kShares; ++k) {
+      if (2 * pr < ntiles) request(2 * pr, next_a[k], k);
+      if (2 * pr + 1 < ntiles) request(2 * pr + 1, next_b[k], k);
+    }
   };
   auto barrier_and_fetch = [&](int k) {
     PKV_PF_WAIT_VMCNT(0);
     asm volatile("s_barrier" ::: "memory");
     request_pair(k + 3);
   };
-  const bool shifted = wave >= kWaves / 2;               // the wavefront's phase against the barrier
+  // the wavefront's phase against the barrier: of the two wavefronts of a SIMD the later runs shifted
+  const bool shifted = wave >= kWaves / 2;
 
   for (int pr = 0; pr < 3; ++pr) {
     locate_pair(pr);
@@ -554,12 +576,13 @@ hipError_t launch_attn_prefill(AttnParams& p, int max_query_len, int max_context
   while ((kTileTokens << p.tpb_shift) < p.block_size) ++p.tpb_shift;
   const int hw = p.group == 1 ? 1 : 2;                       // heads per workgroup
   p.group_tiles = (p.group + hw - 1) / hw;
+  const size_t ids_bytes = (size_t)((max_context_len + p.block_size - 1) / p.block_size) * 4 + 16;
+  const size_t lds_bytes = (size_t)kRingBytes + ids_bytes;
   const int qpg = kWaves / hw * kQueryPerWave;               // query tokens per workgroup
   p.streams_per_xcd = (p.num_kv_heads * p.batch + 7) / 8;
   const int64_t nwg = (int64_t)((max_query_len + qpg - 1) / qpg) * p.group_tiles * p.streams_per_xcd * 8;
   if (nwg > 0x7FFFFFFF) return hipErrorInvalidValue;
   const dim3 grid((unsigned)nwg);
-  const size_t lds_bytes = (size_t)kRingBytes + (size_t)((max_context_len + p.block_size - 1) / p.block_size) * 4 + 16;
   static std::atomic<bool> prepared[kMaxDevices];   // more than 64 KiB of dynamic LDS: ask once per device
   const int slot = current_device_slot();
   if (!prepared[slot].load(std::memory_order_acquire)) {
