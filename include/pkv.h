@@ -262,8 +262,11 @@ int32_t kv_block_swap(const pkv_swap_desc* desc, const void* src_pool,
  * staging_bytes >= 2*num_planes*block_bytes (PKV_ERR_WORKSPACE otherwise; bigger
  * pieces make longer PCIe transfers): the kv_block_swap kernel gathers or
  * scatters one piece on stream_compute while the neighbouring piece crosses
- * PCIe as a strided copy on stream_copy (the two may be the same stream: the
- * pieces then go one after the other).  Both calls only enqueue work.  After
+ * PCIe on stream_copy (the two may be the same stream: the pieces then go one
+ * after the other).  A piece is a group of whole planes, one contiguous copy,
+ * when 2*n_pairs*block_bytes fits into half of `staging` and n_pairs*block_bytes
+ * equals the host plane stride; else a range of pairs of every plane, one
+ * strided copy, which is slower device-to-host.  Both calls only enqueue work.  After
  * kv_swap_out_host, completion of stream_compute implies that all of host_dst
  * is written; after kv_swap_in_host, completion of stream_compute implies that
  * the pool blocks are.  The copy stream is made to wait for work enqueued on
