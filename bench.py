@@ -88,14 +88,16 @@ def time_attention(w, d, steps, warmup, torch, binding, kernel_events=False):
     return out, ev_ms / steps, wall_ms / steps, kern
 
 
+KERNEL_SOURCES = ("attn_stream_mfma.hip", "pkv_internal.h", "api.hip")   # what defines the dominant kernel and its launch
+
+
 def source_fingerprint():
-    """Hash of the HIP sources: counter-derived figures under profiles/ are quoted only while the
-    kernels they were taken from are unchanged."""
-    import glob
+    """Hash of the sources of the dominant kernel: counter-derived figures under profiles/ are
+    quoted only while the kernel they were taken from is unchanged."""
     import hashlib
     h = hashlib.sha256()
-    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2602_07878_amd", "csrc", "*"))):
-        h.update(open(f, "rb").read())
+    for f in KERNEL_SOURCES:
+        h.update(open(os.path.join(ROOT, "paper_2602_07878_amd", "csrc", f), "rb").read())
     return h.hexdigest()[:16]
 
 
