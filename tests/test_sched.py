@@ -118,6 +118,115 @@ def test_requests_that_can_never_run_are_refused():
         s.add_request(1, 2, 2)
 
 
+# ---- chunked prefill (the paper's section "Effects of Chunked Prefill") ---------------------------
+def test_chunked_hand_worked_trace_long_prompt_in_chunks_beside_a_decoding_request():
+    s = ref(num_gpu_blocks=8, block_size=4, max_num_seqs=4, max_num_batched_tokens=8, chunked=True)
+    s.add_request(1, 3, 10)
+    o = s.step()                       # whole prompt in one chunk: block 0
+    assert o["prefill"] == [(1, 3, 3)] and o["free_blocks"] == 7
+    s.add_request(2, 20, 3)            # 2.5 budgets long: impossible without chunking
+    o = s.step()                       # the decode token of request 1 costs 1 of the 8: chunk of 7 -> blocks 1, 2
+    assert o["decode"] == [(1, 4, [0])] and o["prefill"] == [(2, 7, 7)] and o["free_blocks"] == 5
+    o = s.step()                       # request 1 grows into block 3; next 7 tokens -> 14 cached, blocks 4, 5
+    assert o["decode"] == [(1, 5, [0, 3])] and o["prefill"] == [(2, 7, 14)] and o["free_blocks"] == 2
+    o = s.step()                       # the last 6 tokens: 20 cached, block 6; this chunk yields the first token
+    assert o["decode"] == [(1, 6, [0, 3])] and o["prefill"] == [(2, 6, 20)] and o["free_blocks"] == 1
+    o = s.step()                       # now both decode; request 2 starts a new block at 20 = 5 * 4 tokens
+    assert o["decode"] == [(1, 7, [0, 3]), (2, 21, [1, 2, 4, 5, 6, 7])] and o["prefill"] == [] and o["free_blocks"] == 0
+    # request 1 decoded in every iteration (no compute-bound stall behind the long prompt), and
+    # the cache use rose chunk by chunk: 7, 5, 2, 1, 0 blocks free
+    assert s.totals["decoded"] == 5 and s.totals["preemptions"] == 0
+
+
+def test_chunked_running_chunks_are_reported_before_admissions_of_the_same_iteration():
+    s = ref(num_gpu_blocks=8, block_size=4, max_num_seqs=4, max_num_batched_tokens=8, chunked=True)
+    s.add_request(1, 10, 5)
+    o = s.step()
+    assert o["prefill"] == [(1, 8, 8)] and o["free_blocks"] == 6
+    s.add_request(2, 3, 5)
+    o = s.step()                       # the last 2 tokens of request 1 (block 2), then request 2 whole (block 3)
+    assert o["prefill"] == [(1, 2, 10), (2, 3, 3)] and o["decode"] == [] and o["free_blocks"] == 4
+    o = s.step()
+    assert o["decode"] == [(1, 11, [0, 1, 2]), (2, 4, [3])]
+
+
+def test_chunked_without_chunking_the_long_prompt_is_refused():
+    s = ref(num_gpu_blocks=8, block_size=4, max_num_seqs=4, max_num_batched_tokens=8)
+    with pytest.raises(ValueError):
+        s.add_request(2, 20, 3)
+    with pytest.raises(ValueError):    # the budget must pay one decode token per running request
+        ref(max_num_seqs=8, max_num_batched_tokens=4, chunked=True)
+
+
+def test_chunked_partial_prefill_is_the_lifo_victim_and_starts_over_under_recompute():
+    s = ref(num_gpu_blocks=4, block_size=2, max_num_seqs=4, max_num_batched_tokens=4, chunked=True)
+    s.add_request(1, 2, 6)
+    s.add_request(2, 6, 2)
+    o = s.step()                       # request 1 whole (block 0), request 2 gets the 2 tokens left: block 1
+    assert o["prefill"] == [(1, 2, 2), (2, 2, 2)] and o["free_blocks"] == 2
+    s.add_request(3, 2, 2)             # waits: the budget of this iteration is used up by then
+    o = s.step()                       # request 1 takes block 2; the chunk of 3 needs 2 blocks, 1 is free:
+    assert o["preempted"] == [2] and o["prefill"] == []          # the last scheduled request goes: itself
+    assert o["decode"] == [(1, 3, [0, 2])] and o["free_blocks"] == 2 and s.waiting[0].computed == 0
+    assert [r.rid for r in s.waiting] == [2, 3]                  # ... to the front of the queue
+    o = s.step()                       # it starts over: 3 tokens (budget 4 - 1 decode) into blocks 3, 1
+    assert o["prefill"] == [(2, 3, 3)] and o["decode"] == [(1, 4, [0, 2])] and o["free_blocks"] == 0
+    o = s.step()                       # request 1 needs a third block: victim is request 2 again
+    assert o["preempted"] == [2] and o["decode"] == [(1, 5, [0, 2, 3])] and o["free_blocks"] == 1
+    assert s.totals["recomputed"] == 0                           # it never produced a token
+
+
+def test_chunked_swap_keeps_the_progress_of_a_partial_prefill():
+    s = ref(num_gpu_blocks=4, num_cpu_blocks=4, block_size=2, max_num_seqs=4, max_num_batched_tokens=4,
+            chunked=True, mode=SWAP)
+    s.add_request(1, 2, 4)
+    s.add_request(2, 6, 1)
+    s.step()                           # request 1: block 0; request 2: 2 of 6 tokens, block 1
+    o = s.step()                       # request 2 cannot get the 2 blocks of its next chunk: swapped out
+    assert o["preempted"] == [2] and o["swap_out"] == [(1, 0)] and s.waiting[0].computed == 2
+    o = s.step()                       # back at once (1 block), into pool block 3; no chunk in this iteration
+    assert o["swap_in"] == [(0, 3)] and o["prefill"] == [] and o["decode"] == [(1, 4, [0, 2])]
+    o = s.step()                       # request 1 takes the last block, request 2 is squeezed out again;
+    assert o["preempted"] == [2] and o["swap_out"] == [(3, 1)]   # request 1 ends with its fourth token
+    assert o["finished"] == [1] and o["free_blocks"] == 4
+    o = s.step()
+    assert o["swap_in"] == [(1, 3)] and o["prefill"] == []
+    o = s.step()                       # the remaining 4 tokens in one chunk; max_new = 1: done
+    assert o["prefill"] == [(2, 4, 6)] and o["finished"] == [2]
+    assert s.totals["recomputed"] == 0 and s.totals["swap_in"] == s.totals["swap_out"] == 2
+
+
+@pytest.mark.parametrize("mode", [SWAP, RECOMPUTE])
+def test_chunked_invariants_under_overload(mode):
+    total, budget = 64, 96
+    s = ref(num_gpu_blocks=total, num_cpu_blocks=48, block_size=16, max_num_seqs=16,
+            max_num_batched_tokens=budget, max_blocks_per_seq=32, mode=mode, chunked=True)
+    stream = W.poisson_request_stream(6, 400, 0.25, prompt_median=96, out_median=96, max_prompt=256, max_new=200)
+    submitted = sum(len(a) for a in stream)
+    prompts = {rid: p for a in stream for rid, p, _ in a}
+    prefilled = {}
+
+    def check(o):
+        owned = [b for r in s.running for b in r.blocks]
+        assert len(owned) == len(set(owned)) and sorted(owned + s.free_gpu) == list(range(total))
+        assert len(o["decode"]) + sum(t for _, t, _ in o["prefill"]) <= budget      # one budget for both
+        for r in s.running:
+            assert len(r.blocks) == -(-r.computed // 16)
+            assert r.prefilling == (r.computed < r.target) or not r.prefilling
+        for rid, tok, ctx in o["prefill"]:
+            assert 0 < tok <= ctx
+            prefilled[rid] = prefilled.get(rid, 0) + tok
+        assert not (o["preempted"] and o["swap_in"])
+
+    drive(s, stream, 4000, check)
+    assert s.totals["finished"] == submitted and not s.running and not s.waiting
+    assert s.totals["preemptions"] > 0
+    assert s.totals["decoded"] == sum(n - 1 for a in stream for _, _, n in a)
+    if mode == SWAP:                   # with host space for every victim no token is prefilled twice
+        assert s.totals["recomputed"] == 0 or s.totals["swap_out"] > 0
+    assert all(prefilled[rid] >= p for rid, p in prompts.items())
+
+
 def drive(s, stream, extra_steps, on_step):
     for arrivals in stream:
         for rid, p, n in arrivals:
