@@ -260,18 +260,21 @@ def time_prefill(torch, binding, B=16, n=4096, Hq=32, Hkv=8, reps=5):
             "frac": flops / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS}
 
 
-def serve_loop(torch, binding, steps, mode="recompute", seed=1007):
+def serve_loop(torch, binding, steps, mode="recompute", seed=1007, chunked=False):
     """The scheduler model driving the GPU calls for `steps` engine iterations under a benign
     Poisson load that saturates the pool (the Fill state, with preemptions): per iteration the
     swaps, the prefills (new and recomputed requests), the KV append and the decode attention
-    of one layer, 8B-shaped heads.  K/V contents are random; only shapes and tables matter here."""
+    of one layer, 8B-shaped heads.  K/V contents are random; only shapes and tables matter here.
+    chunked: prefills proceed in chunks under a 512-token budget per iteration (the example the
+    paper's section on chunked prefill gives) instead of whole within 8192 tokens."""
     import numpy as np
     from paper_2602_07878_amd import sched, workloads as W
     Hq, Hkv, D, bs = 32, 8, 128, 16
     n_gpu, n_cpu, max_blocks = 12288, 12288, 384
     s = sched.Scheduler(num_gpu_blocks=n_gpu, num_cpu_blocks=n_cpu, block_size=bs, max_num_seqs=256,
-                        max_num_batched_tokens=8192, max_blocks_per_seq=max_blocks, watermark_blocks=n_gpu // 100,
-                        mode=sched.SWAP if mode == "swap" else sched.RECOMPUTE)
+                        max_num_batched_tokens=512 if chunked else 8192, max_blocks_per_seq=max_blocks,
+                        watermark_blocks=n_gpu // 100, mode=sched.SWAP if mode == "swap" else sched.RECOMPUTE,
+                        chunked=chunked)
     stream = W.poisson_request_stream(seed, steps, 0.45, prompt_median=700, prompt_sigma=0.9, out_median=400,
                                       out_sigma=0.7, max_prompt=4096, max_new=1500)
     g = torch.Generator(device="cuda:0")
@@ -306,10 +309,11 @@ def serve_loop(torch, binding, steps, mode="recompute", seed=1007):
         pf_tokens = 0
         if info.num_prefill:
             pid, ptok = s.prefills()
-            rows = [(rid, t) for rid, t in zip(pid.tolist(), ptok.tolist())]
+            pctx = s.prefill_contexts()
+            rows = [(rid, t, c) for rid, t, c in zip(pid.tolist(), ptok.tolist(), pctx.tolist())]
             tabs = np.full((len(rows), max_blocks), -1, np.int32)
             keep = []
-            for i, (rid, t) in enumerate(rows):
+            for i, (rid, t, c) in enumerate(rows):
                 try:
                     b = s.request_blocks(rid)
                 except binding.PkvError:
@@ -318,14 +322,15 @@ def serve_loop(torch, binding, steps, mode="recompute", seed=1007):
                 keep.append(i)
             if keep:
                 tabs = tabs[keep]
-                lens = np.array([rows[i][1] for i in keep], np.int32)
+                lens = np.array([rows[i][1] for i in keep], np.int32)      # query tokens (the chunk)
+                ctxs = np.array([rows[i][2] for i in keep], np.int32)      # cached tokens after it
                 pf_tokens = int(lens.sum())
                 cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
                 qv = q_all[:pf_tokens]
-                desc = binding.attn_desc_for(qv, kp, vp, torch.from_numpy(tabs).cuda(), max_context_len=int(lens.max()))
+                desc = binding.attn_desc_for(qv, kp, vp, torch.from_numpy(tabs).cuda(), max_context_len=int(ctxs.max()))
                 desc.batch = len(keep)
-                dl = torch.from_numpy(lens).cuda()
-                binding.paged_prefill_attention(desc, qv, kp, vp, torch.from_numpy(tabs).cuda(), dl, dl,
+                binding.paged_prefill_attention(desc, qv, kp, vp, torch.from_numpy(tabs).cuda(),
+                                                torch.from_numpy(ctxs).cuda(), torch.from_numpy(lens).cuda(),
                                                 torch.from_numpy(cu).cuda(), int(lens.max()), scale, out[:pf_tokens])
         kv_tokens = 0
         if info.num_decode:
@@ -349,7 +354,8 @@ def serve_loop(torch, binding, steps, mode="recompute", seed=1007):
     quiet = steady & (pft == 0) & (pre == 0) & (dec > 0)     # iterations that only decode
     t = s.totals()
     q = lambda a, f: float(np.percentile(a, f)) if a.size else None
-    return {"iterations": len(rec), "mode": mode, "finished": t["finished"], "preemptions": t["preemptions"],
+    return {"iterations": len(rec), "mode": mode, "chunked_prefill_budget": 512 if chunked else None,
+            "finished": t["finished"], "preemptions": t["preemptions"],
             "head_blocked_iterations": t["blocked"], "recomputed_tokens": t["recomputed"],
             "swapped_blocks": t["swap_out"] + t["swap_in"],
             "pool_occupancy_min_max_after_fill": [float(np.min(np.array(occ)[steady])), float(np.max(np.array(occ)[steady]))],
@@ -522,6 +528,8 @@ def main():
 
     if args.serve > 0:
         result["serving_loop"] = {m: serve_loop(torch, binding, args.serve, mode=m) for m in ("recompute", "swap")}
+        result["serving_loop"]["recompute_chunked_prefill"] = serve_loop(torch, binding, args.serve, mode="recompute",
+                                                                         chunked=True)
         log(f"[bench] serving loop: {result['serving_loop']}")
 
     print(json.dumps(result), flush=True)

@@ -40,6 +40,25 @@
  *      join the running list behind them (so they are the next victims) and
  *      decode from the next iteration on; a prefill yields the first token.
  *
+ * With chunked_prefill = 1 (the paper's section "Effects of Chunked Prefill":
+ * a fixed budget of tokens per iteration, prefill chunks interleaved with the
+ * decoding steps of the other requests, the KV-cache use rising chunk by
+ * chunk) the token budget of an iteration pays first for one decode token of
+ * every running request that decodes, then for prefill chunks:
+ *   1'. a running request that is still prefilling reserves, in its turn, the
+ *       blocks of its next chunk = min(tokens left to prefill, budget left)
+ *       (possibly 0 tokens), with the same last-in-first-out preemption when
+ *       the free queue cannot serve it;
+ *   2'. an admission takes min(tokens to prefill, budget left) tokens as its
+ *       first chunk and the blocks of that chunk only; a chunk of 0 tokens
+ *       ends admission like a request that does not fit;
+ *   3'. a request that is prefilling does not decode; the chunk that completes
+ *       its prefill yields the first token, and it decodes from the next
+ *       iteration on.
+ * A partial prefill is preempted like any running request: swapped out it
+ * keeps its progress, recomputed it starts over.  Prompts may then exceed the
+ * budget; max_num_batched_tokens must be >= max_num_seqs.
+ *
  * All memory here is host memory.  The handle owns its state; the arrays the
  * getters fill are the caller's.  Functions that report a status return a
  * pkv_status code of pkv.h; getters return a count, or minus such a code.
@@ -69,12 +88,15 @@ typedef struct pkv_sched_config {
   int32_t preemption_mode;        /* PKV_PREEMPT_SWAP or PKV_PREEMPT_RECOMPUTE; a
                                      swap that finds no host space falls back to
                                      recomputation                                 */
+  int32_t chunked_prefill;        /* 0: a prefill is one piece within the budget;
+                                     1: prefills proceed in chunks (see above)     */
 } pkv_sched_config;
 
 /* What one iteration did (counts) and the state it left. */
 typedef struct pkv_sched_step_info {
   int32_t num_decode;          /* rows of the decode batch                         */
-  int32_t num_prefill;         /* requests prefilled (new or recomputed)           */
+  int32_t num_prefill;         /* prefill records: requests prefilled (new or
+                                  recomputed), or chunks with chunked prefill      */
   int32_t num_prefill_tokens;
   int32_t num_preempted;       /* evictions in this iteration                      */
   int32_t num_swap_out_blocks; /* pairs in the swap-out mapping                    */
@@ -91,7 +113,8 @@ void pkv_sched_destroy(pkv_sched* s);
 
 /*
  * Append a request to the back of the waiting queue.  PKV_ERR_SHAPE if
- * prompt_len < 1, max_new_tokens < 1, the prompt exceeds the token budget, or
+ * prompt_len < 1, max_new_tokens < 1, the prompt exceeds the token budget
+ * (without chunked prefill), or
  * the request at full length would not fit max_blocks_per_seq or the whole
  * pool (it could never run); PKV_ERR_INDEX if request_id is already known.
  */
@@ -122,8 +145,17 @@ int32_t pkv_sched_decode_batch(const pkv_sched* s, int64_t* request_ids, int32_t
 int32_t pkv_sched_swap_out(const pkv_sched* s, int32_t* mapping, int32_t capacity_pairs);
 int32_t pkv_sched_swap_in(const pkv_sched* s, int32_t* mapping, int32_t capacity_pairs);
 
-/* Prefills of the last iteration: ids and token counts.  Returns the count. */
+/*
+ * Prefills of the last iteration: ids and token counts (with chunked prefill:
+ * one record per chunk, the chunks of requests already running first, in
+ * running order, then the admissions).  Returns the count.
+ * pkv_sched_prefill_contexts: for the same records, the tokens the request has
+ * cached after this prefill (= tokens unless it is a later chunk): query_lens =
+ * tokens and context_lens = these are the arguments of paged_prefill_attention,
+ * the block table rows come from pkv_sched_request_blocks.
+ */
 int32_t pkv_sched_prefills(const pkv_sched* s, int64_t* request_ids, int32_t* tokens, int32_t capacity);
+int32_t pkv_sched_prefill_contexts(const pkv_sched* s, int32_t* context_lens, int32_t capacity);
 /* Requests that finished in the last iteration.  Returns the count. */
 int32_t pkv_sched_finished(const pkv_sched* s, int64_t* request_ids, int32_t capacity);
 

@@ -1,6 +1,7 @@
 // Host-side scheduler / block-manager model (arXiv 2602.07878, Sec. 5.1): FIFO free-block
 // queue, first-come-first-served admission with head-of-line blocking, last-in-first-out
-// preemption with swap or recompute recovery.  It produces, iteration by iteration, the
+// preemption with swap or recompute recovery, optionally chunked prefill (the paper's section
+// "Effects of Chunked Prefill").  It produces, iteration by iteration, the
 // block tables, context lengths and swap mappings that the GPU calls of this library take.
 // Plain C++ on the host; see pkv_sched.h for the iteration it implements.
 
@@ -23,6 +24,10 @@ struct Request {
   int32_t generated = 0;   // output tokens produced so far
   int32_t computed = 0;    // tokens whose K/V sit in pool blocks
   bool swapped = false;
+  // chunked prefill: part of the tokens to prefill is still to come
+  bool prefilling = false;
+  int32_t target = 0;      // ... tokens to have cached before decoding starts
+  int32_t chunk = 0;       // ... tokens of the chunk of the current iteration
   std::vector<int32_t> blocks;      // pool blocks in logical order
   std::vector<int32_t> cpu_blocks;  // host blocks while swapped out
 };
@@ -38,7 +43,7 @@ struct pkv_sched {
   int64_t totals[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   // results of the last iteration
   std::vector<int64_t> dec_ids, prefill_ids, finished_ids;
-  std::vector<int32_t> dec_lens, dec_tables, prefill_tokens, swap_out, swap_in;
+  std::vector<int32_t> dec_lens, dec_tables, prefill_tokens, prefill_contexts, swap_out, swap_in;
   int32_t preempted_now = 0;
 
   int32_t take_block() {
@@ -64,6 +69,7 @@ struct pkv_sched {
     } else {   // recomputation: the cache is dropped
       for (int32_t b : r->blocks) free_gpu.push_back(b);
       r->computed = 0;
+      r->prefilling = false;   // it starts over when it is admitted again
     }
     r->blocks.clear();
     waiting.push_front(r);
@@ -78,16 +84,32 @@ struct pkv_sched {
 
   void step(pkv_sched_step_info* info) {
     dec_ids.clear(); dec_lens.clear(); dec_tables.clear();
-    prefill_ids.clear(); prefill_tokens.clear(); finished_ids.clear();
+    prefill_ids.clear(); prefill_tokens.clear(); prefill_contexts.clear(); finished_ids.clear();
     swap_out.clear(); swap_in.clear();
     preempted_now = 0;
     ++totals[0];
     const int32_t bs = cfg.block_size;
+    const bool chunked = cfg.chunked_prefill != 0;
 
-    // 1. a slot for the next token of every running request, in scheduling order
+    // The token budget of the iteration.  Without chunked prefill it pays for the prefills of
+    // the admissions only; with it, first for one decode token of every decoding request,
+    // then for the prefill chunks of running requests and admissions.
+    int32_t budget = cfg.max_num_batched_tokens;
+    if (chunked)
+      for (const Request* r : running) budget -= r->prefilling ? 0 : 1;
+
+    // 1. in scheduling order, every running request reserves what it needs in this iteration:
+    //    the slot of its next token, or (a request still prefilling) the blocks of its next
+    //    chunk, which is as much of the rest as the budget still allows
     for (size_t i = 0; i < running.size();) {
       Request* r = running[i];
-      const size_t need = r->computed % bs == 0 ? 1 : 0;
+      size_t need;
+      if (r->prefilling) {
+        r->chunk = std::min(r->target - r->computed, budget);
+        need = (size_t)((r->computed + r->chunk + bs - 1) / bs) - r->blocks.size();
+      } else {
+        need = r->computed % bs == 0 ? 1 : 0;
+      }
       bool evicted_self = false;
       while (free_gpu.size() < need) {
         Request* victim = running.back();
@@ -96,7 +118,8 @@ struct pkv_sched {
         if (victim == r) { evicted_self = true; break; }
       }
       if (evicted_self) break;
-      if (need) r->blocks.push_back(take_block());
+      for (size_t k = 0; k < need; ++k) r->blocks.push_back(take_block());
+      if (r->prefilling) budget -= r->chunk;
       ++i;
     }
 
@@ -104,8 +127,9 @@ struct pkv_sched {
     std::vector<Request*> admitted;
     bool head_blocked = false;
     int32_t n_prefill_tokens = 0;
+    std::vector<int64_t> adm_ids;                 // prefill records of the admissions
+    std::vector<int32_t> adm_tokens;
     if (preempted_now == 0) {
-      int32_t budget = cfg.max_num_batched_tokens;
       while (!waiting.empty() && (int32_t)(running.size() + admitted.size()) < cfg.max_num_seqs) {
         Request* r = waiting.front();
         if (r->swapped) {
@@ -121,26 +145,32 @@ struct pkv_sched {
           totals[3] += (int64_t)nb;
           r->cpu_blocks.clear();
           r->swapped = false;
+          r->chunk = 0;
           waiting.pop_front();
           admitted.push_back(r);
           continue;
         }
-        const int32_t tokens = r->generated == 0 ? r->prompt : r->prompt + r->generated - 1;
+        const int32_t total = r->generated == 0 ? r->prompt : r->prompt + r->generated - 1;
+        // all of it or nothing without chunked prefill; else what the budget allows
+        const int32_t tokens = chunked ? std::min(total, budget) : total;
         const size_t nb = (size_t)((tokens + bs - 1) / bs);
-        if (tokens > budget || free_gpu.size() < nb + (size_t)cfg.watermark_blocks) {
+        if (tokens > budget || tokens == 0 || free_gpu.size() < nb + (size_t)cfg.watermark_blocks) {
           head_blocked = true;
           break;
         }
         for (size_t k = 0; k < nb; ++k) r->blocks.push_back(take_block());
+        r->target = total;
         r->computed = tokens;
+        r->chunk = 0;
+        r->prefilling = tokens < total;
         budget -= tokens;
         n_prefill_tokens += tokens;
-        if (r->generated == 0) r->generated = 1;   // the prefill yields the first token
-        else totals[4] += tokens;
-        prefill_ids.push_back(r->id);
-        prefill_tokens.push_back(tokens);
+        if (r->generated > 0) totals[4] += tokens;
+        else if (!r->prefilling) r->generated = 1;   // the (last chunk of the) prefill yields the first token
+        adm_ids.push_back(r->id);
+        adm_tokens.push_back(tokens);
         waiting.pop_front();
-        if (r->generated >= r->max_new) finish(r);
+        if (!r->prefilling && r->generated >= r->max_new) finish(r);
         else admitted.push_back(r);
       }
     }
@@ -161,6 +191,23 @@ struct pkv_sched {
     still.reserve(running.size() + admitted.size());
     const int32_t mb = cfg.max_blocks_per_seq;
     for (Request* r : running) {
+      if (r->prefilling) {           // its chunk of this iteration, if the budget gave it one
+        if (r->chunk > 0) {
+          r->computed += r->chunk;
+          n_prefill_tokens += r->chunk;
+          if (r->generated > 0) totals[4] += r->chunk;
+          prefill_ids.push_back(r->id);
+          prefill_tokens.push_back(r->chunk);
+          prefill_contexts.push_back(r->computed);
+          if (r->computed == r->target) {
+            r->prefilling = false;
+            if (r->generated == 0) r->generated = 1;
+          }
+        }
+        if (!r->prefilling && r->generated >= r->max_new) finish(r);
+        else still.push_back(r);
+        continue;
+      }
       r->computed += 1;
       dec_ids.push_back(r->id);
       dec_lens.push_back(r->computed);
@@ -174,6 +221,13 @@ struct pkv_sched {
     }
     for (Request* r : admitted) still.push_back(r);
     running.swap(still);
+    // prefill records: the chunks of running requests first, then the admissions (whose
+    // cached length is the chunk itself)
+    for (size_t k = 0; k < adm_ids.size(); ++k) {
+      prefill_ids.push_back(adm_ids[k]);
+      prefill_tokens.push_back(adm_tokens[k]);
+      prefill_contexts.push_back(adm_tokens[k]);
+    }
 
     if (info) {
       info->num_decode = (int32_t)dec_ids.size();
@@ -213,7 +267,9 @@ pkv_sched* pkv_sched_create(const pkv_sched_config* cfg) {
   if (!cfg || cfg->num_gpu_blocks < 1 || cfg->num_cpu_blocks < 0 || cfg->block_size < 1 ||
       cfg->max_num_seqs < 1 || cfg->max_num_batched_tokens < 1 || cfg->max_blocks_per_seq < 1 ||
       cfg->watermark_blocks < 0 ||
-      (cfg->preemption_mode != PKV_PREEMPT_SWAP && cfg->preemption_mode != PKV_PREEMPT_RECOMPUTE))
+      (cfg->preemption_mode != PKV_PREEMPT_SWAP && cfg->preemption_mode != PKV_PREEMPT_RECOMPUTE) ||
+      (cfg->chunked_prefill != 0 && cfg->chunked_prefill != 1) ||
+      (cfg->chunked_prefill == 1 && cfg->max_num_batched_tokens < cfg->max_num_seqs))
     return nullptr;
   pkv_sched* s = new pkv_sched;
   s->cfg = *cfg;
@@ -227,7 +283,8 @@ void pkv_sched_destroy(pkv_sched* s) { delete s; }
 int32_t pkv_sched_add_request(pkv_sched* s, int64_t request_id, int32_t prompt_len,
                               int32_t max_new_tokens) {
   if (!s) return PKV_ERR_NULL;
-  if (prompt_len < 1 || max_new_tokens < 1 || prompt_len > s->cfg.max_num_batched_tokens)
+  if (prompt_len < 1 || max_new_tokens < 1 ||
+      (prompt_len > s->cfg.max_num_batched_tokens && !s->cfg.chunked_prefill))
     return PKV_ERR_SHAPE;
   const int64_t full = ((int64_t)prompt_len + max_new_tokens - 1 + s->cfg.block_size - 1) / s->cfg.block_size;
   if (full > s->cfg.max_blocks_per_seq || full > s->cfg.num_gpu_blocks) return PKV_ERR_SHAPE;
@@ -271,6 +328,10 @@ int32_t pkv_sched_prefills(const pkv_sched* s, int64_t* request_ids, int32_t* to
   if (n < 0) return n;
   copy_out(s->prefill_tokens, tokens, capacity);
   return n;
+}
+
+int32_t pkv_sched_prefill_contexts(const pkv_sched* s, int32_t* context_lens, int32_t capacity) {
+  return s ? copy_out(s->prefill_contexts, context_lens, capacity) : -PKV_ERR_NULL;
 }
 
 int32_t pkv_sched_finished(const pkv_sched* s, int64_t* request_ids, int32_t capacity) {

@@ -13,7 +13,7 @@ SWAP, RECOMPUTE = 0, 1
 SCHED_EXPORTS = [
     "pkv_sched_create", "pkv_sched_destroy", "pkv_sched_add_request", "pkv_sched_step",
     "pkv_sched_decode_batch", "pkv_sched_swap_out", "pkv_sched_swap_in", "pkv_sched_prefills",
-    "pkv_sched_finished", "pkv_sched_request_blocks", "pkv_sched_totals",
+    "pkv_sched_finished", "pkv_sched_request_blocks", "pkv_sched_totals", "pkv_sched_prefill_contexts",
 ]
 
 TOTALS = ("steps", "preemptions", "swap_out", "swap_in", "recomputed", "finished", "blocked", "decoded")
@@ -22,7 +22,7 @@ TOTALS = ("steps", "preemptions", "swap_out", "swap_in", "recomputed", "finished
 class SchedConfig(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "num_gpu_blocks", "num_cpu_blocks", "block_size", "max_num_seqs", "max_num_batched_tokens",
-        "max_blocks_per_seq", "watermark_blocks", "preemption_mode")]
+        "max_blocks_per_seq", "watermark_blocks", "preemption_mode", "chunked_prefill")]
 
 
 class StepInfo(ctypes.Structure):
@@ -50,7 +50,7 @@ def _lib():
         L.pkv_sched_step.argtypes = [vp, ctypes.POINTER(StepInfo)]
         L.pkv_sched_decode_batch.restype = i32
         L.pkv_sched_decode_batch.argtypes = [vp, vp, vp, vp, i32]
-        for name in ("pkv_sched_swap_out", "pkv_sched_swap_in", "pkv_sched_finished"):
+        for name in ("pkv_sched_swap_out", "pkv_sched_swap_in", "pkv_sched_finished", "pkv_sched_prefill_contexts"):
             getattr(L, name).restype = i32
             getattr(L, name).argtypes = [vp, vp, i32]
         L.pkv_sched_prefills.restype = i32
@@ -68,9 +68,10 @@ class Scheduler:
     arrays of that iteration are read with decode_batch(), swap_out(), swap_in(), ..."""
 
     def __init__(self, *, num_gpu_blocks, num_cpu_blocks, block_size, max_num_seqs,
-                 max_num_batched_tokens, max_blocks_per_seq, watermark_blocks=0, mode=SWAP):
+                 max_num_batched_tokens, max_blocks_per_seq, watermark_blocks=0, mode=SWAP, chunked=False):
         self.cfg = SchedConfig(num_gpu_blocks, num_cpu_blocks, block_size, max_num_seqs,
-                               max_num_batched_tokens, max_blocks_per_seq, watermark_blocks, mode)
+                               max_num_batched_tokens, max_blocks_per_seq, watermark_blocks, mode,
+                               1 if chunked else 0)
         self._h = _lib().pkv_sched_create(ctypes.byref(self.cfg))
         if not self._h:
             raise ValueError("invalid scheduler configuration")
@@ -126,6 +127,14 @@ class Scheduler:
         got = _lib().pkv_sched_prefills(self._h, ids.ctypes.data, tok.ctypes.data, n)
         assert got == n, got
         return ids, tok
+
+    def prefill_contexts(self):
+        """Cached tokens of each prefill record's request after this iteration (int32 array)."""
+        n = self._info.num_prefill
+        ctx = np.empty(n, np.int32)
+        got = _lib().pkv_sched_prefill_contexts(self._h, ctx.ctypes.data, n)
+        assert got == n, got
+        return ctx
 
     def finished(self):
         n = self._info.num_finished

@@ -22,17 +22,20 @@ def rows_of(rid, n):
     return k, v
 
 
-@pytest.mark.parametrize("mode", ["swap", "recompute"])
-def test_scheduler_driven_decode_with_preemption(mode):
+@pytest.mark.parametrize("mode,chunked", [("swap", False), ("recompute", False), ("swap", True), ("recompute", True)])
+def test_scheduler_driven_decode_with_preemption(mode, chunked):
+    """With chunked=True prompts are prefilled in chunks under a 64-token budget, and the chunks'
+    causal attention over the paged cache (paged_prefill_attention on the scheduler's tables,
+    query_lens = chunk, context_lens = tokens cached after it) is checked against the oracle."""
     import oracle
     import torch
     from paper_2602_07878_amd import binding, sched
     n_gpu, n_cpu = 80, 64
     s = sched.Scheduler(num_gpu_blocks=n_gpu, num_cpu_blocks=n_cpu, block_size=BS, max_num_seqs=16,
-                        max_num_batched_tokens=1024, max_blocks_per_seq=24,
-                        mode=sched.SWAP if mode == "swap" else sched.RECOMPUTE)
+                        max_num_batched_tokens=64 if chunked else 1024, max_blocks_per_seq=24,
+                        mode=sched.SWAP if mode == "swap" else sched.RECOMPUTE, chunked=chunked)
     stream = W.poisson_request_stream(31, 120, 0.35, prompt_median=100, out_median=90, max_prompt=250, max_new=130)
-    stream += [[] for _ in range(500)]
+    stream += [[] for _ in range(1500 if chunked else 500)]      # (a 64-token budget drains the queue more slowly)
     rows = {}
     up = lambda a: torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
     bits = lambda t: t.view(torch.int16).cpu().numpy().view(np.uint16)
@@ -46,7 +49,7 @@ def test_scheduler_driven_decode_with_preemption(mode):
     out_desc = binding.swap_desc(1, block_bytes, n_gpu, n_cpu)
     in_desc = binding.swap_desc(1, block_bytes, n_cpu, n_gpu)
     scale = float(D) ** -0.5
-    checked = swaps = 0
+    checked = swaps = prefill_checked = later_chunks = 0
     rng = np.random.default_rng(99)
     for it, arrivals in enumerate(stream):
         for rid, p, n in arrivals:
@@ -66,17 +69,41 @@ def test_scheduler_driven_decode_with_preemption(mode):
                 swaps += 1
         # 2. prefills (new and recomputed requests): the model's rows land in the request's blocks
         pid, ptok = s.prefills()
-        for rid, tokens in zip(pid.tolist(), ptok.tolist()):
+        pctx = s.prefill_contexts()
+        chunk_rows = []                                     # (block table row, chunk tokens, cached tokens after)
+        for rid, tokens, ctx in zip(pid.tolist(), ptok.tolist(), pctx.tolist()):
+            assert chunked or ctx == tokens
             try:
                 blocks = s.request_blocks(rid)
             except binding.PkvError:
                 continue                                    # finished within its prefill
-            tok = np.arange(tokens)
+            tok = np.arange(ctx - tokens, ctx)              # the chunk's positions
             b, slot = blocks[tok // BS], tok % BS
             k_all, v_all = rows[rid]
-            hk[b, :, slot, :], hv[b, :, slot, :] = k_all[:tokens], v_all[:tokens]
+            hk[b, :, slot, :], hv[b, :, slot, :] = k_all[tok], v_all[tok]
             tb, ts = torch.from_numpy(b.astype(np.int64)).cuda(), torch.from_numpy(slot).cuda()
-            dk[tb, :, ts, :], dv[tb, :, ts, :] = up(k_all[:tokens]), up(v_all[:tokens])
+            dk[tb, :, ts, :], dv[tb, :, ts, :] = up(k_all[tok]), up(v_all[tok])
+            row = np.full(24, -1, np.int32)
+            row[:blocks.size] = blocks
+            chunk_rows.append((row, tokens, ctx))
+            later_chunks += ctx > tokens
+        if chunked and chunk_rows and (it % 5 == 0 or any(c > t for _, t, c in chunk_rows)) and prefill_checked < 60:
+            tabs = np.stack([r for r, _, _ in chunk_rows])
+            ql = np.array([t for _, t, _ in chunk_rows], np.int32)
+            cl = np.array([c for _, _, c in chunk_rows], np.int32)
+            q = W.f32_to_bf16_bits(rng.standard_normal((int(ql.sum()), HQ, D)).astype(np.float32))
+            ref = oracle.paged_prefill_attention(q, hk, hv, tabs, cl, ql, scale, block_size=BS)
+            dq, bt = up(q), torch.from_numpy(tabs).cuda()
+            cu = torch.from_numpy(np.concatenate([[0], np.cumsum(ql)]).astype(np.int32)).cuda()
+            out = torch.empty(int(ql.sum()), HQ, D, dtype=torch.float32, device="cuda")
+            desc = binding.attn_desc_for(dq, dk, dv, bt, max_context_len=int(cl.max()))
+            desc.batch = len(chunk_rows)
+            binding.paged_prefill_attention(desc, dq, dk, dv, bt, torch.from_numpy(cl).cuda(),
+                                            torch.from_numpy(ql).cuda(), cu, int(ql.max()), scale, out)
+            torch.cuda.synchronize()
+            got = out.cpu().numpy().astype(np.float64)
+            assert np.all(np.isfinite(got)) and np.abs(got - ref).max() <= 2e-3, (it, mode, "chunk")
+            prefill_checked += 1
         # 3. decode: append the new tokens' rows, then attention over the grown contexts
         if info.num_decode:
             ids, lens, tabs = s.decode_batch()
@@ -101,8 +128,11 @@ def test_scheduler_driven_decode_with_preemption(mode):
             assert np.array_equal(bits(dk), hk) and np.array_equal(bits(dv), hv), it
             assert np.array_equal(bits(dsk), sk) and np.array_equal(bits(dsv), sv), it
     t = s.totals()
-    print(mode, t, "attention checks", checked, flush=True)
+    print(mode, "chunked" if chunked else "whole prefills", t, "attention checks", checked,
+          "chunk attention checks", prefill_checked, "later chunks", later_chunks, flush=True)
     assert t["finished"] == sum(len(a) for a in stream) and t["preemptions"] > 0 and checked > 20
+    if chunked:
+        assert prefill_checked > 20 and later_chunks > 20
     if mode == "swap":
         assert swaps > 0 and t["swap_in"] == t["swap_out"] > 0
     else:

@@ -283,9 +283,13 @@ def test_header_and_library_agree_on_the_exported_names():
 def test_create_rejects_bad_configurations_and_getters_check_capacity():
     L = sched._lib()
     assert not L.pkv_sched_create(None)
-    bad = sched.SchedConfig(0, 0, 16, 4, 64, 8, 0, 0)
+    bad = sched.SchedConfig(0, 0, 16, 4, 64, 8, 0, 0, 0)
     assert not L.pkv_sched_create(ctypes.byref(bad))
-    bad = sched.SchedConfig(8, 0, 16, 4, 64, 8, 0, 2)
+    bad = sched.SchedConfig(8, 0, 16, 4, 64, 8, 0, 2, 0)
+    assert not L.pkv_sched_create(ctypes.byref(bad))
+    bad = sched.SchedConfig(8, 0, 16, 4, 64, 8, 0, 0, 2)            # chunked_prefill is 0 or 1
+    assert not L.pkv_sched_create(ctypes.byref(bad))
+    bad = sched.SchedConfig(8, 0, 16, 8, 4, 8, 0, 0, 1)             # budget below the decode tokens
     assert not L.pkv_sched_create(ctypes.byref(bad))
     s = sched.Scheduler(num_gpu_blocks=4, num_cpu_blocks=4, block_size=2, max_num_seqs=8,
                         max_num_batched_tokens=64, max_blocks_per_seq=8, mode=sched.RECOMPUTE)
@@ -302,10 +306,12 @@ def test_create_rejects_bad_configurations_and_getters_check_capacity():
         s.request_blocks(12345)
 
 
-@pytest.mark.parametrize("mode,seed,cpu_blocks", [(SWAP, 11, 64), (RECOMPUTE, 12, 0), (SWAP, 13, 6)])
-def test_library_reproduces_the_reference_trace_exactly(mode, seed, cpu_blocks):
+@pytest.mark.parametrize("mode,seed,cpu_blocks,chunked,budget", [
+    (SWAP, 11, 64, False, 1024), (RECOMPUTE, 12, 0, False, 1024), (SWAP, 13, 6, False, 1024),
+    (SWAP, 14, 64, True, 128), (RECOMPUTE, 15, 0, True, 96), (SWAP, 16, 6, True, 64)])
+def test_library_reproduces_the_reference_trace_exactly(mode, seed, cpu_blocks, chunked, budget):
     kw = dict(num_gpu_blocks=96, num_cpu_blocks=cpu_blocks, block_size=16, max_num_seqs=24,
-              max_num_batched_tokens=1024, max_blocks_per_seq=40, watermark_blocks=1)
+              max_num_batched_tokens=budget, max_blocks_per_seq=40, watermark_blocks=1, chunked=chunked)
     r = RefScheduler(mode=mode, **kw)
     s = sched.Scheduler(mode=mode, **kw)
     stream = W.poisson_request_stream(seed, 300, 0.3, prompt_median=120, out_median=100, max_prompt=400, max_new=200)
@@ -322,7 +328,11 @@ def test_library_reproduces_the_reference_trace_exactly(mode, seed, cpu_blocks):
         assert [tuple(p) for p in s.swap_out().tolist()] == o["swap_out"]
         assert [tuple(p) for p in s.swap_in().tolist()] == o["swap_in"]
         pid, ptok = s.prefills()
-        assert list(zip(pid.tolist(), ptok.tolist())) == o["prefill"]
+        if chunked:
+            assert list(zip(pid.tolist(), ptok.tolist(), s.prefill_contexts().tolist())) == o["prefill"]
+        else:
+            assert list(zip(pid.tolist(), ptok.tolist())) == o["prefill"]
+            assert s.prefill_contexts().tolist() == ptok.tolist()
         for q in r.running:
             assert s.request_blocks(q.rid).tolist() == q.blocks
         for q in r.waiting[:3]:
