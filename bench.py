@@ -260,6 +260,44 @@ def time_prefill(torch, binding, B=16, n=4096, Hq=32, Hkv=8, reps=5):
             "frac": flops / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS}
 
 
+def time_prefill_chunk(torch, binding, n=8192, chunk=512, Hq=32, Hkv=8, reps=20):
+    """One chunk of a chunked prefill: the last `chunk` tokens of one sequence of n cached tokens
+    (the paper's example budget is 512 tokens per iteration), with and without the workspace
+    that lets the library split the walk."""
+    D, bs = 128, 16
+    nblk = (n + bs - 1) // bs
+    g = torch.Generator(device="cuda:0")
+    g.manual_seed(1008)
+    kp = torch.randn(nblk, Hkv, bs, D, device="cuda:0", generator=g).bfloat16()
+    vp = torch.randn(nblk, Hkv, bs, D, device="cuda:0", generator=g).bfloat16()
+    bt = torch.randperm(nblk, device="cuda:0", generator=g).int().view(1, -1)
+    cl = torch.full((1,), n, dtype=torch.int32, device="cuda:0")
+    ql = torch.full((1,), chunk, dtype=torch.int32, device="cuda:0")
+    cu = torch.tensor([0, chunk], dtype=torch.int32, device="cuda:0")
+    q = torch.randn(chunk, Hq, D, device="cuda:0", generator=g).bfloat16()
+    out = torch.empty(chunk, Hq, D, device="cuda:0")
+    desc = binding.attn_desc_for(q, kp, vp, bt, max_context_len=n)
+    desc.batch = 1
+    need = binding.prefill_workspace_bytes(desc, chunk, chunk)
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda:0")
+    res = {"workload": f"one {chunk}-token chunk over a context of {n} tokens, {Hq}/{Hkv} heads, bf16",
+           "workspace_MiB": need / 2**20}
+    flops = 4.0 * D * (chunk * (n - chunk) + chunk * (chunk + 1) // 2) * Hq
+    for name, w in (("unsplit", None), ("split", ws if need else None)):
+        f = lambda: binding.paged_prefill_attention(desc, q, kp, vp, bt, cl, ql, cu, chunk, D ** -0.5, out, workspace=w)
+        f()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            f()
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / reps * 1e3
+        res[name] = {"us": us, "tflops": flops / us / 1e6}
+    return res
+
+
 def serve_loop(torch, binding, steps, mode="recompute", seed=1007, chunked=False):
     """The scheduler model driving the GPU calls for `steps` engine iterations under a benign
     Poisson load that saturates the pool (the Fill state, with preemptions): per iteration the
@@ -289,6 +327,7 @@ def serve_loop(torch, binding, steps, mode="recompute", seed=1007, chunked=False
     kn, vn = torch.randn(256, Hkv, D, device="cuda:0", generator=g).bfloat16(), \
         torch.randn(256, Hkv, D, device="cuda:0", generator=g).bfloat16()
     out = torch.empty(8192, Hq, D, device="cuda:0")
+    pf_ws = torch.empty(8192 * Hq * 16 * (D + 2) * 4, dtype=torch.uint8, device="cuda:0")   # most the split prefill asks for
     scale = D ** -0.5
     rec = []
     occ = []
@@ -329,9 +368,11 @@ def serve_loop(torch, binding, steps, mode="recompute", seed=1007, chunked=False
                 qv = q_all[:pf_tokens]
                 desc = binding.attn_desc_for(qv, kp, vp, torch.from_numpy(tabs).cuda(), max_context_len=int(ctxs.max()))
                 desc.batch = len(keep)
+                need = binding.prefill_workspace_bytes(desc, pf_tokens, int(lens.max()))   # > 0: few long walks, split them
                 binding.paged_prefill_attention(desc, qv, kp, vp, torch.from_numpy(tabs).cuda(),
                                                 torch.from_numpy(ctxs).cuda(), torch.from_numpy(lens).cuda(),
-                                                torch.from_numpy(cu).cuda(), int(lens.max()), scale, out[:pf_tokens])
+                                                torch.from_numpy(cu).cuda(), int(lens.max()), scale, out[:pf_tokens],
+                                                workspace=pf_ws[:need] if need else None)
         kv_tokens = 0
         if info.num_decode:
             ids, lens, tabs = s.decode_batch()
@@ -470,6 +511,8 @@ def main():
     result["ceilings"] = probe_ceilings(torch, binding)
     result["prefill"] = time_prefill(torch, binding)
     log(f"[bench] prefill: {result['prefill']}")
+    result["prefill_chunk"] = time_prefill_chunk(torch, binding)
+    log(f"[bench] prefill chunk: {result['prefill_chunk']}")
     log(f"[bench] ceilings: {result['ceilings']}")
 
     if not args.no_cpu:

@@ -205,6 +205,38 @@ int32_t paged_prefill_attention(const pkv_attn_desc* desc, const void* q, const 
                                 float scale, void* out, void* hip_stream);
 
 /*
+ * The same operation for the case that chunked prefill makes the common one
+ * ("Effects of Chunked Prefill": a budget of e.g. 512 tokens per iteration): a
+ * few chunks over long contexts.  One workgroup per (128 query tokens, head
+ * pair) would then leave most of the GPU idle while each walks a whole context,
+ * so the walks are cut into ranges that run side by side and leave fp32
+ * partial results (reference maximum, normaliser, un-normalised output row per
+ * query row, head and range) in `workspace`; a second kernel merges them as the
+ * decode call merges its partitions.
+ *
+ * pkv_prefill_workspace_bytes: device bytes the call needs for `desc`,
+ * total_query_tokens (the number of rows of q, host-known) and max_query_len;
+ * 0 when the walks will not be split (enough workgroups anyway, short
+ * contexts, unsupported or invalid desc).  The split depends on desc->batch,
+ * the head counts, max_query_len, desc->max_context_len and the device's CU
+ * count only.
+ * paged_prefill_attention_ws: as paged_prefill_attention; workspace >= that many
+ * bytes, 16-byte aligned (PKV_ERR_WORKSPACE / PKV_ERR_ALIGN otherwise); NULL
+ * workspace, or total_query_tokens = 0, runs the walks unsplit.
+ * total_query_tokens must not be smaller than cu_query_lens[batch].  Contents
+ * of the workspace on return are unspecified; one buffer must not serve two
+ * calls at the same time.  Results agree with the unsplit call to rounding.
+ */
+size_t pkv_prefill_workspace_bytes(const pkv_attn_desc* desc, int64_t total_query_tokens,
+                                   int32_t max_query_len);
+int32_t paged_prefill_attention_ws(const pkv_attn_desc* desc, const void* q, const void* k_pool,
+                                   const void* v_pool, const int32_t* block_tables,
+                                   const int32_t* context_lens, const int32_t* query_lens,
+                                   const int32_t* cu_query_lens, int32_t max_query_len,
+                                   int64_t total_query_tokens, float scale, void* out,
+                                   void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * KV append (Sec. 2.2 "KV-Cache": the K and V vectors of the token generated
  * in a step join the request's cache before the step's attention reads it).
  * desc is the descriptor of the attention call that follows; context_lens

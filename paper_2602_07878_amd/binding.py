@@ -20,7 +20,8 @@ FLAG_VECTOR_ALU = 1
 
 EXPORTS = [
     "pkv_version", "pkv_status_string", "pkv_last_hip_error_string", "pkv_attn_partition_tokens", "pkv_attn_workspace_bytes",
-    "paged_decode_attention", "paged_decode_attention_timed", "paged_prefill_attention", "kv_append", "kv_block_swap",
+    "paged_decode_attention", "paged_decode_attention_timed", "paged_prefill_attention", "paged_prefill_attention_ws",
+    "pkv_prefill_workspace_bytes", "kv_append", "kv_block_swap",
     "kv_swap_out_host", "kv_swap_in_host",
     "pkv_validate_tables_host",
     "pkv_validate_mapping_host", "pkv_validate_tables", "pkv_validate_mapping",
@@ -85,6 +86,11 @@ def lib() -> ctypes.CDLL:
         L.paged_prefill_attention.restype = i32
         L.paged_prefill_attention.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, vp, i32,
                                               ctypes.c_float, vp, vp]
+        L.paged_prefill_attention_ws.restype = i32
+        L.paged_prefill_attention_ws.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, vp, i32, ctypes.c_int64,
+                                                 ctypes.c_float, vp, vp, ctypes.c_size_t, vp]
+        L.pkv_prefill_workspace_bytes.restype = ctypes.c_size_t
+        L.pkv_prefill_workspace_bytes.argtypes = [ctypes.POINTER(AttnDesc), ctypes.c_int64, i32]
         L.kv_append.restype = i32
         L.kv_append.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, vp]
         for name in ("kv_swap_out_host", "kv_swap_in_host"):
@@ -213,15 +219,28 @@ def swap_desc(num_planes: int, block_bytes: int, src_num_blocks: int, dst_num_bl
     return d
 
 
+def prefill_workspace_bytes(desc: AttnDesc, total_query_tokens: int, max_query_len: int) -> int:
+    """Bytes of device workspace with which paged_prefill_attention splits the walks (0: it will not)."""
+    return int(lib().pkv_prefill_workspace_bytes(ctypes.byref(desc), int(total_query_tokens), int(max_query_len)))
+
+
 def paged_prefill_attention(desc: AttnDesc, q, k_pool, v_pool, block_tables, context_lens, query_lens,
-                            cu_query_lens, max_query_len: int, scale: float, out, *, stream=None):
+                            cu_query_lens, max_query_len: int, scale: float, out, *, stream=None, workspace=None):
     """Causal attention of the last query_lens[i] tokens of every sequence (q, out packed
-    [total, Hq, D]; all tensors on the device)."""
+    [total, Hq, D]; all tensors on the device).  workspace: a device byte tensor of at least
+    prefill_workspace_bytes(desc, q.shape[0], max_query_len) bytes lets few, long walks be split."""
     assert q.is_contiguous() and out.is_contiguous() and out.shape == q.shape
-    st = lib().paged_prefill_attention(ctypes.byref(desc), q.data_ptr(), k_pool.data_ptr(), v_pool.data_ptr(),
-                                       block_tables.data_ptr(), context_lens.data_ptr(), query_lens.data_ptr(),
-                                       cu_query_lens.data_ptr(), int(max_query_len), float(scale),
-                                       out.data_ptr(), _stream_ptr(stream))
+    if workspace is None:
+        st = lib().paged_prefill_attention(ctypes.byref(desc), q.data_ptr(), k_pool.data_ptr(), v_pool.data_ptr(),
+                                           block_tables.data_ptr(), context_lens.data_ptr(), query_lens.data_ptr(),
+                                           cu_query_lens.data_ptr(), int(max_query_len), float(scale),
+                                           out.data_ptr(), _stream_ptr(stream))
+    else:
+        st = lib().paged_prefill_attention_ws(ctypes.byref(desc), q.data_ptr(), k_pool.data_ptr(), v_pool.data_ptr(),
+                                              block_tables.data_ptr(), context_lens.data_ptr(), query_lens.data_ptr(),
+                                              cu_query_lens.data_ptr(), int(max_query_len), int(q.shape[0]), float(scale),
+                                              out.data_ptr(), workspace.data_ptr(),
+                                              workspace.numel() * workspace.element_size(), _stream_ptr(stream))
     _check(st, "paged_prefill_attention")
 
 

@@ -192,14 +192,31 @@ int32_t paged_decode_attention_timed(const pkv_attn_desc* desc, const void* q, c
                         workspace_bytes, hip_stream, ev_kernel_begin, ev_kernel_end);
 }
 
+size_t pkv_prefill_workspace_bytes(const pkv_attn_desc* desc, int64_t total_query_tokens,
+                                   int32_t max_query_len) {
+  if (check_attn_desc(desc) != PKV_OK || max_query_len <= 0 || total_query_tokens <= 0) return 0;
+  if (desc->kv_dtype != PKV_BF16 || !attn_prefill_supported(*desc)) return 0;
+  return prefill_workspace_bytes(*desc, total_query_tokens, max_query_len);
+}
+
 int32_t paged_prefill_attention(const pkv_attn_desc* desc, const void* q, const void* k_pool,
                                 const void* v_pool, const int32_t* block_tables,
                                 const int32_t* context_lens, const int32_t* query_lens,
                                 const int32_t* cu_query_lens, int32_t max_query_len, float scale,
                                 void* out, void* hip_stream) {
+  return paged_prefill_attention_ws(desc, q, k_pool, v_pool, block_tables, context_lens, query_lens,
+                                    cu_query_lens, max_query_len, 0, scale, out, nullptr, 0, hip_stream);
+}
+
+int32_t paged_prefill_attention_ws(const pkv_attn_desc* desc, const void* q, const void* k_pool,
+                                   const void* v_pool, const int32_t* block_tables,
+                                   const int32_t* context_lens, const int32_t* query_lens,
+                                   const int32_t* cu_query_lens, int32_t max_query_len,
+                                   int64_t total_query_tokens, float scale, void* out,
+                                   void* workspace, size_t workspace_bytes, void* hip_stream) {
   const int32_t st = check_attn_desc(desc);
   if (st != PKV_OK) return st;
-  if (max_query_len < 0) return PKV_ERR_SHAPE;
+  if (max_query_len < 0 || total_query_tokens < 0) return PKV_ERR_SHAPE;
   if (desc->batch == 0 || max_query_len == 0) return PKV_OK;
   if (desc->kv_dtype != PKV_BF16) return PKV_ERR_DTYPE;
   if (!attn_prefill_supported(*desc)) return PKV_ERR_SHAPE;
@@ -227,7 +244,20 @@ int32_t paged_prefill_attention(const pkv_attn_desc* desc, const void* q, const 
   p.group = desc->num_q_heads / desc->num_kv_heads;
   p.out_is_bf16 = desc->out_dtype == PKV_BF16;
   p.scale_log2e = scale * 1.4426950408889634f;
-  return hip_status(launch_attn_prefill(p, max_query_len, desc->max_context_len,
+  // the walks are split only if the caller brought the workspace for it
+  p.max_partitions = 1;
+  if (workspace && total_query_tokens > 0) {
+    const int ns = prefill_splits(*desc, max_query_len);
+    const size_t need = prefill_workspace_bytes(*desc, total_query_tokens, max_query_len);
+    if (ns > 1) {
+      if (workspace_bytes < need) return PKV_ERR_WORKSPACE;
+      if (!aligned16(workspace)) return PKV_ERR_ALIGN;
+      p.max_partitions = ns;
+      p.ws_ml = static_cast<float*>(workspace);
+      p.ws_o = p.ws_ml + (size_t)total_query_tokens * desc->num_q_heads * ns * 2;
+    }
+  }
+  return hip_status(launch_attn_prefill(p, max_query_len, desc->max_context_len, total_query_tokens,
                                         static_cast<hipStream_t>(hip_stream)));
 }
 

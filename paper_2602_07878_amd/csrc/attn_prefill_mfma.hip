@@ -74,6 +74,7 @@ constexpr int kQueryPerWave = 32;
 constexpr int kTileBytes = 4096, kStageBytes = 2 * kTileBytes;
 constexpr int kStages = 8;                 // K/V ring depth in tiles: four pairs
 constexpr int kRingBytes = kStages * kStageBytes;
+constexpr float kNoMaximum = -1.0e30f;     // reference maximum of a query that has seen no token yet
 constexpr float kGrowLimit = 0x1p40f;       // a pair's weights relative to a stale reference maximum may sum to this
 constexpr int kMaxIdsBytes = 64 * 1024;     // LDS for one sequence's block table row: 16 Ki blocks
 
@@ -121,11 +122,17 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_mfma_d128(const Attn
   // so stream st gets the ids congruent to st mod 8.  (2) Within a stream the query groups with
   // the most tiles to walk (the latest queries) come first and the short ones fill the gaps at
   // the end; in ascending order every round of workgroups lasts as long as its longest member.
-  const int nq = (int)(gridDim.x / 8) / (p.group_tiles * p.streams_per_xcd);   // query groups per stream
+  // (3) With nsplit > 1 (few workgroups, long walks: chunked prefill of a few sequences) the walk
+  // of a query group is cut into nsplit ranges of pairs, one workgroup each, side by side in
+  // the numbering; they leave partial results that a second kernel merges.
+  const int nsplit = p.max_partitions;
+  const int nq = (int)(gridDim.x / 8) / (p.group_tiles * p.streams_per_xcd * nsplit);   // query groups per stream
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
   const int gtile = slot % p.group_tiles;
-  const int qgroup = nq - 1 - (slot / p.group_tiles) % nq;
-  const int stream = (slot / (p.group_tiles * nq)) * 8 + xcd;
+  const int qs = (slot / p.group_tiles) % (nq * nsplit);
+  const int split = qs % nsplit;
+  const int qgroup = nq - 1 - qs / nsplit;
+  const int stream = (slot / (p.group_tiles * nq * nsplit)) * 8 + xcd;
   if (stream >= p.batch * p.num_kv_heads) return;      // padding of the last round of streams
   const int seq = stream / p.num_kv_heads, kvh = stream - seq * p.num_kv_heads;
   const int n = p.context_lens[seq];
@@ -142,7 +149,11 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_mfma_d128(const Attn
   const int qi = qw + c32;                             // query token of this lane's column
   const bool col_live = qi < ql;
   const int qpos = pos0 + qi;
-  const int ntiles = (pos0 + min(ql, q0 + kQueryPerGroup) - 1) / kTileTokens + 1;
+  const int tiles_all = (pos0 + min(ql, q0 + kQueryPerGroup) - 1) / kTileTokens + 1;   // the group's whole walk
+  // this workgroup's range of pairs [pr_lo, pr_hi) of it, and the tiles that end it
+  const int pairs_all = (tiles_all + 1) / 2;
+  const int pr_lo = (int)((int64_t)split * pairs_all / nsplit), pr_hi = (int)((int64_t)(split + 1) * pairs_all / nsplit);
+  const int ntiles = min(tiles_all, 2 * pr_hi);
   const int wave_last_tile = wave_live ? (pos0 + min(ql, qw + kQueryPerWave) - 1) / kTileTokens : -1;
 
   // ---- per-lane offsets: same swizzled LDS images as the decode kernel -------------------------
@@ -285,7 +296,9 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_mfma_d128(const Attn
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
       u32x4 f0, f1, f2, f3;
-      const uint32_t a0 = krd[4 * half + 0], a1 = krd[4 * half + 1], a2 = krd[4 * half + 2], a3 = krd[4 * half + 3];
+      const uint32_t so = (uint32_t)(((2 * pr_lo) & (kStages - 1)) * kStageBytes);
+      const uint32_t a0 = krd[4 * half + 0] + so, a1 = krd[4 * half + 1] + so, a2 = krd[4 * half + 2] + so,
+                     a3 = krd[4 * half + 3] + so;
       PKV_PF_READ_K4(f0, f1, f2, f3, a0, a1, a2, a3);
       PKV_PF_WAIT_K4(0, f0, f1, f2, f3);
       sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f0), qfrag[4 * half + 0], sc, 0, 0, 0);
@@ -294,7 +307,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_mfma_d128(const Attn
       sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f3), qfrag[4 * half + 3], sc, 0, 0, 0);
     }
     // causal: a query sees positions <= its own (this also removes an absent second tile)
-    const int kpos0 = 4 * hl;
+    const int kpos0 = 2 * pr_lo * kTileTokens + 4 * hl;
     float smax = -INFINITY;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
@@ -302,7 +315,9 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_mfma_d128(const Attn
       smax = fmaxf(smax, d[r]);
     }
     xchg[hl * 32 + c32] = smax;
-    m_ref = fmaxf(xchg[c32], xchg[32 + c32]);
+    // (in a later range of a split walk a query may see nothing of the first pair: the floor
+    // keeps its reference finite, and the first pair it does see raises it by the second path below)
+    m_ref = fmaxf(fmaxf(xchg[c32], xchg[32 + c32]), kNoMaximum);
 #pragma unroll
     for (int r = 0; r < 16; ++r) d[r] -= m_ref;
   };
@@ -474,8 +489,9 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_mfma_d128(const Attn
   };
 
   // ---- walk the pairs ------------------------------------------------------------------------------
-  const int npairs = (ntiles + 1) / 2;
-  const int np_wave = wave_live ? wave_last_tile / 2 + 1 : 0;   // pairs this wavefront weighs
+  const int npairs = pr_hi;                                     // the walk is pairs pr_lo .. pr_hi - 1
+  // pairs this wavefront weighs: up to its own last one, within the workgroup's range
+  const int np_wave = wave_live ? min(wave_last_tile / 2 + 1, pr_hi) : 0;
   // Barrier k.  Before it every wavefront waits for its own shares of the pairs requested so
   // far, so after it the pairs up to k+2 are complete; and every wavefront has finished
   // phase 2 of pair k-1, whose place pair k+3 takes: its two tiles were located ahead of the
@@ -514,18 +530,20 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_mfma_d128(const Attn
   // the wavefront's phase against the barrier: of the two wavefronts of a SIMD the later runs shifted
   const bool shifted = wave >= kWaves / 2;
 
-  for (int pr = 0; pr < 3; ++pr) {
-    locate_pair(pr);
-    request_pair(pr);
+  if (pr_lo < pr_hi) {                           // (uniform over the workgroup)
+    for (int pr = pr_lo; pr < pr_lo + 3; ++pr) {
+      locate_pair(pr);
+      request_pair(pr);
+    }
+    locate_pair(pr_lo + 3);
+    PKV_PF_WAIT_VMCNT(0);
+    asm volatile("s_barrier" ::: "memory");
   }
-  locate_pair(3);
-  PKV_PF_WAIT_VMCNT(0);
-  asm volatile("s_barrier" ::: "memory");
-  if (np_wave > 0) {
+  if (np_wave > pr_lo) {
     first_scores();
-    read_next_k(0);
+    read_next_k(pr_lo);
   }
-  for (int i = 0; i < npairs; ++i) {
+  for (int i = pr_lo; i < npairs; ++i) {
     if (!shifted) barrier_and_fetch(i);
     if (i < np_wave) phase1(i);
     if (shifted) barrier_and_fetch(i);
@@ -542,6 +560,30 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_mfma_d128(const Attn
   if (!wave_live) return;
   xchg[hl * 32 + c32] = l_part;
   const int64_t row0 = (int64_t)p.cu_query_lens[seq] + qw;
+  if (nsplit > 1) {
+    // partial result of this range: reference maximum and normaliser per query, and the
+    // un-normalised output rows; a wavefront that had nothing in the range leaves normaliser 0
+    const bool any = np_wave > pr_lo;
+    if (hl == 0 && qw + c32 < ql) {
+      float* ml = p.ws_ml + (((row0 + c32) * p.num_q_heads + head) * nsplit + split) * 2;
+      ml[0] = any ? m_ref : kNoMaximum;
+      ml[1] = any ? xchg[c32] + xchg[32 + c32] : 0.f;
+    }
+    if (!any) return;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int qq = 8 * k + 4 * hl + e;
+        if (qw + qq < ql) {
+          float* o = p.ws_o + (((row0 + qq) * p.num_q_heads + head) * nsplit + split) * D + c32;
+#pragma unroll
+          for (int nb = 0; nb < 4; ++nb) o[nb * 32] = acc[nb][4 * k + e];
+        }
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
 #pragma unroll
@@ -561,7 +603,56 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_mfma_d128(const Attn
   }
 }
 
+// Merge of the ranges of a split walk: one wavefront per (query row, head), two output dims
+// per lane.  out = sum_s O_s 2^(m_s - M) / sum_s l_s 2^(m_s - M) over the ranges that saw a token.
+__global__ __launch_bounds__(256) void attn_prefill_merge(const AttnParams p) {
+  const int nsplit = p.max_partitions;
+  const int lane = threadIdx.x & (kWaveSize - 1);
+  const int64_t item = (int64_t)blockIdx.x * (256 / kWaveSize) + threadIdx.x / kWaveSize;   // row * Hq + head
+  const int64_t rows = p.cu_query_lens[p.batch];
+  if (item >= rows * p.num_q_heads) return;
+  const float* ml = p.ws_ml + item * nsplit * 2;
+  float mx = kNoMaximum;
+  for (int s = 0; s < nsplit; ++s)
+    if (ml[2 * s + 1] > 0.f) mx = fmaxf(mx, ml[2 * s]);
+  float l = 0.f, o0 = 0.f, o1 = 0.f;
+  for (int s = 0; s < nsplit; ++s) {
+    const float ls = ml[2 * s + 1];
+    if (!(ls > 0.f)) continue;                       // nothing seen in this range (its rows were not written)
+    const float w = __builtin_amdgcn_exp2f(ml[2 * s] - mx);
+    const float2 o = *reinterpret_cast<const float2*>(p.ws_o + (item * nsplit + s) * D + 2 * lane);
+    l += ls * w;
+    o0 += o.x * w;
+    o1 += o.y * w;
+  }
+  const float inv = 1.0f / l;
+  if (p.out_is_bf16) reinterpret_cast<uint32_t*>(p.out)[item * (D / 2) + lane] = bf16x2_rne(o0 * inv, o1 * inv);
+  else *reinterpret_cast<float2*>(reinterpret_cast<float*>(p.out) + item * D + 2 * lane) = float2{o0 * inv, o1 * inv};
+}
+
 }  // namespace
+
+// Ranges a walk is cut into: 1 unless the unsplit grid would leave more than half of the CUs
+// without a workgroup; then as many as fill them, of at least 8 pairs (256 tokens), at most 16.
+int prefill_splits(const pkv_attn_desc& d, int max_query_len) {
+  const int group = d.num_q_heads / d.num_kv_heads;
+  const int hw = group == 1 ? 1 : 2;
+  const int qpg = kWaves / hw * kQueryPerWave;
+  const int64_t base = (int64_t)((max_query_len + qpg - 1) / qpg) * ((group + hw - 1) / hw) * d.num_kv_heads * d.batch;
+  const int ncu = num_cus();
+  if (base <= 0 || 2 * base > ncu) return 1;
+  const int64_t max_pairs = ((int64_t)d.max_context_len + 2 * kTileTokens - 1) / (2 * kTileTokens);
+  int64_t ns = ncu / base;
+  if (ns > max_pairs / 8) ns = max_pairs / 8;
+  if (ns > 16) ns = 16;
+  return ns < 1 ? 1 : (int)ns;
+}
+
+size_t prefill_workspace_bytes(const pkv_attn_desc& d, int64_t total_query_tokens, int max_query_len) {
+  const int ns = prefill_splits(d, max_query_len);
+  if (ns <= 1 || total_query_tokens <= 0) return 0;
+  return (size_t)total_query_tokens * d.num_q_heads * ns * (D + 2) * sizeof(float);
+}
 
 // bf16, head_dim 128, power-of-two block size / 16, block table row of the longest context in LDS
 bool attn_prefill_supported(const pkv_attn_desc& d) {
@@ -571,7 +662,11 @@ bool attn_prefill_supported(const pkv_attn_desc& d) {
          ids_bytes <= kMaxIdsBytes;
 }
 
-hipError_t launch_attn_prefill(AttnParams& p, int max_query_len, int max_context_len, hipStream_t s) {
+// p.max_partitions = ranges per walk (1: results go to p.out; else partials to p.ws_ml /
+// p.ws_o, [rows][Hq][ranges][2] and [rows][Hq][ranges][D] floats, and the merge follows);
+// total_query_tokens bounds the rows (the merge reads the true count from cu_query_lens).
+hipError_t launch_attn_prefill(AttnParams& p, int max_query_len, int max_context_len, int64_t total_query_tokens,
+                               hipStream_t s) {
   p.tpb_shift = 0;
   while ((kTileTokens << p.tpb_shift) < p.block_size) ++p.tpb_shift;
   const int hw = p.group == 1 ? 1 : 2;                       // heads per workgroup
@@ -580,7 +675,8 @@ hipError_t launch_attn_prefill(AttnParams& p, int max_query_len, int max_context
   const size_t lds_bytes = (size_t)kRingBytes + ids_bytes;
   const int qpg = kWaves / hw * kQueryPerWave;               // query tokens per workgroup
   p.streams_per_xcd = (p.num_kv_heads * p.batch + 7) / 8;
-  const int64_t nwg = (int64_t)((max_query_len + qpg - 1) / qpg) * p.group_tiles * p.streams_per_xcd * 8;
+  if (p.max_partitions < 1) p.max_partitions = 1;
+  const int64_t nwg = (int64_t)((max_query_len + qpg - 1) / qpg) * p.max_partitions * p.group_tiles * p.streams_per_xcd * 8;
   if (nwg > 0x7FFFFFFF) return hipErrorInvalidValue;
   const dim3 grid((unsigned)nwg);
   static std::atomic<bool> prepared[kMaxDevices];   // more than 64 KiB of dynamic LDS: ask once per device
@@ -595,6 +691,12 @@ hipError_t launch_attn_prefill(AttnParams& p, int max_query_len, int max_context
   }
   if (hw == 1) hipLaunchKernelGGL((attn_prefill_mfma_d128<1>), grid, dim3(kThreads), lds_bytes, s, p);
   else hipLaunchKernelGGL((attn_prefill_mfma_d128<2>), grid, dim3(kThreads), lds_bytes, s, p);
+  if (p.max_partitions > 1) {
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int64_t items = total_query_tokens * p.num_q_heads;
+    hipLaunchKernelGGL(attn_prefill_merge, dim3((unsigned)((items + 3) / 4)), dim3(256), 0, s, p);
+  }
   return hipGetLastError();
 }
 

@@ -681,20 +681,6 @@ __global__ __launch_bounds__(GH * kWaveSize) void attn_stream_merge_lean(const A
   store(O0 * inv, O1 * inv);
 }
 
-int num_cus() {
-  static std::atomic<int> cached[kMaxDevices];   // zero-initialised: not asked yet
-  const int slot = current_device_slot();
-  int v = cached[slot].load(std::memory_order_relaxed);
-  if (v == 0) {
-    int dev = 0;
-    if (!(hipGetDevice(&dev) == hipSuccess &&
-          hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0))
-      v = 256;   // no device (sizing a workspace on a host without one): the MI355X count
-    cached[slot].store(v, std::memory_order_relaxed);
-  }
-  return v;
-}
-
 template <int GH>
 hipError_t launch(const AttnParams& p, hipStream_t s) {
   const size_t lds = (size_t)p.prefix_bytes + (size_t)kNW * kWaveLds;
@@ -724,6 +710,21 @@ hipError_t launch(const AttnParams& p, hipStream_t s) {
 }
 
 }  // namespace
+
+// CUs of the current device (cached per device).
+int num_cus() {
+  static std::atomic<int> cached[kMaxDevices];   // zero-initialised: not asked yet
+  const int slot = current_device_slot();
+  int v = cached[slot].load(std::memory_order_relaxed);
+  if (v == 0) {
+    int dev = 0;
+    if (!(hipGetDevice(&dev) == hipSuccess &&
+          hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0))
+      v = 256;   // no device (sizing a workspace on a host without one): the MI355X count
+    cached[slot].store(v, std::memory_order_relaxed);
+  }
+  return v;
+}
 
 int stream_heads_per_lane(int group) { return group == 1 ? 1 : group == 2 ? 2 : group <= 4 ? 4 : 8; }
 

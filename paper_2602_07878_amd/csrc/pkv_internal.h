@@ -22,6 +22,8 @@ inline int current_device_slot() {
   return d;
 }
 
+int num_cus();   // CUs of the current device (256 when there is none), attn_stream_mfma.hip
+
 // Launch geometry and pointers of one attention call, passed by value.
 struct AttnParams {
   const void* q;
@@ -80,7 +82,10 @@ hipError_t launch_attn_stream(AttnParams& p, hipStream_t s);
 hipError_t launch_swap(const SwapParams& p, hipStream_t s);
 // attn_prefill_mfma.hip
 bool attn_prefill_supported(const pkv_attn_desc& d);
-hipError_t launch_attn_prefill(AttnParams& p, int max_query_len, int max_context_len, hipStream_t s);
+hipError_t launch_attn_prefill(AttnParams& p, int max_query_len, int max_context_len, int64_t total_query_tokens,
+                               hipStream_t s);
+int prefill_splits(const pkv_attn_desc& d, int max_query_len);
+size_t prefill_workspace_bytes(const pkv_attn_desc& d, int64_t total_query_tokens, int max_query_len);
 // append.hip (uses the pointers, strides and shapes of AttnParams; q/out unused)
 hipError_t launch_kv_append(const AttnParams& p, const void* k_new, const void* v_new, int elem_bytes,
                             hipStream_t s);

@@ -11,8 +11,9 @@ pytestmark = pytest.mark.gpu
 TOL = 2e-3
 
 
-def run_prefill(w, query_lens, seed, out_dtype=None, token_major=False):
-    """Returns (GPU out as float64 [total, Hq, D], oracle out)."""
+def run_prefill(w, query_lens, seed, out_dtype=None, token_major=False, split=False):
+    """Returns (GPU out as float64 [total, Hq, D], oracle out).  split: bring the workspace
+    that lets the library cut the walks into ranges (it must want to for the case)."""
     import oracle
     import torch
     from paper_2602_07878_amd import binding
@@ -36,9 +37,17 @@ def run_prefill(w, query_lens, seed, out_dtype=None, token_major=False):
     desc = binding.attn_desc_for(dq[:max(total, 1)] if total else torch.empty(1, w.Hq, w.D, dtype=torch.bfloat16, device="cuda"),
                                  kp, vp, dev["block_tables"], max_context_len=w.max_context_len, out_dtype=odt)
     desc.batch = w.B
+    ws = None
+    if split:
+        need = binding.prefill_workspace_bytes(desc, total, int(ql.max()))
+        assert need > 0, "this case was meant to be split"
+        ws = torch.full((need + 64,), 0xFF, dtype=torch.uint8, device="cuda")   # NaN-filled: unwritten rows must not be read
     binding.paged_prefill_attention(desc, dq, kp, vp, dev["block_tables"], dev["context_lens"],
-                                    torch.from_numpy(ql).cuda(), cu, int(ql.max()) if ql.size else 0, w.scale, out)
+                                    torch.from_numpy(ql).cuda(), cu, int(ql.max()) if ql.size else 0, w.scale, out,
+                                    workspace=ws)
     torch.cuda.synchronize()
+    if split:
+        assert bool((ws[need:] == 0xFF).all()), "wrote past the workspace"
     assert torch.all(buf[:pad] == 777.0) and torch.all(buf[pad + total * w.Hq * w.D:] == 777.0)
     return out.float().cpu().numpy().astype(np.float64), ref
 
@@ -83,6 +92,45 @@ def test_block_sizes(bs):
 def test_long_context_short_chunk_and_chunk_of_512():
     lens = (5000, 2048, 700)
     check(mk(85, lens), (512, 512, 512))
+
+
+# ---- split walks (few chunks over long contexts: the chunked-prefill case) --------------------
+@pytest.mark.parametrize("lens,qlens,Hq,Hkv", [
+    ((4000,), (100,), 8, 2),                 # one workgroup per head pair would walk 125 pairs: 15 ranges
+    ((3000, 40, 700), (300, 40, 1), 8, 2),   # ragged: the short sequences have fewer pairs than ranges
+    ((2000,), (256,), 4, 4),                 # one query head per KV head
+    ((1500, 0, 900), (512, 0, 0), 8, 2),     # absent sequences
+    ((2049,), (2049,), 8, 2),                # a whole prompt: the first ranges start at position 0
+])
+def test_split_walks_agree_with_the_oracle(lens, qlens, Hq, Hkv):
+    w = mk(88, lens, Hq=Hq, Hkv=Hkv)
+    got, ref = check(w, qlens, split=True)
+    unsplit, _ = run_prefill(w, qlens, 5)
+    assert np.abs(got - unsplit).max() <= 2e-5          # same arithmetic, other order of the sums
+
+
+def test_split_walks_bf16_output_and_small_workspace_is_refused():
+    import torch
+    from paper_2602_07878_amd import binding
+    w = mk(89, (3000,))
+    got, ref = run_prefill(w, (200,), 3, out_dtype=torch.bfloat16, split=True)
+    ulp = np.maximum(np.abs(ref), 2.0 ** -126) * 2.0 ** -8
+    assert np.all(np.abs(got - ref) <= TOL + ulp)
+    dev = to_device(w)
+    q = torch.zeros(200, w.Hq, w.D, dtype=torch.bfloat16, device="cuda")
+    desc = binding.attn_desc_for(q, dev["k_pool"], dev["v_pool"], dev["block_tables"], max_context_len=w.max_context_len)
+    desc.batch = 1
+    need = binding.prefill_workspace_bytes(desc, 200, 200)
+    assert need > 0
+    ql = torch.tensor([200], dtype=torch.int32, device="cuda")
+    cu = torch.tensor([0, 200], dtype=torch.int32, device="cuda")
+    with pytest.raises(binding.PkvError):
+        binding.paged_prefill_attention(desc, q, dev["k_pool"], dev["v_pool"], dev["block_tables"], dev["context_lens"],
+                                        ql, cu, 200, w.scale, torch.empty(200, w.Hq, w.D, device="cuda"),
+                                        workspace=torch.empty(need - 16, dtype=torch.uint8, device="cuda"))
+    # enough workgroups anyway: no workspace wanted
+    desc.batch = 64
+    assert binding.prefill_workspace_bytes(desc, 64 * 200, 200) == 0
 
 
 def test_last_query_token_equals_decode_kernel():

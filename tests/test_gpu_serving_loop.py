@@ -49,7 +49,7 @@ def test_scheduler_driven_decode_with_preemption(mode, chunked):
     out_desc = binding.swap_desc(1, block_bytes, n_gpu, n_cpu)
     in_desc = binding.swap_desc(1, block_bytes, n_cpu, n_gpu)
     scale = float(D) ** -0.5
-    checked = swaps = prefill_checked = later_chunks = 0
+    checked = swaps = prefill_checked = later_chunks = split_used = 0
     rng = np.random.default_rng(99)
     for it, arrivals in enumerate(stream):
         for rid, p, n in arrivals:
@@ -98,8 +98,11 @@ def test_scheduler_driven_decode_with_preemption(mode, chunked):
             out = torch.empty(int(ql.sum()), HQ, D, dtype=torch.float32, device="cuda")
             desc = binding.attn_desc_for(dq, dk, dv, bt, max_context_len=int(cl.max()))
             desc.batch = len(chunk_rows)
+            need = binding.prefill_workspace_bytes(desc, int(ql.sum()), int(ql.max()))      # few chunks: split walks
+            ws = torch.empty(need, dtype=torch.uint8, device="cuda") if need else None
+            split_used += need > 0
             binding.paged_prefill_attention(desc, dq, dk, dv, bt, torch.from_numpy(cl).cuda(),
-                                            torch.from_numpy(ql).cuda(), cu, int(ql.max()), scale, out)
+                                            torch.from_numpy(ql).cuda(), cu, int(ql.max()), scale, out, workspace=ws)
             torch.cuda.synchronize()
             got = out.cpu().numpy().astype(np.float64)
             assert np.all(np.isfinite(got)) and np.abs(got - ref).max() <= 2e-3, (it, mode, "chunk")
@@ -129,7 +132,8 @@ def test_scheduler_driven_decode_with_preemption(mode, chunked):
             assert np.array_equal(bits(dsk), sk) and np.array_equal(bits(dsv), sv), it
     t = s.totals()
     print(mode, "chunked" if chunked else "whole prefills", t, "attention checks", checked,
-          "chunk attention checks", prefill_checked, "later chunks", later_chunks, flush=True)
+          "chunk attention checks", prefill_checked, "of which with split walks", split_used,
+          "later chunks", later_chunks, flush=True)
     assert t["finished"] == sum(len(a) for a in stream) and t["preemptions"] > 0 and checked > 20
     if chunked:
         assert prefill_checked > 20 and later_chunks > 20
