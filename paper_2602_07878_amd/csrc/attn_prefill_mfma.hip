@@ -315,8 +315,9 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_mfma_d128(const Attn
       smax = fmaxf(smax, d[r]);
     }
     xchg[hl * 32 + c32] = smax;
-    // (in a later range of a split walk a query may see nothing of the first pair: the floor
-    // keeps its reference finite, and the first pair it does see raises it by the second path below)
+    // (in a later range of a split walk a query may see nothing of the first pair, and then
+    // nothing of the rest of the range either: the floor keeps its arithmetic finite, its
+    // weights are all 0 and its normaliser stays 0, which the merge takes as "no part")
     m_ref = fmaxf(fmaxf(xchg[c32], xchg[32 + c32]), kNoMaximum);
 #pragma unroll
     for (int r = 0; r < 16; ++r) d[r] -= m_ref;
