@@ -109,6 +109,13 @@ def test_split_walks_agree_with_the_oracle(lens, qlens, Hq, Hkv):
     assert np.abs(got - unsplit).max() <= 2e-5          # same arithmetic, other order of the sums
 
 
+@pytest.mark.parametrize("bs", [32, 128])
+def test_split_walks_with_larger_blocks_and_token_major_pools(bs):
+    w = mk(90, (2500, 300), bs=bs)
+    check(w, (260, 7), split=True)
+    check(w, (100, 0), split=True, token_major=True)
+
+
 def test_split_walks_bf16_output_and_small_workspace_is_refused():
     import torch
     from paper_2602_07878_amd import binding
