@@ -195,20 +195,19 @@ def time_swap(sw, reps, torch, binding):
 
 def time_swap_host(sw, torch, binding, staging_mib=256, reps=2):
     """The same victims' blocks out to pinned host memory and back in (PCIe-bound), in pieces
-    through a device staging buffer with kernel and copy on two streams."""
+    through a device staging buffer."""
     g = torch.Generator(device="cuda:0")
     g.manual_seed(sw.seed)
     pool = torch.randint(-2**31, 2**31 - 1, (sw.pool_bytes // 4,), dtype=torch.int32, device="cuda:0", generator=g)
     host = torch.empty(sw.staging_bytes, dtype=torch.uint8).pin_memory()
     staging = torch.empty(staging_mib << 20, dtype=torch.uint8, device="cuda:0")
-    copy_stream = torch.cuda.Stream()
     gm = torch.from_numpy(sw.gather_mapping).cuda()
     sm = torch.from_numpy(sw.scatter_mapping).cuda()
     d_out = binding.swap_desc(sw.num_planes, sw.block_bytes, sw.num_pool_blocks, sw.n_blocks)
     d_in = binding.swap_desc(sw.num_planes, sw.block_bytes, sw.n_blocks, sw.num_pool_blocks)
     res = {}
-    for name, fn in (("out", lambda: binding.kv_swap_out_host(d_out, pool, host, gm, staging, copy_stream=copy_stream)),
-                     ("in", lambda: binding.kv_swap_in_host(d_in, host, pool, sm, staging, copy_stream=copy_stream))):
+    for name, fn in (("out", lambda: binding.kv_swap_out_host(d_out, pool, host, gm, staging)),
+                     ("in", lambda: binding.kv_swap_in_host(d_in, host, pool, sm, staging))):
         fn()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -219,6 +218,20 @@ def time_swap_host(sw, torch, binding, staging_mib=256, reps=2):
         res[name] = {"ms": ms, "payload_GBps": sw.payload_bytes / ms / 1e6}
     res["payload_GB"] = sw.payload_bytes / 1e9
     res["staging_MiB"] = staging_mib
+    # what this box's PCIe link gives a plain pinned copy, for comparison (the boxes differ)
+    n = min(1 << 30, host.numel(), pool.numel() * 4)
+    dev_bytes = pool.view(torch.uint8)[:n]
+    plain = {}
+    for name, fn in (("d2h", lambda: host[:n].copy_(dev_bytes, non_blocking=True)),
+                     ("h2d", lambda: dev_bytes.copy_(host[:n], non_blocking=True))):
+        fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        plain[name] = n * reps / (time.perf_counter() - t0) / 1e9
+    res["plain_pinned_copy_GBps"] = plain
     del pool, host, staging
     torch.cuda.empty_cache()
     return res

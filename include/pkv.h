@@ -291,28 +291,24 @@ int32_t kv_block_swap(const pkv_swap_desc* desc, const void* src_pool,
  *
  * host_dst / host_src is page-locked HOST memory, everything else is device
  * memory.  The swap moves in pieces through `staging`, a device buffer of
- * staging_bytes >= 2*num_planes*block_bytes (PKV_ERR_WORKSPACE otherwise; bigger
- * pieces make longer PCIe transfers): the kv_block_swap kernel gathers or
- * scatters one piece on stream_compute while the neighbouring piece crosses
- * PCIe on stream_copy (the two may be the same stream: the pieces then go one
- * after the other).  A piece is a group of whole planes, one contiguous copy,
- * when 2*n_pairs*block_bytes fits into half of `staging` and n_pairs*block_bytes
- * equals the host plane stride; else a range of pairs of every plane, one
- * strided copy, which is slower device-to-host.  Both calls only enqueue work.  After
- * kv_swap_out_host, completion of stream_compute implies that all of host_dst
- * is written; after kv_swap_in_host, completion of stream_compute implies that
- * the pool blocks are.  The copy stream is made to wait for work enqueued on
- * stream_compute before the call.  The library keeps one set of events per
- * device for these two calls: do not issue them for one device from several
- * host threads at once.  The bytes arrive exactly; same mapping rules as
- * kv_block_swap.
+ * staging_bytes >= num_planes*block_bytes (PKV_ERR_WORKSPACE otherwise; bigger
+ * pieces make longer PCIe transfers): the kv_block_swap kernel gathers a piece
+ * into it, the piece crosses PCIe as one copy, and the next piece follows, all
+ * on hip_stream (for swap-in the copy comes first and the kernel scatters).
+ * A piece is a group of whole planes, one contiguous copy, when
+ * 2*n_pairs*block_bytes fits into `staging` and n_pairs*block_bytes equals the
+ * host plane stride; else a range of pairs of every plane, one strided copy.
+ * Both calls only enqueue work and keep no state.  After kv_swap_out_host,
+ * completion of hip_stream implies that all of host_dst is written; after
+ * kv_swap_in_host, that the pool blocks are.  The bytes arrive exactly; same
+ * mapping rules as kv_block_swap.
  */
 int32_t kv_swap_out_host(const pkv_swap_desc* desc, const void* src_pool, void* host_dst,
                          const int32_t* block_mapping, int32_t n_pairs, void* staging,
-                         size_t staging_bytes, void* stream_compute, void* stream_copy);
+                         size_t staging_bytes, void* hip_stream);
 int32_t kv_swap_in_host(const pkv_swap_desc* desc, const void* host_src, void* dst_pool,
                         const int32_t* block_mapping, int32_t n_pairs, void* staging,
-                        size_t staging_bytes, void* stream_compute, void* stream_copy);
+                        size_t staging_bytes, void* hip_stream);
 
 /*
  * Host-side range checks of the index arrays the fast path trusts.

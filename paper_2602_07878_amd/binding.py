@@ -95,7 +95,7 @@ def lib() -> ctypes.CDLL:
         L.kv_append.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, vp]
         for name in ("kv_swap_out_host", "kv_swap_in_host"):
             getattr(L, name).restype = i32
-            getattr(L, name).argtypes = [ctypes.POINTER(SwapDesc), vp, vp, vp, i32, vp, sz, vp, vp]
+            getattr(L, name).argtypes = [ctypes.POINTER(SwapDesc), vp, vp, vp, i32, vp, sz, vp]
         L.kv_block_swap.restype = i32
         L.kv_block_swap.argtypes = [ctypes.POINTER(SwapDesc), vp, vp, vp, i32, vp]
         L.pkv_validate_tables_host.restype = i32
@@ -263,26 +263,24 @@ def kv_block_swap(desc: SwapDesc, src_pool, dst, block_mapping, *, stream=None):
     _check(st, "kv_block_swap")
 
 
-def kv_swap_out_host(desc: SwapDesc, src_pool, host_dst, block_mapping, staging, *, stream=None,
-                     copy_stream=None):
+def kv_swap_out_host(desc: SwapDesc, src_pool, host_dst, block_mapping, staging, *, stream=None):
     """Pool blocks block_mapping[:,0] (device) -> slots 0..n-1 of the pinned host tensor host_dst,
     in pieces through the device tensor `staging`."""
     assert host_dst.is_pinned() and block_mapping.is_contiguous()
     st = lib().kv_swap_out_host(ctypes.byref(desc), src_pool.data_ptr(), host_dst.data_ptr(),
                                 block_mapping.data_ptr(), block_mapping.numel() // 2,
                                 staging.data_ptr(), staging.numel() * staging.element_size(),
-                                _stream_ptr(stream), _stream_ptr(copy_stream if copy_stream is not None else stream))
+                                _stream_ptr(stream))
     _check(st, "kv_swap_out_host")
 
 
-def kv_swap_in_host(desc: SwapDesc, host_src, dst_pool, block_mapping, staging, *, stream=None,
-                    copy_stream=None):
+def kv_swap_in_host(desc: SwapDesc, host_src, dst_pool, block_mapping, staging, *, stream=None):
     """Slots 0..n-1 of the pinned host tensor host_src -> pool blocks block_mapping[:,1] (device)."""
     assert host_src.is_pinned() and block_mapping.is_contiguous()
     st = lib().kv_swap_in_host(ctypes.byref(desc), host_src.data_ptr(), dst_pool.data_ptr(),
                                block_mapping.data_ptr(), block_mapping.numel() // 2,
                                staging.data_ptr(), staging.numel() * staging.element_size(),
-                               _stream_ptr(stream), _stream_ptr(copy_stream if copy_stream is not None else stream))
+                               _stream_ptr(stream))
     _check(st, "kv_swap_in_host")
 
 

@@ -316,7 +316,7 @@ int32_t kv_block_swap(const pkv_swap_desc* desc, const void* src_pool, void* dst
 
 static int32_t swap_host_impl(bool out, const pkv_swap_desc* desc, const void* src, void* dst,
                               const int32_t* block_mapping, int32_t n_pairs, void* staging,
-                              size_t staging_bytes, void* stream_compute, void* stream_copy) {
+                              size_t staging_bytes, void* hip_stream) {
   const int32_t st = check_swap_desc(desc);
   if (st != PKV_OK) return st;
   if (n_pairs < 0) return PKV_ERR_SHAPE;
@@ -331,28 +331,26 @@ static int32_t swap_host_impl(bool out, const pkv_swap_desc* desc, const void* s
   const hipError_t e =
       out ? swap_out_host(*desc, static_cast<const uint8_t*>(src), static_cast<uint8_t*>(dst),
                           block_mapping, n_pairs, static_cast<uint8_t*>(staging), staging_bytes,
-                          static_cast<hipStream_t>(stream_compute), static_cast<hipStream_t>(stream_copy),
-                          &too_small)
+                          static_cast<hipStream_t>(hip_stream), &too_small)
           : swap_in_host(*desc, static_cast<const uint8_t*>(src), static_cast<uint8_t*>(dst),
                          block_mapping, n_pairs, static_cast<uint8_t*>(staging), staging_bytes,
-                         static_cast<hipStream_t>(stream_compute), static_cast<hipStream_t>(stream_copy),
-                         &too_small);
+                         static_cast<hipStream_t>(hip_stream), &too_small);
   if (too_small) return PKV_ERR_WORKSPACE;
   return hip_status(e);
 }
 
 int32_t kv_swap_out_host(const pkv_swap_desc* desc, const void* src_pool, void* host_dst,
                          const int32_t* block_mapping, int32_t n_pairs, void* staging,
-                         size_t staging_bytes, void* stream_compute, void* stream_copy) {
+                         size_t staging_bytes, void* hip_stream) {
   return swap_host_impl(true, desc, src_pool, host_dst, block_mapping, n_pairs, staging,
-                        staging_bytes, stream_compute, stream_copy);
+                        staging_bytes, hip_stream);
 }
 
 int32_t kv_swap_in_host(const pkv_swap_desc* desc, const void* host_src, void* dst_pool,
                         const int32_t* block_mapping, int32_t n_pairs, void* staging,
-                        size_t staging_bytes, void* stream_compute, void* stream_copy) {
+                        size_t staging_bytes, void* hip_stream) {
   return swap_host_impl(false, desc, host_src, dst_pool, block_mapping, n_pairs, staging,
-                        staging_bytes, stream_compute, stream_copy);
+                        staging_bytes, hip_stream);
 }
 
 int32_t pkv_validate_tables_host(const pkv_attn_desc* desc, const int32_t* block_tables_host,

@@ -91,11 +91,11 @@ hipError_t launch_kv_append(const AttnParams& p, const void* k_new, const void* 
                             hipStream_t s);
 // swap_host.hip
 hipError_t swap_out_host(const pkv_swap_desc& d, const uint8_t* pool, uint8_t* host_dst, const int32_t* mapping,
-                         int32_t n_pairs, uint8_t* staging, size_t staging_bytes, hipStream_t compute,
-                         hipStream_t copy, bool* too_small);
+                         int32_t n_pairs, uint8_t* staging, size_t staging_bytes, hipStream_t stream,
+                         bool* too_small);
 hipError_t swap_in_host(const pkv_swap_desc& d, const uint8_t* host_src, uint8_t* pool, const int32_t* mapping,
-                        int32_t n_pairs, uint8_t* staging, size_t staging_bytes, hipStream_t compute,
-                        hipStream_t copy, bool* too_small);
+                        int32_t n_pairs, uint8_t* staging, size_t staging_bytes, hipStream_t stream,
+                        bool* too_small);
 hipError_t launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t s);
 hipError_t launch_probe_read(const void* src, void* sink, size_t bytes, hipStream_t s);
 

@@ -141,17 +141,17 @@ def test_swap_host_leg_rejects_bad_arguments_on_host():
     L = binding.lib()
     for fn in (L.kv_swap_out_host, L.kv_swap_in_host):
         f = lambda d, a=0x1000, b=0x2000, m=0x3000, n=5, st=0x4000, sb=1 << 22: fn(
-            ctypes.byref(d), a, b, m, n, st, sb, None, None)
-        assert fn(None, 1, 1, 1, 1, 1, 1, None, None) == ST["NULL"]
+            ctypes.byref(d), a, b, m, n, st, sb, None)
+        assert fn(None, 1, 1, 1, 1, 1, 1, None) == ST["NULL"]
         assert f(swap_desc(block_bytes=24)) == ST["ALIGN"]
         assert f(swap_desc(), st=0) == ST["NULL"]
         assert f(swap_desc(), a=0x1008) == ST["ALIGN"]
         assert f(swap_desc(), n=-1) == ST["SHAPE"]
         assert f(swap_desc(), n=0, a=0, b=0, m=0, st=0) == ST["OK"]
-        assert f(swap_desc(), sb=2 * 4 * 32768 - 16) == ST["WORKSPACE"]   # not even one pair per half
+        assert f(swap_desc(), sb=4 * 32768 - 16) == ST["WORKSPACE"]       # not even one pair of every plane
     # the host side needs a slot per pair: 50 slots in the 100 -> 50 descriptor, 100 the other way round
-    assert L.kv_swap_out_host(ctypes.byref(swap_desc()), 0x1000, 0x2000, 0x3000, 51, 0x4000, 1 << 22, None, None) == ST["SHAPE"]
-    assert L.kv_swap_in_host(ctypes.byref(swap_desc()), 0x1000, 0x2000, 0x3000, 101, 0x4000, 1 << 22, None, None) == ST["SHAPE"]
+    assert L.kv_swap_out_host(ctypes.byref(swap_desc()), 0x1000, 0x2000, 0x3000, 51, 0x4000, 1 << 22, None) == ST["SHAPE"]
+    assert L.kv_swap_in_host(ctypes.byref(swap_desc()), 0x1000, 0x2000, 0x3000, 101, 0x4000, 1 << 22, None) == ST["SHAPE"]
 
 
 def test_host_validators():

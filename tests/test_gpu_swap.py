@@ -97,8 +97,10 @@ def test_swap_is_transparent_to_attention():
 
 
 # ---- host leg (Sec. 5.1.2: the victims' blocks go to CPU host memory and come back) ---------
-@pytest.mark.parametrize("staging_pairs,two_streams", [(1, False), (7, True), (64, True), (1000, False)])
-def test_swap_out_to_pinned_host_and_back_is_bit_exact(staging_pairs, two_streams):
+@pytest.mark.parametrize("staging_pairs,side_stream", [(1, False), (7, True), (64, True), (1000, False)])
+def test_swap_out_to_pinned_host_and_back_is_bit_exact(staging_pairs, side_stream):
+    """Pieces of 1 and 7 pairs of every plane (strided copies), of 2 and of all 6 whole planes
+    (contiguous copies); on the current stream or on another one."""
     import oracle
     import torch
     from paper_2602_07878_amd import binding
@@ -110,12 +112,14 @@ def test_swap_out_to_pinned_host_and_back_is_bit_exact(staging_pairs, two_stream
     d_pool = torch.from_numpy(pool).cuda()
     host = torch.zeros(planes * n * bb + 64, dtype=torch.uint8).pin_memory()
     host[-64:] = 0xA5                                                   # canary behind the slots
-    staging = torch.empty(2 * staging_pairs * planes * bb, dtype=torch.uint8, device="cuda")
-    copy_stream = torch.cuda.Stream() if two_streams else None
+    staging = torch.empty((1 if staging_pairs < 64 else 2) * staging_pairs * planes * bb, dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.Stream() if side_stream else torch.cuda.current_stream()
+    stream.wait_stream(torch.cuda.current_stream())                     # the uploads above
     out_desc = binding.swap_desc(planes, bb, sw.num_pool_blocks, n)
     gm = torch.from_numpy(sw.gather_mapping).cuda()
-    binding.kv_swap_out_host(out_desc, d_pool, host, gm, staging, copy_stream=copy_stream)
-    torch.cuda.current_stream().synchronize()                           # compute stream alone
+    stream.wait_stream(torch.cuda.current_stream())
+    binding.kv_swap_out_host(out_desc, d_pool, host, gm, staging, stream=stream)
+    stream.synchronize()                                                # that stream alone
     ref = np.zeros(planes * n * bb, np.uint8)
     oracle.kv_block_swap(pool, ref, sw.gather_mapping, num_planes=planes, block_bytes=bb)
     assert np.array_equal(host[:-64].numpy(), ref) and bool((host[-64:] == 0xA5).all())
@@ -123,8 +127,9 @@ def test_swap_out_to_pinned_host_and_back_is_bit_exact(staging_pairs, two_stream
     d_new = torch.full_like(d_pool, 0x5A)
     in_desc = binding.swap_desc(planes, bb, n, sw.num_pool_blocks)
     sm = torch.from_numpy(sw.scatter_mapping).cuda()
-    binding.kv_swap_in_host(in_desc, host, d_new, sm, staging, copy_stream=copy_stream)
-    torch.cuda.current_stream().synchronize()
+    stream.wait_stream(torch.cuda.current_stream())
+    binding.kv_swap_in_host(in_desc, host, d_new, sm, staging, stream=stream)
+    stream.synchronize()
     ref_pool = np.full(sw.pool_bytes, 0x5A, np.uint8)
     oracle.kv_block_swap(ref, ref_pool, sw.scatter_mapping, num_planes=planes, block_bytes=bb)
     assert np.array_equal(d_new.cpu().numpy(), ref_pool)                # blocks in place, nothing else touched
