@@ -137,6 +137,26 @@ def test_append_rejects_bad_arguments_on_host():
     assert f(good_desc(batch=0), kn=0, vn=0, kp=0, vp=0, bt=0, cl=0) == ST["OK"]
 
 
+def test_prefill_workspace_size_and_host_side_rejections():
+    L = binding.lib()
+    # one 512-token chunk over 8192 tokens: 64 workgroups unsplit -> 4 ranges (256 CUs assumed
+    # without a device); rows x heads x ranges x (D + 2) floats
+    d = good_desc(batch=1, max_context_len=8192, max_blocks_per_seq=512, num_pool_blocks=1024)
+    need = L.pkv_prefill_workspace_bytes(ctypes.byref(d), 512, 512)
+    assert need == 512 * 32 * 4 * (128 + 2) * 4
+    assert L.pkv_prefill_workspace_bytes(ctypes.byref(good_desc(batch=64)), 64 * 512, 512) == 0   # enough workgroups
+    assert L.pkv_prefill_workspace_bytes(ctypes.byref(good_desc(batch=1, max_context_len=256)), 256, 256) == 0  # short walks
+    assert L.pkv_prefill_workspace_bytes(ctypes.byref(d), 0, 512) == 0 and L.pkv_prefill_workspace_bytes(None, 512, 512) == 0
+    assert L.pkv_prefill_workspace_bytes(ctypes.byref(good_desc(batch=1, kv_dtype=0)), 512, 512) == 0      # fp32: unsupported
+    f = lambda ws, wsb, total=512, q=0x1000: L.paged_prefill_attention_ws(
+        ctypes.byref(d), q, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, 0x7000, 512, total, 0.1, 0x8000, ws, wsb, None)
+    # fake (never dereferenced) pointers: every case must be rejected before anything is enqueued
+    assert f(0x9000, need - 16) == ST["WORKSPACE"]
+    assert f(0x9008, need) == ST["ALIGN"]
+    assert f(0x9000, need, total=-1) == ST["SHAPE"]
+    assert f(0x9000, need, q=0) == ST["NULL"]
+
+
 def test_swap_host_leg_rejects_bad_arguments_on_host():
     L = binding.lib()
     for fn in (L.kv_swap_out_host, L.kv_swap_in_host):
