@@ -1,0 +1,83 @@
+"""A decode step (kv_append, then paged_decode_attention: stream kernel + merge) and a prefill
+chunk with split walks captured into a HIP graph and replayed: the calls enqueue kernels only
+(no allocation, no synchronisation, no memset), so a launch-bound serving loop can replay them.
+The graph is replayed several times with the program's own eager work and synchronisations in
+between, the inputs changed in place before each replay, and every replay is checked against
+the eager result of the same inputs and against the oracle."""
+import numpy as np
+import pytest
+
+from paper_2602_07878_amd import workloads as W
+from helpers import to_device
+
+pytestmark = pytest.mark.gpu
+
+
+def up(a):
+    import torch
+    return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def test_decode_step_and_split_prefill_replayed_from_a_graph():
+    import oracle
+    import torch
+    from paper_2602_07878_amd import binding
+    w = W.make_attn_workload("graph", 91, dtype="bf16", Hq=32, Hkv=8, D=128, block_size=16,
+                             context_lens=list(W.lens_uniform(91, 24, 40, 3000)), pool_factor=1.2)
+    dev = to_device(w)
+    q, kp, vp, bt, cl = dev["q"], dev["k_pool"], dev["v_pool"], dev["block_tables"], dev["context_lens"]
+    kn = torch.zeros(w.B, w.Hkv, w.D, dtype=torch.bfloat16, device="cuda")
+    vn = torch.zeros_like(kn)
+    out_g = torch.zeros(w.B, w.Hq, w.D, dtype=torch.float32, device="cuda")
+    out_e = torch.zeros_like(out_g)
+    desc = binding.attn_desc_for(q, kp, vp, bt, max_context_len=w.max_context_len)
+    ws = binding.new_workspace(binding.attn_workspace_bytes(desc), "cuda")
+    # the chunk: the last 200 tokens of sequence 0 alone (few workgroups, so the walks are split)
+    n0 = int(w.context_lens[0])
+    w1 = W.make_attn_workload("graph_chunk", 92, dtype="bf16", Hq=32, Hkv=8, D=128, block_size=16,
+                              context_lens=[2600], pool_factor=1.1)
+    d1 = to_device(w1)
+    cq = torch.zeros(200, 32, 128, dtype=torch.bfloat16, device="cuda")
+    cout_g = torch.zeros(200, 32, 128, dtype=torch.float32, device="cuda")
+    cout_e = torch.zeros_like(cout_g)
+    ql = torch.tensor([200], dtype=torch.int32, device="cuda")
+    cu = torch.tensor([0, 200], dtype=torch.int32, device="cuda")
+    desc1 = binding.attn_desc_for(cq, d1["k_pool"], d1["v_pool"], d1["block_tables"], max_context_len=2600)
+    desc1.batch = 1
+    need = binding.prefill_workspace_bytes(desc1, 200, 200)
+    assert need > 0
+    pws = torch.empty(need, dtype=torch.uint8, device="cuda")
+
+    def step(out, cout):
+        binding.kv_append(desc, kn, vn, kp, vp, bt, cl)
+        binding.paged_decode_attention(q, kp, vp, bt, cl, w.scale, out, max_context_len=w.max_context_len,
+                                       workspace=ws, desc=desc)
+        binding.paged_prefill_attention(desc1, cq, d1["k_pool"], d1["v_pool"], d1["block_tables"], d1["context_lens"],
+                                        ql, cu, 200, w1.scale, cout, workspace=pws)
+
+    step(out_e, cout_e)                                   # warm-up: kernel attributes are set on first use
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step(out_g, cout_g)
+    rng = np.random.default_rng(93)
+    hk, hv = w.k_pool, w.v_pool
+    for replay in range(4):
+        # new inputs in place: queries, the rows to append, the chunk's queries
+        qn = W.f32_to_bf16_bits(rng.standard_normal((w.B, w.Hq, w.D)).astype(np.float32))
+        knn = W.f32_to_bf16_bits(rng.standard_normal((w.B, w.Hkv, w.D)).astype(np.float32))
+        vnn = W.f32_to_bf16_bits(rng.standard_normal((w.B, w.Hkv, w.D)).astype(np.float32))
+        cqn = W.f32_to_bf16_bits(rng.standard_normal((200, 32, 128)).astype(np.float32))
+        q.copy_(up(qn)); kn.copy_(up(knn)); vn.copy_(up(vnn)); cq.copy_(up(cqn))
+        out_g.fill_(-7.0); cout_g.fill_(-7.0)
+        g.replay()
+        torch.cuda.synchronize()
+        step(out_e, cout_e)                               # eager work of the same inputs between the replays
+        torch.cuda.synchronize()
+        assert torch.equal(out_g, out_e) and torch.equal(cout_g, cout_e), replay     # same kernels, same split: bit-equal
+        oracle.kv_append(hk, hv, knn, vnn, w.block_tables, w.context_lens, block_size=16)
+        ref = oracle.paged_decode_attention(qn, hk, hv, w.block_tables, w.context_lens, w.scale, block_size=16)
+        assert np.abs(out_g.cpu().numpy().astype(np.float64) - ref).max() <= 2e-3, replay
+        cref = oracle.paged_prefill_attention(cqn, w1.k_pool, w1.v_pool, w1.block_tables, w1.context_lens,
+                                              np.array([200], np.int32), w1.scale, block_size=16)
+        assert np.abs(cout_g.cpu().numpy().astype(np.float64) - cref).max() <= 2e-3, replay
