@@ -162,6 +162,11 @@ static int32_t attention_impl(const pkv_attn_desc* desc, const void* q, const vo
     p.ws_ml = reinterpret_cast<float*>(base + w.dir_bytes);
     p.ws_o = reinterpret_cast<float*>(base + w.dir_bytes + w.ml_bytes);
     p.chunk_tiles_max = w.chunk_tiles_max;
+    // With a cap on the chunk there can be more partial rows than the 32 MiB of L2 hold: stored
+    // the ordinary way they trickle out to HBM between the reads of the K/V stream, which cost
+    // 16 % on the long-context configuration; nontemporal stores cost 12 % there (988 -> 953 us).
+    // Few partials are better left in L2 for the merge kernel (90 against 92 us on the B=64 batch).
+    p.partials_streaming = w.chunk_tiles_max > 0 && w.o_bytes > (32 << 20);
     const hipError_t e = launch_attn_stream(p, static_cast<hipStream_t>(hip_stream));
     return hip_status(e);
   }

@@ -541,7 +541,15 @@ __global__ __launch_bounds__(kStreamThreads, 2) void attn_stream_mfma_d128(const
                     f32x4{o4[0] * inv, o4[1] * inv, o4[2] * inv, o4[3] * inv};
               }
             } else {
-              *reinterpret_cast<f32x4*>(p.ws_o + (slot * GH + g) * D + piece * 4) = o4;
+              f32x4* const row = reinterpret_cast<f32x4*>(p.ws_o + (slot * GH + g) * D + piece * 4);
+              if (p.partials_streaming) {
+                // (the empty statements keep the compiler from merging the two stores into a plain one)
+                asm volatile("" ::: "memory");
+                __builtin_nontemporal_store(o4, row);
+                asm volatile("" ::: "memory");
+              } else {
+                *row = o4;
+              }
               if (piece == 0)
                 *reinterpret_cast<f32x2*>(p.ws_ml + (slot * GH + g) * 2) = f32x2{xchg[64 + g], lsum};
             }

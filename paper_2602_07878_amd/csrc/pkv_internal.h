@@ -51,6 +51,7 @@ struct AttnParams {
   int32_t chunk_tiles_max;  // stream kernel: most tiles one wavefront takes per chunk (<= 64)
   int32_t prefix_bytes;     // stream kernel: LDS bytes of the tile prefix table
   int32_t streams_per_xcd;  // prefill kernel: (sequence, KV head) streams dealt to one XCD
+  int32_t partials_streaming;  // stream kernel: partial rows are stored past the caches (there are more of them than L2 holds)
   float scale_log2e;        // scale * log2(e)
   // host side only: optional events recorded right before / after the partial kernel
   hipEvent_t ev_begin, ev_end;
