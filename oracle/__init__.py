@@ -173,6 +173,26 @@ def kv_append(k_pool, v_pool, k_new, v_new, block_tables, context_lens, *, block
     return k_pool, v_pool
 
 
+def kv_append_chunk(k_pool, v_pool, k_new, v_new, block_tables, context_lens, query_lens, *, block_size):
+    """The K/V rows of a prefill chunk join the cache (Sec. 2.2 "KV-Cache"; Sec. 2.1 prefill):
+    k_new, v_new are packed [total, Hkv, D] in sequence order; row j of sequence i's
+    query_lens[i] rows goes to token position context_lens[i] - query_lens[i] + j (the chunk is the
+    tail of the context, as in paged_prefill_attention; query_lens above the context are clipped).
+    Pools [blocks, Hkv, block_size, D], modified in place.  Plain loops."""
+    first = 0
+    for i, (n, q) in enumerate(zip(context_lens.tolist(), query_lens.tolist())):
+        ql = min(q, n)
+        for j in range(ql):
+            pos = n - ql + j
+            blk = int(block_tables[i, pos // block_size])
+            if not 0 <= blk < k_pool.shape[0]:
+                raise IndexError("oracle: chunk row outside the pool")
+            k_pool[blk, :, pos % block_size, :] = k_new[first + j]
+            v_pool[blk, :, pos % block_size, :] = v_new[first + j]
+        first += q
+    return k_pool, v_pool
+
+
 def paged_prefill_attention(q, k_pool, v_pool, block_tables, context_lens, query_lens, scale,
                             *, block_size, k_strides=None, v_strides=None):
     """Causal attention of the last query_lens[i] tokens of every sequence over the paged cache

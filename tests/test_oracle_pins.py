@@ -510,3 +510,35 @@ def test_prefill_chunk_is_the_tail_of_the_full_causal_result_and_one_token_is_de
     for i, s in enumerate(starts):
         for h in range(4):
             assert np.array_equal(full[s, h], _contiguous(w, i, h // 2)[1][0])
+
+
+# ---- chunk append --------------------------------------------------------------------------------
+def test_chunk_append_equals_token_by_token_append_and_touches_nothing_else():
+    """The chunk routine (Python loops) against the single-token routine (C) applied once per
+    token with a growing context, and against positions worked out here."""
+    w = W.make_attn_workload("chunk", 31, dtype="bf16", Hq=4, Hkv=2, D=16, block_size=4,
+                             context_lens=(9, 4, 17, 6), pool_factor=1.5)
+    ql = np.array([5, 4, 0, 9], np.int32)                 # a tail, a whole prompt, nothing, more than the context (clipped to 6)
+    rng = np.random.default_rng(32)
+    total = int(ql.sum())
+    kn = rng.integers(0, 2**16, (total, 2, 16)).astype(np.uint16)
+    vn = rng.integers(0, 2**16, (total, 2, 16)).astype(np.uint16)
+    k1, v1 = w.k_pool.copy(), w.v_pool.copy()
+    oracle.kv_append_chunk(k1, v1, kn, vn, w.block_tables, w.context_lens, ql, block_size=4)
+    # token by token with the C routine: sequence i alone, context growing from n - ql + 1 to n
+    k2, v2 = w.k_pool.copy(), w.v_pool.copy()
+    first = 0
+    for i, (n, q) in enumerate(zip(w.context_lens.tolist(), ql.tolist())):
+        use = min(q, n)
+        for j in range(use):
+            cl = np.zeros(w.B, np.int32)
+            cl[i] = n - use + j + 1
+            rows_k = np.zeros((w.B, 2, 16), np.uint16); rows_v = np.zeros((w.B, 2, 16), np.uint16)
+            rows_k[i], rows_v[i] = kn[first + j], vn[first + j]
+            oracle.kv_append(k2, v2, rows_k, rows_v, w.block_tables, cl, block_size=4)
+        first += q
+    assert np.array_equal(k1, k2) and np.array_equal(v1, v2)
+    # positions by hand for sequence 0: the last 5 of 9 tokens are positions 4..8 = blocks 1, 1, 1, 1, 2
+    for j, pos in enumerate(range(4, 9)):
+        assert np.array_equal(k1[w.block_tables[0, pos // 4], :, pos % 4], kn[j])
+    assert int(np.any(k1 != w.k_pool, axis=(1, 3)).sum()) <= 5 + 4 + 6   # at most one (block, slot) per written token
