@@ -314,8 +314,8 @@ def time_prefill_chunk(torch, binding, n=8192, chunk=512, Hq=32, Hkv=8, reps=20)
 def serve_loop(torch, binding, steps, mode="recompute", seed=1007, chunked=False):
     """The scheduler model driving the GPU calls for `steps` engine iterations under a benign
     Poisson load that saturates the pool (the Fill state, with preemptions): per iteration the
-    swaps, the prefills (new and recomputed requests), the KV append and the decode attention
-    of one layer, 8B-shaped heads.  K/V contents are random; only shapes and tables matter here.
+    swaps, the prefills (new and recomputed requests: their K/V rows into the cache, then their
+    attention), the KV append and the decode attention of one layer, 8B-shaped heads.  K/V contents are random; only shapes and tables matter here.
     chunked: prefills proceed in chunks under a 512-token budget per iteration (the example the
     paper's section on chunked prefill gives) instead of whole within 8192 tokens."""
     import numpy as np
@@ -340,6 +340,8 @@ def serve_loop(torch, binding, steps, mode="recompute", seed=1007, chunked=False
     kn, vn = torch.randn(256, Hkv, D, device="cuda:0", generator=g).bfloat16(), \
         torch.randn(256, Hkv, D, device="cuda:0", generator=g).bfloat16()
     out = torch.empty(8192, Hq, D, device="cuda:0")
+    kc_all = torch.randn(8192, Hkv, D, device="cuda:0", generator=g).bfloat16()     # the chunks' new K/V rows
+    vc_all = torch.randn(8192, Hkv, D, device="cuda:0", generator=g).bfloat16()
     pf_ws = torch.empty(8192 * Hq * 16 * (D + 2) * 4, dtype=torch.uint8, device="cuda:0")   # most the split prefill asks for
     scale = D ** -0.5
     rec = []
@@ -381,11 +383,11 @@ def serve_loop(torch, binding, steps, mode="recompute", seed=1007, chunked=False
                 qv = q_all[:pf_tokens]
                 desc = binding.attn_desc_for(qv, kp, vp, torch.from_numpy(tabs).cuda(), max_context_len=int(ctxs.max()))
                 desc.batch = len(keep)
+                d_tabs, d_ctx, d_len, d_cu = (torch.from_numpy(a).cuda() for a in (tabs, ctxs, lens, cu))
+                binding.kv_append_chunk(desc, kc_all[:pf_tokens], vc_all[:pf_tokens], kp, vp, d_tabs, d_ctx, d_len, d_cu)
                 need = binding.prefill_workspace_bytes(desc, pf_tokens, int(lens.max()))   # > 0: few long walks, split them
-                binding.paged_prefill_attention(desc, qv, kp, vp, torch.from_numpy(tabs).cuda(),
-                                                torch.from_numpy(ctxs).cuda(), torch.from_numpy(lens).cuda(),
-                                                torch.from_numpy(cu).cuda(), int(lens.max()), scale, out[:pf_tokens],
-                                                workspace=pf_ws[:need] if need else None)
+                binding.paged_prefill_attention(desc, qv, kp, vp, d_tabs, d_ctx, d_len, d_cu, int(lens.max()), scale,
+                                                out[:pf_tokens], workspace=pf_ws[:need] if need else None)
         kv_tokens = 0
         if info.num_decode:
             ids, lens, tabs = s.decode_batch()

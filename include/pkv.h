@@ -257,6 +257,26 @@ int32_t kv_append(const pkv_attn_desc* desc, const void* k_new, const void* v_ne
                   const int32_t* context_lens, void* hip_stream);
 
 /*
+ * The same for the tokens of a prefill chunk (Sec. 2.1: the prefill computes the
+ * K/V of all prompt tokens; Sec. 2.2: they are kept in the paged cache; with
+ * chunked prefill a chunk at a time).  k_new / v_new are packed
+ * [total_query_tokens][num_kv_heads][head_dim] in sequence order, as q is for
+ * paged_prefill_attention, with the same query_lens / cu_query_lens: row j of
+ * sequence i's query_lens[i] rows is copied bit-exactly to token position
+ * context_lens[i] - query_lens[i] + j (the chunk is the tail of the context;
+ * query_lens[i] above context_lens[i] is clipped and the surplus rows are
+ * skipped, as are rows at or beyond cu_query_lens[batch]).  total_query_tokens
+ * is a host-known upper bound of the number of rows (it sizes the grid).
+ * Enqueued ahead of the paged_prefill_attention call that reads the pools.
+ * Trust and errors as for kv_append.
+ */
+int32_t kv_append_chunk(const pkv_attn_desc* desc, const void* k_new, const void* v_new,
+                        void* k_pool, void* v_pool, const int32_t* block_tables,
+                        const int32_t* context_lens, const int32_t* query_lens,
+                        const int32_t* cu_query_lens, int64_t total_query_tokens,
+                        void* hip_stream);
+
+/*
  * Block gather/scatter of the preemption swap path (Sec. 5.1.2 "Swapping":
  * the victim's KV blocks leave the pool and are later migrated back, in
  * general to different physical blocks).  For every plane p and every pair

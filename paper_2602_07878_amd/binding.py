@@ -21,7 +21,7 @@ FLAG_VECTOR_ALU = 1
 EXPORTS = [
     "pkv_version", "pkv_status_string", "pkv_last_hip_error_string", "pkv_attn_partition_tokens", "pkv_attn_workspace_bytes",
     "paged_decode_attention", "paged_decode_attention_timed", "paged_prefill_attention", "paged_prefill_attention_ws",
-    "pkv_prefill_workspace_bytes", "kv_append", "kv_block_swap",
+    "pkv_prefill_workspace_bytes", "kv_append", "kv_append_chunk", "kv_block_swap",
     "kv_swap_out_host", "kv_swap_in_host",
     "pkv_validate_tables_host",
     "pkv_validate_mapping_host", "pkv_validate_tables", "pkv_validate_mapping",
@@ -93,6 +93,8 @@ def lib() -> ctypes.CDLL:
         L.pkv_prefill_workspace_bytes.argtypes = [ctypes.POINTER(AttnDesc), ctypes.c_int64, i32]
         L.kv_append.restype = i32
         L.kv_append.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, vp]
+        L.kv_append_chunk.restype = i32
+        L.kv_append_chunk.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_int64, vp]
         for name in ("kv_swap_out_host", "kv_swap_in_host"):
             getattr(L, name).restype = i32
             getattr(L, name).argtypes = [ctypes.POINTER(SwapDesc), vp, vp, vp, i32, vp, sz, vp]
@@ -251,6 +253,18 @@ def kv_append(desc: AttnDesc, k_new, v_new, k_pool, v_pool, block_tables, contex
                          v_pool.data_ptr(), block_tables.data_ptr(), context_lens.data_ptr(),
                          _stream_ptr(stream))
     _check(st, "kv_append")
+
+
+def kv_append_chunk(desc: AttnDesc, k_new, v_new, k_pool, v_pool, block_tables, context_lens, query_lens,
+                    cu_query_lens, *, stream=None):
+    """Write the rows of a prefill chunk (k_new, v_new packed [total, Hkv, D], device) to the tail
+    positions context_lens[i] - query_lens[i] .. context_lens[i] - 1 of their sequences."""
+    assert k_new.is_contiguous() and v_new.is_contiguous() and k_new.shape == v_new.shape
+    st = lib().kv_append_chunk(ctypes.byref(desc), k_new.data_ptr(), v_new.data_ptr(), k_pool.data_ptr(),
+                               v_pool.data_ptr(), block_tables.data_ptr(), context_lens.data_ptr(),
+                               query_lens.data_ptr(), cu_query_lens.data_ptr(), int(k_new.shape[0]),
+                               _stream_ptr(stream))
+    _check(st, "kv_append_chunk")
 
 
 def kv_block_swap(desc: SwapDesc, src_pool, dst, block_mapping, *, stream=None):

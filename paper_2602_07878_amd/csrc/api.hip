@@ -295,6 +295,40 @@ int32_t kv_append(const pkv_attn_desc* desc, const void* k_new, const void* v_ne
   return hip_status(e);
 }
 
+int32_t kv_append_chunk(const pkv_attn_desc* desc, const void* k_new, const void* v_new, void* k_pool,
+                        void* v_pool, const int32_t* block_tables, const int32_t* context_lens,
+                        const int32_t* query_lens, const int32_t* cu_query_lens,
+                        int64_t total_query_tokens, void* hip_stream) {
+  const int32_t st = check_attn_desc(desc);
+  if (st != PKV_OK) return st;
+  if (total_query_tokens < 0) return PKV_ERR_SHAPE;
+  if (desc->batch == 0 || total_query_tokens == 0) return PKV_OK;
+  if (!k_new || !v_new || !k_pool || !v_pool || !block_tables || !context_lens || !query_lens || !cu_query_lens)
+    return PKV_ERR_NULL;
+  if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k_pool) || !aligned16(v_pool) ||
+      (reinterpret_cast<uintptr_t>(block_tables) & 3u) || (reinterpret_cast<uintptr_t>(context_lens) & 3u) ||
+      (reinterpret_cast<uintptr_t>(query_lens) & 3u) || (reinterpret_cast<uintptr_t>(cu_query_lens) & 3u))
+    return PKV_ERR_ALIGN;
+  const int eb = elem_bytes(desc->kv_dtype);
+  AttnParams p;
+  std::memset(&p, 0, sizeof p);
+  p.k_pool = k_pool; p.v_pool = v_pool;
+  p.block_tables = block_tables; p.context_lens = context_lens;
+  p.query_lens = query_lens; p.cu_query_lens = cu_query_lens;
+  p.k_stride_block = desc->k_stride_block * eb;
+  p.k_stride_head = desc->k_stride_head * eb;
+  p.k_stride_token = desc->k_stride_token * eb;
+  p.v_stride_block = desc->v_stride_block * eb;
+  p.v_stride_head = desc->v_stride_head * eb;
+  p.v_stride_token = desc->v_stride_token * eb;
+  p.batch = desc->batch; p.num_kv_heads = desc->num_kv_heads;
+  p.head_dim = desc->head_dim; p.block_size = desc->block_size;
+  p.max_blocks_per_seq = desc->max_blocks_per_seq;
+  const hipError_t e = launch_kv_append_chunk(p, k_new, v_new, eb, total_query_tokens,
+                                              static_cast<hipStream_t>(hip_stream));
+  return hip_status(e);
+}
+
 int32_t kv_block_swap(const pkv_swap_desc* desc, const void* src_pool, void* dst,
                       const int32_t* block_mapping, int32_t n_pairs, void* hip_stream) {
   const int32_t st = check_swap_desc(desc);

@@ -90,6 +90,8 @@ size_t prefill_workspace_bytes(const pkv_attn_desc& d, int64_t total_query_token
 // append.hip (uses the pointers, strides and shapes of AttnParams; q/out unused)
 hipError_t launch_kv_append(const AttnParams& p, const void* k_new, const void* v_new, int elem_bytes,
                             hipStream_t s);
+hipError_t launch_kv_append_chunk(const AttnParams& p, const void* k_new, const void* v_new, int elem_bytes,
+                                  int64_t total_rows, hipStream_t s);
 // swap_host.hip
 hipError_t swap_out_host(const pkv_swap_desc& d, const uint8_t* pool, uint8_t* host_dst, const int32_t* mapping,
                          int32_t n_pairs, uint8_t* staging, size_t staging_bytes, hipStream_t stream,

@@ -96,3 +96,37 @@ def test_append_empty_batch_is_a_no_op():
     binding.kv_append(desc, empty, empty, dev["k_pool"], dev["v_pool"], dev["block_tables"], dev["context_lens"])
     torch.cuda.synchronize()
     assert torch.equal(before.view(torch.int32), dev["k_pool"].view(torch.int32))
+
+
+# ---- the rows of a prefill chunk --------------------------------------------------------------
+@pytest.mark.parametrize("lens,qlens,bs,token_major", [
+    ((9, 4, 17, 6), (5, 4, 0, 9), 16, False),            # a tail, a whole prompt, nothing, more than the context
+    ((700, 33, 1200, 16, 90), (128, 1, 1200, 16, 0), 16, False),
+    ((300, 65), (300, 7), 64, True),
+])
+def test_chunk_rows_land_at_the_tail_positions_bit_exactly(lens, qlens, bs, token_major):
+    import oracle
+    import torch
+    from paper_2602_07878_amd import binding
+    w = W.make_attn_workload("chunk", 95, dtype="bf16", Hq=8, Hkv=2, D=128, block_size=bs,
+                             context_lens=list(lens), pool_factor=1.3)
+    ql = np.asarray(qlens, np.int32)
+    total = int(ql.sum())
+    rng = np.random.default_rng(96)
+    kn = rng.integers(0, 2**16, (total, w.Hkv, w.D)).astype(np.uint16)
+    vn = rng.integers(0, 2**16, (total, w.Hkv, w.D)).astype(np.uint16)
+    dev = to_device(w)
+    kp, vp = dev["k_pool"], dev["v_pool"]
+    if token_major:
+        kp = kp.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+        vp = vp.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    desc = binding.attn_desc_for(dev["q"], kp, vp, dev["block_tables"], max_context_len=w.max_context_len)
+    cu = torch.from_numpy(np.concatenate([[0], np.cumsum(ql)]).astype(np.int32)).cuda()
+    pad = 3                                                # more rows in the buffers than the packed total: ignored
+    dk = torch.from_numpy(np.concatenate([kn, np.full((pad, w.Hkv, w.D), 0x7FC0, np.uint16)]).view(np.int16)).cuda().view(torch.bfloat16)
+    dv = torch.from_numpy(np.concatenate([vn, np.full((pad, w.Hkv, w.D), 0x7FC0, np.uint16)]).view(np.int16)).cuda().view(torch.bfloat16)
+    binding.kv_append_chunk(desc, dk, dv, kp, vp, dev["block_tables"], dev["context_lens"],
+                            torch.from_numpy(ql).cuda(), cu)
+    torch.cuda.synchronize()
+    oracle.kv_append_chunk(w.k_pool, w.v_pool, kn, vn, w.block_tables, w.context_lens, ql, block_size=bs)
+    assert np.array_equal(to_bits(kp), w.k_pool) and np.array_equal(to_bits(vp), w.v_pool)   # whole pool images

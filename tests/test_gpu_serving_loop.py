@@ -71,6 +71,7 @@ def test_scheduler_driven_decode_with_preemption(mode, chunked):
         pid, ptok = s.prefills()
         pctx = s.prefill_contexts()
         chunk_rows = []                                     # (block table row, chunk tokens, cached tokens after)
+        new_k, new_v = [], []
         for rid, tokens, ctx in zip(pid.tolist(), ptok.tolist(), pctx.tolist()):
             assert chunked or ctx == tokens
             try:
@@ -78,15 +79,26 @@ def test_scheduler_driven_decode_with_preemption(mode, chunked):
             except binding.PkvError:
                 continue                                    # finished within its prefill
             tok = np.arange(ctx - tokens, ctx)              # the chunk's positions
-            b, slot = blocks[tok // BS], tok % BS
             k_all, v_all = rows[rid]
-            hk[b, :, slot, :], hv[b, :, slot, :] = k_all[tok], v_all[tok]
-            tb, ts = torch.from_numpy(b.astype(np.int64)).cuda(), torch.from_numpy(slot).cuda()
-            dk[tb, :, ts, :], dv[tb, :, ts, :] = up(k_all[tok]), up(v_all[tok])
+            new_k.append(k_all[tok]); new_v.append(v_all[tok])
             row = np.full(24, -1, np.int32)
             row[:blocks.size] = blocks
             chunk_rows.append((row, tokens, ctx))
             later_chunks += ctx > tokens
+        if chunk_rows:                                      # the chunks' K/V rows join the cache: kv_append_chunk
+            tabs_c = np.stack([r for r, _, _ in chunk_rows])
+            ql_c = np.array([t for _, t, _ in chunk_rows], np.int32)
+            cl_c = np.array([c for _, _, c in chunk_rows], np.int32)
+            kn_c, vn_c = np.concatenate(new_k), np.concatenate(new_v)
+            oracle.kv_append_chunk(hk, hv, kn_c, vn_c, tabs_c, cl_c, ql_c, block_size=BS)
+            d_bt = torch.from_numpy(tabs_c).cuda()
+            dkn, dvn = up(kn_c), up(vn_c)
+            desc_c = binding.attn_desc_for(torch.empty(1, HQ, D, dtype=torch.bfloat16, device="cuda"), dk, dv, d_bt,
+                                           max_context_len=int(cl_c.max()))
+            desc_c.batch = len(chunk_rows)
+            cu_c = torch.from_numpy(np.concatenate([[0], np.cumsum(ql_c)]).astype(np.int32)).cuda()
+            binding.kv_append_chunk(desc_c, dkn, dvn, dk, dv, d_bt, torch.from_numpy(cl_c).cuda(),
+                                    torch.from_numpy(ql_c).cuda(), cu_c)
         if chunked and chunk_rows and (it % 5 == 0 or any(c > t for _, t, c in chunk_rows)) and prefill_checked < 60:
             tabs = np.stack([r for r, _, _ in chunk_rows])
             ql = np.array([t for _, t, _ in chunk_rows], np.int32)
