@@ -338,6 +338,22 @@ int32_t kv_swap_in_host(const pkv_swap_desc* desc, const void* host_src, void* d
  * max_blocks_per_seq blocks; a used table entry outside [0, num_pool_blocks);
  * a mapping entry outside its plane; a destination block named twice.
  */
+/*
+ * The same for the chunk arrays of paged_prefill_attention[_ws] and
+ * kv_append_chunk, which those calls trust: PKV_ERR_INDEX unless
+ * cu_query_lens[0] = 0, cu_query_lens[i+1] - cu_query_lens[i] = query_lens[i],
+ * 0 <= query_lens[i] <= max_query_len, 0 <= context_lens[i] <= max_context_len
+ * and cu_query_lens[batch] <= total_query_tokens (the rows the caller's q, out,
+ * k_new, v_new buffers hold).
+ */
+int32_t pkv_validate_chunks_host(const pkv_attn_desc* desc, const int32_t* context_lens_host,
+                                 const int32_t* query_lens_host,
+                                 const int32_t* cu_query_lens_host, int32_t max_query_len,
+                                 int64_t total_query_tokens);
+int32_t pkv_validate_chunks(const pkv_attn_desc* desc, const int32_t* context_lens,
+                            const int32_t* query_lens, const int32_t* cu_query_lens,
+                            int32_t max_query_len, int64_t total_query_tokens,
+                            void* hip_stream);
 int32_t pkv_validate_tables_host(const pkv_attn_desc* desc,
                                  const int32_t* block_tables_host,
                                  const int32_t* context_lens_host);

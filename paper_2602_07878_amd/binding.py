@@ -24,7 +24,8 @@ EXPORTS = [
     "pkv_prefill_workspace_bytes", "kv_append", "kv_append_chunk", "kv_block_swap",
     "kv_swap_out_host", "kv_swap_in_host",
     "pkv_validate_tables_host",
-    "pkv_validate_mapping_host", "pkv_validate_tables", "pkv_validate_mapping",
+    "pkv_validate_mapping_host", "pkv_validate_tables", "pkv_validate_mapping", "pkv_validate_chunks_host",
+    "pkv_validate_chunks",
     "pkv_probe_copy", "pkv_probe_read",
 ]
 
@@ -296,6 +297,18 @@ def kv_swap_in_host(desc: SwapDesc, host_src, dst_pool, block_mapping, staging, 
                                staging.data_ptr(), staging.numel() * staging.element_size(),
                                _stream_ptr(stream))
     _check(st, "kv_swap_in_host")
+
+
+def validate_chunks(desc: AttnDesc, context_lens, query_lens, cu_query_lens, max_query_len: int,
+                    total_query_tokens: int, *, stream=None) -> int:
+    """Status of the range check of the chunk arrays (device tensors; copies them and waits)."""
+    L = lib()
+    L.pkv_validate_chunks.restype = ctypes.c_int32
+    L.pkv_validate_chunks.argtypes = [ctypes.POINTER(AttnDesc), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                      ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p]
+    return int(L.pkv_validate_chunks(ctypes.byref(desc), context_lens.data_ptr(), query_lens.data_ptr(),
+                                     cu_query_lens.data_ptr(), int(max_query_len), int(total_query_tokens),
+                                     _stream_ptr(stream)))
 
 
 def validate_tables(desc: AttnDesc, block_tables, context_lens, *, stream=None) -> int:

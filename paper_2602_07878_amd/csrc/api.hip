@@ -428,6 +428,43 @@ int32_t pkv_validate_mapping_host(const pkv_swap_desc* desc, const int32_t* bloc
   return PKV_OK;
 }
 
+int32_t pkv_validate_chunks_host(const pkv_attn_desc* desc, const int32_t* context_lens_host,
+                                 const int32_t* query_lens_host, const int32_t* cu_query_lens_host,
+                                 int32_t max_query_len, int64_t total_query_tokens) {
+  const int32_t st = check_attn_desc(desc);
+  if (st != PKV_OK) return st;
+  if (max_query_len < 0 || total_query_tokens < 0) return PKV_ERR_SHAPE;
+  if (desc->batch == 0) return PKV_OK;
+  if (!context_lens_host || !query_lens_host || !cu_query_lens_host) return PKV_ERR_NULL;
+  if (cu_query_lens_host[0] != 0) return PKV_ERR_INDEX;
+  for (int i = 0; i < desc->batch; ++i) {
+    const int64_t q = query_lens_host[i], n = context_lens_host[i];
+    if (q < 0 || q > max_query_len || n < 0 || n > desc->max_context_len) return PKV_ERR_INDEX;
+    // the rows of sequence i are exactly its query_lens[i] rows, back to back
+    if ((int64_t)cu_query_lens_host[i + 1] - cu_query_lens_host[i] != q) return PKV_ERR_INDEX;
+  }
+  if (cu_query_lens_host[desc->batch] > total_query_tokens) return PKV_ERR_INDEX;
+  return PKV_OK;
+}
+
+int32_t pkv_validate_chunks(const pkv_attn_desc* desc, const int32_t* context_lens,
+                            const int32_t* query_lens, const int32_t* cu_query_lens,
+                            int32_t max_query_len, int64_t total_query_tokens, void* hip_stream) {
+  const int32_t st = check_attn_desc(desc);
+  if (st != PKV_OK) return st;
+  if (desc->batch == 0) return PKV_OK;
+  if (!context_lens || !query_lens || !cu_query_lens) return PKV_ERR_NULL;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const size_t B = (size_t)desc->batch;
+  std::vector<int32_t> cl(B), ql(B), cu(B + 1);
+  if (hipMemcpyAsync(cl.data(), context_lens, B * 4, hipMemcpyDeviceToHost, s) != hipSuccess ||
+      hipMemcpyAsync(ql.data(), query_lens, B * 4, hipMemcpyDeviceToHost, s) != hipSuccess ||
+      hipMemcpyAsync(cu.data(), cu_query_lens, (B + 1) * 4, hipMemcpyDeviceToHost, s) != hipSuccess ||
+      hipStreamSynchronize(s) != hipSuccess)
+    return PKV_ERR_HIP;
+  return pkv_validate_chunks_host(desc, cl.data(), ql.data(), cu.data(), max_query_len, total_query_tokens);
+}
+
 int32_t pkv_validate_tables(const pkv_attn_desc* desc, const int32_t* block_tables,
                             const int32_t* context_lens, void* hip_stream) {
   const int32_t st = check_attn_desc(desc);

@@ -174,6 +174,26 @@ def test_swap_host_leg_rejects_bad_arguments_on_host():
     assert L.kv_swap_in_host(ctypes.byref(swap_desc()), 0x1000, 0x2000, 0x3000, 101, 0x4000, 1 << 22, None) == ST["SHAPE"]
 
 
+def test_chunk_validator_on_host():
+    L = binding.lib()
+    L.pkv_validate_chunks_host.restype = ctypes.c_int32
+    L.pkv_validate_chunks_host.argtypes = [ctypes.POINTER(AttnDesc), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                           ctypes.c_int32, ctypes.c_int64]
+    d = good_desc(batch=3)
+    def f(cl, ql, cu, maxq=512, total=None):
+        a, b, c = (np.asarray(x, np.int32) for x in (cl, ql, cu))
+        return L.pkv_validate_chunks_host(ctypes.byref(d), a.ctypes.data, b.ctypes.data, c.ctypes.data, maxq,
+                                          int(c[-1]) if total is None else total)
+    assert f([100, 7, 512], [100, 0, 512], [0, 100, 100, 612]) == ST["OK"]
+    assert f([100, 7, 512], [100, 0, 512], [1, 101, 101, 613]) == ST["INDEX"]        # first row is not 0
+    assert f([100, 7, 512], [100, 0, 512], [0, 100, 101, 613]) == ST["INDEX"]        # a row that belongs to nobody
+    assert f([100, 7, 512], [100, 0, 512], [0, 100, 100, 612], total=611) == ST["INDEX"]   # more rows than the buffers hold
+    assert f([100, 7, 512], [100, -1, 512], [0, 100, 99, 611]) == ST["INDEX"]
+    assert f([100, 7, 512], [100, 0, 512], [0, 100, 100, 612], maxq=511) == ST["INDEX"]
+    assert f([100, 7, 1025], [100, 0, 512], [0, 100, 100, 612]) == ST["INDEX"]       # context above max_context_len
+    assert L.pkv_validate_chunks_host(ctypes.byref(d), None, None, None, 1, 1) == ST["NULL"]
+
+
 def test_host_validators():
     L = binding.lib()
     d = good_desc(batch=2, max_blocks_per_seq=4, max_context_len=64)

@@ -175,3 +175,17 @@ def test_rejects_unsupported_shapes():
     with pytest.raises(binding.PkvError):
         binding.paged_prefill_attention(desc, dev["q"], dev["k_pool"], dev["v_pool"], dev["block_tables"],
                                         dev["context_lens"], z, z, 4, 0.1, torch.empty_like(dev["q"]))
+
+
+def test_chunk_validator_reads_the_device_arrays():
+    import torch
+    from paper_2602_07878_amd import binding
+    w = mk(97, (300, 40, 90))
+    dev = to_device(w)
+    q = torch.zeros(1, w.Hq, w.D, dtype=torch.bfloat16, device="cuda")
+    desc = binding.attn_desc_for(q, dev["k_pool"], dev["v_pool"], dev["block_tables"], max_context_len=w.max_context_len)
+    desc.batch = 3
+    t = lambda a: torch.tensor(a, dtype=torch.int32, device="cuda")
+    assert binding.validate_chunks(desc, dev["context_lens"], t([128, 0, 90]), t([0, 128, 128, 218]), 128, 218) == binding.PKV_OK
+    assert binding.validate_chunks(desc, dev["context_lens"], t([128, 0, 90]), t([0, 128, 130, 220]), 128, 220) == 6   # PKV_ERR_INDEX
+    assert binding.validate_chunks(desc, dev["context_lens"], t([128, 0, 90]), t([0, 128, 128, 218]), 128, 217) == 6
