@@ -311,6 +311,64 @@ def time_prefill_chunk(torch, binding, n=8192, chunk=512, Hq=32, Hkv=8, reps=20)
     return res
 
 
+def time_model_sweep(torch, binding, B=64, Hq=32, Hkv=8, seed=1009, tables=16, reps=3):
+    """The execution-time model of the paper's Sec. 4.2, T_exec ~ N_ctx * d * sizeof(T) / BW_HBM:
+    decode attention of a fixed batch of B sequences (8B-shaped heads, bf16) while their contexts
+    grow from about 13 K to 262 K cached tokens in total; a straight line is fitted to time against
+    KV bytes.  Every call reads other physical blocks of a 4 GiB pool (a fresh random table), so
+    nothing is re-read from a cache."""
+    import numpy as np
+    from paper_2602_07878_amd import workloads as W
+    D, bs = 128, 16
+    nblk = (4 << 30) // (2 * Hkv * bs * D * 2)                      # K and V pools of 2 GiB each
+    g = torch.Generator(device="cuda:0")
+    g.manual_seed(seed)
+    kp = torch.randn(nblk, Hkv, bs, D, device="cuda:0", generator=g).bfloat16()
+    vp = torch.randn(nblk, Hkv, bs, D, device="cuda:0", generator=g).bfloat16()
+    q = torch.randn(B, Hq, D, device="cuda:0", generator=g).bfloat16()
+    out = torch.empty(B, Hq, D, device="cuda:0")
+    base = W.lens_uniform(seed, B, 128, 4096).astype(np.int64)     # the cfg2 length mix, scaled
+    pts = []
+    for frac in (0.1, 0.2, 0.3, 0.4, 0.5, 0.65, 0.8, 1.0, 1.25, 1.5, 2.0):
+        lens = np.maximum(16, (base * frac).astype(np.int64)).astype(np.int32)
+        nb = (lens + bs - 1) // bs
+        maxb = int(nb.max())
+        tabs = []
+        for _ in range(tables):
+            perm = torch.randperm(nblk, device="cuda:0", generator=g)[:int(nb.sum())].int().cpu().numpy()
+            t = np.full((B, maxb), -1, np.int32)
+            pos = 0
+            for i in range(B):
+                t[i, :nb[i]] = perm[pos:pos + nb[i]]
+                pos += int(nb[i])
+            tabs.append(torch.from_numpy(t).cuda())
+        cl = torch.from_numpy(lens).cuda()
+        desc = binding.attn_desc_for(q, kp, vp, tabs[0], max_context_len=int(lens.max()))
+        ws = binding.new_workspace(binding.attn_workspace_bytes(desc), "cuda:0")
+        f = lambda i: binding.paged_decode_attention(q, kp, vp, tabs[i % tables], cl, D ** -0.5, out,
+                                                     max_context_len=int(lens.max()), workspace=ws, desc=desc)
+        for i in range(tables):
+            f(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(tables * reps):
+            f(i)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / (tables * reps) * 1e3
+        pts.append((int(lens.sum()), us))
+    x = np.array([t * 2 * Hkv * D * 2 for t, _ in pts], np.float64)   # KV bytes per call
+    y = np.array([u for _, u in pts], np.float64)
+    slope, icpt = np.polyfit(x, y, 1)
+    r2 = 1.0 - float(((y - (slope * x + icpt)) ** 2).sum() / ((y - y.mean()) ** 2).sum())
+    del kp, vp
+    torch.cuda.empty_cache()
+    return {"model": "T_exec = a + N_ctx * bytes_per_token / BW (Sec. 4.2)", "batch": B,
+            "points_tokens_us": [[t, round(u, 2)] for t, u in pts],
+            "marginal_bandwidth_GBps": float(1e-3 / slope), "intercept_us": float(icpt), "r_squared": float(r2)}
+
+
 def serve_loop(torch, binding, steps, mode="recompute", seed=1007, chunked=False):
     """The scheduler model driving the GPU calls for `steps` engine iterations under a benign
     Poisson load that saturates the pool (the Fill state, with preemptions): per iteration the
@@ -469,6 +527,8 @@ def main():
     ap.add_argument("--no-swap", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--extra", action="store_true", help="also time the Fill and long-context configs")
+    ap.add_argument("--sweep", action="store_true",
+                    help="also fit the paper's linear execution-time model to a sweep of the cached context")
     ap.add_argument("--serve", type=int, default=0, metavar="ITERATIONS",
                     help="also run the scheduler-driven serving loop for this many engine iterations")
     args = ap.parse_args()
@@ -584,6 +644,9 @@ def main():
             torch.cuda.empty_cache()
         result["other_configs"] = extra
 
+    if args.sweep:
+        result["time_model"] = time_model_sweep(torch, binding)
+        log(f"[bench] time model: {result['time_model']}")
     if args.serve > 0:
         result["serving_loop"] = {m: serve_loop(torch, binding, args.serve, mode=m) for m in ("recompute", "swap")}
         result["serving_loop"]["recompute_chunked_prefill"] = serve_loop(torch, binding, args.serve, mode="recompute",
