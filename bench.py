@@ -88,16 +88,18 @@ def time_attention(w, d, steps, warmup, torch, binding, kernel_events=False):
     return out, ev_ms / steps, wall_ms / steps, kern
 
 
-KERNEL_SOURCES = ("attn_stream_mfma.hip", "pkv_internal.h")   # the dominant kernel, its launch and the constants it uses
-
-
 def source_fingerprint():
-    """Hash of the sources of the dominant kernel: counter-derived figures under profiles/ are
-    quoted only while the kernel they were taken from is unchanged."""
+    """Hash of what defines the dominant kernel: its source file and, of the shared header, the
+    constants and the parameter block it is launched with (the part up to the end of AttnParams;
+    the prototypes of other files further down do not touch the kernel).  Counter-derived figures
+    under profiles/ are quoted only while this is unchanged."""
     import hashlib
+    csrc = os.path.join(ROOT, "paper_2602_07878_amd", "csrc")
     h = hashlib.sha256()
-    for f in KERNEL_SOURCES:
-        h.update(open(os.path.join(ROOT, "paper_2602_07878_amd", "csrc", f), "rb").read())
+    h.update(open(os.path.join(csrc, "attn_stream_mfma.hip"), "rb").read())
+    head = open(os.path.join(csrc, "pkv_internal.h")).read()
+    end = head.index("};", head.index("struct AttnParams {")) + 2
+    h.update(head[:end].encode())
     return h.hexdigest()[:16]
 
 
