@@ -11,9 +11,10 @@ pytestmark = pytest.mark.gpu
 TOL = 2e-3
 
 
-def run_prefill(w, query_lens, seed, out_dtype=None, token_major=False, split=False):
+def run_prefill(w, query_lens, seed, out_dtype=None, token_major=False, split=False, q_hook=None):
     """Returns (GPU out as float64 [total, Hq, D], oracle out).  split: bring the workspace
-    that lets the library cut the walks into ranges (it must want to for the case)."""
+    that lets the library cut the walks into ranges (it must want to for the case).  q_hook maps
+    the drawn query bits [total, Hq, D] to the ones both sides get."""
     import oracle
     import torch
     from paper_2602_07878_amd import binding
@@ -21,6 +22,8 @@ def run_prefill(w, query_lens, seed, out_dtype=None, token_major=False, split=Fa
     total = int(ql.sum())
     rng = np.random.default_rng(seed)
     q = W.f32_to_bf16_bits(rng.standard_normal((total, w.Hq, w.D)).astype(np.float32))
+    if q_hook is not None:
+        q = q_hook(q)
     ref = oracle.paged_prefill_attention(q, w.k_pool, w.v_pool, w.block_tables, w.context_lens, ql,
                                          w.scale, block_size=w.block_size)
     dev = to_device(w)
