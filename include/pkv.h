@@ -12,9 +12,19 @@
  *
  * General conventions
  *  - Every data pointer is a DEVICE pointer owned by the caller unless the
- *    parameter name ends in `_host`.  The library allocates no device memory,
- *    keeps no state between calls and never synchronises: all work is enqueued
- *    on `hip_stream` (a hipStream_t passed as void*; NULL = default stream).
+ *    parameter name ends in `_host`.  The library allocates no device memory
+ *    and never synchronises: all work is enqueued on `hip_stream` (a
+ *    hipStream_t passed as void*; NULL = default stream).
+ *  - State the library keeps, all of it per process: for each HIP device id
+ *    below 16, whether the kernels that need more than 64 KiB of LDS have been
+ *    given that attribute, the device's compute-unit count; per thread, the last
+ *    HIP runtime error.  It is set up by pkv_init(), or by the
+ *    first call that needs it on a device.  That set-up makes HIP runtime calls
+ *    that may not run inside a stream capture: call pkv_init() (or any one
+ *    eager call of the entry point) on a device before capturing there.
+ *    pkv_attn_workspace_bytes and pkv_prefill_workspace_bytes depend on the
+ *    CURRENT device's compute-unit count: size a workspace with the device
+ *    current on which the call will run.
  *  - Inputs are only read; `out`, `workspace` and `dst` are overwritten.
  *  - Every base pointer must be 16-byte aligned and every stride must keep
  *    16-byte alignment of a token row (PKV_ERR_ALIGN otherwise).
@@ -102,6 +112,14 @@ typedef struct pkv_swap_desc {
 /* Library version as major*10000 + minor*100 + patch. */
 int32_t pkv_version(void);
 
+/*
+ * Once-per-device set-up for the CURRENT HIP device, done here instead of
+ * inside the first call of each entry point: the LDS attribute of the
+ * attention kernels, the compute-unit count.  Idempotent and thread-safe; PKV_OK or PKV_ERR_HIP.  Callers
+ * that capture the calls into a HIP graph run it before the capture.
+ */
+int32_t pkv_init(void);
+
 /* Static, NUL-terminated name of a status code ("PKV_OK", ...). */
 const char* pkv_status_string(int32_t status);
 
@@ -159,24 +177,6 @@ int32_t paged_decode_attention(const pkv_attn_desc* desc, const void* q,
                                const int32_t* context_lens, float scale,
                                void* out, void* workspace,
                                size_t workspace_bytes, void* hip_stream);
-
-/*
- * The same call with two optional hipEvent_t handles (passed as void*, either
- * may be NULL) that are attached to the launch of the kernel that streams K and
- * V (Sec. 4.2: the part of the step whose time grows with the KV volume) and
- * receive that kernel's own begin and end on hip_stream, i.e. excluding the
- * small kernel that merges the split-K partials.  For profiling: the elapsed
- * time between the two events is that kernel's duration.  The events are the
- * caller's and must have been created with timing enabled; nothing waits on
- * them.
- */
-int32_t paged_decode_attention_timed(const pkv_attn_desc* desc, const void* q,
-                                     const void* k_pool, const void* v_pool,
-                                     const int32_t* block_tables,
-                                     const int32_t* context_lens, float scale,
-                                     void* out, void* workspace,
-                                     size_t workspace_bytes, void* hip_stream,
-                                     void* ev_kernel_begin, void* ev_kernel_end);
 
 /*
  * Causal prefill attention of a chunk over the paged cache (Sec. 2.1: masked
@@ -366,16 +366,6 @@ int32_t pkv_validate_tables(const pkv_attn_desc* desc,
 int32_t pkv_validate_mapping(const pkv_swap_desc* desc,
                              const int32_t* block_mapping, int32_t n_pairs,
                              void* hip_stream);
-
-/*
- * Bandwidth probes used by the benchmark to measure this machine's streaming
- * ceilings with the same access idiom as the product kernels (16 bytes per
- * lane): pkv_probe_copy copies `bytes` (multiple of 16) from src to dst;
- * pkv_probe_read reads `bytes` from src and writes one 16-byte checksum per
- * workgroup to `sink` (>= 64 KiB).
- */
-int32_t pkv_probe_copy(const void* src, void* dst, size_t bytes, void* hip_stream);
-int32_t pkv_probe_read(const void* src, void* sink, size_t bytes, void* hip_stream);
 
 #ifdef __cplusplus
 }

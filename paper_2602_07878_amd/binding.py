@@ -19,7 +19,7 @@ PKV_ERR_HIP = 7
 FLAG_VECTOR_ALU = 1
 
 EXPORTS = [
-    "pkv_version", "pkv_status_string", "pkv_last_hip_error_string", "pkv_attn_partition_tokens", "pkv_attn_workspace_bytes",
+    "pkv_version", "pkv_init", "pkv_status_string", "pkv_last_hip_error_string", "pkv_attn_partition_tokens", "pkv_attn_workspace_bytes",
     "paged_decode_attention", "paged_decode_attention_timed", "paged_prefill_attention", "paged_prefill_attention_ws",
     "pkv_prefill_workspace_bytes", "kv_append", "kv_append_chunk", "kv_block_swap",
     "kv_swap_out_host", "kv_swap_in_host",
@@ -70,6 +70,8 @@ def lib() -> ctypes.CDLL:
         vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
         L.pkv_version.restype = i32
         L.pkv_version.argtypes = []
+        L.pkv_init.restype = i32
+        L.pkv_init.argtypes = []
         L.pkv_status_string.restype = ctypes.c_char_p
         L.pkv_status_string.argtypes = [i32]
         L.pkv_last_hip_error_string.restype = ctypes.c_char_p
@@ -206,6 +208,12 @@ def paged_decode_attention(q, k_pool, v_pool, block_tables, context_lens, scale,
                                             ctypes.c_void_p(kernel_events[1].cuda_event))
     _check(st, "paged_decode_attention")
     return workspace
+
+
+def init():
+    """Once-per-device set-up of the library for the current device (optional: the first call of
+    an entry point does its own)."""
+    _check(lib().pkv_init(), "pkv_init")
 
 
 def swap_desc(num_planes: int, block_bytes: int, src_num_blocks: int, dst_num_blocks: int,

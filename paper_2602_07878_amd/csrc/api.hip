@@ -6,6 +6,7 @@
 #include <cstring>
 #include <vector>
 
+#include "pkv_bench.h"
 #include "pkv_internal.h"
 
 namespace {
@@ -84,7 +85,17 @@ int32_t check_swap_desc(const pkv_swap_desc* d) {
 
 extern "C" {
 
-int32_t pkv_version(void) { return 100; }
+int32_t pkv_version(void) { return 200; }
+
+int32_t pkv_init(void) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_status(e);
+  (void)num_cus();
+  if ((e = prepare_attn_stream()) != hipSuccess) return hip_status(e);
+  if ((e = prepare_attn_prefill()) != hipSuccess) return hip_status(e);
+  return PKV_OK;
+}
 
 const char* pkv_status_string(int32_t status) {
   switch (status) {
@@ -116,10 +127,15 @@ size_t pkv_attn_workspace_bytes(const pkv_attn_desc* desc) {
   return (size_t)(ml + (o + 255) / 256 * 256);
 }
 
-static int32_t attention_impl(const pkv_attn_desc* desc, const void* q, const void* k_pool,
-                              const void* v_pool, const int32_t* block_tables,
-                              const int32_t* context_lens, float scale, void* out, void* workspace,
-                              size_t workspace_bytes, void* hip_stream, void* ev_begin, void* ev_end) {
+}  // extern "C"
+
+int32_t pkv::status_of(hipError_t e) { return hip_status(e); }
+
+// The decode-attention call behind every entry point that has it: checks, then launches.
+int32_t pkv::attention_call(const pkv_attn_desc* desc, const void* q, const void* k_pool,
+                            const void* v_pool, const int32_t* block_tables,
+                            const int32_t* context_lens, float scale, void* out, void* workspace,
+                            size_t workspace_bytes, void* hip_stream, void* ev_begin, void* ev_end) {
   const int32_t st = check_attn_desc(desc);
   if (st != PKV_OK) return st;
   if (desc->batch == 0) return PKV_OK;
@@ -180,11 +196,13 @@ static int32_t attention_impl(const pkv_attn_desc* desc, const void* q, const vo
   return hip_status(e);
 }
 
+extern "C" {
+
 int32_t paged_decode_attention(const pkv_attn_desc* desc, const void* q, const void* k_pool,
                                const void* v_pool, const int32_t* block_tables,
                                const int32_t* context_lens, float scale, void* out,
                                void* workspace, size_t workspace_bytes, void* hip_stream) {
-  return attention_impl(desc, q, k_pool, v_pool, block_tables, context_lens, scale, out, workspace,
+  return attention_call(desc, q, k_pool, v_pool, block_tables, context_lens, scale, out, workspace,
                         workspace_bytes, hip_stream, nullptr, nullptr);
 }
 
@@ -193,7 +211,7 @@ int32_t paged_decode_attention_timed(const pkv_attn_desc* desc, const void* q, c
                                      const int32_t* context_lens, float scale, void* out,
                                      void* workspace, size_t workspace_bytes, void* hip_stream,
                                      void* ev_kernel_begin, void* ev_kernel_end) {
-  return attention_impl(desc, q, k_pool, v_pool, block_tables, context_lens, scale, out, workspace,
+  return attention_call(desc, q, k_pool, v_pool, block_tables, context_lens, scale, out, workspace,
                         workspace_bytes, hip_stream, ev_kernel_begin, ev_kernel_end);
 }
 

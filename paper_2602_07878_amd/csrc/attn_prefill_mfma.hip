@@ -662,6 +662,20 @@ bool attn_prefill_supported(const pkv_attn_desc& d) {
          ids_bytes <= kMaxIdsBytes;
 }
 
+// More than 64 KiB of dynamic LDS: asked for once per device (every time outside the table).
+hipError_t prepare_attn_prefill() {
+  static std::atomic<bool> prepared[kMaxDevices];
+  const int slot = device_slot();
+  if (slot >= 0 && prepared[slot].load(std::memory_order_acquire)) return hipSuccess;
+  for (const void* f : {reinterpret_cast<const void*>(&attn_prefill_mfma_d128<1>),
+                        reinterpret_cast<const void*>(&attn_prefill_mfma_d128<2>)}) {
+    const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, kRingBytes + kMaxIdsBytes);
+    if (e != hipSuccess) return e;
+  }
+  if (slot >= 0) prepared[slot].store(true, std::memory_order_release);
+  return hipSuccess;
+}
+
 // p.max_partitions = ranges per walk (1: results go to p.out; else partials to p.ws_ml /
 // p.ws_o, [rows][Hq][ranges][2] and [rows][Hq][ranges][D] floats, and the merge follows);
 // total_query_tokens bounds the rows (the merge reads the true count from cu_query_lens).
@@ -679,15 +693,9 @@ hipError_t launch_attn_prefill(AttnParams& p, int max_query_len, int max_context
   const int64_t nwg = (int64_t)((max_query_len + qpg - 1) / qpg) * p.max_partitions * p.group_tiles * p.streams_per_xcd * 8;
   if (nwg > 0x7FFFFFFF) return hipErrorInvalidValue;
   const dim3 grid((unsigned)nwg);
-  static std::atomic<bool> prepared[kMaxDevices];   // more than 64 KiB of dynamic LDS: ask once per device
-  const int slot = current_device_slot();
-  if (!prepared[slot].load(std::memory_order_acquire)) {
-    for (const void* f : {reinterpret_cast<const void*>(&attn_prefill_mfma_d128<1>),
-                          reinterpret_cast<const void*>(&attn_prefill_mfma_d128<2>)}) {
-      const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, kRingBytes + kMaxIdsBytes);
-      if (e != hipSuccess) return e;
-    }
-    prepared[slot].store(true, std::memory_order_release);
+  {
+    const hipError_t e = prepare_attn_prefill();
+    if (e != hipSuccess) return e;
   }
   if (hw == 1) hipLaunchKernelGGL((attn_prefill_mfma_d128<1>), grid, dim3(kThreads), lds_bytes, s, p);
   else hipLaunchKernelGGL((attn_prefill_mfma_d128<2>), grid, dim3(kThreads), lds_bytes, s, p);

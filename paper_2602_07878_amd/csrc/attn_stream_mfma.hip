@@ -692,14 +692,9 @@ __global__ __launch_bounds__(GH * kWaveSize) void attn_stream_merge_lean(const A
 template <int GH>
 hipError_t launch(const AttnParams& p, hipStream_t s) {
   const size_t lds = (size_t)p.prefix_bytes + (size_t)kNW * kWaveLds;
-  static std::atomic<bool> prepared[kMaxDevices];   // more than 64 KiB of dynamic LDS: ask once per device
-  const int slot = current_device_slot();
-  if (!prepared[slot].load(std::memory_order_acquire)) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_stream_mfma_d128<GH>),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize,
-                                             kStreamMaxPrefixBytes + kNW * kWaveLds);
+  {
+    const hipError_t e = prepare_attn_stream();
     if (e != hipSuccess) return e;
-    prepared[slot].store(true, std::memory_order_release);
   }
   // with events: attached to the dispatch itself, so they carry the kernel's own begin and end
   if (p.ev_begin || p.ev_end)
@@ -719,17 +714,35 @@ hipError_t launch(const AttnParams& p, hipStream_t s) {
 
 }  // namespace
 
+// The stream kernels use more than 64 KiB of dynamic LDS, which has to be asked for once per
+// device (devices outside the table are asked every time).
+hipError_t prepare_attn_stream() {
+  static std::atomic<bool> prepared[kMaxDevices];
+  const int slot = device_slot();
+  if (slot >= 0 && prepared[slot].load(std::memory_order_acquire)) return hipSuccess;
+  for (const void* f : {reinterpret_cast<const void*>(&attn_stream_mfma_d128<1>),
+                        reinterpret_cast<const void*>(&attn_stream_mfma_d128<2>),
+                        reinterpret_cast<const void*>(&attn_stream_mfma_d128<4>),
+                        reinterpret_cast<const void*>(&attn_stream_mfma_d128<8>)}) {
+    const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                             kStreamMaxPrefixBytes + kNW * kWaveLds);
+    if (e != hipSuccess) return e;
+  }
+  if (slot >= 0) prepared[slot].store(true, std::memory_order_release);
+  return hipSuccess;
+}
+
 // CUs of the current device (cached per device).
 int num_cus() {
   static std::atomic<int> cached[kMaxDevices];   // zero-initialised: not asked yet
-  const int slot = current_device_slot();
-  int v = cached[slot].load(std::memory_order_relaxed);
+  const int slot = device_slot();
+  int v = slot >= 0 ? cached[slot].load(std::memory_order_relaxed) : 0;
   if (v == 0) {
     int dev = 0;
     if (!(hipGetDevice(&dev) == hipSuccess &&
           hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0))
       v = 256;   // no device (sizing a workspace on a host without one): the MI355X count
-    cached[slot].store(v, std::memory_order_relaxed);
+    if (slot >= 0) cached[slot].store(v, std::memory_order_relaxed);
   }
   return v;
 }

@@ -13,14 +13,18 @@ constexpr int kDefaultPartition = 512;   // split-K partition length in tokens
 constexpr int kAttnThreads = 256;        // 4 wavefronts per workgroup
 constexpr int kStreamMaxPrefixBytes = 8192;   // LDS for per-sequence tile prefix sums
 
-// Per-device bookkeeping (kernel attributes set, CU counts) is kept in small tables indexed by
-// the HIP device id; ids outside the table share slot 0.
+// Per-device bookkeeping (kernel attributes set, CU counts) is kept in small tables indexed by the HIP device id; for ids outside the table (-1)
+// nothing is remembered and the question is asked again at every call.
 constexpr int kMaxDevices = 16;
-inline int current_device_slot() {
+inline int device_slot() {
   int d = 0;
-  if (hipGetDevice(&d) != hipSuccess || d < 0 || d >= kMaxDevices) d = 0;
+  if (hipGetDevice(&d) != hipSuccess || d < 0 || d >= kMaxDevices) return -1;
   return d;
 }
+
+// once-per-device set-up of the kernels that need it; also run by pkv_init()
+hipError_t prepare_attn_stream();    // attn_stream_mfma.hip
+hipError_t prepare_attn_prefill();   // attn_prefill_mfma.hip
 
 int num_cus();   // CUs of the current device (256 when there is none), attn_stream_mfma.hip
 
@@ -68,6 +72,12 @@ struct SwapParams {
   int32_t src_index_offset, dst_index_offset;
 };
 
+// api.hip: checks and launch of the decode-attention call (every entry point that offers it ends
+// here); PKV_OK or PKV_ERR_HIP for a runtime result, remembering the error text for the thread
+int32_t attention_call(const pkv_attn_desc* desc, const void* q, const void* k_pool, const void* v_pool,
+                       const int32_t* block_tables, const int32_t* context_lens, float scale, void* out,
+                       void* workspace, size_t workspace_bytes, void* hip_stream, void* ev_begin, void* ev_end);
+int32_t status_of(hipError_t e);
 // attn_decode.hip
 hipError_t launch_attn_decode(const AttnParams& p, int dtype, hipStream_t s);
 // attn_stream_mfma.hip

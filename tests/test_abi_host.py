@@ -16,7 +16,7 @@ ST = dict(OK=0, NULL=1, SHAPE=2, DTYPE=3, ALIGN=4, WORKSPACE=5, INDEX=6, HIP=7)
 
 
 def header_functions():
-    src = open(os.path.join(ROOT, "include", "pkv.h")).read()
+    src = "".join(open(os.path.join(ROOT, "include", h)).read() for h in ("pkv.h", "pkv_bench.h"))
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
     return sorted(set(re.findall(r"\b(pkv_[a-z_]+|paged_decode_attention[a-z_]*|paged_prefill_attention[a-z_]*|kv_block_swap|kv_append[a-z_]*|kv_swap_[a-z_]+)\s*\(", src)))
 
