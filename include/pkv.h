@@ -17,8 +17,9 @@
  *    hipStream_t passed as void*; NULL = default stream).
  *  - State the library keeps, all of it per process: for each HIP device id
  *    below 16, whether the kernels that need more than 64 KiB of LDS have been
- *    given that attribute, the device's compute-unit count; per thread, the last
- *    HIP runtime error.  It is set up by pkv_init(), or by the
+ *    given that attribute, the device's compute-unit count, and the device
+ *    address of the static scratch array of paged_decode_attention_static; per
+ *    thread, the last HIP runtime error.  It is set up by pkv_init(), or by the
  *    first call that needs it on a device.  That set-up makes HIP runtime calls
  *    that may not run inside a stream capture: call pkv_init() (or any one
  *    eager call of the entry point) on a device before capturing there.
@@ -115,7 +116,8 @@ int32_t pkv_version(void);
 /*
  * Once-per-device set-up for the CURRENT HIP device, done here instead of
  * inside the first call of each entry point: the LDS attribute of the
- * attention kernels, the compute-unit count.  Idempotent and thread-safe; PKV_OK or PKV_ERR_HIP.  Callers
+ * attention kernels, the compute-unit count, the address of the static
+ * scratch array.  Idempotent and thread-safe; PKV_OK or PKV_ERR_HIP.  Callers
  * that capture the calls into a HIP graph run it before the capture.
  */
 int32_t pkv_init(void);
@@ -177,6 +179,30 @@ int32_t paged_decode_attention(const pkv_attn_desc* desc, const void* q,
                                const int32_t* context_lens, float scale,
                                void* out, void* workspace,
                                size_t workspace_bytes, void* hip_stream);
+
+/*
+ * paged_decode_attention for callers that cannot allocate device memory: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  The same operation, arguments, kernels and results (bit for
+ * bit), but the scratch for the split-K partials is not brought by the caller:
+ * it is a device array inside the library's code object, of
+ * pkv_static_scratch_bytes() = 16 MiB, which every GPU the library runs on
+ * holds until the process ends.  Returns PKV_ERR_WORKSPACE, enqueueing
+ * nothing, when pkv_attn_workspace_bytes(desc) exceeds that (the five
+ * benchmark shapes need 6-10 MiB with partition_tokens = 0; a caller-set
+ * partition_tokens on a very long batch can need more).  The call allocates
+ * nothing and frees nothing.  All calls on one GPU share the array: calls that
+ * overlap in time on one GPU (different streams or threads) race, and the
+ * array keeps the previous call's contents (the kernels write everything they
+ * later read, nothing needs clearing).  The first call on a device resolves
+ * the array's device address (pkv_init does the same ahead of time).
+ */
+size_t pkv_static_scratch_bytes(void);
+int32_t paged_decode_attention_static(const pkv_attn_desc* desc, const void* q,
+                                      const void* k_pool, const void* v_pool,
+                                      const int32_t* block_tables,
+                                      const int32_t* context_lens, float scale,
+                                      void* out, void* hip_stream);
 
 /*
  * Causal prefill attention of a chunk over the paged cache (Sec. 2.1: masked

@@ -19,7 +19,7 @@ PKV_ERR_HIP = 7
 FLAG_VECTOR_ALU = 1
 
 EXPORTS = [
-    "pkv_version", "pkv_init", "pkv_status_string", "pkv_last_hip_error_string", "pkv_attn_partition_tokens", "pkv_attn_workspace_bytes",
+    "pkv_version", "pkv_init", "pkv_static_scratch_bytes", "paged_decode_attention_static", "pkv_status_string", "pkv_last_hip_error_string", "pkv_attn_partition_tokens", "pkv_attn_workspace_bytes",
     "paged_decode_attention", "paged_decode_attention_timed", "paged_prefill_attention", "paged_prefill_attention_ws",
     "pkv_prefill_workspace_bytes", "kv_append", "kv_append_chunk", "kv_block_swap",
     "kv_swap_out_host", "kv_swap_in_host",
@@ -72,6 +72,11 @@ def lib() -> ctypes.CDLL:
         L.pkv_version.argtypes = []
         L.pkv_init.restype = i32
         L.pkv_init.argtypes = []
+        L.pkv_static_scratch_bytes.restype = sz
+        L.pkv_static_scratch_bytes.argtypes = []
+        L.paged_decode_attention_static.restype = i32
+        L.paged_decode_attention_static.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp,
+                                                    ctypes.c_float, vp, vp]
         L.pkv_status_string.restype = ctypes.c_char_p
         L.pkv_status_string.argtypes = [i32]
         L.pkv_last_hip_error_string.restype = ctypes.c_char_p
@@ -214,6 +219,20 @@ def init():
     """Once-per-device set-up of the library for the current device (optional: the first call of
     an entry point does its own)."""
     _check(lib().pkv_init(), "pkv_init")
+
+
+def paged_decode_attention_static(q, k_pool, v_pool, block_tables, context_lens, scale, out, *,
+                                  max_context_len: int, partition_tokens: int = 0,
+                                  desc: Optional[AttnDesc] = None, stream=None, flags: int = 0):
+    """paged_decode_attention with the library's static device scratch instead of a workspace:
+    no tensor is allocated here or in the library."""
+    if desc is None:
+        desc = attn_desc_for(q, k_pool, v_pool, block_tables, max_context_len=max_context_len,
+                             partition_tokens=partition_tokens, out_dtype=out.dtype, flags=flags)
+    st = lib().paged_decode_attention_static(
+        ctypes.byref(desc), q.data_ptr(), k_pool.data_ptr(), v_pool.data_ptr(), block_tables.data_ptr(),
+        context_lens.data_ptr(), float(scale), out.data_ptr(), _stream_ptr(stream))
+    _check(st, "paged_decode_attention_static")
 
 
 def swap_desc(num_planes: int, block_bytes: int, src_num_blocks: int, dst_num_blocks: int,

@@ -94,6 +94,7 @@ int32_t pkv_init(void) {
   (void)num_cus();
   if ((e = prepare_attn_stream()) != hipSuccess) return hip_status(e);
   if ((e = prepare_attn_prefill()) != hipSuccess) return hip_status(e);
+  if ((e = prepare_static_scratch()) != hipSuccess) return hip_status(e);
   return PKV_OK;
 }
 

@@ -13,7 +13,8 @@ constexpr int kDefaultPartition = 512;   // split-K partition length in tokens
 constexpr int kAttnThreads = 256;        // 4 wavefronts per workgroup
 constexpr int kStreamMaxPrefixBytes = 8192;   // LDS for per-sequence tile prefix sums
 
-// Per-device bookkeeping (kernel attributes set, CU counts) is kept in small tables indexed by the HIP device id; for ids outside the table (-1)
+// Per-device bookkeeping (kernel attributes set, CU counts, the address of the static scratch
+// array) is kept in small tables indexed by the HIP device id; for ids outside the table (-1)
 // nothing is remembered and the question is asked again at every call.
 constexpr int kMaxDevices = 16;
 inline int device_slot() {
@@ -25,6 +26,7 @@ inline int device_slot() {
 // once-per-device set-up of the kernels that need it; also run by pkv_init()
 hipError_t prepare_attn_stream();    // attn_stream_mfma.hip
 hipError_t prepare_attn_prefill();   // attn_prefill_mfma.hip
+hipError_t prepare_static_scratch(); // attn_static.hip
 
 int num_cus();   // CUs of the current device (256 when there is none), attn_stream_mfma.hip
 
