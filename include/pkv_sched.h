@@ -31,7 +31,12 @@
  *      ceil(tokens/block_size) blocks for the tokens it has to prefill
  *      (prompt, plus generated-1 after a recomputation), within the token
  *      budget and the limit on running requests, and leaving
- *      watermark_blocks free; the first one that does not fit ends admission;
+ *      watermark_blocks free; the first one that does not fit ends admission.
+ *      Without chunked prefill a prefill is atomic (the paper's section
+ *      "Effects of Chunked Prefill"): a recomputation that has outgrown the
+ *      budget of a whole iteration is neither split nor dropped, it is
+ *      admitted as the only prefill of an iteration (else it would block the
+ *      head of the queue for ever);
  *   3. every request that was running before step 2 decodes one token: its
  *      cached length grows by one (that is the context length of the
  *      attention call, which counts the token being decoded) and it finishes
@@ -114,9 +119,11 @@ void pkv_sched_destroy(pkv_sched* s);
 /*
  * Append a request to the back of the waiting queue.  PKV_ERR_SHAPE if
  * prompt_len < 1, max_new_tokens < 1, the prompt exceeds the token budget
- * (without chunked prefill), or
- * the request at full length would not fit max_blocks_per_seq or the whole
- * pool (it could never run); PKV_ERR_INDEX if request_id is already known.
+ * (without chunked prefill), or the request at full length
+ * (prompt_len + max_new_tokens - 1 tokens) would not fit max_blocks_per_seq,
+ * or its blocks plus watermark_blocks would not fit the pool (evicted at that
+ * length it could never be admitted again and would block the queue for
+ * ever); PKV_ERR_INDEX if request_id is already known.
  */
 int32_t pkv_sched_add_request(pkv_sched* s, int64_t request_id, int32_t prompt_len,
                               int32_t max_new_tokens);

@@ -48,8 +48,9 @@ class RefScheduler:
 
     def add_request(self, rid, prompt, max_new):
         full = -(-(prompt + max_new - 1) // self.bs)      # blocks at full length
+        # a request evicted at its full length returns only if its blocks fit beside the watermark
         if prompt < 1 or max_new < 1 or (prompt > self.budget and not self.chunked) \
-                or full > self.max_blocks or full > self.num_gpu_blocks:
+                or full > self.max_blocks or full + self.watermark > self.num_gpu_blocks:
             raise ValueError("request can never run")
         if rid in self.known:
             raise KeyError(rid)
@@ -126,12 +127,17 @@ class RefScheduler:
                     continue
                 tokens = r.prompt if r.generated == 0 else r.prompt + r.generated - 1
                 nb = -(-tokens // self.bs)
-                if tokens > budget or len(self.free_gpu) < nb + self.watermark:
+                # Sec. "Effects of Chunked Prefill": without chunking a prefill is atomic.  A
+                # re-prefill that exceeds the budget of a whole iteration is not split and not
+                # dropped: it is the only prefill of its iteration.
+                oversized = r.generated > 0 and tokens > self.budget
+                fits_budget = (budget == self.budget) if oversized else (tokens <= budget)
+                if not fits_budget or len(self.free_gpu) < nb + self.watermark:
                     out["head_blocked"] = True
                     break
                 r.blocks = [self.free_gpu.pop(0) for _ in range(nb)]
                 r.computed = tokens
-                budget -= tokens
+                budget = 0 if oversized else budget - tokens
                 if r.generated == 0:
                     r.generated = 1                      # the prefill yields the first token
                 else:

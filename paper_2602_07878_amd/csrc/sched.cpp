@@ -154,7 +154,12 @@ struct pkv_sched {
         // all of it or nothing without chunked prefill; else what the budget allows
         const int32_t tokens = chunked ? std::min(total, budget) : total;
         const size_t nb = (size_t)((tokens + bs - 1) / bs);
-        if (tokens > budget || tokens == 0 || free_gpu.size() < nb + (size_t)cfg.watermark_blocks) {
+        // An unchunked prefill is atomic: it is neither split nor dropped.  A recomputation that
+        // has outgrown the whole budget (prompt + generated - 1 tokens) therefore runs as the
+        // only prefill of an iteration; everything else has to fit what the budget has left.
+        const bool alone = !chunked && r->generated > 0 && tokens > cfg.max_num_batched_tokens &&
+                           budget == cfg.max_num_batched_tokens;
+        if ((tokens > budget && !alone) || tokens == 0 || free_gpu.size() < nb + (size_t)cfg.watermark_blocks) {
           head_blocked = true;
           break;
         }
@@ -163,7 +168,7 @@ struct pkv_sched {
         r->computed = tokens;
         r->chunk = 0;
         r->prefilling = tokens < total;
-        budget -= tokens;
+        budget = alone ? 0 : budget - tokens;
         n_prefill_tokens += tokens;
         if (r->generated > 0) totals[4] += tokens;
         else if (!r->prefilling) r->generated = 1;   // the (last chunk of the) prefill yields the first token
@@ -287,7 +292,9 @@ int32_t pkv_sched_add_request(pkv_sched* s, int64_t request_id, int32_t prompt_l
       (prompt_len > s->cfg.max_num_batched_tokens && !s->cfg.chunked_prefill))
     return PKV_ERR_SHAPE;
   const int64_t full = ((int64_t)prompt_len + max_new_tokens - 1 + s->cfg.block_size - 1) / s->cfg.block_size;
-  if (full > s->cfg.max_blocks_per_seq || full > s->cfg.num_gpu_blocks) return PKV_ERR_SHAPE;
+  // a victim evicted at full length must be able to return: its blocks plus the watermark
+  if (full > s->cfg.max_blocks_per_seq || full + s->cfg.watermark_blocks > s->cfg.num_gpu_blocks)
+    return PKV_ERR_SHAPE;
   if (s->requests.count(request_id)) return PKV_ERR_INDEX;
   auto r = std::make_unique<Request>();
   r->id = request_id;

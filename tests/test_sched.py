@@ -118,6 +118,125 @@ def test_requests_that_can_never_run_are_refused():
         s.add_request(1, 2, 2)
 
 
+def test_hand_worked_trace_recomputation_larger_than_the_budget_runs_alone():
+    """Without chunking a prefill is atomic.  A victim whose prompt + generated - 1 tokens exceed
+    the budget of a whole iteration must still come back (it sits at the head of the queue and
+    would otherwise block it for ever): it is prefilled as the only prefill of an iteration."""
+    s = ref(max_num_batched_tokens=2)  # 4 blocks of 2 tokens, recompute mode, budget = one prompt
+    s.add_request(1, 2, 6)
+    s.add_request(2, 2, 5)
+    o = s.step()                       # request 1 uses the whole budget; request 2 waits for the next iteration
+    assert o["prefill"] == [(1, 2)] and o["head_blocked"] and o["free_blocks"] == 3
+    o = s.step()                       # 1 grows into block 1; 2 is prefilled into block 2
+    assert o["prefill"] == [(2, 2)] and o["decode"] == [(1, 3, [0, 1])] and o["free_blocks"] == 1
+    o = s.step()                       # 2 grows into block 3: the pool is full
+    assert o["decode"] == [(1, 4, [0, 1]), (2, 3, [2, 3])] and o["free_blocks"] == 0
+    o = s.step()                       # 1 needs a third block: the last scheduled request (2) is evicted
+    assert o["preempted"] == [2] and o["decode"] == [(1, 5, [0, 1, 2])] and o["free_blocks"] == 1
+    o = s.step()                       # 2 has 2 output tokens: 2 + 2 - 1 = 3 tokens = 2 blocks, only 1 free
+    assert o["head_blocked"] and o["prefill"] == [] and o["decode"] == [(1, 6, [0, 1, 2])]
+    s.add_request(3, 2, 2)             # a newcomer queues behind the victim
+    o = s.step()                       # 1 takes the last block and ends with its sixth token
+    assert o["decode"] == [(1, 7, [0, 1, 2, 3])] and o["finished"] == [1] and o["free_blocks"] == 4
+    o = s.step()                       # 3 tokens > budget 2: admitted alone; 3 would fit the pool but waits
+    assert o["prefill"] == [(2, 3)] and o["head_blocked"] and o["free_blocks"] == 2
+    assert [r.rid for r in s.waiting] == [3] and s.totals["recomputed"] == 3
+    o = s.step()                       # 2 decodes where it stopped (context 4); 3 is prefilled
+    assert o["decode"] == [(2, 4, [0, 1])] and o["prefill"] == [(3, 2)]
+    for _ in range(3):
+        o = s.step()
+    assert s.totals["finished"] == 3 and not s.running and not s.waiting
+    assert s.totals["decoded"] == 5 + 4 + 1
+
+
+def test_a_request_that_could_not_return_beside_the_watermark_is_refused():
+    """Evicted at full length a request needs all its blocks plus the watermark to be admitted
+    again; if the pool cannot give that, it would block the head of the queue for ever."""
+    kw = dict(num_gpu_blocks=8, block_size=16, max_num_batched_tokens=128, watermark_blocks=2)
+    s = ref(**kw)
+    with pytest.raises(ValueError):
+        s.add_request(1, 120, 1)       # 8 blocks + 2 > 8
+    with pytest.raises(ValueError):
+        s.add_request(1, 90, 8)        # 97 tokens at full length: 7 blocks + 2 > 8
+    s.add_request(1, 96, 1)            # 6 blocks + 2 = 8: runs at once
+    o = s.step()
+    assert o["prefill"] == [(1, 96)] and o["finished"] == [1] and not o["head_blocked"]
+    L = sched.Scheduler(mode=RECOMPUTE, num_cpu_blocks=0, max_num_seqs=8, max_blocks_per_seq=8, **kw)
+    with pytest.raises(binding.PkvError):
+        L.add_request(1, 120, 1)
+    with pytest.raises(binding.PkvError):
+        L.add_request(1, 90, 8)
+    L.add_request(1, 96, 1)
+    assert L.step().num_finished == 1
+
+
+@pytest.mark.parametrize("mode,budget,chunked", [(RECOMPUTE, 256, False), (SWAP, 256, False), (RECOMPUTE, 64, True)])
+def test_liveness_an_idle_engine_always_admits_the_head(mode, budget, chunked):
+    """Whatever the load did before: when nothing runs and the whole pool is free, the request
+    at the head of the queue is admitted in that iteration, and every request finishes."""
+    total = 48
+    s = ref(num_gpu_blocks=total, num_cpu_blocks=8, block_size=16, max_num_seqs=12, max_num_batched_tokens=budget,
+            max_blocks_per_seq=40, watermark_blocks=2, mode=mode, chunked=chunked)
+    stream = W.poisson_request_stream(21, 300, 0.3, prompt_median=100, out_median=150, max_prompt=256, max_new=380)
+    submitted, oversized, steps = 0, 0, 0
+    while steps < len(stream) or ((s.running or s.waiting) and steps < 60000):
+        arrivals = stream[steps] if steps < len(stream) else []
+        steps += 1
+        for rid, p, n in arrivals:
+            s.add_request(rid, p, n)
+            submitted += 1
+        idle = not s.running and len(s.free_gpu) == total and bool(s.waiting)
+        o = s.step()
+        if idle:
+            assert o["prefill"] or o["swap_in"], "idle engine left the head of the queue waiting"
+        if not chunked:
+            oversized += sum(1 for _, t in o["prefill"] if t > budget)
+    assert s.totals["finished"] == submitted and not s.running and not s.waiting
+    assert s.totals["preemptions"] > 0
+    if mode == RECOMPUTE and not chunked:
+        assert oversized > 0           # the load did produce recomputations beyond the budget
+
+
+# ---- properties the paper states, over seeded loads ------------------------------------------
+@pytest.mark.parametrize("mode", [SWAP, RECOMPUTE])
+@pytest.mark.parametrize("seed", [31, 32, 33])
+def test_paper_properties_persistent_blocks_victim_first_and_recompute_length(mode, seed):
+    """Sec. 5.1.1: a running request keeps its blocks until it finishes, so between finishes and
+    preemptions the number of free blocks never rises.  Sec. 5.1.2: the victim goes to the front
+    of the waiting queue, so no request that has never run is admitted while a victim waits; a
+    recomputed request re-processes its prompt and all previously generated tokens (all but the
+    newest, whose K/V the next decode step writes)."""
+    s = ref(num_gpu_blocks=64, num_cpu_blocks=24, block_size=16, max_num_seqs=16, max_num_batched_tokens=2048,
+            max_blocks_per_seq=40, mode=mode)
+    stream = W.poisson_request_stream(seed, 400, 0.25, prompt_median=96, out_median=120, max_prompt=256, max_new=300)
+    prompts, decoded, ran_before, victims_waiting = {}, {}, set(), set()
+    free_before, steps = 64, 0
+    while steps < len(stream) or ((s.running or s.waiting) and steps < 60000):
+        arrivals = stream[steps] if steps < len(stream) else []
+        steps += 1
+        for rid, p, n in arrivals:
+            s.add_request(rid, p, n)
+            prompts[rid] = p
+        o = s.step()
+        if not o["finished"] and not o["preempted"]:
+            assert o["free_blocks"] <= free_before
+        free_before = o["free_blocks"]
+        for rid, tokens in o["prefill"]:
+            if rid in ran_before:      # a recomputation
+                assert tokens == prompts[rid] + (1 + decoded.get(rid, 0)) - 1
+            victims_waiting.discard(rid)
+        back = {r.rid for r in s.running}
+        victims_waiting -= back
+        newcomers = [rid for rid, _ in o["prefill"] if rid not in ran_before]
+        if newcomers:
+            assert not victims_waiting, "a newcomer was admitted while a victim was waiting"
+        ran_before |= {rid for rid, _ in o["prefill"]}
+        for rid, _, _ in o["decode"]:
+            decoded[rid] = decoded.get(rid, 0) + 1
+        victims_waiting |= set(o["preempted"])
+    assert s.totals["preemptions"] > 0 and s.totals["finished"] == len(prompts)
+
+
 # ---- chunked prefill (the paper's section "Effects of Chunked Prefill") ---------------------------
 def test_chunked_hand_worked_trace_long_prompt_in_chunks_beside_a_decoding_request():
     s = ref(num_gpu_blocks=8, block_size=4, max_num_seqs=4, max_num_batched_tokens=8, chunked=True)
@@ -308,7 +427,8 @@ def test_create_rejects_bad_configurations_and_getters_check_capacity():
 
 @pytest.mark.parametrize("mode,seed,cpu_blocks,chunked,budget", [
     (SWAP, 11, 64, False, 1024), (RECOMPUTE, 12, 0, False, 1024), (SWAP, 13, 6, False, 1024),
-    (SWAP, 14, 64, True, 128), (RECOMPUTE, 15, 0, True, 96), (SWAP, 16, 6, True, 64)])
+    (SWAP, 14, 64, True, 128), (RECOMPUTE, 15, 0, True, 96), (SWAP, 16, 6, True, 64),
+    (RECOMPUTE, 17, 0, False, 400), (SWAP, 18, 6, False, 400)])   # recomputations beyond the budget
 def test_library_reproduces_the_reference_trace_exactly(mode, seed, cpu_blocks, chunked, budget):
     kw = dict(num_gpu_blocks=96, num_cpu_blocks=cpu_blocks, block_size=16, max_num_seqs=24,
               max_num_batched_tokens=budget, max_blocks_per_seq=40, watermark_blocks=1, chunked=chunked)
@@ -316,6 +436,7 @@ def test_library_reproduces_the_reference_trace_exactly(mode, seed, cpu_blocks, 
     s = sched.Scheduler(mode=mode, **kw)
     stream = W.poisson_request_stream(seed, 300, 0.3, prompt_median=120, out_median=100, max_prompt=400, max_new=200)
     stream += [[] for _ in range(2500)]
+    oversized = 0
     for arrivals in stream:
         for rid, p, n in arrivals:
             r.add_request(rid, p, n)
@@ -333,6 +454,7 @@ def test_library_reproduces_the_reference_trace_exactly(mode, seed, cpu_blocks, 
         else:
             assert list(zip(pid.tolist(), ptok.tolist())) == o["prefill"]
             assert s.prefill_contexts().tolist() == ptok.tolist()
+            oversized += sum(1 for t in ptok.tolist() if t > budget)
         for q in r.running:
             assert s.request_blocks(q.rid).tolist() == q.blocks
         for q in r.waiting[:3]:
@@ -341,3 +463,5 @@ def test_library_reproduces_the_reference_trace_exactly(mode, seed, cpu_blocks, 
         assert (info.free_blocks, info.running, info.waiting, info.swapped, info.head_blocked, info.num_preempted) == \
                (o["free_blocks"], o["running"], o["waiting"], o["swapped"], int(o["head_blocked"]), len(o["preempted"]))
     assert s.totals() == r.totals and r.totals["preemptions"] > 0 and r.totals["finished"] > 0
+    if budget == 400 and mode == RECOMPUTE:
+        assert oversized > 0           # the trace covers recomputations beyond the budget
