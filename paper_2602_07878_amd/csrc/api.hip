@@ -130,13 +130,12 @@ size_t pkv_attn_workspace_bytes(const pkv_attn_desc* desc) {
 
 }  // extern "C"
 
-int32_t pkv::status_of(hipError_t e) { return hip_status(e); }
-
 // The decode-attention call behind every entry point that has it: checks, then launches.
 int32_t pkv::attention_call(const pkv_attn_desc* desc, const void* q, const void* k_pool,
                             const void* v_pool, const int32_t* block_tables,
                             const int32_t* context_lens, float scale, void* out, void* workspace,
-                            size_t workspace_bytes, void* hip_stream, void* ev_begin, void* ev_end) {
+                            size_t workspace_bytes, void* hip_stream, void* ev_begin, void* ev_end,
+                            bool static_scratch) {
   const int32_t st = check_attn_desc(desc);
   if (st != PKV_OK) return st;
   if (desc->batch == 0) return PKV_OK;
@@ -147,7 +146,17 @@ int32_t pkv::attention_call(const pkv_attn_desc* desc, const void* q, const void
     return PKV_ERR_ALIGN;
   if (!std::isfinite(scale)) return PKV_ERR_SHAPE;
   const size_t need = pkv_attn_workspace_bytes(desc);
-  if (need > 0 && (!workspace || workspace_bytes < need)) return PKV_ERR_WORKSPACE;
+  if (static_scratch) {
+    // the library's own array takes the place of the caller's workspace; its device address is
+    // asked for only now, after every check that needs no device
+    if (need > static_scratch_bytes()) return PKV_ERR_WORKSPACE;
+    if (need > 0) {
+      const hipError_t e = static_scratch_address(&workspace);
+      if (e != hipSuccess) return hip_status(e);
+    }
+  } else if (need > 0 && (!workspace || workspace_bytes < need)) {
+    return PKV_ERR_WORKSPACE;
+  }
 
   const int eb = elem_bytes(desc->kv_dtype);
   AttnParams p;
@@ -204,7 +213,7 @@ int32_t paged_decode_attention(const pkv_attn_desc* desc, const void* q, const v
                                const int32_t* context_lens, float scale, void* out,
                                void* workspace, size_t workspace_bytes, void* hip_stream) {
   return attention_call(desc, q, k_pool, v_pool, block_tables, context_lens, scale, out, workspace,
-                        workspace_bytes, hip_stream, nullptr, nullptr);
+                        workspace_bytes, hip_stream, nullptr, nullptr, false);
 }
 
 int32_t paged_decode_attention_timed(const pkv_attn_desc* desc, const void* q, const void* k_pool,
@@ -213,7 +222,7 @@ int32_t paged_decode_attention_timed(const pkv_attn_desc* desc, const void* q, c
                                      void* workspace, size_t workspace_bytes, void* hip_stream,
                                      void* ev_kernel_begin, void* ev_kernel_end) {
   return attention_call(desc, q, k_pool, v_pool, block_tables, context_lens, scale, out, workspace,
-                        workspace_bytes, hip_stream, ev_kernel_begin, ev_kernel_end);
+                        workspace_bytes, hip_stream, ev_kernel_begin, ev_kernel_end, false);
 }
 
 size_t pkv_prefill_workspace_bytes(const pkv_attn_desc* desc, int64_t total_query_tokens,

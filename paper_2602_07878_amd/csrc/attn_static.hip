@@ -47,6 +47,8 @@ hipError_t prepare_static_scratch() {
   void* ptr = nullptr;
   return scratch_on_current_device(&ptr);
 }
+size_t static_scratch_bytes() { return kScratchBytes; }
+hipError_t static_scratch_address(void** ptr) { return scratch_on_current_device(ptr); }
 }  // namespace pkv
 
 extern "C" {
@@ -57,16 +59,8 @@ int32_t paged_decode_attention_static(const pkv_attn_desc* desc, const void* q, 
                                       const void* v_pool, const int32_t* block_tables,
                                       const int32_t* context_lens, float scale, void* out,
                                       void* hip_stream) {
-  // an invalid descriptor sizes to 0 and is reported by the checks of the call itself
-  const size_t need = pkv_attn_workspace_bytes(desc);
-  if (need > kScratchBytes) return PKV_ERR_WORKSPACE;
-  void* ptr = nullptr;
-  if (need > 0) {
-    const hipError_t e = scratch_on_current_device(&ptr);
-    if (e != hipSuccess) return pkv::status_of(e);
-  }
-  return pkv::attention_call(desc, q, k_pool, v_pool, block_tables, context_lens, scale, out, ptr,
-                             need > 0 ? kScratchBytes : 0, hip_stream, nullptr, nullptr);
+  return pkv::attention_call(desc, q, k_pool, v_pool, block_tables, context_lens, scale, out, nullptr, 0,
+                             hip_stream, nullptr, nullptr, /*static_scratch=*/true);
 }
 
 }  // extern "C"

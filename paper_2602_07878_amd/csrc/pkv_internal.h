@@ -75,11 +75,15 @@ struct SwapParams {
 };
 
 // api.hip: checks and launch of the decode-attention call (every entry point that offers it ends
-// here); PKV_OK or PKV_ERR_HIP for a runtime result, remembering the error text for the thread
+// here).  static_scratch: the partials go to the library's static device array (attn_static.hip)
+// and `workspace` is ignored.
 int32_t attention_call(const pkv_attn_desc* desc, const void* q, const void* k_pool, const void* v_pool,
                        const int32_t* block_tables, const int32_t* context_lens, float scale, void* out,
-                       void* workspace, size_t workspace_bytes, void* hip_stream, void* ev_begin, void* ev_end);
-int32_t status_of(hipError_t e);
+                       void* workspace, size_t workspace_bytes, void* hip_stream, void* ev_begin, void* ev_end,
+                       bool static_scratch);
+// attn_static.hip: size of the static scratch array, and its device address on the current device
+size_t static_scratch_bytes();
+hipError_t static_scratch_address(void** ptr);
 // attn_decode.hip
 hipError_t launch_attn_decode(const AttnParams& p, int dtype, hipStream_t s);
 // attn_stream_mfma.hip
