@@ -328,12 +328,14 @@ int32_t kv_block_swap(const pkv_swap_desc* desc, const void* src_pool,
  * kv_swap_out_host: for every plane p and pair j < n_pairs, pool block
  * s_j = block_mapping[2j] goes to host slot j:
  *   host_dst + p*desc->dst_plane_stride_bytes + j*block_bytes
- * (block_mapping[2j+1] must equal j: the victims' blocks are stored back to
- * back in swap order; desc->src_* describe the pool, desc->dst_* the host
- * buffer, dst_num_blocks >= n_pairs).
- * kv_swap_in_host: the reverse: host slot j (block_mapping[2j] must equal j) of
- * host_src goes to pool block block_mapping[2j+1] (desc->src_* describe the host
- * buffer, desc->dst_* the pool).
+ * (the victims' blocks are stored back to back in swap order: the host slot of
+ * pair j is j by definition; block_mapping[2j+1], where callers normally write
+ * j, is NOT read, so no value there can send a block outside the host buffer;
+ * desc->src_* describe the pool, desc->dst_* the host buffer,
+ * dst_num_blocks >= n_pairs).
+ * kv_swap_in_host: the reverse: host slot j of host_src goes to pool block
+ * block_mapping[2j+1]; block_mapping[2j] is not read (desc->src_* describe the
+ * host buffer, desc->dst_* the pool).
  *
  * host_dst / host_src is page-locked HOST memory, everything else is device
  * memory.  The swap moves in pieces through `staging`, a device buffer of

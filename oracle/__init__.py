@@ -204,18 +204,26 @@ def paged_prefill_attention(q, k_pool, v_pool, block_tables, context_lens, query
     Query token j of sequence i sits at position context_lens[i] - query_lens[i] + j and sees
     positions 0..that, which is exactly the decode definition with that many tokens: the
     function is written as one decode-oracle row per query token.  Returns float64 [sum, Hq, D].
+
+    A query length above the context length is clipped, by the rule the library's header gives for
+    this call and for kv_append_chunk: only the first min(query_lens[i], context_lens[i]) rows of
+    sequence i exist (row j at position j then); the surplus rows have no definition and come back
+    as NaN.
     """
     cl = np.ascontiguousarray(context_lens, dtype=np.int64)
     ql = np.ascontiguousarray(query_lens, dtype=np.int64)
     bt = np.ascontiguousarray(block_tables, dtype=np.int32)
-    assert cl.shape == ql.shape and np.all(ql >= 0) and np.all(ql <= cl)
+    assert cl.shape == ql.shape and np.all(ql >= 0) and np.all(cl >= 0)
     q = np.ascontiguousarray(q)
     assert q.shape[0] == int(ql.sum())
+    live = np.minimum(ql, cl)                                          # rows of a sequence that exist
     rows_seq = np.repeat(np.arange(len(ql)), ql)                       # sequence of every query row
     first = np.cumsum(ql) - ql                                         # first packed row of a sequence
     j = np.arange(int(ql.sum())) - first[rows_seq]                     # index inside its sequence
-    ctx = (cl[rows_seq] - ql[rows_seq] + j + 1).astype(np.int32)       # tokens that row may see
-    if q.shape[0] == 0:
-        return np.zeros(q.shape, np.float64)
-    return paged_decode_attention(q, k_pool, v_pool, bt[rows_seq], ctx, scale, block_size=block_size,
-                                  k_strides=k_strides, v_strides=v_strides)
+    ctx = (cl[rows_seq] - live[rows_seq] + j + 1).astype(np.int32)     # tokens that row may see
+    out = np.full(q.shape, np.nan, np.float64)
+    keep = j < live[rows_seq]
+    if keep.any():
+        out[keep] = paged_decode_attention(q[keep], k_pool, v_pool, bt[rows_seq[keep]], ctx[keep], scale,
+                                           block_size=block_size, k_strides=k_strides, v_strides=v_strides)
+    return out

@@ -375,8 +375,8 @@ int32_t kv_block_swap(const pkv_swap_desc* desc, const void* src_pool, void* dst
   p.dst_plane_stride = desc->dst_plane_stride_bytes;
   p.num_planes = desc->num_planes;
   p.n_pairs = n_pairs;
-  p.src_index_offset = 0;
-  p.dst_index_offset = 0;
+  p.src_slot_is_pair = 0;
+  p.dst_slot_is_pair = 0;
   const hipError_t e = launch_swap(p, static_cast<hipStream_t>(hip_stream));
   return hip_status(e);
 }

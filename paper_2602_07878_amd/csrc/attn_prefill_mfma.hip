@@ -611,6 +611,19 @@ __global__ __launch_bounds__(256) void attn_prefill_merge(const AttnParams p) {
   const int64_t item = (int64_t)blockIdx.x * (256 / kWaveSize) + threadIdx.x / kWaveSize;   // row * Hq + head
   const int64_t rows = p.cu_query_lens[p.batch];
   if (item >= rows * p.num_q_heads) return;
+  {
+    // Rows beyond min(query_lens, context_lens) of their sequence do not exist for the walk (a
+    // query length above the context is clipped): nothing was written for them, and as in the
+    // unsplit call their output rows are left alone.  The row's sequence is the last one whose
+    // first row is not behind it.
+    const int row = (int)(item / p.num_q_heads);
+    int lo = 0, hi = p.batch;
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (p.cu_query_lens[mid] <= row) lo = mid; else hi = mid;
+    }
+    if (row - p.cu_query_lens[lo] >= min(p.query_lens[lo], p.context_lens[lo])) return;   // wave-uniform
+  }
   const float* ml = p.ws_ml + item * nsplit * 2;
   float mx = kNoMaximum;
   for (int s = 0; s < nsplit; ++s)

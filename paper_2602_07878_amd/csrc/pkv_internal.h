@@ -69,9 +69,9 @@ struct SwapParams {
   const int32_t* mapping;  // [n_pairs][2]
   int64_t block_bytes, src_plane_stride, dst_plane_stride;
   int32_t num_planes, n_pairs;
-  // subtracted from the mapping's block ids: lets a window of a longer mapping address a
-  // buffer that holds only that window (the host leg moves a swap in pieces)
-  int32_t src_index_offset, dst_index_offset;
+  // The host leg moves a swap in pieces through a buffer that holds only the piece: on that side
+  // pair j of the (windowed) mapping uses slot j of the buffer, whatever the mapping's column says.
+  int32_t src_slot_is_pair, dst_slot_is_pair;
 };
 
 // api.hip: checks and launch of the decode-attention call (every entry point that offers it ends

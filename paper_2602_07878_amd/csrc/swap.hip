@@ -56,8 +56,8 @@ __global__ __launch_bounds__(kCopyThreads) void swap_blocks(const SwapParams p) 
     // plane-major order: consecutive chunks are consecutive pairs of one plane
     const int plane = (int)(cc / p.n_pairs);
     const int pair = (int)(cc % p.n_pairs);
-    const int64_t sb = __builtin_amdgcn_readfirstlane(p.mapping[2 * pair]) - p.src_index_offset;
-    const int64_t db = __builtin_amdgcn_readfirstlane(p.mapping[2 * pair + 1]) - p.dst_index_offset;
+    const int64_t sb = p.src_slot_is_pair ? pair : __builtin_amdgcn_readfirstlane(p.mapping[2 * pair]);
+    const int64_t db = p.dst_slot_is_pair ? pair : __builtin_amdgcn_readfirstlane(p.mapping[2 * pair + 1]);
     const u32x4* s = reinterpret_cast<const u32x4*>(p.src + plane * p.src_plane_stride +
                                                     sb * p.block_bytes);
     u32x4* d = reinterpret_cast<u32x4*>(p.dst + plane * p.dst_plane_stride + db * p.block_bytes);

@@ -58,7 +58,10 @@ hipError_t swap_out_host(const pkv_swap_desc& d, const uint8_t* pool, uint8_t* h
   p.src_plane_stride = d.src_plane_stride_bytes;
   p.block_bytes = d.block_bytes;
   p.dst = staging;
-  p.src_index_offset = 0;
+  // the host slot of pair j is j (the mapping's second column is not read); in the staging
+  // buffer, which holds one piece, that is the pair's index within the piece
+  p.src_slot_is_pair = 0;
+  p.dst_slot_is_pair = 1;
   if (pc.planes_per_piece > 0) {
     const int64_t pp = pc.planes_per_piece, plane_bytes = (int64_t)n_pairs * d.block_bytes;
     for (int64_t first = 0; first < d.num_planes; first += pp) {
@@ -68,7 +71,6 @@ hipError_t swap_out_host(const pkv_swap_desc& d, const uint8_t* pool, uint8_t* h
       p.dst_plane_stride = plane_bytes;
       p.num_planes = npl;
       p.n_pairs = n_pairs;
-      p.dst_index_offset = 0;
       PKV_TRY(launch_swap(p, stream));
       PKV_TRY(hipMemcpyAsync(host_dst + first * plane_bytes, staging, (size_t)npl * plane_bytes, hipMemcpyDeviceToHost,
                              stream));
@@ -83,7 +85,6 @@ hipError_t swap_out_host(const pkv_swap_desc& d, const uint8_t* pool, uint8_t* h
     p.dst_plane_stride = cp * d.block_bytes;
     p.num_planes = d.num_planes;
     p.n_pairs = np;
-    p.dst_index_offset = (int32_t)first;   // host slot j sits at j - first in the piece
     PKV_TRY(launch_swap(p, stream));
     PKV_TRY(hipMemcpy2DAsync(host_dst + first * d.block_bytes, (size_t)d.dst_plane_stride_bytes, staging,
                              (size_t)(cp * d.block_bytes), (size_t)np * d.block_bytes, (size_t)d.num_planes,
@@ -101,7 +102,8 @@ hipError_t swap_in_host(const pkv_swap_desc& d, const uint8_t* host_src, uint8_t
   p.dst_plane_stride = d.dst_plane_stride_bytes;
   p.block_bytes = d.block_bytes;
   p.src = staging;
-  p.dst_index_offset = 0;
+  p.src_slot_is_pair = 1;   // host slot of pair j is j: the mapping's first column is not read
+  p.dst_slot_is_pair = 0;
   if (pc.planes_per_piece > 0) {
     const int64_t pp = pc.planes_per_piece, plane_bytes = (int64_t)n_pairs * d.block_bytes;
     for (int64_t first = 0; first < d.num_planes; first += pp) {
@@ -113,7 +115,6 @@ hipError_t swap_in_host(const pkv_swap_desc& d, const uint8_t* host_src, uint8_t
       p.src_plane_stride = plane_bytes;
       p.num_planes = npl;
       p.n_pairs = n_pairs;
-      p.src_index_offset = 0;
       PKV_TRY(launch_swap(p, stream));
     }
     return hipSuccess;
@@ -129,7 +130,6 @@ hipError_t swap_in_host(const pkv_swap_desc& d, const uint8_t* host_src, uint8_t
     p.src_plane_stride = cp * d.block_bytes;
     p.num_planes = d.num_planes;
     p.n_pairs = np;
-    p.src_index_offset = (int32_t)first;
     PKV_TRY(launch_swap(p, stream));
   }
   return hipSuccess;

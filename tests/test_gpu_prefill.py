@@ -58,7 +58,9 @@ def run_prefill(w, query_lens, seed, out_dtype=None, token_major=False, split=Fa
 def check(w, query_lens, seed=5, **kw):
     got, ref = run_prefill(w, query_lens, seed, **kw)
     assert np.all(np.isfinite(got)), "non-finite output (poison leaked?)"
-    err = np.abs(got - ref).max() if got.size else 0.0
+    absent = np.isnan(ref)               # rows beyond a clipped query length: left as they were
+    assert np.all(got[absent] == 777.0), "a row that does not exist was written"
+    err = np.abs(got[~absent] - ref[~absent]).max() if got[~absent].size else 0.0
     print(f"{w.name}: Hq={w.Hq} Hkv={w.Hkv} bs={w.block_size} ctx={list(w.context_lens)[:6]} q={list(query_lens)[:6]} "
           f"max_abs_err={err:.3e}", flush=True)
     assert err <= TOL, err
@@ -141,6 +143,83 @@ def test_split_walks_bf16_output_and_small_workspace_is_refused():
     # enough workgroups anyway: no workspace wanted
     desc.batch = 64
     assert binding.prefill_workspace_bytes(desc, 64 * 200, 200) == 0
+
+
+def test_query_lens_above_the_context_are_clipped_and_surplus_rows_left_alone():
+    """query_lens[i] > context_lens[i]: only the first context_lens[i] rows of the sequence exist
+    (row j at position j); the others keep what the output buffer held, with and without split
+    walks (whose merge kernel must not touch them either)."""
+    lens = (100, 40, 700, 0, 16)
+    check(mk(91, lens), (130, 40, 50, 3, 17))
+    w = mk(92, (3000, 20, 600))
+    check(w, (300, 64, 700), split=True)
+
+
+def sampled_rows_check(w, q_bits, ql, out, rows):
+    """Rows `rows` of the packed output against one oracle decode row each (a query token is the
+    decode definition over the positions it may see)."""
+    import oracle
+    cu = np.concatenate([[0], np.cumsum(ql)])
+    seq = np.searchsorted(cu, rows, side="right") - 1
+    ctx = (w.context_lens[seq] - ql[seq] + (rows - cu[seq]) + 1).astype(np.int32)
+    ref = oracle.paged_decode_attention(q_bits[rows], w.k_pool, w.v_pool, w.block_tables[seq], ctx, w.scale,
+                                        block_size=w.block_size)
+    got = out[rows].astype(np.float64)
+    assert np.all(np.isfinite(got))
+    return float(np.abs(got - ref).max())
+
+
+def test_parity_at_the_benchmarked_reprefill_shape():
+    """16 sequences x 4096 tokens, 32/8 heads: 128 K/V streams (16 per XCD), 32 query groups per
+    stream, the workgroup numbering at the sizes the benchmark times.  More than 512 query rows
+    (all heads of each) are checked: for every sequence the first and last rows, both ends of
+    wavefronts and of 128-row query groups in the first, a middle and the last group, and random
+    rows."""
+    import torch
+    from paper_2602_07878_amd import binding
+    B, n = 16, 4096
+    w = W.make_attn_workload("reprefill_16x4096", 1006, dtype="bf16", Hq=32, Hkv=8, D=128, block_size=16,
+                             context_lens=[n] * B, pool_factor=1.0, poison=False)
+    q_bits = W.normal_array((B * n, w.Hq, w.D), np.random.SeedSequence(1016), "bf16")
+    ql = np.full(B, n, np.int32)
+    dev = to_device(w)
+    dq = torch.from_numpy(q_bits.view(np.int16)).cuda().view(torch.bfloat16)
+    cu = torch.arange(0, (B + 1) * n, n, dtype=torch.int32, device="cuda")
+    out = torch.full((B * n, w.Hq, w.D), 777.0, dtype=torch.float32, device="cuda")
+    desc = binding.attn_desc_for(dq, dev["k_pool"], dev["v_pool"], dev["block_tables"], max_context_len=n)
+    desc.batch = B
+    binding.paged_prefill_attention(desc, dq, dev["k_pool"], dev["v_pool"], dev["block_tables"],
+                                    dev["context_lens"], dev["context_lens"], cu, n, w.scale, out)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(3)
+    inside = [0, 1, 31, 32, 63, 64, 127, 128, 129, 2016, 2047, 2048, 2079, 2080, 3968, 3999, 4000, 4064, 4095]
+    rows = sorted({i * n + j for i in range(B) for j in inside} | set(rng.integers(0, B * n, 256).tolist()))
+    assert len(rows) >= 512
+    rows = np.array(rows)
+    got = out[torch.from_numpy(rows).cuda()].cpu().numpy()
+    err = sampled_rows_check(w, q_bits, ql, _Rows(rows, got), rows)   # only the sampled rows were brought back
+    print(f"16 x 4096 re-prefill, 32/8 heads: {len(rows)} rows x 32 heads, max_abs_err={err:.3e}", flush=True)
+    assert err <= TOL
+    assert not bool((out[::997] == 777.0).all(dim=(1, 2)).any()), "an output row was never written"
+
+
+class _Rows:
+    """out[rows] lookup for rows brought back from the device."""
+    def __init__(self, rows, values):
+        self.pos = {int(r): k for k, r in enumerate(rows)}
+        self.values = values
+
+    def __getitem__(self, rows):
+        return self.values[[self.pos[int(r)] for r in rows]]
+
+
+def test_parity_at_the_benchmarked_chunk_shape_split_and_unsplit():
+    """One 512-token chunk over a context of 8192 tokens, 32/8 heads (the chunked-prefill leg of
+    the benchmark), every row, with the walks split (16 ranges) and unsplit."""
+    w = W.make_attn_workload("chunk_512_over_8192", 1008, dtype="bf16", Hq=32, Hkv=8, D=128, block_size=16,
+                             context_lens=[8192], pool_factor=1.0, poison=False)
+    for split in (True, False):
+        check(w, (512,), seed=1018, split=split)
 
 
 def test_last_query_token_equals_decode_kernel():

@@ -97,10 +97,13 @@ def test_swap_is_transparent_to_attention():
 
 
 # ---- host leg (Sec. 5.1.2: the victims' blocks go to CPU host memory and come back) ---------
-@pytest.mark.parametrize("staging_pairs,side_stream", [(1, False), (7, True), (64, True), (1000, False)])
-def test_swap_out_to_pinned_host_and_back_is_bit_exact(staging_pairs, side_stream):
+@pytest.mark.parametrize("staging_pairs,side_stream,junk_slots", [(1, False, False), (7, True, False), (64, True, False),
+                                                                  (1000, False, False), (7, False, True), (64, False, True)])
+def test_swap_out_to_pinned_host_and_back_is_bit_exact(staging_pairs, side_stream, junk_slots):
     """Pieces of 1 and 7 pairs of every plane (strided copies), of 2 and of all 6 whole planes
-    (contiguous copies); on the current stream or on another one."""
+    (contiguous copies); on the current stream or on another one.  junk_slots: the host-slot
+    column of the mappings holds arbitrary numbers; the host slot of pair j is j whatever it says,
+    so the result is the same and nothing outside the buffers is touched."""
     import oracle
     import torch
     from paper_2602_07878_amd import binding
@@ -116,7 +119,11 @@ def test_swap_out_to_pinned_host_and_back_is_bit_exact(staging_pairs, side_strea
     stream = torch.cuda.Stream() if side_stream else torch.cuda.current_stream()
     stream.wait_stream(torch.cuda.current_stream())                     # the uploads above
     out_desc = binding.swap_desc(planes, bb, sw.num_pool_blocks, n)
-    gm = torch.from_numpy(sw.gather_mapping).cuda()
+    gmap, smap = sw.gather_mapping.copy(), sw.scatter_mapping.copy()
+    if junk_slots:
+        gmap[:, 1] = np.random.default_rng(1).integers(-2**31, 2**31 - 1, n)
+        smap[:, 0] = np.random.default_rng(2).integers(-2**31, 2**31 - 1, n)
+    gm = torch.from_numpy(gmap).cuda()
     stream.wait_stream(torch.cuda.current_stream())
     binding.kv_swap_out_host(out_desc, d_pool, host, gm, staging, stream=stream)
     stream.synchronize()                                                # that stream alone
@@ -126,7 +133,7 @@ def test_swap_out_to_pinned_host_and_back_is_bit_exact(staging_pairs, side_strea
     # back into fresh blocks of a poisoned pool
     d_new = torch.full_like(d_pool, 0x5A)
     in_desc = binding.swap_desc(planes, bb, n, sw.num_pool_blocks)
-    sm = torch.from_numpy(sw.scatter_mapping).cuda()
+    sm = torch.from_numpy(smap).cuda()
     stream.wait_stream(torch.cuda.current_stream())
     binding.kv_swap_in_host(in_desc, host, d_new, sm, staging, stream=stream)
     stream.synchronize()

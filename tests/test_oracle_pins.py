@@ -512,6 +512,35 @@ def test_prefill_chunk_is_the_tail_of_the_full_causal_result_and_one_token_is_de
             assert np.array_equal(full[s, h], _contiguous(w, i, h // 2)[1][0])
 
 
+def test_prefill_query_length_above_the_context_is_clipped_like_the_chunk_append():
+    """The library's rule for a query length above the context length (the same one kv_append_chunk
+    follows): only the first min(query, context) rows of the sequence exist, row j at position j,
+    so they equal the whole-sequence result; the surplus rows have no value (NaN)."""
+    lens = (7, 12, 0, 5)
+    over = (9, 12, 2, 30)
+    w = small(33, dtype="f32", Hq=4, Hkv=2, D=8, bs=4, lens=lens)
+    rng = np.random.default_rng(6)
+    q_over = rng.standard_normal((sum(over), 4, 8)).astype(np.float32)
+    got = oracle.paged_prefill_attention(q_over, w.k_pool, w.v_pool, w.block_tables, w.context_lens,
+                                         over, w.scale, block_size=4)
+    first = np.cumsum(over) - np.array(over)
+    q_exact = np.concatenate([q_over[f:f + n] for f, n in zip(first, lens)])
+    whole = oracle.paged_prefill_attention(q_exact, w.k_pool, w.v_pool, w.block_tables, w.context_lens,
+                                           lens, w.scale, block_size=4)
+    row = 0
+    for f, n, o in zip(first, lens, over):
+        assert np.array_equal(got[f:f + n], whole[row:row + n])
+        assert np.isnan(got[f + n:f + o]).all()
+        row += n
+    # the rows the chunk append writes for the same lengths are exactly the rows that exist
+    kp, vp = w.k_pool.copy(), w.v_pool.copy()
+    kn = rng.standard_normal((sum(over), 2, 8)).astype(np.float32)
+    oracle.kv_append_chunk(kp, vp, kn, kn, w.block_tables, w.context_lens, np.array(over), block_size=4)
+    for i, (f, n) in enumerate(zip(first, lens)):
+        for j in range(n):
+            assert np.array_equal(kp[w.block_tables[i, j // 4], :, j % 4], kn[f + j])
+
+
 # ---- chunk append --------------------------------------------------------------------------------
 def test_chunk_append_equals_token_by_token_append_and_touches_nothing_else():
     """The chunk routine (Python loops) against the single-token routine (C) applied once per
