@@ -151,12 +151,16 @@ def time_append(w, d, torch, binding, reps=200):
             "bytes_written": 2 * w.B * w.Hkv * w.D * 2}
 
 
-def time_swap(sw, reps, torch, binding):
+def time_swap(sw, reps, torch, binding, oracle_check=True):
     """Gather the victims' blocks to contiguous staging, then scatter to fresh blocks."""
     g = torch.Generator(device="cuda:0")
     g.manual_seed(sw.seed)
     pool = torch.randint(-2**31, 2**31 - 1, (sw.pool_bytes // 4,), dtype=torch.int32,
                          device="cuda:0", generator=g)
+    pool_before = {}
+    if oracle_check:
+        pv = pool.view(sw.num_planes, -1)
+        pool_before = {p: pv[p].cpu().numpy().view(np.uint8).copy() for p in (0, sw.num_planes - 1)}
     staging = torch.zeros(sw.staging_bytes // 4, dtype=torch.int32, device="cuda:0")
     gm = torch.from_numpy(sw.gather_mapping).cuda()
     # the order of the pairs is free: listing them by ascending destination block makes the
@@ -181,12 +185,27 @@ def time_swap(sw, reps, torch, binding):
         res[name] = {"ms": ms, "payload_GBps": sw.payload_bytes / ms / 1e6,
                      "traffic_GBps": 2 * sw.payload_bytes / ms / 1e6,
                      "frac_hbm_peak": 2 * sw.payload_bytes / ms / 1e6 / HBM_PEAK_GBS}
-    # bit-exact round trip of the victims' blocks (sampled planes), on the device
+    # (1) on the device, no oracle involved: after the scatter the victims' new blocks hold what
+    #     staging holds, on three planes; (2) against the oracle (memcpy per pair on the host): the
+    #     gathered staging plane and the scattered pool plane of the first and the last plane,
+    #     byte for byte, from the pool bytes as they were before the scatter
     v = pool.view(sw.num_planes, sw.num_pool_blocks, sw.block_bytes // 4)
     s = staging.view(sw.num_planes, sw.n_blocks, sw.block_bytes // 4)
     idx = torch.from_numpy(sw.new_blocks).long().cuda()
     ok = all(bool(torch.equal(v[p][idx], s[p])) for p in (0, sw.num_planes // 2, sw.num_planes - 1))
-    res["round_trip_bit_exact_sampled"] = ok
+    res["device_self_check_new_blocks_equal_staging_3_planes"] = ok
+    if oracle_check:
+        import oracle
+        planes_ok = []
+        for p in (0, sw.num_planes - 1):
+            before = pool_before[p]                                  # host copy taken before any swap
+            st_ref = np.zeros(sw.n_blocks * sw.block_bytes, np.uint8)
+            oracle.kv_block_swap(before, st_ref, sw.gather_mapping, num_planes=1, block_bytes=sw.block_bytes)
+            pool_ref = before.copy()
+            oracle.kv_block_swap(st_ref, pool_ref, smap, num_planes=1, block_bytes=sw.block_bytes)
+            planes_ok.append(bool(np.array_equal(s[p].cpu().numpy().view(np.uint8).reshape(-1), st_ref)) and
+                             bool(np.array_equal(v[p].cpu().numpy().view(np.uint8).reshape(-1), pool_ref)))
+        res["bit_exact_vs_oracle_first_and_last_plane"] = all(planes_ok)
     res["payload_GB"] = sw.payload_bytes / 1e9
     res["victims"] = int(sw.victim_lens.size)
     res["blocks"] = sw.n_blocks
@@ -242,7 +261,7 @@ def time_swap_host(sw, torch, binding, staging_mib=256, reps=2):
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 matrix-core rate
 
 
-def time_prefill(torch, binding, B=16, n=4096, Hq=32, Hkv=8, reps=5):
+def time_prefill(torch, binding, B=16, n=4096, Hq=32, Hkv=8, reps=5, oracle_rows=256):
     """Re-prefill of B preempted requests of n tokens each (the recompute recovery path): causal
     attention of all n tokens over the paged cache, 8B-shaped heads.  Flops counted: 4*D per
     (query, visible key) pair and query head, i.e. the causal half only."""
@@ -270,12 +289,32 @@ def time_prefill(torch, binding, B=16, n=4096, Hq=32, Hkv=8, reps=5):
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1) / reps
     flops = 4.0 * D * (n * (n + 1) // 2) * Hq * B
-    return {"workload": f"causal re-prefill, {B} sequences x {n} tokens, {Hq}/{Hkv} heads, bf16", "ms": ms,
-            "tflops": flops / ms / 1e9, "bound": "mfma", "peak_tflops": MFMA_BF16_PEAK_TFLOPS,
-            "frac": flops / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS}
+    res = {"workload": f"causal re-prefill, {B} sequences x {n} tokens, {Hq}/{Hkv} heads, bf16", "ms": ms,
+           "tflops": flops / ms / 1e9, "bound": "mfma", "peak_tflops": MFMA_BF16_PEAK_TFLOPS,
+           "frac": flops / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS}
+    if oracle_rows:
+        rows = np.unique(np.concatenate([np.random.default_rng(1).integers(0, B * n, oracle_rows),
+                                         np.arange(B) * n, np.arange(B) * n + n - 1]))
+        res.update(prefill_error(torch, q, kp, vp, bt, np.full(B, n), np.full(B, n), out, rows, D ** -0.5))
+    return res
 
 
-def time_prefill_chunk(torch, binding, n=8192, chunk=512, Hq=32, Hkv=8, reps=20):
+def prefill_error(torch, q, kp, vp, bt, ctx_lens, q_lens, out, rows, scale):
+    """Max abs error of the sampled packed output rows (all heads) against the fp64 oracle: a query
+    token is one decode-oracle row over the positions it may see."""
+    import oracle
+    bits = lambda t: t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+    cu = np.concatenate([[0], np.cumsum(q_lens)])
+    seq = np.searchsorted(cu, rows, side="right") - 1
+    ctx = (np.asarray(ctx_lens)[seq] - np.asarray(q_lens)[seq] + (rows - cu[seq]) + 1).astype(np.int32)
+    ridx = torch.from_numpy(rows).cuda()
+    ref = oracle.paged_decode_attention(bits(q[ridx]), bits(kp), bits(vp), bt.cpu().numpy()[seq], ctx,
+                                        float(np.float32(scale)), block_size=kp.shape[2])
+    err = float(np.abs(out[ridx].double().cpu().numpy() - ref).max())
+    return {"max_abs_err_vs_oracle": err, "oracle_rows_checked": int(rows.size)}
+
+
+def time_prefill_chunk(torch, binding, n=8192, chunk=512, Hq=32, Hkv=8, reps=20, oracle_check=True):
     """One chunk of a chunked prefill: the last `chunk` tokens of one sequence of n cached tokens
     (the paper's example budget is 512 tokens per iteration), with and without the workspace
     that lets the library split the walk."""
@@ -310,6 +349,9 @@ def time_prefill_chunk(torch, binding, n=8192, chunk=512, Hq=32, Hkv=8, reps=20)
         torch.cuda.synchronize()
         us = e0.elapsed_time(e1) / reps * 1e3
         res[name] = {"us": us, "tflops": flops / us / 1e6}
+        if oracle_check:   # every row of the chunk
+            res[name].update(prefill_error(torch, q, kp, vp, bt, np.array([n]), np.array([chunk]), out,
+                                           np.arange(chunk), D ** -0.5))
     return res
 
 
@@ -528,9 +570,9 @@ def main():
     ap.add_argument("--layers", type=int, default=16, help="distinct KV layer pools cycled over")
     ap.add_argument("--no-swap", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
-    ap.add_argument("--extra", action="store_true", help="also time the Fill and long-context configs")
-    ap.add_argument("--sweep", action="store_true",
-                    help="also fit the paper's linear execution-time model to a sweep of the cached context")
+    ap.add_argument("--no-extra", action="store_true", help="skip the Fill and long-context configurations")
+    ap.add_argument("--no-sweep", action="store_true",
+                    help="skip the fit of the paper's linear execution-time model to a sweep of the cached context")
     ap.add_argument("--serve", type=int, default=0, metavar="ITERATIONS",
                     help="also run the scheduler-driven serving loop for this many engine iterations")
     args = ap.parse_args()
@@ -577,6 +619,8 @@ def main():
         "wall_ms_per_step": wall_ms,
         "roofline": {"bound": "hbm", "achieved": kern_gbps, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": kern_gbps / HBM_PEAK_GBS, "traffic": recorded_traffic(w.name, STREAM_KERNEL),
+                     "traffic_source": "recorded: profiles/attn_stream_cfg2_hbm_traffic.txt (rocprofv3 --pmc, "
+                                       "null when the kernel's sources have changed since)",
                      "kernel": STREAM_KERNEL, "us_per_launch": kern_ms * 1e3,
                      "us_per_launch_p10_p50_p90": [pct(0.1), pct(0.5), pct(0.9)],
                      "algorithmic_bytes_per_launch": w.kv_bytes,
@@ -615,7 +659,8 @@ def main():
     # every kernel family against the roofline that bounds it (the headline one is `roofline`)
     rl = {"paged_prefill_attention": {"bound": "mfma", "achieved": result["prefill"]["tflops"],
                                       "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                                      "frac": result["prefill"]["frac"], "workload": result["prefill"]["workload"]}}
+                                      "frac": result["prefill"]["frac"], "workload": result["prefill"]["workload"],
+                                      "max_abs_err_vs_oracle": result["prefill"].get("max_abs_err_vs_oracle")}}
     for name, sres in result.get("swap", {}).items():
         for leg in ("gather", "scatter"):
             rl[f"kv_block_swap_{leg}_{name}"] = {"bound": "hbm", "achieved": sres[leg]["traffic_GBps"],
@@ -624,30 +669,47 @@ def main():
                                                  "algorithmic_bytes": 2 * int(sres["payload_GB"] * 1e9)}
     result["other_rooflines"] = rl
 
-    if args.extra:
+    if not args.no_extra:
+        # The other decode configurations, each through the same call, with its own kernel time
+        # (events attached to the streaming kernel's dispatch) and its error against the oracle on
+        # the full workload: the Fill-state mix, and the long-context batch as configured
+        # (512-token partials) and with the library's own split.
         extra = {}
         for mk, layers in ((W.config3_fill, 4), (W.config5_long70b, 2)):
             t = time.time()
             wx = mk()
             dx = upload_attn(wx, layers, torch)
-            # as configured, and (if the configuration caps the partial length) with the
-            # library's own split
+            refx = None
+            if not args.no_cpu:
+                import oracle
+                refx = oracle.paged_decode_attention(wx.q, wx.k_pool, wx.v_pool, wx.block_tables, wx.context_lens,
+                                                     wx.scale, block_size=wx.block_size)
             for pt in sorted({wx.partition_tokens, 0}, reverse=True):
                 wx.partition_tokens = pt
-                _, msx, _, kxs = time_attention(wx, dx, 40, 8, torch, binding, kernel_events=True)
+                outx, msx, _, kxs = time_attention(wx, dx, 40, 8, torch, binding, kernel_events=True)
                 kx = sum(kxs) / len(kxs)
                 g = wx.kv_bytes / msx / 1e6
                 key = wx.name + (f"_partition{pt}" if pt else "")
                 extra[key] = {"ms": msx, "kv_GBps": g, "frac_hbm_peak": g / HBM_PEAK_GBS,
                               "kernel_ms": kx, "context_tokens": wx.total_tokens,
-                              "partition_tokens": pt}
+                              "partition_tokens": pt, "kv_bytes_per_call": wx.kv_bytes}
+                if refx is not None:
+                    extra[key]["max_abs_err_vs_oracle"] = float(np.abs(outx.cpu().numpy().astype(np.float64) - refx).max())
+                rl[f"paged_decode_attention_{key}"] = {
+                    "bound": "hbm", "achieved": wx.kv_bytes / kx / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": wx.kv_bytes / kx / 1e6 / HBM_PEAK_GBS, "us_per_launch": kx * 1e3,
+                    "per_call_GBps": g, "per_call_frac": g / HBM_PEAK_GBS,
+                    "algorithmic_bytes_per_launch": wx.kv_bytes,
+                    "max_abs_err_vs_oracle": extra[key].get("max_abs_err_vs_oracle")}
                 log(f"[bench] {key}: {extra[key]} (setup {time.time()-t:.0f}s)")
             del dx
             torch.cuda.empty_cache()
         result["other_configs"] = extra
 
-    if args.sweep:
+    if not args.no_sweep:
+        # Sec. 4.2: time linear in the KV bytes streamed; the fit is an acceptance item (R^2 >= 0.98)
         result["time_model"] = time_model_sweep(torch, binding)
+        result["time_model"]["r_squared_at_least_0.98"] = result["time_model"]["r_squared"] >= 0.98
         log(f"[bench] time model: {result['time_model']}")
     if args.serve > 0:
         result["serving_loop"] = {m: serve_loop(torch, binding, args.serve, mode=m) for m in ("recompute", "swap")}
