@@ -22,7 +22,7 @@ _LIB = os.path.join(_HERE, "libpkv_oracle.so")
 _lock = threading.Lock()
 _lib = None
 
-F32, BF16 = 0, 1
+F32, BF16, F8E4M3 = 0, 1, 2
 
 
 def build(force: bool = False) -> str:
@@ -48,6 +48,9 @@ def _load():
         lib.orc_paged_decode_attention.restype = ctypes.c_int
         lib.orc_paged_decode_attention.argtypes = (
             [i32] * 8 + [i64] * 6 + [vp] * 5 + [ctypes.c_float, vp, vp, i32])
+        lib.orc_paged_decode_attention_kv.restype = ctypes.c_int
+        lib.orc_paged_decode_attention_kv.argtypes = (
+            [i32] * 9 + [ctypes.c_float] * 2 + [i64] * 6 + [vp] * 5 + [ctypes.c_float, vp, vp, i32])
         lib.orc_kv_block_swap.restype = ctypes.c_int
         lib.orc_kv_block_swap.argtypes = [i32, i64, i64, i64, i32, i32, vp, vp, vp, i32]
         lib.orc_kv_append.restype = ctypes.c_int
@@ -66,7 +69,9 @@ def _dtype_code(a: np.ndarray) -> int:
         return F32
     if a.dtype == np.uint16:
         return BF16
-    raise TypeError(f"oracle takes float32 or uint16 (bf16 bits), got {a.dtype}")
+    if a.dtype == np.uint8:
+        return F8E4M3
+    raise TypeError(f"oracle takes float32, uint16 (bf16 bits) or uint8 (e4m3 codes), got {a.dtype}")
 
 
 def _ptr(a: np.ndarray) -> int:
@@ -75,8 +80,11 @@ def _ptr(a: np.ndarray) -> int:
 
 def paged_decode_attention(q, k_pool, v_pool, block_tables, context_lens, scale,
                            *, block_size, k_strides=None, v_strides=None,
-                           return_weights=False):
+                           return_weights=False, k_scale=1.0, v_scale=1.0):
     """out[i,h,:] = softmax_t(scale * q[i,h] . K_t) @ V over the paged pool.
+
+    The pools may be 8-bit (numpy.uint8 holding OCP E4M3 codes) beside a bfloat16 q; K and V are
+    then k_scale / v_scale times the stored values.
 
     q [B,Hq,D]; k_pool/v_pool [num_blocks,Hkv,bs,D] C-contiguous unless
     element strides (block, head, token) are given, in which case the pools may
@@ -90,8 +98,9 @@ def paged_decode_attention(q, k_pool, v_pool, block_tables, context_lens, scale,
     bt = np.ascontiguousarray(block_tables, dtype=np.int32)
     cl = np.ascontiguousarray(context_lens, dtype=np.int32)
     code = _dtype_code(q)
-    if _dtype_code(k_pool) != code or _dtype_code(v_pool) != code:
-        raise TypeError("q, k_pool, v_pool must share one dtype")
+    kv_code = _dtype_code(k_pool)
+    if _dtype_code(v_pool) != kv_code or (kv_code != code and (kv_code, code) != (F8E4M3, BF16)):
+        raise TypeError("q, k_pool, v_pool must share one dtype, or be bf16 with 8-bit pools")
     B, Hq, D = q.shape
     nblk, Hkv = k_pool.shape[0], k_pool.shape[1]
     if k_strides is None:
@@ -104,8 +113,9 @@ def paged_decode_attention(q, k_pool, v_pool, block_tables, context_lens, scale,
     out = np.empty((B, Hq, D), dtype=np.float64)
     max_ctx = int(cl.max()) if (return_weights and B > 0) else 0
     w = np.zeros((B, Hq, max_ctx), dtype=np.float64) if return_weights else None
-    rc = lib.orc_paged_decode_attention(
-        B, Hq, Hkv, D, block_size, nblk, bt.shape[1], code,
+    rc = lib.orc_paged_decode_attention_kv(
+        B, Hq, Hkv, D, block_size, nblk, bt.shape[1], code, kv_code,
+        float(np.float32(k_scale)), float(np.float32(v_scale)),
         *[int(x) for x in k_strides], *[int(x) for x in v_strides],
         _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(bt), _ptr(cl),
         float(np.float32(scale)), _ptr(out), _ptr(w) if w is not None else None,

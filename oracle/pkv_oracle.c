@@ -26,14 +26,16 @@
  * key shift invariance, one-hot limit, GQA = replicated MHA, split-merge
  * algebra, a library attention routine in fp64, exact-rational brute force on
  * tiny inputs, NaN poison outside the defined reads; for the copy: identity,
- * permutation and inverse, round trip, untouched bytes.
+ * permutation and inverse, round trip, untouched bytes; for the 8-bit pools: all
+ * 256 codes against a library conversion and the format's closed forms, the
+ * dequantisation factors against the same call on pre-scaled wider pools.
  */
 #include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
 
-enum { ORC_F32 = 0, ORC_BF16 = 1 };
+enum { ORC_F32 = 0, ORC_BF16 = 1, ORC_F8E4M3 = 2 };
 
 /* bfloat16 = the upper 16 bits of an IEEE-754 binary32: widening is exact. */
 static double bf16_bits_to_double(uint16_t bits) {
@@ -43,8 +45,22 @@ static double bf16_bits_to_double(uint16_t bits) {
   return (double)f;
 }
 
+/*
+ * 8-bit float E4M3 of the OCP 8-bit floating point specification: 1 sign bit, 4
+ * exponent bits (bias 7), 3 mantissa bits; exponent field 0 holds the
+ * subnormals m/8 * 2^-6; there are no infinities and the one NaN pattern per
+ * sign is S.1111.111, so the largest magnitude is S.1111.110 = 1.75 * 2^8 = 448.
+ */
+static double f8e4m3_bits_to_double(uint8_t code) {
+  const int sign = code >> 7, e = (code >> 3) & 15, m = code & 7;
+  if (e == 15 && m == 7) return NAN;
+  const double mag = e == 0 ? ldexp((double)m / 8.0, -6) : ldexp(1.0 + (double)m / 8.0, e - 7);
+  return sign ? -mag : mag;
+}
+
 static double load_elem(const void* base, int64_t index, int dtype) {
   if (dtype == ORC_BF16) return bf16_bits_to_double(((const uint16_t*)base)[index]);
+  if (dtype == ORC_F8E4M3) return f8e4m3_bits_to_double(((const uint8_t*)base)[index]);
   return (double)((const float*)base)[index];
 }
 
@@ -59,9 +75,38 @@ static double load_elem(const void* base, int64_t index, int dtype) {
  *   weights_out  optional [B][Hq][max_ctx] double: softmax weights (tests)
  * Returns 0, or a negative number for an index that leaves the pool/table.
  */
+int orc_paged_decode_attention_kv(
+    int B, int Hq, int Hkv, int D, int block_size, int num_pool_blocks,
+    int max_blocks_per_seq, int q_dtype, int kv_dtype, float k_scale, float v_scale,
+    int64_t ksb, int64_t ksh, int64_t kst,
+    int64_t vsb, int64_t vsh, int64_t vst, const void* q, const void* k_pool,
+    const void* v_pool, const int32_t* block_tables,
+    const int32_t* context_lens, float scale, double* out, double* weights_out,
+    int max_ctx);
+
+/* q and the pools in one element type, stored values taken as they are. */
 int orc_paged_decode_attention(
     int B, int Hq, int Hkv, int D, int block_size, int num_pool_blocks,
     int max_blocks_per_seq, int dtype, int64_t ksb, int64_t ksh, int64_t kst,
+    int64_t vsb, int64_t vsh, int64_t vst, const void* q, const void* k_pool,
+    const void* v_pool, const int32_t* block_tables,
+    const int32_t* context_lens, float scale, double* out, double* weights_out,
+    int max_ctx) {
+  return orc_paged_decode_attention_kv(B, Hq, Hkv, D, block_size, num_pool_blocks, max_blocks_per_seq,
+                                       dtype, dtype, 1.0f, 1.0f, ksb, ksh, kst, vsb, vsh, vst, q, k_pool,
+                                       v_pool, block_tables, context_lens, scale, out, weights_out, max_ctx);
+}
+
+/*
+ * The same with the pools in their own element type (a quantised KV cache: the
+ * time model of Sec. 4.2 charges sizeof(T) bytes per cached element) and a
+ * dequantisation factor per pool: K_t[d] = k_scale * stored value, V likewise.
+ * Strides count pool elements.
+ */
+int orc_paged_decode_attention_kv(
+    int B, int Hq, int Hkv, int D, int block_size, int num_pool_blocks,
+    int max_blocks_per_seq, int q_dtype, int kv_dtype, float k_scale, float v_scale,
+    int64_t ksb, int64_t ksh, int64_t kst,
     int64_t vsb, int64_t vsh, int64_t vst, const void* q, const void* k_pool,
     const void* v_pool, const int32_t* block_tables,
     const int32_t* context_lens, float scale, double* out, double* weights_out,
@@ -99,8 +144,8 @@ int orc_paged_decode_attention(
         const int64_t kbase = blk * ksb + g * ksh + slot * kst;
         const int64_t vbase = blk * vsb + g * vsh + slot * vst;
         for (int d = 0; d < D; ++d) {
-          Kc[(int64_t)t * D + d] = load_elem(k_pool, kbase + d, dtype);
-          Vc[(int64_t)t * D + d] = load_elem(v_pool, vbase + d, dtype);
+          Kc[(int64_t)t * D + d] = (double)k_scale * load_elem(k_pool, kbase + d, kv_dtype);
+          Vc[(int64_t)t * D + d] = (double)v_scale * load_elem(v_pool, vbase + d, kv_dtype);
         }
       }
       if (bad) {
@@ -115,7 +160,7 @@ int orc_paged_decode_attention(
       for (int t = 0; t < n; ++t) {
         double acc = 0.0;
         for (int d = 0; d < D; ++d)
-          acc += load_elem(q, qbase + d, dtype) * Kc[(int64_t)t * D + d];
+          acc += load_elem(q, qbase + d, q_dtype) * Kc[(int64_t)t * D + d];
         s[t] = (double)scale * acc;
       }
 

@@ -44,6 +44,27 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
             << np.uint32(16)).view(np.float32)
 
 
+def f32_to_f8e4m3_bits(x: np.ndarray) -> np.ndarray:
+    """Round float32 to OCP E4M3 (1-4-3 bits, bias 7, no infinities; nearest, ties to even,
+    saturating at the largest finite value 448); returns uint8 codes.  NaN becomes 0x7F."""
+    a = np.ascontiguousarray(x, dtype=np.float32)
+    mag = np.minimum(np.abs(np.nan_to_num(a, nan=0.0)), np.float32(448.0)).astype(np.float64)
+    # below the smallest normal (2^-6) the grid is uniform with step 2^-9; above it each binade
+    # [2^e, 2^(e+1)) has eight steps of 2^(e-3)
+    e = np.floor(np.log2(np.maximum(mag, 2.0 ** -6)))
+    step = 2.0 ** (e - 3)
+    n = np.rint(mag / step)                       # multiples of the step; rint rounds half to even
+    val = n * step                                # may have moved up into the next binade: still on the grid
+    e2 = np.floor(np.log2(np.maximum(val, 2.0 ** -6)))
+    sub = val < 2.0 ** -6
+    mant = np.where(sub, np.rint(val * 2.0 ** 9), np.rint((val / 2.0 ** e2 - 1.0) * 8.0)).astype(np.int64)
+    expo = np.where(sub, 0, e2.astype(np.int64) + 7)
+    code = ((expo << 3) | mant).astype(np.uint8)
+    code |= (np.signbit(a).astype(np.uint8) << np.uint8(7))
+    code[np.isnan(a)] = 0x7F
+    return code
+
+
 def _normal_fill(out_flat: np.ndarray, seed_seq: np.random.SeedSequence, bf16: bool):
     """Fill a flat array with N(0,1) draws, chunked over threads, reproducibly."""
     n = out_flat.size
@@ -54,7 +75,10 @@ def _normal_fill(out_flat: np.ndarray, seed_seq: np.random.SeedSequence, bf16: b
         lo, hi = c * _FILL_CHUNK, min(n, (c + 1) * _FILL_CHUNK)
         g = np.random.Generator(np.random.PCG64(children[c]))
         x = g.standard_normal(hi - lo, dtype=np.float32)
-        out_flat[lo:hi] = f32_to_bf16_bits(x) if bf16 else x
+        if out_flat.dtype == np.uint8:
+            out_flat[lo:hi] = f32_to_f8e4m3_bits(x)
+        else:
+            out_flat[lo:hi] = f32_to_bf16_bits(x) if bf16 else x
 
     if nchunks == 1:
         work(0)
@@ -64,14 +88,16 @@ def _normal_fill(out_flat: np.ndarray, seed_seq: np.random.SeedSequence, bf16: b
 
 
 def normal_array(shape, seed_seq, dtype: str) -> np.ndarray:
-    """N(0,1) array; dtype 'f32' -> float32, 'bf16' -> uint16 bit patterns."""
+    """N(0,1) array; dtype 'f32' -> float32, 'bf16' -> uint16 bit patterns, 'f8' -> uint8 E4M3 codes."""
     bf16 = dtype == "bf16"
-    a = np.empty(shape, dtype=np.uint16 if bf16 else np.float32)
+    a = np.empty(shape, dtype=np.uint8 if dtype == "f8" else np.uint16 if bf16 else np.float32)
     _normal_fill(a.reshape(-1), seed_seq, bf16)
     return a
 
 
 def nan_bits(dtype: str):
+    if dtype == "f8":
+        return np.uint8(0x7F)
     return np.uint16(0x7FC0) if dtype == "bf16" else np.float32(np.nan)
 
 
@@ -80,7 +106,7 @@ class AttnWorkload:
     """One paged_decode_attention call's inputs (host arrays)."""
     name: str
     seed: int
-    dtype: str                 # 'f32' | 'bf16'
+    dtype: str                 # 'f32' | 'bf16' | 'f8' (bf16 q, 8-bit E4M3 pools)
     B: int
     Hq: int
     Hkv: int
@@ -95,10 +121,13 @@ class AttnWorkload:
     scale: float
     partition_tokens: int = 0
     notes: dict = field(default_factory=dict)
+    k_scale: float = 1.0       # 'f8' only: K = k_scale * stored value, V = v_scale * stored value
+    v_scale: float = 1.0
 
     @property
     def elem_bytes(self) -> int:
-        return 2 if self.dtype == "bf16" else 4
+        """Bytes of one cached K or V element."""
+        return 1 if self.dtype == "f8" else 2 if self.dtype == "bf16" else 4
 
     @property
     def total_tokens(self) -> int:
@@ -149,7 +178,7 @@ def make_attn_workload(name: str, seed: int, *, dtype: str, Hq: int, Hkv: int, D
     for i in range(B):
         bt[i, :nb[i]] = perm[pos:pos + nb[i]]
         pos += int(nb[i])
-    q = normal_array((B, Hq, D), s_q, dtype)
+    q = normal_array((B, Hq, D), s_q, "bf16" if dtype == "f8" else dtype)
     k_pool = normal_array((num_pool_blocks, Hkv, block_size, D), s_k, dtype)
     v_pool = normal_array((num_pool_blocks, Hkv, block_size, D), s_v, dtype)
     if poison:
@@ -208,6 +237,13 @@ def config1_tiny(seed: int = 1001) -> AttnWorkload:
 def config2_llama8b(seed: int = 1002, B: int = 64, lo: int = 128, hi: int = 4096
                     ) -> AttnWorkload:
     return make_attn_workload("cfg2_llama3_8b_b64_bf16", seed, dtype="bf16", Hq=32, Hkv=8,
+                              D=128, block_size=16,
+                              context_lens=lens_uniform(seed, B, lo, hi), pool_factor=1.1)
+
+
+def config2_llama8b_f8(seed: int = 1012, B: int = 64, lo: int = 128, hi: int = 4096) -> AttnWorkload:
+    """The 8B-shaped decode batch with an 8-bit KV cache: half the bytes per cached token."""
+    return make_attn_workload("cfg2_llama3_8b_b64_kv_f8e4m3", seed, dtype="f8", Hq=32, Hkv=8,
                               D=128, block_size=16,
                               context_lens=lens_uniform(seed, B, lo, hi), pool_factor=1.1)
 

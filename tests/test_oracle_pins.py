@@ -571,3 +571,104 @@ def test_chunk_append_equals_token_by_token_append_and_touches_nothing_else():
     for j, pos in enumerate(range(4, 9)):
         assert np.array_equal(k1[w.block_tables[0, pos // 4], :, pos % 4], kn[j])
     assert int(np.any(k1 != w.k_pool, axis=(1, 3)).sum()) <= 5 + 4 + 6   # at most one (block, slot) per written token
+
+
+# ---- 8-bit (OCP E4M3) pools -------------------------------------------------------------------------
+def torch_f8_to_f64(codes):
+    """Library decode of E4M3 codes, independent of the oracle's."""
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(codes, np.uint8)).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+
+
+def test_f8_all_256_codes_decode_as_the_format_defines():
+    """Every code through the oracle's V path (a 1-token context returns the V row: its 128 dims hold
+    codes 0..127, those of a second sequence 128..255) against a library conversion, and a few
+    codes against the values the format definition fixes."""
+    D = 128
+    k_pool = np.zeros((2, 1, 16, D), np.uint8)
+    v_pool = np.zeros((2, 1, 16, D), np.uint8)
+    v_pool[0, 0, 0] = np.arange(128)
+    v_pool[1, 0, 0] = np.arange(128, 256)
+    q = np.zeros((2, 1, D), np.uint16)
+    out = oracle.paged_decode_attention(q, k_pool, v_pool, np.array([[0], [1]], np.int32), np.array([1, 1], np.int32),
+                                        1.0, block_size=16)
+    got = out.reshape(256)
+    ref = torch_f8_to_f64(np.arange(256))
+    assert np.isnan(got[0x7F]) and np.isnan(got[0xFF]) and np.isnan(ref[0x7F]) and np.isnan(ref[0xFF])
+    ok = ~np.isnan(ref)
+    assert ok.sum() == 254 and np.array_equal(got[ok], ref[ok])
+    assert got[0x80] == 0.0                  # the sign of -0.0 (code 0x80) does not survive the weighted sum
+    fixed = {0x00: 0.0, 0x01: 2.0 ** -9, 0x07: 7 * 2.0 ** -9, 0x08: 2.0 ** -6, 0x38: 1.0, 0x39: 1.125, 0x40: 2.0,
+             0x7E: 448.0, 0xB8: -1.0, 0xFE: -448.0, 0x78: 256.0, 0x77: 240.0}
+    for code, value in fixed.items():
+        assert got[code] == value, (hex(code), got[code], value)
+
+
+def test_f8_keys_decode_in_the_score_path():
+    """q = unit vector along dim 3 and scale 1: the score of token t is its key's dim-3 value, so the
+    log of a weight ratio is a difference of decoded key values."""
+    codes = np.array([c for c in range(256) if c not in (0x7F, 0xFF)], np.uint8)
+    codes = codes[np.abs(torch_f8_to_f64(codes)) <= 32]          # keep exp() far from overflow
+    n, D = len(codes), 8
+    nb = (n + 15) // 16
+    k_pool = np.zeros((nb, 1, 16, D), np.uint8)
+    k_pool.reshape(nb * 16, D)[:n, 3] = codes
+    v_pool = np.zeros_like(k_pool)
+    q = np.zeros((1, 1, D), np.uint16)
+    q[0, 0, 3] = 0x3F80                                          # bf16 1.0
+    _, w = oracle.paged_decode_attention(q, k_pool, v_pool, np.arange(nb, dtype=np.int32)[None], np.array([n], np.int32),
+                                         1.0, block_size=16, return_weights=True)
+    vals = torch_f8_to_f64(codes)
+    np.testing.assert_allclose(np.log(w[0, 0, :n] / w[0, 0, 0]), vals - vals[0], rtol=0, atol=1e-9)
+
+
+@pytest.mark.parametrize("Hq,Hkv,D", [(8, 2, 32), (16, 2, 128)])
+def test_f8_pools_match_library_sdpa_on_dequantised_tensors(Hq, Hkv, D):
+    import torch
+    import torch.nn.functional as F
+    ks, vs = 0.75, 1.5
+    w = W.make_attn_workload("t8", 12, dtype="f8", Hq=Hq, Hkv=Hkv, D=D, block_size=16,
+                             context_lens=(17, 64, 100, 256), num_pool_blocks=64)
+    assert w.k_pool.dtype == np.uint8 and w.q.dtype == np.uint16
+    out = run(w, k_scale=ks, v_scale=vs)
+    G = Hq // Hkv
+    for i in range(w.B):
+        n = int(w.context_lens[i])
+        k = np.stack([torch_f8_to_f64(gather_rows(w.k_pool, w.block_tables[i], n, g, 16)) for g in range(Hkv)]) * ks
+        v = np.stack([torch_f8_to_f64(gather_rows(w.v_pool, w.block_tables[i], n, g, 16)) for g in range(Hkv)]) * vs
+        kt = torch.from_numpy(k).repeat_interleave(G, dim=0)[None]
+        vt = torch.from_numpy(v).repeat_interleave(G, dim=0)[None]
+        qt = torch.from_numpy(as_f64(w.q[i]))[None, :, None, :]
+        ref = F.scaled_dot_product_attention(qt, kt, vt, attn_mask=None, dropout_p=0.0, is_causal=False,
+                                             scale=float(np.float32(w.scale)))
+        np.testing.assert_allclose(out[i], ref[0, :, 0].numpy(), rtol=0, atol=1e-12)
+
+
+def test_f8_scales_equal_prescaled_wider_pools_and_poison_is_not_read():
+    """k_scale and v_scale are plain factors on the stored values: the same call on bf16 pools that
+    hold scale * value (powers of two: exact in bf16) gives the same result bit for bit; NaN codes
+    in free blocks and dead tail slots are never read."""
+    w = W.make_attn_workload("t8s", 13, dtype="f8", Hq=4, Hkv=2, D=16, block_size=16,
+                             context_lens=(5, 33, 16, 0), pool_factor=1.5, poison=True)
+    assert (w.k_pool == 0x7F).any()
+    got = run(w, k_scale=0.25, v_scale=4.0)
+    assert np.isfinite(got).all() and np.all(got[3] == 0.0)
+    kb = W.f32_to_bf16_bits((torch_f8_to_f64(w.k_pool) * 0.25).astype(np.float32))
+    vb = W.f32_to_bf16_bits((torch_f8_to_f64(w.v_pool) * 4.0).astype(np.float32))
+    wide = oracle.paged_decode_attention(w.q, kb, vb, w.block_tables, w.context_lens, w.scale, block_size=16)
+    assert np.array_equal(got, wide)
+
+
+def test_f8_generator_rounds_to_nearest_even_and_saturates():
+    """The input generator's float32 -> E4M3 rounding against the library conversion (in range), and
+    its closed-form corner cases."""
+    import torch
+    rng = np.random.default_rng(0)
+    x = (rng.standard_normal(100000) * rng.choice([1e-3, 0.01, 0.1, 1, 10, 100], 100000)).astype(np.float32)
+    x = x[np.abs(x) <= 448]
+    ref = torch.from_numpy(x).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert np.array_equal(W.f32_to_f8e4m3_bits(x), ref)
+    corner = np.array([0.0, -0.0, 2.0 ** -10, 1.5 * 2.0 ** -10, 2.5 * 2.0 ** -9, 3.5 * 2.0 ** -9, 1.0625, 1.1875, 448.0,
+                       1e9, -1e9, np.nan], np.float32)
+    want = np.array([0x00, 0x80, 0x00, 0x01, 0x02, 0x04, 0x38, 0x3A, 0x7E, 0x7E, 0xFE, 0x7F], np.uint8)
+    assert np.array_equal(W.f32_to_f8e4m3_bits(corner), want)
