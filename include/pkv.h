@@ -56,7 +56,10 @@ typedef enum pkv_status {
   PKV_ERR_HIP = 7        /* the HIP runtime reported an error on launch         */
 } pkv_status;
 
-typedef enum pkv_dtype { PKV_F32 = 0, PKV_BF16 = 1 } pkv_dtype;
+/* PKV_F8_E4M3: the 8-bit float E4M3 of the OCP 8-bit floating point specification (1 sign,
+ * 4 exponent bits with bias 7, 3 mantissa bits, subnormals, no infinities, NaN =
+ * S.1111.111, largest finite value 448).  Allowed for the K/V pools only. */
+typedef enum pkv_dtype { PKV_F32 = 0, PKV_BF16 = 1, PKV_F8_E4M3 = 2 } pkv_dtype;
 
 /* Use the vector-ALU kernel even where the matrix-core kernel applies (a
  * second, independent code path: tests run both against the oracle). */
@@ -87,11 +90,18 @@ typedef struct pkv_attn_desc {
   int32_t max_context_len;    /* host-known upper bound of all n_i; sizes grid   */
   int32_t partition_tokens;   /* most tokens per split-K partial, multiple of 64;
                                  0 = chosen by the library                       */
-  int32_t kv_dtype;           /* pkv_dtype of q, k_pool and v_pool               */
+  int32_t kv_dtype;           /* pkv_dtype of k_pool and v_pool; q has the same
+                                 type, except that q is PKV_BF16 beside
+                                 PKV_F8_E4M3 pools (a quantised KV cache: half
+                                 the bytes per cached token that Sec. 4.2's time
+                                 model charges)                                  */
   int32_t out_dtype;          /* pkv_dtype of out: PKV_F32 or PKV_BF16           */
   int32_t flags;              /* 0, or PKV_ATTN_FLAG_* bits                      */
   int64_t k_stride_block, k_stride_head, k_stride_token;
   int64_t v_stride_block, v_stride_head, v_stride_token;
+  /* PKV_F8_E4M3 pools only (ignored otherwise): K = k_scale * stored value,
+   * V = v_scale * stored value; finite and positive, 0 is read as 1. */
+  float k_scale, v_scale;
 } pkv_attn_desc;
 
 /*
@@ -172,6 +182,9 @@ size_t pkv_attn_workspace_bytes(const pkv_attn_desc* desc);
  *               descriptors, but not two calls at the same time.
  * Accumulation is fp32.  The result does not depend on where blocks sit in
  * the pool; for a fixed partition length it is bit-reproducible run to run.
+ * With PKV_F8_E4M3 pools (head_dim 128 or 256; strides then count bytes) the
+ * stored codes are decoded exactly (every E4M3 value is a bfloat16 value) and
+ * the arithmetic is that of the bfloat16 call on k_scale * K, v_scale * V.
  */
 int32_t paged_decode_attention(const pkv_attn_desc* desc, const void* q,
                                const void* k_pool, const void* v_pool,

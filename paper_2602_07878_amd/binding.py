@@ -13,7 +13,7 @@ from typing import Optional
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpkv.so")
 
-PKV_F32, PKV_BF16 = 0, 1
+PKV_F32, PKV_BF16, PKV_F8_E4M3 = 0, 1, 2
 PKV_OK = 0
 PKV_ERR_HIP = 7
 FLAG_VECTOR_ALU = 1
@@ -36,7 +36,8 @@ class AttnDesc(ctypes.Structure):
         "max_blocks_per_seq", "max_context_len", "partition_tokens", "kv_dtype", "out_dtype",
         "flags")] + [(n, ctypes.c_int64) for n in (
             "k_stride_block", "k_stride_head", "k_stride_token",
-            "v_stride_block", "v_stride_head", "v_stride_token")]
+            "v_stride_block", "v_stride_head", "v_stride_token")] + [
+        ("k_scale", ctypes.c_float), ("v_scale", ctypes.c_float)]
 
 
 class SwapDesc(ctypes.Structure):
@@ -147,20 +148,25 @@ def _torch_dtype_code(t) -> int:
         return PKV_F32
     if t.dtype == torch.bfloat16:
         return PKV_BF16
+    if t.dtype in (torch.uint8, torch.float8_e4m3fn):   # 8-bit pools: E4M3 codes
+        return PKV_F8_E4M3
     raise TypeError(f"unsupported dtype {t.dtype}")
 
 
 def attn_desc_for(q, k_pool, v_pool, block_tables, *, max_context_len: int,
-                  partition_tokens: int = 0, out_dtype=None, flags: int = 0) -> AttnDesc:
+                  partition_tokens: int = 0, out_dtype=None, flags: int = 0,
+                  k_scale: float = 1.0, v_scale: float = 1.0) -> AttnDesc:
     """Descriptor for torch tensors: q [B,Hq,D]; pools [blocks,Hkv,bs,D] (any strides with a
-    unit-stride last dim); block_tables [B,max_blocks]."""
+    unit-stride last dim); block_tables [B,max_blocks].  8-bit pools (uint8 or float8_e4m3fn
+    tensors of E4M3 codes) go with a bfloat16 q and the factors k_scale, v_scale."""
     import torch
     B, Hq, D = q.shape
     nblk, Hkv, bs, Dk = k_pool.shape
     assert Dk == D and v_pool.shape == k_pool.shape
     assert k_pool.stride(3) == 1 and v_pool.stride(3) == 1 and q.is_contiguous()
-    code = _torch_dtype_code(q)
-    assert _torch_dtype_code(k_pool) == code and _torch_dtype_code(v_pool) == code
+    code = _torch_dtype_code(k_pool)
+    assert _torch_dtype_code(v_pool) == code
+    assert _torch_dtype_code(q) == (PKV_BF16 if code == PKV_F8_E4M3 else code)
     d = AttnDesc()
     d.batch, d.num_q_heads, d.num_kv_heads, d.head_dim = B, Hq, Hkv, D
     d.block_size, d.num_pool_blocks = bs, nblk
@@ -172,6 +178,7 @@ def attn_desc_for(q, k_pool, v_pool, block_tables, *, max_context_len: int,
     d.flags = int(flags)
     d.k_stride_block, d.k_stride_head, d.k_stride_token = (k_pool.stride(i) for i in range(3))
     d.v_stride_block, d.v_stride_head, d.v_stride_token = (v_pool.stride(i) for i in range(3))
+    d.k_scale, d.v_scale = float(k_scale), float(v_scale)
     return d
 
 
@@ -188,14 +195,15 @@ def new_workspace(nbytes: int, device, *, stream=None):
 def paged_decode_attention(q, k_pool, v_pool, block_tables, context_lens, scale, out, *,
                            max_context_len: int, partition_tokens: int = 0, workspace=None,
                            desc: Optional[AttnDesc] = None, stream=None, flags: int = 0,
-                           kernel_events=None):
+                           kernel_events=None, k_scale: float = 1.0, v_scale: float = 1.0):
     """out[i,h,:] = softmax_t(scale * q[i,h] . K_t) V_t over the paged pool (device tensors).
     Returns the workspace tensor used (reusable by the caller)."""
     import torch
     L = lib()
     if desc is None:
         desc = attn_desc_for(q, k_pool, v_pool, block_tables, max_context_len=max_context_len,
-                             partition_tokens=partition_tokens, out_dtype=out.dtype, flags=flags)
+                             partition_tokens=partition_tokens, out_dtype=out.dtype, flags=flags,
+                             k_scale=k_scale, v_scale=v_scale)
     assert block_tables.dtype == torch.int32 and context_lens.dtype == torch.int32
     assert block_tables.is_contiguous() and context_lens.is_contiguous() and out.is_contiguous()
     need = int(L.pkv_attn_workspace_bytes(ctypes.byref(desc)))

@@ -24,7 +24,10 @@ inline int32_t hip_status(hipError_t e) {
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-inline int elem_bytes(int dtype) { return dtype == PKV_BF16 ? 2 : dtype == PKV_F32 ? 4 : 0; }
+inline int elem_bytes(int dtype) { return dtype == PKV_BF16 ? 2 : dtype == PKV_F32 ? 4 : dtype == PKV_F8_E4M3 ? 1 : 0; }
+
+// dequantisation factor of an 8-bit pool as given in the descriptor (0 stands for 1)
+inline float pool_scale(const pkv_attn_desc* d, float s) { return d->kv_dtype == PKV_F8_E4M3 && s != 0.f ? s : 1.0f; }
 
 int32_t partition_tokens_of(const pkv_attn_desc* d) {
   if (!d) return 0;
@@ -56,6 +59,9 @@ int32_t check_attn_desc(const pkv_attn_desc* d) {
   const int row_bytes = d->head_dim * eb;
   if (row_bytes != 128 && row_bytes != 256 && row_bytes != 512) return PKV_ERR_SHAPE;
   if (partition_tokens_of(d) == 0) return PKV_ERR_SHAPE;
+  if (d->kv_dtype == PKV_F8_E4M3 &&
+      (!std::isfinite(d->k_scale) || !std::isfinite(d->v_scale) || d->k_scale < 0.f || d->v_scale < 0.f))
+    return PKV_ERR_SHAPE;
   if ((int64_t)d->max_blocks_per_seq * d->block_size < d->max_context_len) return PKV_ERR_SHAPE;
   const int64_t st[6] = {d->k_stride_block, d->k_stride_head, d->k_stride_token,
                          d->v_stride_block, d->v_stride_head, d->v_stride_token};
@@ -178,7 +184,8 @@ int32_t pkv::attention_call(const pkv_attn_desc* desc, const void* q, const void
   p.max_partitions = max_partitions_of(desc);
   p.out_is_bf16 = desc->out_dtype == PKV_BF16;
   p.no_mfma = (desc->flags & PKV_ATTN_FLAG_VECTOR_ALU) != 0;
-  p.scale_log2e = scale * 1.4426950408889634f;
+  p.scale_log2e = scale * pool_scale(desc, desc->k_scale) * 1.4426950408889634f;
+  p.v_scale = pool_scale(desc, desc->v_scale);
   p.ev_begin = static_cast<hipEvent_t>(ev_begin);
   p.ev_end = static_cast<hipEvent_t>(ev_end);
   if (attn_stream_supported(*desc)) {
@@ -277,6 +284,7 @@ int32_t paged_prefill_attention_ws(const pkv_attn_desc* desc, const void* q, con
   p.group = desc->num_q_heads / desc->num_kv_heads;
   p.out_is_bf16 = desc->out_dtype == PKV_BF16;
   p.scale_log2e = scale * 1.4426950408889634f;
+  p.v_scale = 1.0f;
   // the walks are split only if the caller brought the workspace for it
   p.max_partitions = 1;
   if (workspace && total_query_tokens > 0) {

@@ -70,6 +70,20 @@ template <> struct Unpack<2> {  // bf16: 8 elements per 16 bytes, widening is a 
   }
 };
 
+template <> struct Unpack<1> {  // OCP E4M3: 16 elements per 16 bytes, decoded by the hardware conversion
+  static constexpr int N = 16;
+  __device__ static __forceinline__ void run(const U4& u, float* f) {
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[i], false);   // bytes 0, 1
+      const f32x2 hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[i], true);    // bytes 2, 3
+      f[4 * i] = lo[0]; f[4 * i + 1] = lo[1]; f[4 * i + 2] = hi[0]; f[4 * i + 3] = hi[1];
+    }
+  }
+};
+
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
   uint32_t u = __builtin_bit_cast(uint32_t, f);
   if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40);  // NaN
@@ -84,7 +98,8 @@ struct Tile {
   U4 v[NJ];
 };
 
-template <int EB, int LPR, int GT>
+// EB = bytes of a K/V element, QEB = bytes of a q element (equal, except bf16 q beside 8-bit pools)
+template <int EB, int QEB, int LPR, int GT>
 __global__ __launch_bounds__(kAttnThreads) void attn_partial_valu(const AttnParams p) {
   constexpr int EPL = Unpack<EB>::N;       // elements per lane per row
   constexpr int TPL = kWaveSize / LPR;     // token rows per wave-wide load
@@ -123,10 +138,13 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_valu(const AttnPara
 #pragma unroll
   for (int g = 0; g < GT; ++g) {
     const int h = h0 + (g < nheads ? g : 0);
+    // the lane's EPL dims of the query row: EPL * QEB bytes, in 16-byte pieces
     const uint8_t* qp = reinterpret_cast<const uint8_t*>(p.q) +
-                        ((int64_t)seq * p.num_q_heads + h) * D * EB + ck * 16;
+                        (((int64_t)seq * p.num_q_heads + h) * D + ck * EPL) * QEB;
+    constexpr int QN = Unpack<QEB>::N;
     float t[EPL];
-    Unpack<EB>::run(load16(qp), t);
+#pragma unroll
+    for (int c = 0; c < EPL / QN; ++c) Unpack<QEB>::run(load16(qp + c * 16), t + c * QN);
 #pragma unroll
     for (int e = 0; e < EPL; ++e) qf[g][e] = t[e] * p.scale_log2e;
   }
@@ -274,7 +292,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_valu(const AttnPara
     }
     const int h = h0 + g;
     if (single) {
-      const float r = O / L;
+      const float r = O / L * p.v_scale;
       const int64_t o = ((int64_t)seq * p.num_q_heads + h) * D + d;
       if (p.out_is_bf16) reinterpret_cast<uint16_t*>(p.out)[o] = f32_to_bf16_rne(r);
       else reinterpret_cast<float*>(p.out)[o] = r;
@@ -305,51 +323,59 @@ __global__ __launch_bounds__(256) void attn_merge(const AttnParams p) {
       L = fmaf(p.ws_ml[(pr0 + q) * 2 + 1], f, L);
       O = fmaf(p.ws_o[(pr0 + q) * D + d], f, O);
     }
-    const float r = O / L;
+    const float r = O / L * p.v_scale;
     const int64_t o = ((int64_t)seq * p.num_q_heads + h) * D + d;
     if (p.out_is_bf16) reinterpret_cast<uint16_t*>(p.out)[o] = f32_to_bf16_rne(r);
     else reinterpret_cast<float*>(p.out)[o] = r;
   }
 }
 
-template <int EB, int LPR, int GT>
+template <int EB, int QEB, int LPR, int GT>
 hipError_t launch_valu(const AttnParams& p, hipStream_t s) {
   dim3 grid(p.max_partitions, p.num_kv_heads * p.group_tiles, p.batch);
   const size_t lds = sizeof(float) * (kAttnThreads / kWaveSize) * GT * (p.head_dim + 2);
   if (p.ev_begin || p.ev_end)
-    hipExtLaunchKernelGGL((attn_partial_valu<EB, LPR, GT>), grid, dim3(kAttnThreads), lds, s,
+    hipExtLaunchKernelGGL((attn_partial_valu<EB, QEB, LPR, GT>), grid, dim3(kAttnThreads), lds, s,
                           p.ev_begin, p.ev_end, 0, p);
   else
-    hipLaunchKernelGGL((attn_partial_valu<EB, LPR, GT>), grid, dim3(kAttnThreads), lds, s, p);
+    hipLaunchKernelGGL((attn_partial_valu<EB, QEB, LPR, GT>), grid, dim3(kAttnThreads), lds, s, p);
   const hipError_t e = hipGetLastError();
   return e;
 }
 
-template <int EB, int LPR>
+template <int EB, int QEB, int LPR>
 hipError_t launch_valu_g(AttnParams& p, hipStream_t s) {
   const int G = p.group;
-  if (G == 1) { p.group_tiles = 1; return launch_valu<EB, LPR, 1>(p, s); }
-  if (G == 2) { p.group_tiles = 1; return launch_valu<EB, LPR, 2>(p, s); }
-  if (G <= 4) { p.group_tiles = 1; return launch_valu<EB, LPR, 4>(p, s); }
-  p.group_tiles = (G + 7) / 8;
-  return launch_valu<EB, LPR, 8>(p, s);
+  if (G == 1) { p.group_tiles = 1; return launch_valu<EB, QEB, LPR, 1>(p, s); }
+  if (G == 2) { p.group_tiles = 1; return launch_valu<EB, QEB, LPR, 2>(p, s); }
+  // 16 elements per lane with 8-bit pools: four heads per lane fill the registers
+  if (G <= 4 || EB == 1) { p.group_tiles = (G + 3) / 4; return launch_valu<EB, QEB, LPR, 4>(p, s); }
+  if constexpr (EB != 1) {
+    p.group_tiles = (G + 7) / 8;
+    return launch_valu<EB, QEB, LPR, 8>(p, s);
+  }
+  return hipErrorInvalidValue;
 }
 
 }  // namespace
 
 hipError_t launch_attn_decode(const AttnParams& pin, int dtype, hipStream_t s) {
   AttnParams p = pin;
-  const int eb = dtype == PKV_BF16 ? 2 : 4;
+  const int eb = dtype == PKV_BF16 ? 2 : dtype == PKV_F8_E4M3 ? 1 : 4;
   const int row_bytes = p.head_dim * eb;
   hipError_t e = hipErrorInvalidValue;
   if (eb == 2) {
-    if (row_bytes == 128) e = launch_valu_g<2, 8>(p, s);
-    else if (row_bytes == 256) e = launch_valu_g<2, 16>(p, s);
-    else if (row_bytes == 512) e = launch_valu_g<2, 32>(p, s);
+    if (row_bytes == 128) e = launch_valu_g<2, 2, 8>(p, s);
+    else if (row_bytes == 256) e = launch_valu_g<2, 2, 16>(p, s);
+    else if (row_bytes == 512) e = launch_valu_g<2, 2, 32>(p, s);
+  } else if (eb == 1) {   // 8-bit pools, bf16 q
+    if (row_bytes == 128) e = launch_valu_g<1, 2, 8>(p, s);
+    else if (row_bytes == 256) e = launch_valu_g<1, 2, 16>(p, s);
+    else if (row_bytes == 512) e = launch_valu_g<1, 2, 32>(p, s);
   } else {
-    if (row_bytes == 128) e = launch_valu_g<4, 8>(p, s);
-    else if (row_bytes == 256) e = launch_valu_g<4, 16>(p, s);
-    else if (row_bytes == 512) e = launch_valu_g<4, 32>(p, s);
+    if (row_bytes == 128) e = launch_valu_g<4, 4, 8>(p, s);
+    else if (row_bytes == 256) e = launch_valu_g<4, 4, 16>(p, s);
+    else if (row_bytes == 512) e = launch_valu_g<4, 4, 32>(p, s);
   }
   if (e != hipSuccess) return e;
   if (p.max_partitions > 1) {

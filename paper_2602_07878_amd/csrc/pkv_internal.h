@@ -58,7 +58,8 @@ struct AttnParams {
   int32_t prefix_bytes;     // stream kernel: LDS bytes of the tile prefix table
   int32_t streams_per_xcd;  // prefill kernel: (sequence, KV head) streams dealt to one XCD
   int32_t partials_streaming;  // stream kernel: partial rows are stored past the caches (there are more of them than L2 holds)
-  float scale_log2e;        // scale * log2(e)
+  float scale_log2e;        // scale * log2(e) (times the K dequantisation factor of 8-bit pools)
+  float v_scale;            // factor on the output: the V dequantisation factor of 8-bit pools, else 1
   // host side only: optional events recorded right before / after the partial kernel
   hipEvent_t ev_begin, ev_end;
 };

@@ -5,10 +5,10 @@ import numpy as np
 
 def to_device(w, device="cuda:0"):
     import torch
-    if w.dtype == "bf16":
-        conv = lambda a: torch.from_numpy(a.view(np.int16)).to(device).view(torch.bfloat16)
-    else:
-        conv = lambda a: torch.from_numpy(a).to(device)
+    def conv(a):     # uint16 = bf16 bits, uint8 = E4M3 codes (passed as they are), else float32
+        if a.dtype == np.uint16:
+            return torch.from_numpy(a.view(np.int16)).to(device).view(torch.bfloat16)
+        return torch.from_numpy(a).to(device)
     return dict(q=conv(w.q), k_pool=conv(w.k_pool), v_pool=conv(w.v_pool),
                 block_tables=torch.from_numpy(w.block_tables).to(device),
                 context_lens=torch.from_numpy(w.context_lens).to(device))
@@ -29,7 +29,7 @@ def run_hip(w, dev=None, *, partition_tokens=None, out_dtype=None, max_context_l
     mcl = w.max_context_len if max_context_len is None else max_context_len
     binding.paged_decode_attention(dev["q"], dev["k_pool"], dev["v_pool"], dev["block_tables"],
                                    dev["context_lens"], w.scale, out, max_context_len=mcl,
-                                   partition_tokens=pt, flags=flags)
+                                   partition_tokens=pt, flags=flags, k_scale=w.k_scale, v_scale=w.v_scale)
     torch.cuda.synchronize()
     if canary:
         assert torch.all(buf[:pad] == 12345.0) and torch.all(buf[pad + n:] == 12345.0)
@@ -39,4 +39,5 @@ def run_hip(w, dev=None, *, partition_tokens=None, out_dtype=None, max_context_l
 def run_oracle(w):
     import oracle
     return oracle.paged_decode_attention(w.q, w.k_pool, w.v_pool, w.block_tables,
-                                         w.context_lens, w.scale, block_size=w.block_size)
+                                         w.context_lens, w.scale, block_size=w.block_size,
+                                         k_scale=w.k_scale, v_scale=w.v_scale)
