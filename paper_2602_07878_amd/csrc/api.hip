@@ -184,6 +184,7 @@ int32_t pkv::attention_call(const pkv_attn_desc* desc, const void* q, const void
   p.max_partitions = max_partitions_of(desc);
   p.out_is_bf16 = desc->out_dtype == PKV_BF16;
   p.no_mfma = (desc->flags & PKV_ATTN_FLAG_VECTOR_ALU) != 0;
+  p.kv_is_f8 = desc->kv_dtype == PKV_F8_E4M3;
   p.scale_log2e = scale * pool_scale(desc, desc->k_scale) * 1.4426950408889634f;
   p.v_scale = pool_scale(desc, desc->v_scale);
   p.ev_begin = static_cast<hipEvent_t>(ev_begin);

@@ -53,6 +53,7 @@ struct AttnParams {
   int32_t max_partitions;   // P
   int32_t out_is_bf16;
   int32_t no_mfma;          // force the vector-ALU kernel
+  int32_t kv_is_f8;         // the pools hold 8-bit E4M3 codes (q is bf16)
   int32_t tpb_shift;        // log2(block_size / 16) (matrix-core kernel only)
   int32_t chunk_tiles_max;  // stream kernel: most tiles one wavefront takes per chunk (<= 64)
   int32_t prefix_bytes;     // stream kernel: LDS bytes of the tile prefix table

@@ -36,6 +36,16 @@ def test_config2_full():
     assert np.abs(vec - got).max() <= 2e-3
 
 
+def test_config2_with_8_bit_pools_full():
+    """The 8B-shaped batch with an E4M3 KV cache (half the bytes per cached token), as bench.py times it."""
+    w = W.config2_llama8b_f8()
+    got, dev = full_check(w)
+    again = run_hip(w, dev)
+    assert np.array_equal(got, again)
+    vec = run_hip(w, dev, flags=1)
+    assert np.abs(vec - got).max() <= 2e-3
+
+
 def test_config3_fill_state_full():
     w = W.config3_fill()
     assert w.notes["occupancy"] >= 0.949

@@ -48,9 +48,12 @@ def lean_queries(q_bits, w, u):
 
 
 def set_key(w, i, t, vec):
-    """Key of token t of sequence i, all KV heads: vec [Hkv, D]."""
+    """Key of token t of sequence i, all KV heads: vec [Hkv, D] (8-bit pools store vec / k_scale)."""
     blk = w.block_tables[i, t // w.block_size]
-    w.k_pool[blk, :, t % w.block_size, :] = bf16(vec)
+    if w.dtype == "f8":
+        w.k_pool[blk, :, t % w.block_size, :] = W.f32_to_f8e4m3_bits(np.asarray(vec, np.float32) / np.float32(w.k_scale))
+    else:
+        w.k_pool[blk, :, t % w.block_size, :] = bf16(vec)
 
 
 def plant_profile(w, u, kind, step, every=11, first=5):
@@ -155,6 +158,49 @@ def test_decode_constant_vector_added_to_every_key(scale, pt):
             w.k_pool[blk, :, t % 16, :] = bf16(f32(w.k_pool[blk, :, t % 16, :]) + 40.0 * u)
     if scale is not None:
         w.scale = scale
+    check_decode(w, pt)
+
+
+# --------------------------------------------------------------- 8-bit pools (the same kernel family)
+def f8_case(name, seed, lens, Hq=32, Hkv=8):
+    w = W.make_attn_workload(name, seed, dtype="f8", Hq=Hq, Hkv=Hkv, D=128, block_size=16, context_lens=lens,
+                             pool_factor=1.15)
+    w.k_scale = 64.0      # planted keys reach lengths of thousands; the stored codes stay below 448
+    return w
+
+
+@pytest.mark.parametrize("kind", ["up", "down", "mixed"])
+@pytest.mark.parametrize("gap_log2", [9.0, 45.0])
+@pytest.mark.parametrize("pt", [0, 64, 512])
+def test_f8_decode_planted_keys_along_the_query(kind, gap_log2, pt):
+    w = f8_case(f"f8_plant_{kind}_{gap_log2:g}", 322, [700, 1500, 333, 64, 2500, 17, 1, 2049])
+    u = directions(w, 21)
+    w.q = lean_queries(w.q, w, u)
+    plant_profile(w, u, kind, gap_log2 / LOG2_PER_BETA * 1.6 * 1.2, every=29)   # 1.2: room for the 8-bit rounding of the keys
+    check_decode(w, pt)
+
+
+@pytest.mark.parametrize("pt", [0, 64])
+def test_f8_decode_one_key_takes_all_at_every_position(pt):
+    n = 150
+    w = f8_case("f8_onehot", 323, [n] * n, Hq=8, Hkv=8)
+    w.k_scale = 1.0       # (with the other keys 64 times longer the planted one would not always win)
+    u = directions(w, 22)
+    w.q = lean_queries(w.q, w, u)
+    for i in range(n):
+        set_key(w, i, i, 400.0 * u)
+    got = check_decode(w, pt)
+    import torch
+    for i in range(n):
+        codes = torch.from_numpy(np.ascontiguousarray(w.v_pool[w.block_tables[i, i // 16], :, i % 16, :]))
+        v = codes.view(torch.float8_e4m3fn).to(torch.float64).numpy()
+        assert np.abs(got[i] - v).max() <= TOL
+
+
+@pytest.mark.parametrize("pt", [0, 512])
+def test_f8_decode_unit_scale_and_benchmark_batch(pt):
+    w = W.config2_llama8b_f8()
+    w.scale = 1.0
     check_decode(w, pt)
 
 
