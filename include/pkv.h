@@ -218,6 +218,46 @@ int32_t paged_decode_attention_static(const pkv_attn_desc* desc, const void* q,
                                       void* out, void* hip_stream);
 
 /*
+ * A per-step plan for paged_decode_attention (Sec. 4.2: a decode step makes
+ * one attention call per layer, and all of them walk the same block tables
+ * with the same context lengths; only q and the layer's pools differ).  What
+ * every one of those calls would work out again from block_tables and
+ * context_lens -- the tile counts per sequence, the cut of the work into
+ * per-wavefront ranges, the pool offset of every 16-token tile, where each
+ * sequence's split-K partials go -- is written once into `plan` (device memory)
+ * by pkv_attn_plan, and paged_decode_attention_planned reads it instead.  The
+ * cut of the work is the same as without a plan, so are the partials and
+ * their order; the result is bit-reproducible from call to call, bit-identical
+ * to paged_decode_attention's with 8-bit pools, and equal to it up to fp32
+ * rounding with bf16 pools (where the unplanned call has a kernel of its own).
+ *
+ *  pkv_attn_plan_bytes(desc)  size of the plan buffer; 0 when the call for
+ *      `desc` has no use for a plan (not bf16 / 8-bit pools with head_dim 128,
+ *      PKV_ATTN_FLAG_VECTOR_ALU, batch 0, invalid desc): pkv_attn_plan then
+ *      enqueues nothing and the planned call is the ordinary call.
+ *  pkv_attn_plan  enqueues one kernel on hip_stream that reads block_tables and
+ *      context_lens (device) and writes `plan` (>= pkv_attn_plan_bytes bytes,
+ *      16-byte aligned, else PKV_ERR_WORKSPACE / PKV_ERR_ALIGN).  Context
+ *      lengths beyond desc->max_context_len leave the plan marked invalid.
+ *  paged_decode_attention_planned  arguments as paged_decode_attention (same
+ *      workspace size), plus the plan, which it only reads.  desc,
+ *      block_tables and context_lens must be those the plan was made with (and
+ *      the device the same); k_scale, v_scale, out_dtype, q, the pools, scale
+ *      and out may differ from call to call.  A plan made for another geometry,
+ *      or an invalid one, is detected on the device: out is then filled with
+ *      NaN.  Changed table or length contents are not detected.
+ */
+size_t pkv_attn_plan_bytes(const pkv_attn_desc* desc);
+int32_t pkv_attn_plan(const pkv_attn_desc* desc, const int32_t* block_tables,
+                      const int32_t* context_lens, void* plan, size_t plan_bytes,
+                      void* hip_stream);
+int32_t paged_decode_attention_planned(const pkv_attn_desc* desc, const void* plan, size_t plan_bytes,
+                                       const void* q, const void* k_pool, const void* v_pool,
+                                       const int32_t* block_tables, const int32_t* context_lens,
+                                       float scale, void* out, void* workspace,
+                                       size_t workspace_bytes, void* hip_stream);
+
+/*
  * Causal prefill attention of a chunk over the paged cache (Sec. 2.1: masked
  * self-attention, a token attends to itself and to what precedes it; this is
  * the prefill phase and, after a preemption, the re-prefill of Sec. 5.1.2

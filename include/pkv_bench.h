@@ -30,6 +30,14 @@ int32_t paged_decode_attention_timed(const pkv_attn_desc* desc, const void* q,
                                      size_t workspace_bytes, void* hip_stream,
                                      void* ev_kernel_begin, void* ev_kernel_end);
 
+/* The same for paged_decode_attention_planned. */
+int32_t paged_decode_attention_planned_timed(const pkv_attn_desc* desc, const void* plan, size_t plan_bytes,
+                                             const void* q, const void* k_pool, const void* v_pool,
+                                             const int32_t* block_tables, const int32_t* context_lens,
+                                             float scale, void* out, void* workspace,
+                                             size_t workspace_bytes, void* hip_stream,
+                                             void* ev_kernel_begin, void* ev_kernel_end);
+
 /*
  * Bandwidth probes used by the benchmark to measure this machine's streaming
  * ceilings with the same access idiom as the product kernels (16 bytes per

@@ -20,6 +20,8 @@ FLAG_VECTOR_ALU = 1
 
 EXPORTS = [
     "pkv_version", "pkv_init", "pkv_static_scratch_bytes", "paged_decode_attention_static", "pkv_status_string", "pkv_last_hip_error_string", "pkv_attn_partition_tokens", "pkv_attn_workspace_bytes",
+    "pkv_attn_plan_bytes", "pkv_attn_plan", "paged_decode_attention_planned",
+    "paged_decode_attention_planned_timed",
     "paged_decode_attention", "paged_decode_attention_timed", "paged_prefill_attention", "paged_prefill_attention_ws",
     "pkv_prefill_workspace_bytes", "kv_append", "kv_append_chunk", "kv_block_swap",
     "kv_swap_out_host", "kv_swap_in_host",
@@ -92,6 +94,16 @@ def lib() -> ctypes.CDLL:
         L.paged_decode_attention_timed.restype = i32
         L.paged_decode_attention_timed.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp,
                                                    ctypes.c_float, vp, vp, sz, vp, vp, vp]
+        L.pkv_attn_plan_bytes.restype = sz
+        L.pkv_attn_plan_bytes.argtypes = [ctypes.POINTER(AttnDesc)]
+        L.pkv_attn_plan.restype = i32
+        L.pkv_attn_plan.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, sz, vp]
+        L.paged_decode_attention_planned.restype = i32
+        L.paged_decode_attention_planned.argtypes = [ctypes.POINTER(AttnDesc), vp, sz, vp, vp, vp, vp, vp,
+                                                     ctypes.c_float, vp, vp, sz, vp]
+        L.paged_decode_attention_planned_timed.restype = i32
+        L.paged_decode_attention_planned_timed.argtypes = [ctypes.POINTER(AttnDesc), vp, sz, vp, vp, vp, vp, vp,
+                                                           ctypes.c_float, vp, vp, sz, vp, vp, vp]
         L.paged_prefill_attention.restype = i32
         L.paged_prefill_attention.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, vp, i32,
                                               ctypes.c_float, vp, vp]
@@ -220,6 +232,41 @@ def paged_decode_attention(q, k_pool, v_pool, block_tables, context_lens, scale,
         st = L.paged_decode_attention_timed(*args, ctypes.c_void_p(kernel_events[0].cuda_event),
                                             ctypes.c_void_p(kernel_events[1].cuda_event))
     _check(st, "paged_decode_attention")
+    return workspace
+
+
+def attn_plan(desc: AttnDesc, block_tables, context_lens, plan=None, *, stream=None):
+    """Write the per-step plan for `desc`, `block_tables` and `context_lens` (device tensors) into
+    `plan` (a uint8 device tensor; allocated here when None or too small).  Returns the plan tensor."""
+    import torch
+    L = lib()
+    need = int(L.pkv_attn_plan_bytes(ctypes.byref(desc)))
+    if plan is None or plan.numel() * plan.element_size() < need:
+        plan = torch.empty(max(need, 256), dtype=torch.uint8, device=block_tables.device)
+    _check(L.pkv_attn_plan(ctypes.byref(desc), block_tables.data_ptr(), context_lens.data_ptr(), plan.data_ptr(),
+                           plan.numel() * plan.element_size(), _stream_ptr(stream)), "pkv_attn_plan")
+    return plan
+
+
+def paged_decode_attention_planned(desc: AttnDesc, plan, q, k_pool, v_pool, block_tables, context_lens, scale, out, *,
+                                   workspace=None, stream=None, kernel_events=None):
+    """paged_decode_attention with a plan from attn_plan (same desc, tables and lengths).
+    Returns the workspace tensor used."""
+    L = lib()
+    need = int(L.pkv_attn_workspace_bytes(ctypes.byref(desc)))
+    if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
+        workspace = new_workspace(need, q.device, stream=stream)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    args = (ctypes.byref(desc), plan.data_ptr(), plan.numel() * plan.element_size(), q.data_ptr(), k_pool.data_ptr(),
+            v_pool.data_ptr(), block_tables.data_ptr(), context_lens.data_ptr(), float(scale), out.data_ptr(),
+            ws_ptr, ws_bytes, _stream_ptr(stream))
+    if kernel_events is None:
+        st = L.paged_decode_attention_planned(*args)
+    else:
+        st = L.paged_decode_attention_planned_timed(*args, ctypes.c_void_p(kernel_events[0].cuda_event),
+                                                    ctypes.c_void_p(kernel_events[1].cuda_event))
+    _check(st, "paged_decode_attention_planned")
     return workspace
 
 

@@ -134,41 +134,32 @@ size_t pkv_attn_workspace_bytes(const pkv_attn_desc* desc) {
   return (size_t)(ml + (o + 255) / 256 * 256);
 }
 
+size_t pkv_attn_plan_bytes(const pkv_attn_desc* desc) {
+  if (check_attn_desc(desc) != PKV_OK || desc->batch == 0 || !attn_stream_supported(*desc)) return 0;
+  return (size_t)plan_layout(*desc).total();
+}
+
 }  // extern "C"
 
-// The decode-attention call behind every entry point that has it: checks, then launches.
-int32_t pkv::attention_call(const pkv_attn_desc* desc, const void* q, const void* k_pool,
-                            const void* v_pool, const int32_t* block_tables,
-                            const int32_t* context_lens, float scale, void* out, void* workspace,
-                            size_t workspace_bytes, void* hip_stream, void* ev_begin, void* ev_end,
-                            bool static_scratch) {
-  const int32_t st = check_attn_desc(desc);
-  if (st != PKV_OK) return st;
-  if (desc->batch == 0) return PKV_OK;
-  if (!q || !k_pool || !v_pool || !block_tables || !context_lens || !out) return PKV_ERR_NULL;
-  if (!aligned16(q) || !aligned16(k_pool) || !aligned16(v_pool) || !aligned16(out) ||
-      !aligned16(workspace) || (reinterpret_cast<uintptr_t>(block_tables) & 3u) ||
-      (reinterpret_cast<uintptr_t>(context_lens) & 3u))
-    return PKV_ERR_ALIGN;
-  if (!std::isfinite(scale)) return PKV_ERR_SHAPE;
-  const size_t need = pkv_attn_workspace_bytes(desc);
-  if (static_scratch) {
-    // the library's own array takes the place of the caller's workspace; its device address is
-    // asked for only now, after every check that needs no device
-    if (need > static_scratch_bytes()) return PKV_ERR_WORKSPACE;
-    if (need > 0) {
-      const hipError_t e = static_scratch_address(&workspace);
-      if (e != hipSuccess) return hip_status(e);
-    }
-  } else if (need > 0 && (!workspace || workspace_bytes < need)) {
-    return PKV_ERR_WORKSPACE;
-  }
+namespace {
 
+// What of a descriptor a plan depends on, folded into one positive number.
+int32_t plan_key_of(const pkv_attn_desc* d) {
+  const int64_t f[] = {d->batch, d->num_q_heads, d->num_kv_heads, d->head_dim, d->block_size, d->num_pool_blocks,
+                       d->max_blocks_per_seq, d->max_context_len, d->partition_tokens, d->kv_dtype,
+                       d->k_stride_block, d->k_stride_head, d->k_stride_token,
+                       d->v_stride_block, d->v_stride_head, d->v_stride_token, num_cus()};
+  uint64_t h = 0x9E3779B97F4A7C15ull;
+  for (int64_t v : f) {
+    h ^= (uint64_t)v + 0x9E3779B97F4A7C15ull + (h << 6) + (h >> 2);
+    h *= 0xFF51AFD7ED558CCDull;
+  }
+  return (int32_t)((h >> 33) | 1u);
+}
+
+// geometry fields of the launch parameters that the attention call and the plan share
+void fill_geometry(AttnParams& p, const pkv_attn_desc* desc) {
   const int eb = elem_bytes(desc->kv_dtype);
-  AttnParams p;
-  std::memset(&p, 0, sizeof p);
-  p.q = q; p.k_pool = k_pool; p.v_pool = v_pool;
-  p.block_tables = block_tables; p.context_lens = context_lens; p.out = out;
   p.k_stride_block = desc->k_stride_block * eb;
   p.k_stride_head = desc->k_stride_head * eb;
   p.k_stride_token = desc->k_stride_token * eb;
@@ -182,9 +173,81 @@ int32_t pkv::attention_call(const pkv_attn_desc* desc, const void* q, const void
   p.group_tiles = 1;
   p.partition_tokens = partition_tokens_of(desc);
   p.max_partitions = max_partitions_of(desc);
+  p.kv_is_f8 = desc->kv_dtype == PKV_F8_E4M3;
+}
+
+// the plan buffer's parts as launch parameters
+void fill_plan(AttnParams& p, const pkv_attn_desc* desc, const void* plan) {
+  const PlanLayout l = plan_layout(*desc);
+  // (the directory is written by the plan kernel only: the attention call, which has the
+  // plan as read-only memory, reads it through the same field)
+  uint8_t* base = const_cast<uint8_t*>(reinterpret_cast<const uint8_t*>(plan));
+  p.plan_hdr = reinterpret_cast<const int32_t*>(base);
+  p.ws_dir = reinterpret_cast<int32_t*>(base + l.hdr_bytes);
+  p.plan_desc = base + l.hdr_bytes + l.dir_bytes;
+  p.plan_key = plan_key_of(desc);
+  p.plan_tiles_cap = (int32_t)l.tiles_cap;
+}
+
+}  // namespace
+
+extern "C" int32_t pkv_attn_plan(const pkv_attn_desc* desc, const int32_t* block_tables, const int32_t* context_lens,
+                                 void* plan, size_t plan_bytes, void* hip_stream) {
+  const int32_t st = check_attn_desc(desc);
+  if (st != PKV_OK) return st;
+  const size_t need = pkv_attn_plan_bytes(desc);
+  if (need == 0) return PKV_OK;                 // a call that has no use for a plan
+  if (!block_tables || !context_lens || !plan) return PKV_ERR_NULL;
+  if (!aligned16(plan) || (reinterpret_cast<uintptr_t>(block_tables) & 3u) ||
+      (reinterpret_cast<uintptr_t>(context_lens) & 3u))
+    return PKV_ERR_ALIGN;
+  if (plan_bytes < need) return PKV_ERR_WORKSPACE;
+  AttnParams p;
+  std::memset(&p, 0, sizeof p);
+  p.block_tables = block_tables; p.context_lens = context_lens;
+  fill_geometry(p, desc);
+  fill_plan(p, desc, plan);
+  p.chunk_tiles_max = stream_workspace(*desc).chunk_tiles_max;
+  return hip_status(launch_attn_plan(p, static_cast<int32_t*>(plan), static_cast<hipStream_t>(hip_stream)));
+}
+
+// The decode-attention call behind every entry point that has it: checks, then launches.
+int32_t pkv::attention_call(const pkv_attn_desc* desc, const void* q, const void* k_pool,
+                            const void* v_pool, const int32_t* block_tables,
+                            const int32_t* context_lens, float scale, void* out, void* workspace,
+                            size_t workspace_bytes, void* hip_stream, void* ev_begin, void* ev_end,
+                            bool static_scratch, const void* plan, size_t plan_bytes) {
+  const int32_t st = check_attn_desc(desc);
+  if (st != PKV_OK) return st;
+  if (desc->batch == 0) return PKV_OK;
+  if (!q || !k_pool || !v_pool || !block_tables || !context_lens || !out) return PKV_ERR_NULL;
+  if (!aligned16(q) || !aligned16(k_pool) || !aligned16(v_pool) || !aligned16(out) ||
+      !aligned16(workspace) || (reinterpret_cast<uintptr_t>(block_tables) & 3u) ||
+      (reinterpret_cast<uintptr_t>(context_lens) & 3u))
+    return PKV_ERR_ALIGN;
+  if (!std::isfinite(scale)) return PKV_ERR_SHAPE;
+  if (plan && pkv_attn_plan_bytes(desc) == 0) plan = nullptr;     // a call that has no use for a plan
+  if (plan && (!aligned16(plan) || plan_bytes < pkv_attn_plan_bytes(desc))) return aligned16(plan) ? PKV_ERR_WORKSPACE : PKV_ERR_ALIGN;
+  const size_t need = pkv_attn_workspace_bytes(desc);
+  if (static_scratch) {
+    // the library's own array takes the place of the caller's workspace; its device address is
+    // asked for only now, after every check that needs no device
+    if (need > static_scratch_bytes()) return PKV_ERR_WORKSPACE;
+    if (need > 0) {
+      const hipError_t e = static_scratch_address(&workspace);
+      if (e != hipSuccess) return hip_status(e);
+    }
+  } else if (need > 0 && (!workspace || workspace_bytes < need)) {
+    return PKV_ERR_WORKSPACE;
+  }
+
+  AttnParams p;
+  std::memset(&p, 0, sizeof p);
+  p.q = q; p.k_pool = k_pool; p.v_pool = v_pool;
+  p.block_tables = block_tables; p.context_lens = context_lens; p.out = out;
+  fill_geometry(p, desc);
   p.out_is_bf16 = desc->out_dtype == PKV_BF16;
   p.no_mfma = (desc->flags & PKV_ATTN_FLAG_VECTOR_ALU) != 0;
-  p.kv_is_f8 = desc->kv_dtype == PKV_F8_E4M3;
   p.scale_log2e = scale * pool_scale(desc, desc->k_scale) * 1.4426950408889634f;
   p.v_scale = pool_scale(desc, desc->v_scale);
   p.ev_begin = static_cast<hipEvent_t>(ev_begin);
@@ -193,6 +256,7 @@ int32_t pkv::attention_call(const pkv_attn_desc* desc, const void* q, const void
     const StreamWorkspace w = stream_workspace(*desc);
     uint8_t* base = reinterpret_cast<uint8_t*>(workspace);
     p.ws_dir = reinterpret_cast<int32_t*>(base);
+    if (plan) fill_plan(p, desc, plan);      // (the directory is the plan's)
     p.ws_ml = reinterpret_cast<float*>(base + w.dir_bytes);
     p.ws_o = reinterpret_cast<float*>(base + w.dir_bytes + w.ml_bytes);
     p.chunk_tiles_max = w.chunk_tiles_max;
@@ -221,7 +285,15 @@ int32_t paged_decode_attention(const pkv_attn_desc* desc, const void* q, const v
                                const int32_t* context_lens, float scale, void* out,
                                void* workspace, size_t workspace_bytes, void* hip_stream) {
   return attention_call(desc, q, k_pool, v_pool, block_tables, context_lens, scale, out, workspace,
-                        workspace_bytes, hip_stream, nullptr, nullptr, false);
+                        workspace_bytes, hip_stream, nullptr, nullptr, false, nullptr, 0);
+}
+
+int32_t paged_decode_attention_planned(const pkv_attn_desc* desc, const void* plan, size_t plan_bytes, const void* q,
+                                       const void* k_pool, const void* v_pool, const int32_t* block_tables,
+                                       const int32_t* context_lens, float scale, void* out, void* workspace,
+                                       size_t workspace_bytes, void* hip_stream) {
+  return attention_call(desc, q, k_pool, v_pool, block_tables, context_lens, scale, out, workspace,
+                        workspace_bytes, hip_stream, nullptr, nullptr, false, plan, plan_bytes);
 }
 
 int32_t paged_decode_attention_timed(const pkv_attn_desc* desc, const void* q, const void* k_pool,
@@ -230,7 +302,16 @@ int32_t paged_decode_attention_timed(const pkv_attn_desc* desc, const void* q, c
                                      void* workspace, size_t workspace_bytes, void* hip_stream,
                                      void* ev_kernel_begin, void* ev_kernel_end) {
   return attention_call(desc, q, k_pool, v_pool, block_tables, context_lens, scale, out, workspace,
-                        workspace_bytes, hip_stream, ev_kernel_begin, ev_kernel_end, false);
+                        workspace_bytes, hip_stream, ev_kernel_begin, ev_kernel_end, false, nullptr, 0);
+}
+
+int32_t paged_decode_attention_planned_timed(const pkv_attn_desc* desc, const void* plan, size_t plan_bytes, const void* q,
+                                             const void* k_pool, const void* v_pool, const int32_t* block_tables,
+                                             const int32_t* context_lens, float scale, void* out, void* workspace,
+                                             size_t workspace_bytes, void* hip_stream, void* ev_kernel_begin,
+                                             void* ev_kernel_end) {
+  return attention_call(desc, q, k_pool, v_pool, block_tables, context_lens, scale, out, workspace,
+                        workspace_bytes, hip_stream, ev_kernel_begin, ev_kernel_end, false, plan, plan_bytes);
 }
 
 size_t pkv_prefill_workspace_bytes(const pkv_attn_desc* desc, int64_t total_query_tokens,

@@ -42,103 +42,10 @@
 
 #include <hip/hip_ext.h>
 
-#include "pkv_internal.h"
+#include "attn_stream_common.h"
 
 namespace pkv {
 namespace {
-
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-typedef __attribute__((ext_vector_type(2))) float f32x2;
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
-typedef __attribute__((ext_vector_type(2))) int32_t i32x2;
-
-constexpr float kNegBig = -1.0e30f;
-constexpr float kSlack = 8.0f;             // log2 units the reference may lag the true max
-constexpr int kStreamThreads = 512;        // one workgroup of 8 wavefronts per CU
-constexpr int kNW = kStreamThreads / kWaveSize;
-constexpr int kTileBytes = 4096;           // 16 tokens x 256-byte rows
-constexpr int kStages = 2;
-constexpr int kDescBatch = 64;             // tile descriptors per table
-constexpr int kStageBytes = 2 * kTileBytes; // K tile, then V tile
-constexpr int kXchgBytes = 512;            // per-head values passed between lanes
-// per wavefront: ring of (K, V) stages, exchange area, two descriptor tables
-constexpr int kWaveLds = kStages * kStageBytes + kXchgBytes + 2 * kDescBatch * 16;
-constexpr int kStageRow = 132;             // floats per head row when a flush stages O in LDS
-constexpr int kMinGroupTiles = 32;         // tiles per workgroup range below which fewer workgroups work
-constexpr int D = 128;
-
-#define PKV_WAIT_VMCNT(n) \
-  __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (((n) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
-
-__device__ __forceinline__ uint32_t pack_bf16x2_rne(float lo, float hi) {
-  auto cv = [](float f) -> uint32_t {
-    uint32_t u = __builtin_bit_cast(uint32_t, f);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x40u;
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return u >> 16;
-  };
-  return cv(lo) | (cv(hi) << 16);
-}
-
-__device__ __forceinline__ int rfl(int v) { return __builtin_amdgcn_readfirstlane(v); }
-
-typedef const void __attribute__((address_space(1)))* gptr_t;
-typedef void __attribute__((address_space(3)))* lptr_t;
-
-// Chunk schedule.  The tile axis is cut into contiguous ranges, one per workgroup, and each
-// range into ns = 8k chunks whose lengths differ by at most one tile: one chunk per wavefront,
-// or k per wavefront when the caller caps the tokens per partial (wavefront w then takes
-// chunks w, w+8, ...).  Chunk ids grow along the axis without gaps: id = workgroup * ns + local
-// id, every workgroup owning exactly ns of them.
-//
-// Workgroups are dealt to the eight XCDs round-robin, and on this part the odd XCDs finish an
-// equal range 6-7 % later than their even neighbours (seen on every machine tried; which pair
-// of XCDs is ahead varies, that does not).  Of every two consecutive workgroups the even one
-// therefore takes kEvenShare/256 of a fair share and the odd one the rest (measured optimum
-// 268-272 on two machines, +2 % throughput; 276 and more overshoots).
-constexpr int kEvenShare = 268;
-static_assert(kEvenShare >= 224 && kEvenShare <= 288, "the workspace bound allows ranges up to 9/8 of a fair share");
-
-struct ChunkPlan {
-  int lg;      // fair share of a workgroup, in tiles
-  int ns;      // chunks (and chunk ids) per workgroup
-  int first;   // tiles of the even workgroup of a pair
-  bool skew;
-  __device__ __forceinline__ int bound(int g) const {   // first tile of workgroup g's range
-    return skew ? (g >> 1) * 2 * lg + ((g & 1) ? first : 0) : g * lg;
-  }
-  __device__ __forceinline__ int length(int g) const {  // nominal length of that range
-    return skew ? ((g & 1) ? 2 * lg - first : first) : lg;
-  }
-  // first tile (relative to the range) of chunk i of a range of `len` tiles
-  __device__ __forceinline__ int chunk_start(int len, int i) const { return (int)((int64_t)i * len / ns); }
-  __device__ __forceinline__ int chunk_of(int x) const {
-    int g;
-    if (skew) {
-      const int pr = x / (2 * lg);
-      g = 2 * pr + (x - pr * 2 * lg >= first ? 1 : 0);
-    } else {
-      g = x / lg;
-    }
-    const int u = x - bound(g);
-    return g * ns + (int)((((int64_t)u + 1) * ns - 1) / length(g));   // inverse of chunk_start
-  }
-};
-
-__device__ __forceinline__ ChunkPlan plan_chunks(int T, int nwg, int cap) {
-  ChunkPlan pl;
-  pl.lg = max(kMinGroupTiles, (T + nwg - 1) / nwg);
-  pl.skew = kEvenShare != 256 && (nwg & 1) == 0;
-  pl.first = pl.skew ? (kEvenShare * pl.lg) >> 8 : pl.lg;
-  const int longest = pl.skew ? max(pl.first, 2 * pl.lg - pl.first) : pl.lg;
-  const int k = cap > 0 ? (longest + kNW * cap - 1) / (kNW * cap) : 1;
-  pl.ns = kNW * k;
-  return pl;
-}
 
 // GH = query heads accumulated per lane (1, 2, 4 or 8).
 template <int GH>
@@ -577,522 +484,13 @@ __global__ __launch_bounds__(kStreamThreads, 2) void attn_stream_mfma_d128(const
 }
 
 
-// ---------------------------------------------------------------------------------------------
-// The same call with 8-bit (OCP E4M3) K/V pools and a bfloat16 query: half the bytes per cached
-// token (Sec. 4.2: the time model charges sizeof(T) per cached element).
-//
-// Every E4M3 value is a bfloat16 value, so a tile is decoded exactly to the bf16 LDS images of
-// the kernel above and from there on the arithmetic is the same: scores and P V on the matrix
-// cores, lazy reference maximum, bf16 head + remainder of the weights.  What differs is how a
-// tile gets there.  A 16-token tile is 2 KiB per pool, so twice as many tiles have to be in
-// flight for the same bytes: a wavefront keeps the raw bytes of the next FOUR tiles in registers
-// (16-byte loads, 2 x 1 KiB contiguous per pool and tile), decodes the current one with the
-// hardware conversion (two codes per instruction) and writes the bf16 rows into one K and one V
-// image in LDS, swizzled as above; LDS needs no ring, because a wavefront's LDS operations run in
-// order.  The tile loop is flat: a tile descriptor says whether the tile opens or closes a
-// (sequence, pair), so segments, batches of descriptors and chunks need no nested loops, and the
-// lookahead simply walks ahead through the descriptor tables.
-constexpr int kF8ImageBytes = 2 * kTileBytes;   // decoded K image, then decoded V image
-constexpr int kF8Sets = 4;                      // tiles in flight per wavefront (register sets of four 16-byte loads)
-#define PKV_F8_WAIT_OTHER_SETS "s_waitcnt vmcnt(12)"   // 4 * (kF8Sets - 1): the loads of the younger sets may stay out
-static_assert(kF8Sets == 4, "the wait above and the unrolled tile loop are written for four sets");
-constexpr int kF8Tables = 6;                    // descriptor tables: the batch being consumed and up to five after it
-constexpr int kF8WaveLds = kF8ImageBytes + kXchgBytes + kF8Tables * kDescBatch * 16;   // images, exchange area, tables
-
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
-
-// 16 codes (one 16-byte piece of a row) to 16 bf16 values in order: two 16-byte pieces
-__device__ __forceinline__ void decode_f8x16(const u32x4 raw, u32x4& lo, u32x4& hi) {
-  uint32_t o[8];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    o[2 * i] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((int)raw[i], 1.0f, false));
-    o[2 * i + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((int)raw[i], 1.0f, true));
-  }
-  lo = u32x4{o[0], o[1], o[2], o[3]};
-  hi = u32x4{o[4], o[5], o[6], o[7]};
-}
-
-template <int GH>
-__global__ __launch_bounds__(kStreamThreads) void attn_stream_f8_d128(const AttnParams p) {
-  extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-  __shared__ int wave_total[kNW];
-  __shared__ int progress[kNW];   // tiles consumed so far, per wavefront
-
-  const int tid = threadIdx.x;
-  const int lane = tid & (kWaveSize - 1);
-  const int wave = rfl(tid / kWaveSize);
-  const int t16 = lane & 15;   // score layout: token of the tile; V layout: 16-byte piece
-  const int q4 = lane >> 4;    // score layout: head slots 4*q4..+3; V layout: row of a load
-  const int B = p.batch;
-  const int NP = p.num_kv_heads * p.group_tiles;   // (KV head, head sub-group) pairs per sequence
-
-  // ---- set-up: exclusive prefix sums of per-sequence tile counts, in LDS (as above) ---------
-  int* prefix = reinterpret_cast<int*>(lds);       // [B + 1]
-  {
-    if (tid < kNW) progress[tid] = 0;
-    const int per = (B + kStreamThreads - 1) / kStreamThreads;
-    const int i0 = tid * per, i1 = min(B, i0 + per);
-    int sum = 0;
-    for (int i = i0; i < i1; ++i) sum += (max(p.context_lens[i], 0) + kTileTokens - 1) / kTileTokens;
-    int v = sum;
-#pragma unroll
-    for (int off = 1; off < kWaveSize; off <<= 1) {
-      const int t = __shfl_up(v, off, kWaveSize);
-      if (lane >= off) v += t;
-    }
-    if (lane == kWaveSize - 1) wave_total[wave] = v;
-    __syncthreads();
-    int run = v - sum;
-    for (int w = 0; w < wave; ++w) run += wave_total[w];
-    if (tid == 0) prefix[0] = 0;
-    for (int i = i0; i < i1; ++i) {
-      run += (max(p.context_lens[i], 0) + kTileTokens - 1) / kTileTokens;
-      prefix[i + 1] = run;
-    }
-    __syncthreads();
-  }
-  const int T = rfl(prefix[B]) * NP;               // tiles of the whole call
-  if (T == 0) return;
-
-  const ChunkPlan plan = plan_chunks(T, gridDim.x, p.chunk_tiles_max);
-  const int g0 = plan.bound(blockIdx.x);
-  const int gfull = plan.length(blockIdx.x);
-  const int glen = min(gfull, T - g0);
-  if (glen <= 0) return;
-
-  // ---- per-lane, loop-invariant offsets ---------------------------------------------------------
-  // Raw fetch: load h of a tile brings token rows 8h..8h+7, 128 bytes each; this lane takes the
-  // 16-byte piece p8 (dims 16 p8..+15) of row 8h + r8.  Decoded, that is pieces 2 p8 and 2 p8 + 1
-  // of the 256-byte bf16 row, which go to the images with the swizzles of the kernel above:
-  // K row t keeps piece c at slot c ^ t, V row t at slot c ^ 2(t mod 8).
-  const int r8 = lane >> 3, p8 = lane & 7;
-  uint32_t koff[2], voff[2], kwr[2][2], vwr[2][2], krd[4], vrd[8];
-  uint8_t* wlds = lds + p.prefix_bytes + wave * kF8WaveLds;
-  const uint32_t wbase = (uint32_t)(uintptr_t)(lptr_t)wlds;
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    const int tok = 8 * h + r8;
-    koff[h] = (uint32_t)(tok * p.k_stride_token) + (uint32_t)(p8 * 16);
-    voff[h] = (uint32_t)(tok * p.v_stride_token) + (uint32_t)(p8 * 16);
-#pragma unroll
-    for (int e = 0; e < 2; ++e) {
-      const int c = 2 * p8 + e;
-      kwr[h][e] = (uint32_t)(tok * 256 + (((c ^ tok) & 15) * 16));
-      vwr[h][e] = (uint32_t)(kTileBytes + tok * 256 + ((c ^ (2 * (tok & 7))) * 16));
-    }
-  }
-#pragma unroll
-  for (int j = 0; j < 4; ++j) krd[j] = (uint32_t)(t16 * 256 + (((4 * j + q4) ^ t16) * 16));
-  {
-    const int tv = 4 * q4 + (t16 >> 2);
-    const uint32_t vbase = (uint32_t)(tv * 256 + ((tv & 7) << 5) + (t16 & 3) * 8);
-#pragma unroll
-    for (int nb = 0; nb < 8; ++nb) vrd[nb] = (vbase ^ (uint32_t)(nb << 5)) + wbase;
-  }
-  float* xchg = reinterpret_cast<float*>(wlds + kF8ImageBytes);   // 128 floats
-  const uint8_t* kpool = reinterpret_cast<const uint8_t*>(p.k_pool);
-  const uint8_t* vpool = reinterpret_cast<const uint8_t*>(p.v_pool);
-  const int tile_mask = (1 << p.tpb_shift) - 1;
-
-  int tiles_done = 0;
-  float m_ref = kNegBig, l_part = 0.f;
-  f32x4 acc[8];          // O[head 4q4+r][dim 16nb+t16] in acc[nb][r]
-  bf16x8 qfrag[4];
-  u32x4* dtabs = reinterpret_cast<u32x4*>(wlds + kF8ImageBytes + kXchgBytes);   // [kF8Tables][kDescBatch]
-
-  // Tile descriptors as in the kernel above (x, y: byte offset / 16 of the tile's first K / V
-  // row; z: sequence << 8 | pair; w: valid tokens | first-of-pair << 5 | last-of-pair << 6 |
-  // tiles of the pair << 8), `count` of them from axis position xb, one per lane.
-  auto build_desc = [&](int xb, int count, u32x4* tab) {
-    const int x = xb + min(lane, count - 1);
-    const int xq = x / NP;
-    int lo = 0, hi = B;
-    while (hi - lo > 1) {
-      const int mid = (lo + hi) >> 1;
-      if (prefix[mid] <= xq) lo = mid; else hi = mid;
-    }
-    const int seq = lo;
-    const int pstart = prefix[seq];
-    const int tiles = prefix[seq + 1] - pstart;
-    const int rem = x - pstart * NP;
-    const int pp = rem / tiles;
-    const int t = rem - pp * tiles;
-    const int kvh = pp / p.group_tiles;
-    const int n = p.context_lens[seq];
-    const int blk = p.block_tables[(int64_t)seq * p.max_blocks_per_seq + (t >> p.tpb_shift)];
-    const int slot0 = (t & tile_mask) * kTileTokens;
-    u32x4 d;
-    d[0] = (uint32_t)((blk * p.k_stride_block + kvh * p.k_stride_head + slot0 * p.k_stride_token) >> 4);
-    d[1] = (uint32_t)((blk * p.v_stride_block + kvh * p.v_stride_head + slot0 * p.v_stride_token) >> 4);
-    d[2] = (uint32_t)((seq << 8) | pp);
-    const int ntok = min(kTileTokens, n - t * kTileTokens);
-    d[3] = (uint32_t)(ntok | ((t == 0) << 5) | ((t == tiles - 1) << 6) | (tiles << 8));
-    tab[lane] = d;
-  };
-
-  // The raw bytes of the tiles in flight: set s holds K rows in raw[s][0..1], V rows in
-  // raw[s][2..3].  Every global load of the tile loop is issued by hand and waited for by hand:
-  // left to the compiler, the waits it places for the query rows (loaded only where a segment
-  // opens) also wait for the tiles in flight on every path, which takes the lookahead away.
-  // Loads return in order, so a wait that leaves the youngest n loads outstanding completes
-  // everything older; each wait names the registers it completes as in/out operands, so that
-  // nothing that reads them can be moved in front of it.
-  u32x4 raw[kF8Sets][4];
-  u32x4 qnext[4];           // query rows of the segment that opens at tile q_for
-  auto fetch = [&](uint32_t sk, uint32_t sv, auto set_tag) {
-    constexpr int S = decltype(set_tag)::value;
-    const uint8_t* kb = kpool + ((uint64_t)sk << 4);
-    const uint8_t* vb = vpool + ((uint64_t)sv << 4);
-    u32x4(&r)[4] = raw[S];
-    const uint32_t k0 = koff[0], k1 = koff[1], v0 = voff[0], v1 = voff[1];
-    asm volatile(
-        "global_load_dwordx4 %0, %4, %8 nt\n\t"
-        "global_load_dwordx4 %1, %5, %8 nt\n\t"
-        "global_load_dwordx4 %2, %6, %9 nt\n\t"
-        "global_load_dwordx4 %3, %7, %9 nt"
-        : "=&v"(r[0]), "=&v"(r[1]), "=&v"(r[2]), "=&v"(r[3])
-        : "v"(k0), "v"(k1), "v"(v0), "v"(v1), "s"(kb), "s"(vb)
-        : "memory");
-  };
-  // Decode a set into the LDS images.  At this point the loads that may still be outstanding
-  // behind the set's own are those of the other sets, issued one, two and three tiles later.
-  auto stash = [&](auto set_tag) {
-    constexpr int S = decltype(set_tag)::value;
-    u32x4(&r)[4] = raw[S];
-    u32x4(&qn)[4] = qnext;
-    asm volatile(PKV_F8_WAIT_OTHER_SETS
-                 : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]), "+v"(qn[0]), "+v"(qn[1]), "+v"(qn[2]), "+v"(qn[3])
-                 :
-                 : "memory");
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      u32x4 a, b;
-      decode_f8x16(raw[S][h], a, b);
-      *reinterpret_cast<u32x4*>(wlds + kwr[h][0]) = a;
-      *reinterpret_cast<u32x4*>(wlds + kwr[h][1]) = b;
-      decode_f8x16(raw[S][2 + h], a, b);
-      *reinterpret_cast<u32x4*>(wlds + vwr[h][0]) = a;
-      *reinterpret_cast<u32x4*>(wlds + vwr[h][1]) = b;
-    }
-  };
-
-  // Query rows as the B operand of the first product (column t16 is head min(t16, nheads-1) of
-  // the group): four 16-byte loads per lane, in flight until a wait names their registers.
-  auto load_q = [&](u32x4* dst, int sp) {
-    const int seq = sp >> 8, pp = sp & 255;
-    const int kvh = pp / p.group_tiles, gtile = pp - kvh * p.group_tiles;
-    const int h0 = kvh * p.group + gtile * GH;
-    const int nheads = min(GH, p.group - gtile * GH);
-    const int hs = min(t16, nheads - 1);
-    const uint8_t* qp = reinterpret_cast<const uint8_t*>(p.q) +
-                        ((int64_t)seq * p.num_q_heads + h0 + hs) * (D * 2) + q4 * 16;
-    asm volatile(
-        "global_load_dwordx4 %0, %4, off\n\t"
-        "global_load_dwordx4 %1, %4, off offset:64\n\t"
-        "global_load_dwordx4 %2, %4, off offset:128\n\t"
-        "global_load_dwordx4 %3, %4, off offset:192"
-        : "=&v"(dst[0]), "=&v"(dst[1]), "=&v"(dst[2]), "=&v"(dst[3])
-        : "v"(qp)
-        : "memory");
-  };
-  u32x4 qraw[4];            // query rows of the open segment (qfrag below is their operand view)
-
-  // the arithmetic of one decoded tile: as in the kernel above, on the single pair of images
-  auto consume = [&](int ntok) {
-    const bool tail = ntok < kTileTokens;            // wave-uniform
-    f32x4 cfr = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int jj = 0; jj < 4; ++jj) {
-      const bf16x8 kf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(wlds + krd[jj]));
-      cfr = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qfrag[jj], cfr, 0, 0, 0);
-    }
-    float d[4];
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      d[r] = fmaf(cfr[r], p.scale_log2e, -m_ref);
-      if (tail && 4 * q4 + r >= ntok) d[r] = -INFINITY;   // stale slot: may hold NaN codes
-    }
-    const float dmax = fmaxf(fmaxf(d[0], d[1]), fmaxf(d[2], d[3]));
-    if (__builtin_amdgcn_ballot_w64(dmax > kSlack) != 0) {   // wave-uniform, rare after a first tile
-      float s[4];
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        s[r] = cfr[r] * p.scale_log2e;
-        if (tail && 4 * q4 + r >= ntok) s[r] = -INFINITY;
-      }
-      xchg[q4 * 16 + t16] = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
-      const float tm = fmaxf(fmaxf(xchg[t16], xchg[16 + t16]), fmaxf(xchg[32 + t16], xchg[48 + t16]));
-      const float mn = fmaxf(m_ref, tm);
-      const float alpha = __builtin_amdgcn_exp2f(m_ref - mn);
-      m_ref = mn;
-      l_part *= alpha;
-#pragma unroll
-      for (int r = 0; r < 4; ++r) d[r] = s[r] - mn;
-      xchg[64 + t16] = alpha;
-      const f32x4 a = *reinterpret_cast<const f32x4*>(xchg + 64 + 4 * q4);
-#pragma unroll
-      for (int nb = 0; nb < 8; ++nb)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) acc[nb][r] *= a[r];
-    }
-    uint32_t hi[4], lo[4];
-    float psum = 0.f;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const float pw = __builtin_amdgcn_exp2f(d[r]);
-      psum += pw;
-      hi[r] = __builtin_bit_cast(uint32_t, pw);
-      const float rest = pw - __builtin_bit_cast(float, hi[r] & 0xFFFF0000u);   // exact, >= 0
-      lo[r] = __builtin_bit_cast(uint32_t, rest) + 0x8000u;
-    }
-    l_part += psum;
-    const s16x4 p_hi = __builtin_bit_cast(s16x4, u32x2{__builtin_amdgcn_perm(hi[1], hi[0], 0x07060302u),
-                                                       __builtin_amdgcn_perm(hi[3], hi[2], 0x07060302u)});
-    const s16x4 p_lo = __builtin_bit_cast(s16x4, u32x2{__builtin_amdgcn_perm(lo[1], lo[0], 0x07060302u),
-                                                       __builtin_amdgcn_perm(lo[3], lo[2], 0x07060302u)});
-    u32x2 vt[8];
-    asm volatile(
-        "ds_read_b64_tr_b16 %0, %8 offset:%16\n\t"
-        "ds_read_b64_tr_b16 %1, %9 offset:%16\n\t"
-        "ds_read_b64_tr_b16 %2, %10 offset:%16\n\t"
-        "ds_read_b64_tr_b16 %3, %11 offset:%16\n\t"
-        "ds_read_b64_tr_b16 %4, %12 offset:%16\n\t"
-        "ds_read_b64_tr_b16 %5, %13 offset:%16\n\t"
-        "ds_read_b64_tr_b16 %6, %14 offset:%16\n\t"
-        "ds_read_b64_tr_b16 %7, %15 offset:%16\n\t"
-        "s_waitcnt lgkmcnt(0)"
-        : "=&v"(vt[0]), "=&v"(vt[1]), "=&v"(vt[2]), "=&v"(vt[3]), "=&v"(vt[4]), "=&v"(vt[5]),
-          "=&v"(vt[6]), "=&v"(vt[7])
-        : "v"(vrd[0]), "v"(vrd[1]), "v"(vrd[2]), "v"(vrd[3]), "v"(vrd[4]), "v"(vrd[5]), "v"(vrd[6]),
-          "v"(vrd[7]), "n"(kTileBytes)
-        : "memory");
-    s16x4 vf[8];
-    if (tail) {   // V rows past the context: zero, not NaN
-      const uint32_t keep0 = (4 * q4 + 0 < ntok ? 0x0000FFFFu : 0u) | (4 * q4 + 1 < ntok ? 0xFFFF0000u : 0u);
-      const uint32_t keep1 = (4 * q4 + 2 < ntok ? 0x0000FFFFu : 0u) | (4 * q4 + 3 < ntok ? 0xFFFF0000u : 0u);
-#pragma unroll
-      for (int nb = 0; nb < 8; ++nb) { vt[nb][0] &= keep0; vt[nb][1] &= keep1; }
-    }
-#pragma unroll
-    for (int nb = 0; nb < 8; ++nb) vf[nb] = __builtin_bit_cast(s16x4, vt[nb]);
-#pragma unroll
-    for (int nb = 0; nb < 8; ++nb)
-      acc[nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_hi, vf[nb], acc[nb], 0, 0, 0);
-#pragma unroll
-    for (int nb = 0; nb < 8; ++nb)
-      acc[nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_lo, vf[nb], acc[nb], 0, 0, 0);
-    ++tiles_done;
-    if (lane == 0) progress[wave] = tiles_done;
-    if (progress[wave ^ (kNW / 2)] > tiles_done) __builtin_amdgcn_s_setprio(2);
-    else __builtin_amdgcn_s_setprio(0);
-  };
-
-  auto chunk_first = [&](int ci) { return plan.chunk_start(gfull, ci); };
-  auto chunk_valid = [&](int ci) { return ci < plan.ns && chunk_first(ci) < glen; };
-  auto chunk_tiles = [&](int ci) { return min(glen, chunk_first(ci + 1)) - chunk_first(ci); };
-
-  // A wavefront's work is a sequence of batches of up to kDescBatch tiles: the batches of its
-  // first chunk, then those of its next chunk (local ids wave, wave+8, ...).  A ring of
-  // descriptor tables holds the batch being consumed and those after it, far enough ahead that
-  // the fetch cursor, kF8Sets tiles in front of the consumer, always finds its descriptor:
-  // whenever the consumer enters a batch, tables are built until kDescBatch + kF8Sets tiles lie
-  // ahead, or five tables (batches can be as short as one tile), or the work ends.
-  struct Batch {
-    int ci, b0;     // chunk (local id) and first tile of the batch within it
-    int nt, tab;    // tiles of the batch, and which table describes them
-    int ntc, x0;    // tiles of the chunk, axis position of the chunk's first tile
-    bool valid;
-  };
-  auto enter_chunk = [&](Batch& b, int ci) {
-    b.ci = ci;
-    b.b0 = 0;
-    b.valid = chunk_valid(ci);
-    b.ntc = b.valid ? chunk_tiles(ci) : 0;
-    b.x0 = g0 + chunk_first(ci);
-  };
-  auto next_batch = [&](const Batch& b) {
-    Batch n = b;
-    n.b0 = b.b0 + kDescBatch;
-    if (b.valid && n.b0 >= b.ntc) enter_chunk(n, b.ci + kNW);
-    n.nt = n.valid ? min(kDescBatch, n.ntc - n.b0) : 0;
-    n.tab = b.tab == kF8Tables - 1 ? 0 : b.tab + 1;
-    return n;
-  };
-  auto build = [&](const Batch& b) {
-    if (b.valid) build_desc(b.x0 + b.b0, b.nt, dtabs + b.tab * kDescBatch);
-  };
-
-  Batch cb;                                    // the batch being consumed, and the tile in it
-  enter_chunk(cb, wave);
-  if (!cb.valid) return;
-  cb.nt = min(kDescBatch, cb.ntc);
-  cb.tab = 0;
-  build(cb);
-  Batch bb = cb;                               // the last batch whose table is built
-  int tables_ahead = 0, tiles_beyond = 0;      // built batches after cb, and their tiles
-  bool more = true;                            // batches after bb exist
-  auto ensure_ahead = [&]() {
-    while (more && tables_ahead < kF8Tables - 1 && cb.nt + tiles_beyond < kDescBatch + kF8Sets) {
-      const Batch n = next_batch(bb);
-      if (!n.valid) { more = false; break; }
-      build(n);
-      bb = n;
-      ++tables_ahead;
-      tiles_beyond += n.nt;
-    }
-  };
-  Batch fb = cb;                               // the fetch cursor: batch and tile
-  int j = 0, fj = 0;
-  int k = 0;                                   // tiles consumed so far
-  int q_for = -1;                              // the tile whose segment's query waits in qnext
-  int seg_sp = 0, seg_info0 = 0, seg_x = 0;
-
-  using set0 = std::integral_constant<int, 0>;
-  using set1 = std::integral_constant<int, 1>;
-
-  // The tile at the fetch cursor goes in flight into a register set (the wavefront's last tile
-  // once more when the cursor has run off the end: never consumed); if that tile opens a
-  // segment, its query rows go in flight in front of it, unless qnext still holds the query of
-  // the segment that opens at the tile before it.
-  int fk = 0;                                  // number of the tile at the fetch cursor
-  auto fetch_ahead = [&](auto set_tag, const u32x4 fallback, int opened) {   // opened: last tile whose segment has its query
-    u32x4 d2 = fallback;
-    bool opens2 = false;
-    if (fb.valid) {
-      d2 = dtabs[fb.tab * kDescBatch + fj];
-      opens2 = (((int)d2[3] >> 5) & 1) || (fj == 0 && fb.b0 == 0);
-    }
-    if (opens2 && q_for <= opened) {
-      load_q(qnext, rfl((int)d2[2]));
-      q_for = fk;
-    }
-    ++fk;
-    fetch((uint32_t)rfl((int)d2[0]), (uint32_t)rfl((int)d2[1]), set_tag);
-    if (fb.valid && ++fj == fb.nt) {
-      fb = next_batch(fb);
-      fj = 0;
-    }
-  };
-
-  auto tile = [&](auto set_tag) -> bool {
-    const u32x4 dsc = dtabs[cb.tab * kDescBatch + j];   // the same entry for every lane
-    const int sp = rfl((int)dsc[2]), info = rfl((int)dsc[3]);
-    stash(set_tag);
-    if ((j == 0 && cb.b0 == 0) || ((info >> 5) & 1)) {     // the tile opens a segment
-      seg_sp = sp;
-      seg_info0 = info;
-      seg_x = cb.x0 + cb.b0 + j;
-      m_ref = kNegBig;
-      l_part = 0.f;
-#pragma unroll
-      for (int nb = 0; nb < 8; ++nb) acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
-      if (q_for == k) {   // fetched two tiles ago, in front of this tile's bytes: complete since the wait above
-#pragma unroll
-        for (int cidx = 0; cidx < 4; ++cidx) qraw[cidx] = qnext[cidx];
-      } else {            // (only the first two tiles of a wavefront, and segments of a single tile in a row)
-        load_q(qraw, sp);
-        asm volatile("s_waitcnt vmcnt(0)" : "+v"(qraw[0]), "+v"(qraw[1]), "+v"(qraw[2]), "+v"(qraw[3]) : : "memory");
-      }
-#pragma unroll
-      for (int cidx = 0; cidx < 4; ++cidx) qfrag[cidx] = __builtin_bit_cast(bf16x8, qraw[cidx]);
-    }
-    fetch_ahead(set_tag, dsc, k);
-
-    consume(info & 31);
-
-    const bool last = (info >> 6) & 1;
-    const bool chunk_ends_here = cb.b0 + cb.nt == cb.ntc;
-    if (last || (chunk_ends_here && j == cb.nt - 1)) {
-      // ---- flush the open segment (as in the kernel above; O is staged in the image area,
-      // which the next tile's decode overwrites only after these reads: LDS runs in order) ----
-      const int c = blockIdx.x * plan.ns + cb.ci;    // chunk id on the whole axis
-      const int seq = seg_sp >> 8, pp = seg_sp & 255;
-      const int kvh = pp / p.group_tiles, gtile = pp - kvh * p.group_tiles;
-      const int h0 = kvh * p.group + gtile * GH;
-      const int nheads = min(GH, p.group - gtile * GH);
-      const bool first = (seg_info0 >> 5) & 1;
-      const int prank = seq * NP + pp;
-      xchg[q4 * 16 + t16] = l_part;
-      xchg[64 + t16] = m_ref;
-      float* st = reinterpret_cast<float*>(wlds);
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        if (4 * q4 + r < GH) {
-#pragma unroll
-          for (int nb = 0; nb < 8; ++nb) st[(4 * q4 + r) * kStageRow + nb * 16 + t16] = acc[nb][r];
-        }
-      }
-      const int64_t slot = (int64_t)prank + c;
-      const int hh = lane >> 5, piece = lane & 31;
-#pragma unroll
-      for (int g2 = 0; g2 < GH; g2 += 2) {
-        const int g = g2 + hh;
-        if (g < nheads) {
-          const f32x4 o4 = *reinterpret_cast<const f32x4*>(st + g * kStageRow + piece * 4);
-          const float lsum = (xchg[g] + xchg[16 + g]) + (xchg[32 + g] + xchg[48 + g]);
-          if (first && last) {
-            const float inv = (1.0f / lsum) * p.v_scale;
-            const int64_t o = ((int64_t)seq * p.num_q_heads + h0 + g) * D + piece * 4;
-            if (p.out_is_bf16) {
-              i32x2 w;
-              w[0] = (int)pack_bf16x2_rne(o4[0] * inv, o4[1] * inv);
-              w[1] = (int)pack_bf16x2_rne(o4[2] * inv, o4[3] * inv);
-              *reinterpret_cast<i32x2*>(reinterpret_cast<uint16_t*>(p.out) + o) = w;
-            } else {
-              *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(p.out) + o) =
-                  f32x4{o4[0] * inv, o4[1] * inv, o4[2] * inv, o4[3] * inv};
-            }
-          } else {
-            f32x4* const row = reinterpret_cast<f32x4*>(p.ws_o + (slot * GH + g) * D + piece * 4);
-            if (p.partials_streaming) {
-              asm volatile("" ::: "memory");
-              __builtin_nontemporal_store(o4, row);
-              asm volatile("" ::: "memory");
-            } else {
-              *row = o4;
-            }
-            if (piece == 0)
-              *reinterpret_cast<f32x2*>(p.ws_ml + (slot * GH + g) * 2) = f32x2{xchg[64 + g], lsum};
-          }
-        }
-      }
-      if (lane == 0) {
-        if (first && last) {
-          *reinterpret_cast<i32x2*>(p.ws_dir + 2 * (int64_t)prank) = i32x2{0, 1};
-        } else if (first) {
-          const int tiles = seg_info0 >> 8;
-          const int c_last = plan.chunk_of(seg_x + tiles - 1);
-          *reinterpret_cast<i32x2*>(p.ws_dir + 2 * (int64_t)prank) = i32x2{(int)slot, c_last - c + 1};
-        }
-      }
-    }
-    ++k;
-    if (++j == cb.nt) {            // on to the next batch
-      cb = next_batch(cb);
-      j = 0;
-      if (cb.valid) {
-        --tables_ahead;
-        tiles_beyond -= cb.nt;
-        ensure_ahead();
-      }
-    }
-    return cb.valid;
-  };
-
-  using set2 = std::integral_constant<int, 2>;
-  using set3 = std::integral_constant<int, 3>;
-  // the first tiles go in flight together; the tables further ahead are built behind the first
-  fetch_ahead(set0{}, dtabs[0], -1);
-  ensure_ahead();
-  fetch_ahead(set1{}, dtabs[0], -1);
-  fetch_ahead(set2{}, dtabs[0], -1);
-  fetch_ahead(set3{}, dtabs[0], -1);
-  while (tile(set0{}) && tile(set1{}) && tile(set2{}) && tile(set3{})) {
-  }
-}
-
 constexpr int kMergeThreads = 256, kMW = kMergeThreads / kWaveSize;
+
+// Calls with a per-step plan: whether the plan is one for this call (else the output is filled
+// with NaN).
+__device__ __forceinline__ bool plan_ok(const AttnParams& p) {
+  return !p.plan_hdr || p.plan_hdr[kPlanKey] == p.plan_key;
+}
 
 template <int GH>
 __global__ __launch_bounds__(kMergeThreads) void attn_stream_merge(const AttnParams p) {
@@ -1105,6 +503,13 @@ __global__ __launch_bounds__(kMergeThreads) void attn_stream_merge(const AttnPar
   const int64_t prank = ((int64_t)seq * p.num_kv_heads + kvh) * p.group_tiles + gtile;
   const int n = p.context_lens[seq];
   const int64_t o = ((int64_t)seq * p.num_q_heads + h) * D;
+  if (!plan_ok(p)) {                     // block-uniform
+    if (tid < D) {
+      if (p.out_is_bf16) reinterpret_cast<uint16_t*>(p.out)[o + tid] = 0x7FC0;
+      else reinterpret_cast<float*>(p.out)[o + tid] = __builtin_nanf("");
+    }
+    return;
+  }
   if (n <= 0) {                          // block-uniform
     if (tid < D) {
       if (p.out_is_bf16) reinterpret_cast<uint16_t*>(p.out)[o + tid] = 0;
@@ -1162,6 +567,7 @@ __global__ __launch_bounds__(GH * kWaveSize) void attn_stream_merge_lean(const A
   const int seq = prank / NP, pp = prank - seq * NP;
   const int kvh = pp / p.group_tiles, gtile = pp - kvh * p.group_tiles;
   const int lane = threadIdx.x & (kWaveSize - 1), g = threadIdx.x / kWaveSize;
+  const bool ok = plan_ok(p);
   if (gtile * GH + g >= p.group) return;               // wave-uniform
   const int h = kvh * p.group + gtile * GH + g;
   const int64_t o = ((int64_t)seq * p.num_q_heads + h) * D + 2 * lane;
@@ -1169,6 +575,7 @@ __global__ __launch_bounds__(GH * kWaveSize) void attn_stream_merge_lean(const A
     if (p.out_is_bf16) reinterpret_cast<uint32_t*>(p.out)[o / 2] = pack_bf16x2_rne(a, b);
     else *reinterpret_cast<f32x2*>(reinterpret_cast<float*>(p.out) + o) = f32x2{a, b};
   };
+  if (!ok) { store(__builtin_nanf(""), __builtin_nanf("")); return; }
   if (p.context_lens[seq] <= 0) { store(0.f, 0.f); return; }
   const i32x2 de = *reinterpret_cast<const i32x2*>(p.ws_dir + 2 * (int64_t)prank);
   const int count = de[1];
@@ -1207,25 +614,20 @@ __global__ __launch_bounds__(GH * kWaveSize) void attn_stream_merge_lean(const A
 
 template <int GH>
 hipError_t launch(const AttnParams& p, hipStream_t s) {
-  const size_t lds = (size_t)p.prefix_bytes + (size_t)kNW * kWaveLds;
-  {
-    const hipError_t e = prepare_attn_stream();
-    if (e != hipSuccess) return e;
-  }
-  // with events: attached to the dispatch itself, so they carry the kernel's own begin and end
-  if (p.kv_is_f8) {
-    const size_t lds8 = (size_t)p.prefix_bytes + (size_t)kNW * kF8WaveLds;
+  hipError_t e;
+  if (p.kv_is_f8 || p.plan_hdr) {
+    e = launch_attn_flat(p, GH, s);
+  } else {
+    const size_t lds = (size_t)p.prefix_bytes + (size_t)kNW * kWaveLds;
+    if ((e = prepare_attn_stream()) != hipSuccess) return e;
+    // with events: attached to the dispatch itself, so they carry the kernel's own begin and end
     if (p.ev_begin || p.ev_end)
-      hipExtLaunchKernelGGL((attn_stream_f8_d128<GH>), dim3(num_cus()), dim3(kStreamThreads), lds8, s,
+      hipExtLaunchKernelGGL((attn_stream_mfma_d128<GH>), dim3(num_cus()), dim3(kStreamThreads), lds, s,
                             p.ev_begin, p.ev_end, 0, p);
     else
-      hipLaunchKernelGGL((attn_stream_f8_d128<GH>), dim3(num_cus()), dim3(kStreamThreads), lds8, s, p);
-  } else if (p.ev_begin || p.ev_end)
-    hipExtLaunchKernelGGL((attn_stream_mfma_d128<GH>), dim3(num_cus()), dim3(kStreamThreads), lds, s,
-                          p.ev_begin, p.ev_end, 0, p);
-  else
-    hipLaunchKernelGGL((attn_stream_mfma_d128<GH>), dim3(num_cus()), dim3(kStreamThreads), lds, s, p);
-  hipError_t e = hipGetLastError();
+      hipLaunchKernelGGL((attn_stream_mfma_d128<GH>), dim3(num_cus()), dim3(kStreamThreads), lds, s, p);
+    e = hipGetLastError();
+  }
   if (e != hipSuccess) return e;
   if (p.chunk_tiles_max == 0)   // the library's own split: few partials per pair
     hipLaunchKernelGGL((attn_stream_merge_lean<GH>), dim3(p.batch * p.num_kv_heads * p.group_tiles),
@@ -1246,13 +648,13 @@ hipError_t prepare_attn_stream() {
   for (const void* f : {reinterpret_cast<const void*>(&attn_stream_mfma_d128<1>),
                         reinterpret_cast<const void*>(&attn_stream_mfma_d128<2>),
                         reinterpret_cast<const void*>(&attn_stream_mfma_d128<4>),
-                        reinterpret_cast<const void*>(&attn_stream_mfma_d128<8>),
-                        reinterpret_cast<const void*>(&attn_stream_f8_d128<1>),
-                        reinterpret_cast<const void*>(&attn_stream_f8_d128<2>),
-                        reinterpret_cast<const void*>(&attn_stream_f8_d128<4>),
-                        reinterpret_cast<const void*>(&attn_stream_f8_d128<8>)}) {
+                        reinterpret_cast<const void*>(&attn_stream_mfma_d128<8>)}) {
     const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize,
                                              kStreamMaxPrefixBytes + kNW * kWaveLds);
+    if (e != hipSuccess) return e;
+  }
+  {
+    const hipError_t e = prepare_attn_flat();
     if (e != hipSuccess) return e;
   }
   if (slot >= 0) prepared[slot].store(true, std::memory_order_release);
@@ -1319,13 +721,17 @@ StreamWorkspace stream_workspace(const pkv_attn_desc& d) {
   return w;
 }
 
-hipError_t launch_attn_stream(AttnParams& p, hipStream_t s) {
+int stream_geometry(AttnParams& p) {
   p.tpb_shift = 0;
   while ((kTileTokens << p.tpb_shift) < p.block_size) ++p.tpb_shift;
   p.prefix_bytes = ((p.batch + 1) * 4 + 15) / 16 * 16;
   const int gh = stream_heads_per_lane(p.group);
   p.group_tiles = (p.group + gh - 1) / gh;
-  switch (gh) {
+  return gh;
+}
+
+hipError_t launch_attn_stream(AttnParams& p, hipStream_t s) {
+  switch (stream_geometry(p)) {
     case 1: return launch<1>(p, s);
     case 2: return launch<2>(p, s);
     case 4: return launch<4>(p, s);

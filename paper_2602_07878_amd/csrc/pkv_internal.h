@@ -25,6 +25,7 @@ inline int device_slot() {
 
 // once-per-device set-up of the kernels that need it; also run by pkv_init()
 hipError_t prepare_attn_stream();    // attn_stream_mfma.hip
+hipError_t prepare_attn_flat();      // attn_stream_flat.hip
 hipError_t prepare_attn_prefill();   // attn_prefill_mfma.hip
 hipError_t prepare_static_scratch(); // attn_static.hip
 
@@ -43,6 +44,10 @@ struct AttnParams {
   float* ws_ml;   // [B][Hq][P][2]  (running max in log2 units, normaliser)
   float* ws_o;    // [B][Hq][P][D]  un-normalised partial output rows
   int32_t* ws_dir;          // stream kernel: [pairs][2] (first slot, partial count)
+  const int32_t* plan_hdr;  // stream kernel, calls with a per-step plan: its header words, else null
+  const void* plan_desc;    // ... and its tile descriptors, 16 bytes per tile of the axis
+  int32_t plan_key;         // ... and the number that names the call geometry a plan is made for
+  int32_t plan_tiles_cap;   // ... and how many descriptors the plan has room for
   int64_t k_stride_block, k_stride_head, k_stride_token;  // BYTES
   int64_t v_stride_block, v_stride_head, v_stride_token;  // BYTES
   int32_t batch, num_q_heads, num_kv_heads, head_dim;
@@ -78,11 +83,12 @@ struct SwapParams {
 
 // api.hip: checks and launch of the decode-attention call (every entry point that offers it ends
 // here).  static_scratch: the partials go to the library's static device array (attn_static.hip)
-// and `workspace` is ignored.
+// and `workspace` is ignored.  plan: a buffer written by pkv_attn_plan for this descriptor, tables
+// and lengths, or null.
 int32_t attention_call(const pkv_attn_desc* desc, const void* q, const void* k_pool, const void* v_pool,
                        const int32_t* block_tables, const int32_t* context_lens, float scale, void* out,
                        void* workspace, size_t workspace_bytes, void* hip_stream, void* ev_begin, void* ev_end,
-                       bool static_scratch);
+                       bool static_scratch, const void* plan, size_t plan_bytes);
 // attn_static.hip: size of the static scratch array, and its device address on the current device
 size_t static_scratch_bytes();
 hipError_t static_scratch_address(void** ptr);
@@ -96,7 +102,20 @@ struct StreamWorkspace {
 };
 bool attn_stream_supported(const pkv_attn_desc& d);
 StreamWorkspace stream_workspace(const pkv_attn_desc& d);
+int stream_heads_per_lane(int group);
+int stream_geometry(AttnParams& p);   // fills tpb_shift, prefix_bytes and group_tiles; returns the heads per lane
 hipError_t launch_attn_stream(AttnParams& p, hipStream_t s);
+// attn_stream_flat.hip: the streaming kernel for 8-bit pools and for calls with a per-step plan
+// (launch_attn_stream puts the merge kernel behind it), and the kernel that writes a plan.
+// Plan layout: header words, directory [pairs][2] int32, one 16-byte descriptor per tile.
+struct PlanLayout {
+  int64_t hdr_bytes, dir_bytes, desc_bytes;
+  int64_t tiles_cap;         // descriptors the buffer has room for
+  int64_t total() const { return hdr_bytes + dir_bytes + desc_bytes; }
+};
+PlanLayout plan_layout(const pkv_attn_desc& d);
+hipError_t launch_attn_flat(const AttnParams& p, int gh, hipStream_t s);
+hipError_t launch_attn_plan(AttnParams& p, int32_t* plan_hdr, hipStream_t s);
 // swap.hip
 hipError_t launch_swap(const SwapParams& p, hipStream_t s);
 // attn_prefill_mfma.hip

@@ -15,8 +15,9 @@ def to_device(w, device="cuda:0"):
 
 
 def run_hip(w, dev=None, *, partition_tokens=None, out_dtype=None, max_context_len=None,
-            canary=True, flags=0):
-    """Returns float64 numpy [B,Hq,D] from the HIP library (and checks canaries round `out`)."""
+            canary=True, flags=0, planned=False, calls=1):
+    """Returns float64 numpy [B,Hq,D] from the HIP library (and checks canaries round `out`).
+    planned: through pkv_attn_plan + paged_decode_attention_planned, `calls` calls on one plan."""
     import torch
     from paper_2602_07878_amd import binding
     dev = dev or to_device(w)
@@ -27,9 +28,20 @@ def run_hip(w, dev=None, *, partition_tokens=None, out_dtype=None, max_context_l
     out = buf[pad:pad + n].view(w.B, w.Hq, w.D)
     pt = w.partition_tokens if partition_tokens is None else partition_tokens
     mcl = w.max_context_len if max_context_len is None else max_context_len
-    binding.paged_decode_attention(dev["q"], dev["k_pool"], dev["v_pool"], dev["block_tables"],
-                                   dev["context_lens"], w.scale, out, max_context_len=mcl,
-                                   partition_tokens=pt, flags=flags, k_scale=w.k_scale, v_scale=w.v_scale)
+    if planned:
+        desc = binding.attn_desc_for(dev["q"], dev["k_pool"], dev["v_pool"], dev["block_tables"], max_context_len=mcl,
+                                     partition_tokens=pt, out_dtype=odt, flags=flags, k_scale=w.k_scale,
+                                     v_scale=w.v_scale)
+        plan = binding.attn_plan(desc, dev["block_tables"], dev["context_lens"])
+        ws = None
+        for _ in range(calls):
+            ws = binding.paged_decode_attention_planned(desc, plan, dev["q"], dev["k_pool"], dev["v_pool"],
+                                                        dev["block_tables"], dev["context_lens"], w.scale, out,
+                                                        workspace=ws)
+    else:
+        binding.paged_decode_attention(dev["q"], dev["k_pool"], dev["v_pool"], dev["block_tables"],
+                                       dev["context_lens"], w.scale, out, max_context_len=mcl,
+                                       partition_tokens=pt, flags=flags, k_scale=w.k_scale, v_scale=w.v_scale)
     torch.cuda.synchronize()
     if canary:
         assert torch.all(buf[:pad] == 12345.0) and torch.all(buf[pad + n:] == 12345.0)

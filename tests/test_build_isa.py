@@ -36,7 +36,8 @@ def kernel_metadata(isa):
 
 @pytest.mark.skipif(not os.path.exists(HIPCC), reason="needs hipcc")
 @pytest.mark.parametrize("src,kernel,max_vgprs", [("attn_prefill_mfma.hip", "attn_prefill_mfma_d128", 256),
-                                                  ("attn_stream_mfma.hip", "attn_stream_mfma_d128", 256)])
+                                                  ("attn_stream_mfma.hip", "attn_stream_mfma_d128", 256),
+                                                  ("attn_stream_flat.hip", "attn_stream_flat_", 256)])
 def test_attention_kernels_do_not_spill(src, kernel, max_vgprs):
     meta = kernel_metadata(isa_of(src))
     hot = {n: m for n, m in meta.items() if kernel in n}
@@ -47,8 +48,55 @@ def test_attention_kernels_do_not_spill(src, kernel, max_vgprs):
         assert m["vgpr_count"] <= max_vgprs, (n, m)          # two wavefronts per SIMD
 
 
+def registers_named(line):
+    """Vector register numbers an instruction line names (v7, v[8:11])."""
+    regs = set()
+    for m in re.finditer(r"\bv(\d+)\b", line):
+        regs.add(int(m.group(1)))
+    for m in re.finditer(r"\bv\[(\d+):(\d+)\]", line):
+        regs.update(range(int(m.group(1)), int(m.group(2)) + 1))
+    return regs
+
+
+@pytest.mark.skipif(not os.path.exists(HIPCC), reason="needs hipcc")
+def test_registers_that_wait_for_data_in_flight_are_left_alone():
+    """The flat streaming kernels leave loads in flight across several tiles, into registers the
+    compiler must not touch (it may move a value it manages at any join of control flow, and a
+    register moved while its load is in flight takes the old contents along): v174 and up in the
+    8-bit kernels, v238 and up in the bf16 kernels.  Only the kernels' own statements (between
+    the compiler's inline-assembly markers) may name them, and the loads that stay in flight must
+    target exactly them."""
+    isa = isa_of("attn_stream_flat.hip")
+    bodies = re.findall(r"^(_ZN\S*attn_stream_flat_(f8|bf16)_d128\S*):[^\n]*\n(.*?)s_endpgm", isa, re.S | re.M)
+    assert len(bodies) == 12
+    for name, kind, body in bodies:
+        first = 174 if kind == "f8" else 238
+        in_asm = False
+        for line in body.splitlines():
+            if "#ASMSTART" in line:
+                in_asm = True
+            elif "#ASMEND" in line:
+                in_asm = False
+            text = line.split(";")[0]
+            high = {r for r in registers_named(text) if r >= first}
+            if not in_asm:
+                assert not high, (name, line)
+            elif re.search(r"global_load_dwordx4 v\[\d+:\d+\], v\d+, s\[", text):
+                dest = re.search(r"global_load_dwordx4 (v\[\d+:\d+\]),", text).group(1)
+                assert min(registers_named(dest)) >= first, (name, line)     # tile bytes
+            elif re.search(r"global_load_dwordx4 v\[\d+:\d+\], v\[\d+:\d+\], off", text):
+                dest = min(registers_named(re.search(r"global_load_dwordx4 (v\[\d+:\d+\]),", text).group(1)))
+                assert dest >= 238 or "s_waitcnt vmcnt(0)" in body[body.index(line):body.index(line) + 400], (name, line)
+
+
 @pytest.mark.skipif(not os.path.exists(HIPCC), reason="needs hipcc")
 def test_cache_policy_hints_survive():
+    flat = isa_of("attn_stream_flat.hip")
+    # tiles are streamed past L2; a plan's descriptors are not (every layer call reads them again)
+    lds_loads = re.findall(r"global_load_lds_dwordx4[^\n]*", flat)
+    assert sum(" nt" in l for l in lds_loads) >= 4 * 16 and any(" nt" not in l for l in lds_loads)
+    raw_loads = re.findall(r"global_load_dwordx4 v\[(?:1[7-9]\d|2[0-3]\d):\d+\], v\d+, s\[[^\n]*", flat)   # into v170..v239
+    assert len(raw_loads) >= 8 * 32 and all(" nt" in l for l in raw_loads)
     stream = isa_of("attn_stream_mfma.hip")
     lds_loads = re.findall(r"global_load_lds_dwordx4[^\n]*", stream)
     assert lds_loads and all(" nt" in l for l in lds_loads)              # K/V are read once: streamed past L2
