@@ -26,6 +26,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 STREAM_KERNEL = "attn_stream_mfma_d128<4>"   # the kernel that streams K and V for the timed workload
+PLAN_EVERY = 32   # layer calls that share one plan: the decoder layers of the 8B model (Sec. 4.2)
 
 
 def log(*a):
@@ -48,10 +49,12 @@ def upload_attn(w, layers, torch):
                 cl=torch.from_numpy(w.context_lens).to(dev))
 
 
-def time_attention(w, d, steps, warmup, torch, binding, kernel_events=False):
+def time_attention(w, d, steps, warmup, torch, binding, kernel_events=False, planned=False):
     """Returns (out, ms per call, wall ms per call, sorted ms of every launch of the K/V-streaming kernel).
     With kernel_events, every call also records an event right before and right after that
-    kernel (paged_decode_attention_timed), on the stream the kernels run on."""
+    kernel (paged_decode_attention_timed), on the stream the kernels run on.  planned: the calls
+    go through paged_decode_attention_planned, and every PLAN_EVERY-th call is preceded by
+    pkv_attn_plan, inside the timed region (a decode step plans once and calls once per layer)."""
     out = torch.empty(w.B, w.Hq, w.D, dtype=torch.float32, device="cuda:0")
     desc = binding.attn_desc_for(d["q"], d["ks"][0], d["vs"][0], d["bt"],
                                  max_context_len=w.max_context_len,
@@ -67,10 +70,18 @@ def time_attention(w, d, steps, warmup, torch, binding, kernel_events=False):
             a.record()
             b.record()
 
+    plan = binding.attn_plan(desc, d["bt"], d["cl"]) if planned else None
+
     def step(i, ke=None):
-        binding.paged_decode_attention(d["q"], d["ks"][i % L], d["vs"][i % L], d["bt"], d["cl"],
-                                       w.scale, out, max_context_len=w.max_context_len,
-                                       workspace=ws, desc=desc, kernel_events=ke)
+        if planned:
+            if i % PLAN_EVERY == 0:
+                binding.attn_plan(desc, d["bt"], d["cl"], plan)
+            binding.paged_decode_attention_planned(desc, plan, d["q"], d["ks"][i % L], d["vs"][i % L], d["bt"],
+                                                   d["cl"], w.scale, out, workspace=ws, kernel_events=ke)
+        else:
+            binding.paged_decode_attention(d["q"], d["ks"][i % L], d["vs"][i % L], d["bt"], d["cl"],
+                                           w.scale, out, max_context_len=w.max_context_len,
+                                           workspace=ws, desc=desc, kernel_events=ke)
 
     for i in range(warmup):
         step(i)
@@ -96,7 +107,8 @@ def source_fingerprint():
     import hashlib
     csrc = os.path.join(ROOT, "paper_2602_07878_amd", "csrc")
     h = hashlib.sha256()
-    h.update(open(os.path.join(csrc, "attn_stream_mfma.hip"), "rb").read())
+    for name in ("attn_stream_flat.hip", "attn_stream_common.h", "attn_stream_mfma.hip"):   # (the last holds the merge)
+        h.update(open(os.path.join(csrc, name), "rb").read())
     head = open(os.path.join(csrc, "pkv_internal.h")).read()
     end = head.index("};", head.index("struct AttnParams {")) + 2
     h.update(head[:end].encode())
@@ -598,6 +610,9 @@ def main():
     # markers per call cost a few microseconds, which is why `value` does not come from it.
     out, ms, wall_ms, _ = time_attention(w, d, args.steps, args.warmup, torch, binding)
     _, ms_ev, _, kern = time_attention(w, d, args.steps, 4, torch, binding, kernel_events=True)
+    # the same calls with a per-step plan, written once per PLAN_EVERY calls inside the timed region
+    out_p, ms_p, _, _ = time_attention(w, d, args.steps, args.warmup, torch, binding, planned=True)
+    _, _, _, kern_p = time_attention(w, d, args.steps, 4, torch, binding, kernel_events=True, planned=True)
     kern_ms = sum(kern) / len(kern)
     pct = lambda q: kern[min(len(kern) - 1, int(q * len(kern)))] * 1e3
     gbps = w.kv_bytes / ms / 1e6
@@ -627,6 +642,13 @@ def main():
                      "timed_region": f"second pass of {args.steps} steps with an event before and after "
                                      f"each launch ({ms_ev * 1e3:.1f} us per call in that pass)"},
     }
+    kp = sum(kern_p) / len(kern_p)
+    result["with_plan"] = {"ms": ms_p, "kv_GBps": w.kv_bytes / ms_p / 1e6, "frac_hbm_peak": w.kv_bytes / ms_p / 1e6 / HBM_PEAK_GBS,
+                           "plan": f"pkv_attn_plan once per {PLAN_EVERY} calls, inside the timed region",
+                           "kernel": "attn_stream_flat_bf16_d128<4>", "kernel_us": kp * 1e3,
+                           "kernel_GBps": w.kv_bytes / kp / 1e6, "kernel_frac": w.kv_bytes / kp / 1e6 / HBM_PEAK_GBS,
+                           "max_abs_diff_to_unplanned": float((out - out_p).abs().max())}
+    log(f"[bench] with a plan: {result['with_plan']}")
     result["kv_append"] = time_append(w, d, torch, binding)
     log(f"[bench] append ahead of attention: {result['kv_append']}")
     result["ceilings"] = probe_ceilings(torch, binding)
@@ -674,12 +696,15 @@ def main():
         t = time.time()
         w8 = W.config2_llama8b_f8()
         d8 = upload_attn(w8, args.layers, torch)
-        out8, ms8, _, k8s = time_attention(w8, d8, 100, 10, torch, binding, kernel_events=True)
-        k8 = sum(k8s) / len(k8s)
+        out8u, ms8u, _, k8us = time_attention(w8, d8, 128, 32, torch, binding, kernel_events=True)
+        out8, ms8, _, k8s = time_attention(w8, d8, 128, 32, torch, binding, kernel_events=True, planned=True)
+        k8, k8u = sum(k8s) / len(k8s), sum(k8us) / len(k8us)
         g8 = w8.kv_bytes / ms8 / 1e6
         f8 = {"ms": ms8, "kv_GBps": g8, "frac_hbm_peak": g8 / HBM_PEAK_GBS, "kernel_ms": k8,
               "context_tokens": w8.total_tokens, "kv_bytes_per_call": w8.kv_bytes, "bytes_per_token": 2 * w8.Hkv * w8.D,
-              "kv_tokens_per_s": w8.total_tokens / (ms8 * 1e-3)}
+              "kv_tokens_per_s": w8.total_tokens / (ms8 * 1e-3),
+              "plan": f"pkv_attn_plan once per {PLAN_EVERY} calls, inside the timed region",
+              "without_plan": {"ms": ms8u, "kernel_ms": k8u, "same_bits": bool((out8 == out8u).all())}}
         if not args.no_cpu:
             import oracle
             ref8 = oracle.paged_decode_attention(w8.q, w8.k_pool, w8.v_pool, w8.block_tables, w8.context_lens,

@@ -34,6 +34,10 @@ def test_config2_full():
     assert np.array_equal(got, again)                 # bit-reproducible launch to launch
     vec = run_hip(w, dev, flags=1)                    # the vector-ALU kernel on the same inputs
     assert np.abs(vec - got).max() <= 2e-3
+    ref = run_oracle(w)
+    planned = run_hip(w, dev, planned=True, calls=2)  # with a per-step plan, as bench.py times it
+    assert np.abs(planned - ref).max() <= 2e-3
+    assert np.array_equal(planned, run_hip(w, dev, planned=True))
 
 
 def test_config2_with_8_bit_pools_full():
@@ -44,12 +48,14 @@ def test_config2_with_8_bit_pools_full():
     assert np.array_equal(got, again)
     vec = run_hip(w, dev, flags=1)
     assert np.abs(vec - got).max() <= 2e-3
+    assert np.array_equal(got, run_hip(w, dev, planned=True))     # same kernel code with a plan: same bits
 
 
 def test_config3_fill_state_full():
     w = W.config3_fill()
     assert w.notes["occupancy"] >= 0.949
-    full_check(w)
+    got, dev = full_check(w)
+    assert np.abs(run_hip(w, dev, planned=True) - got).max() <= 1e-5
 
 
 def test_config5_long_context_full_as_configured_and_auto_split():
@@ -58,6 +64,7 @@ def test_config5_long_context_full_as_configured_and_auto_split():
     got, dev = full_check(w)                          # 512-token partials, as configured
     auto = run_hip(w, dev, partition_tokens=0)        # library-chosen split
     assert np.abs(auto - got).max() <= 2e-3
+    assert np.abs(run_hip(w, dev, planned=True) - got).max() <= 1e-5
 
 
 def test_config4_swap_full_size_round_trip():
