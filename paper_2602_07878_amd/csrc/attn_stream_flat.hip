@@ -145,7 +145,11 @@ __device__ __forceinline__ void flat_body(const AttnParams& p) {
   // 8-bit pools.  Raw fetch: load h of a tile brings token rows 8h..8h+7, 128 bytes each; this
   // lane takes the 16-byte piece p8 (dims 16 p8..+15) of row 8h + r8.  Decoded, that is pieces
   // 2 p8 and 2 p8 + 1 of the 256-byte bf16 row, which go to the images with the swizzles of the
-  // bf16 kernel: K row t keeps piece c at slot c ^ t, V row t at slot c ^ 2(t mod 8).
+  // bf16 kernel, K row t keeps piece c at slot c ^ t, and a V swizzle of its own: V row t keeps
+  // piece c at slot c ^ 2(t mod 8) ^ (t mod 2).  (The last term swaps the halves of a 32-byte
+  // unit, which the transposing reads take whole.  Without it the sixteen lanes that the LDS
+  // serves together, two rows of eight pieces, would write only the eight even or the eight odd
+  // slots: every V write of the decode a two-way bank conflict.)
   // bf16 pools.  Load j of a tile brings token rows 4j..4j+3 straight to LDS slot (j, lane); the
   // piece of row 4j + q4 this lane fetches fixes the same swizzles on the global side.
   uint32_t koff[4], voff[4], kwr[2][2], vwr[2][2], krd[4], vrd[8];
@@ -160,7 +164,7 @@ __device__ __forceinline__ void flat_body(const AttnParams& p) {
       for (int e = 0; e < 2; ++e) {
         const int c = 2 * p8 + e;
         kwr[h][e] = (uint32_t)(tok * 256 + (((c ^ tok) & 15) * 16));
-        vwr[h][e] = (uint32_t)(kTileBytes + tok * 256 + ((c ^ (2 * (tok & 7))) * 16));
+        vwr[h][e] = (uint32_t)(kTileBytes + tok * 256 + ((c ^ (2 * (tok & 7)) ^ (tok & 1)) * 16));
       }
     }
   } else {
@@ -168,7 +172,7 @@ __device__ __forceinline__ void flat_body(const AttnParams& p) {
     for (int j = 0; j < 4; ++j) {
       const int tok = 4 * j + q4;
       koff[j] = (uint32_t)(tok * p.k_stride_token) + (uint32_t)((t16 ^ tok) * 16);
-      voff[j] = (uint32_t)(tok * p.v_stride_token) + (uint32_t)((t16 ^ (2 * (tok & 7))) * 16);
+      voff[j] = (uint32_t)(tok * p.v_stride_token) + (uint32_t)((t16 ^ (2 * (tok & 7)) ^ (tok & 1)) * 16);
     }
   }
 #pragma unroll
@@ -177,7 +181,7 @@ __device__ __forceinline__ void flat_body(const AttnParams& p) {
     // second product, output dims 16nb..16nb+15: the transposing read hands lane i of a 16-lane
     // group element (i mod 4) of the 8-byte pieces addressed by lanes i/4, 4+i/4, 8+i/4, 12+i/4
     const int tv = 4 * q4 + (t16 >> 2);
-    const uint32_t vbase = (uint32_t)(tv * 256 + ((tv & 7) << 5) + (t16 & 3) * 8);
+    const uint32_t vbase = (uint32_t)(tv * 256 + ((((tv & 7) << 5) | ((tv & 1) << 4)) ^ ((t16 & 3) * 8)));
 #pragma unroll
     for (int nb = 0; nb < 8; ++nb) vrd[nb] = (vbase ^ (uint32_t)(nb << 5)) + wbase;
   }
@@ -281,13 +285,17 @@ __device__ __forceinline__ void flat_body(const AttnParams& p) {
     lo = u32x4{o0, o1, o2, o3};                                                       \
     hi = u32x4{o4, o5, o6, o7};                                                       \
   }
-  // The tile of a set is complete once only the loads of the tiles behind it are outstanding
-  // (8-bit: three younger sets of four loads; bf16: the one younger stage of eight loads, and
-  // query rows that were sent behind it).
-  auto arrive = [&](auto set_tag, bool q_behind) {
+  // The tile of a set is complete once only the loads of the tiles sent after it are outstanding:
+  // `younger` of them (8-bit: up to three sets of four loads; bf16: at most the other stage's
+  // eight loads, and query rows that were sent behind it).  Anything else that is on its way
+  // (query rows, a plan's descriptors) only makes such a wait stricter.
+  auto arrive = [&](auto set_tag, int younger, bool q_behind) {
     constexpr int S = decltype(set_tag)::value;
     if constexpr (KV8) {
-      asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+      if (younger >= 3) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+      else if (younger == 2) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+      else if (younger == 1) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+      else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       // decode into the LDS images
       u32x4 a0, b0, a1, b1, a2, b2, a3, b3;
 #define PKV_DECODE_SET(K0, K1, K2, K3, K4, K5, K6, K7, V0, V1, V2, V3, V4, V5, V6, V7) \
@@ -318,7 +326,8 @@ __device__ __forceinline__ void flat_body(const AttnParams& p) {
       *reinterpret_cast<u32x4*>(wlds + vwr[1][0]) = a3;
       *reinterpret_cast<u32x4*>(wlds + vwr[1][1]) = b3;
     } else {
-      if (q_behind) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+      if (younger == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      else if (q_behind) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
       else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
     }
   };
@@ -591,34 +600,30 @@ __device__ __forceinline__ void flat_body(const AttnParams& p) {
   using set2 = std::integral_constant<int, 2>;
   using set3 = std::integral_constant<int, 3>;
 
-  // The tile at the fetch cursor goes in flight (the wavefront's last tile once more when the
-  // cursor has run off the end: never consumed).  If that tile opens a segment, its query rows
-  // go in flight with it, unless qnext still holds the query of a segment not yet opened: in
-  // front of the tile for 8-bit pools, behind it for bf16 pools (where the wait for the tile
-  // before it must not have to wait for them).
-  auto fetch_ahead = [&](auto set_tag, const u32x4 fallback, int opened) {   // opened: last tile whose segment has its query
-    u32x4 d2 = fallback;
-    bool opens2 = false;
-    if (fvalid) {
-      d2 = dtabs[(fn % kTables) * BT + fj];
-      opens2 = ((int)d2[3] >> 7) & 1;
-    }
+  // The tile at the fetch cursor goes in flight (nothing, once the cursor has run off the end of
+  // the wavefront's work).  If that tile opens a segment, its query rows go in flight with it,
+  // unless v[238:253] still hold the query of a segment not yet opened: in front of the tile for
+  // 8-bit pools, behind it for bf16 pools (where the wait for the tile before it must not have
+  // to wait for them).
+  auto fetch_ahead = [&](auto set_tag, int opened) {   // opened: last tile whose segment has its query
+    q_late = false;
+    if (!fvalid) return;
+    const u32x4 d2 = dtabs[(fn % kTables) * BT + fj];
+    const bool opens2 = ((int)d2[3] >> 7) & 1;
     const bool with_q = opens2 && q_for <= opened;
     if (KV8 && with_q) load_q_ahead(rfl((int)d2[2]));
     fetch((uint32_t)rfl((int)d2[0]), (uint32_t)rfl((int)d2[1]), set_tag);
     if (!KV8 && with_q) load_q_ahead(rfl((int)d2[2]));
     if (with_q) q_for = fk;
     q_late = !KV8 && with_q;
-    if (fvalid) {
-      ++fk;
-      if (++fj == fnt) {             // on to the next batch, which may have to be described first
-        if (need(fn + 1)) {
-          ++fn;
-          fnt = rec(fn, 2);
-          fj = 0;
-        } else {
-          fvalid = false;
-        }
+    ++fk;
+    if (++fj == fnt) {               // on to the next batch, which may have to be described first
+      if (need(fn + 1)) {
+        ++fn;
+        fnt = rec(fn, 2);
+        fj = 0;
+      } else {
+        fvalid = false;
       }
     }
   };
@@ -628,8 +633,8 @@ __device__ __forceinline__ void flat_body(const AttnParams& p) {
     using img = std::integral_constant<int, KV8 ? 0 : S>;
     const u32x4 dsc = dtabs[(cn % kTables) * BT + j];   // the same entry for every lane
     const int sp = rfl((int)dsc[2]), info = rfl((int)dsc[3]);
-    if constexpr (!KV8) fetch_ahead(std::integral_constant<int, 1 - (S & 1)>{}, dsc, k - 1);
-    arrive(set_tag, q_late);
+    if constexpr (!KV8) fetch_ahead(std::integral_constant<int, 1 - (S & 1)>{}, k - 1);
+    arrive(set_tag, fk - 1 - k, q_late);
     if ((info >> 7) & 1) {                                 // the tile opens a segment
       seg_sp = sp;
       seg_info0 = info;
@@ -643,7 +648,7 @@ __device__ __forceinline__ void flat_body(const AttnParams& p) {
 #pragma unroll
       for (int cidx = 0; cidx < 4; ++cidx) qfrag[cidx] = __builtin_bit_cast(bf16x8, qraw[cidx]);
     }
-    if constexpr (KV8) fetch_ahead(set_tag, dsc, k);
+    if constexpr (KV8) fetch_ahead(set_tag, k);
 
     consume(info & 31, img{});
 
@@ -727,21 +732,19 @@ __device__ __forceinline__ void flat_body(const AttnParams& p) {
 
   // the first tiles go in flight together; the tables further ahead are built behind the first
   if constexpr (KV8) {
-    fetch_ahead(set0{}, dtabs[0], -1);
+    fetch_ahead(set0{}, -1);
     ensure_ahead();
-    fetch_ahead(set1{}, dtabs[0], -1);
-    fetch_ahead(set2{}, dtabs[0], -1);
-    fetch_ahead(set3{}, dtabs[0], -1);
+    fetch_ahead(set1{}, -1);
+    fetch_ahead(set2{}, -1);
+    fetch_ahead(set3{}, -1);
     while (tile(set0{}) && tile(set1{}) && tile(set2{}) && tile(set3{})) {
     }
   } else {
-    fetch_ahead(set0{}, dtabs[0], -1);
-    q_late = false;               // (the first wait of the loop covers them: they are older than its tile)
+    fetch_ahead(set0{}, -1);
     ensure_ahead();
     while (tile(set0{}) && tile(set1{})) {
     }
   }
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // (tiles fetched past the end are still on their way into registers or LDS)
 }
 
 // The register budgets: on this target the attribute counts in units of two registers, so 87
@@ -870,10 +873,9 @@ hipError_t launch_flat_gh(const AttnParams& p, hipStream_t s) {
   return launch_flat_kernel(attn_stream_flat_bf16_d128<GH>, (size_t)kNW * flat_wave_lds<false>(), p, s);
 }
 
-constexpr int kFlatLdsMax = kStreamMaxPrefixBytes + kNW * flat_wave_lds<true>() > kNW * flat_wave_lds<false>()
-                                ? kStreamMaxPrefixBytes + kNW * flat_wave_lds<true>()
-                                : kNW * flat_wave_lds<false>();
-static_assert(kFlatLdsMax <= 160 * 1024, "one workgroup per CU has 160 KiB of LDS");
+constexpr int kFlatLdsMax = kStreamMaxPrefixBytes + kNW * (flat_wave_lds<true>() > flat_wave_lds<false>() ? flat_wave_lds<true>()
+                                                                                                           : flat_wave_lds<false>());
+static_assert(kFlatLdsMax + 2 * kNW * 4 <= 160 * 1024, "one workgroup per CU has 160 KiB of LDS");
 
 template <int GH>
 hipError_t prepare_gh() {
