@@ -502,6 +502,7 @@ __global__ __launch_bounds__(kMergeThreads) void attn_stream_merge(const AttnPar
   const int gtile = gi / GH, g = gi - gtile * GH;
   const int64_t prank = ((int64_t)seq * p.num_kv_heads + kvh) * p.group_tiles + gtile;
   const int n = p.context_lens[seq];
+  const i32x2 de = *reinterpret_cast<const i32x2*>(p.ws_dir + 2 * prank);   // (requested with the length, not behind it)
   const int64_t o = ((int64_t)seq * p.num_q_heads + h) * D;
   if (!plan_ok(p)) {                     // block-uniform
     if (tid < D) {
@@ -517,7 +518,6 @@ __global__ __launch_bounds__(kMergeThreads) void attn_stream_merge(const AttnPar
     }
     return;
   }
-  const i32x2 de = *reinterpret_cast<const i32x2*>(p.ws_dir + 2 * prank);
   const int count = de[1];
   if (count <= 1) return;                // finished by the stream kernel (block-uniform)
   const int64_t s0 = de[0];
@@ -567,6 +567,10 @@ __global__ __launch_bounds__(GH * kWaveSize) void attn_stream_merge_lean(const A
   const int seq = prank / NP, pp = prank - seq * NP;
   const int kvh = pp / p.group_tiles, gtile = pp - kvh * p.group_tiles;
   const int lane = threadIdx.x & (kWaveSize - 1), g = threadIdx.x / kWaveSize;
+  // everything the decisions below depend on is requested at once (the kernel is a chain of
+  // dependent loads; the directory entry exists for every pair, also for empty contexts)
+  const int n = p.context_lens[seq];
+  const i32x2 de = *reinterpret_cast<const i32x2*>(p.ws_dir + 2 * (int64_t)prank);
   const bool ok = plan_ok(p);
   if (gtile * GH + g >= p.group) return;               // wave-uniform
   const int h = kvh * p.group + gtile * GH + g;
@@ -576,8 +580,7 @@ __global__ __launch_bounds__(GH * kWaveSize) void attn_stream_merge_lean(const A
     else *reinterpret_cast<f32x2*>(reinterpret_cast<float*>(p.out) + o) = f32x2{a, b};
   };
   if (!ok) { store(__builtin_nanf(""), __builtin_nanf("")); return; }
-  if (p.context_lens[seq] <= 0) { store(0.f, 0.f); return; }
-  const i32x2 de = *reinterpret_cast<const i32x2*>(p.ws_dir + 2 * (int64_t)prank);
+  if (n <= 0) { store(0.f, 0.f); return; }
   const int count = de[1];
   if (count <= 1) return;                               // finished by the stream kernel
   const int64_t s0 = de[0];
