@@ -142,17 +142,23 @@ __device__ __forceinline__ void flat_body(const AttnParams& p) {
   // ---- per-lane, loop-invariant offsets ---------------------------------------------------------
   uint8_t* wlds = lds + (PLANNED ? 0 : p.prefix_bytes) + wave * kWaveBytes;
   const uint32_t wbase = (uint32_t)(uintptr_t)(lptr_t)wlds;
+  // bf16 pools.  Load j of a tile brings token rows 4j..4j+3 straight to LDS slot (j, lane); the
+  // piece of row 4j + q4 this lane fetches fixes the swizzles of the bf16 kernel on the global
+  // side: K row t keeps 16-byte piece c at slot c ^ t, V row t at slot c ^ 2(t mod 8).
   // 8-bit pools.  Raw fetch: load h of a tile brings token rows 8h..8h+7, 128 bytes each; this
   // lane takes the 16-byte piece p8 (dims 16 p8..+15) of row 8h + r8.  Decoded, that is pieces
-  // 2 p8 and 2 p8 + 1 of the 256-byte bf16 row, which go to the images with the swizzles of the
-  // bf16 kernel, K row t keeps piece c at slot c ^ t, and a V swizzle of its own: V row t keeps
-  // piece c at slot c ^ 2(t mod 8) ^ (t mod 2).  (The last term swaps the halves of a 32-byte
-  // unit, which the transposing reads take whole.  Without it the sixteen lanes that the LDS
-  // serves together, two rows of eight pieces, would write only the eight even or the eight odd
-  // slots: every V write of the decode a two-way bank conflict.)
-  // bf16 pools.  Load j of a tile brings token rows 4j..4j+3 straight to LDS slot (j, lane); the
-  // piece of row 4j + q4 this lane fetches fixes the same swizzles on the global side.
+  // 2 p8 and 2 p8 + 1 of the 256-byte bf16 row, written by two 16-byte LDS stores.  The LDS
+  // serves such a store eight lanes at a time, 128 bytes wide: the eight lanes of a row must
+  // hit eight different 16-byte columns modulo 8.  With the bf16 kernel's swizzles they would
+  // write the even pieces in one store and the odd ones in the other: columns 0, 2, 4, 6 twice,
+  // every store a two-way conflict (36 % of the kernel's LDS cycles, measured).  So these
+  // images place piece c at sigma(c) ^ row, with sigma(even c) = c / 2 and sigma(odd c) =
+  // 8 + (c / 2 ^ 4): even pieces fill the lower half of a row, odd ones the upper half, each
+  // store covers all eight columns, and the reads stay free of conflicts too (sixteen rows of
+  // one piece for the scores; for the transposing reads four rows of two pieces, whose columns
+  // x ^ m and x ^ m ^ 4, m = 0..3, are all different).
   uint32_t koff[4], voff[4], kwr[2][2], vwr[2][2], krd[4], vrd[8];
+  auto sigma = [](int c) { return (c & 1) ? 8 + ((c >> 1) ^ 4) : (c >> 1); };
   if constexpr (KV8) {
     const int r8 = lane >> 3, p8 = lane & 7;
 #pragma unroll
@@ -163,25 +169,31 @@ __device__ __forceinline__ void flat_body(const AttnParams& p) {
 #pragma unroll
       for (int e = 0; e < 2; ++e) {
         const int c = 2 * p8 + e;
-        kwr[h][e] = (uint32_t)(tok * 256 + (((c ^ tok) & 15) * 16));
-        vwr[h][e] = (uint32_t)(kTileBytes + tok * 256 + ((c ^ (2 * (tok & 7)) ^ (tok & 1)) * 16));
+        kwr[h][e] = (uint32_t)(tok * 256 + ((sigma(c) ^ tok) * 16));
+        vwr[h][e] = (uint32_t)(kTileBytes + tok * 256 + ((sigma(c) ^ (tok & 7)) * 16));
       }
     }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) krd[j] = (uint32_t)(t16 * 256 + ((sigma(4 * j + q4) ^ t16) * 16));
+    // second product, output dims 16nb..16nb+15: the transposing read hands lane i of a 16-lane
+    // group element (i mod 4) of the 8-byte pieces addressed by lanes i/4, 4+i/4, 8+i/4, 12+i/4;
+    // this lane points at token tv, dims 16nb + 4(t16 mod 4)..+3: half (t16 mod 2) of piece
+    // 2nb + hp, which sits at column nb ^ (tv mod 8), in the upper half with bit 2 flipped if hp
+    const int tv = 4 * q4 + (t16 >> 2), hp = (t16 >> 1) & 1;
+    const uint32_t vbase = (uint32_t)(tv * 256 + ((hp << 7) | ((((hp ? 4 : 0) ^ (tv & 7))) << 4) | ((t16 & 1) << 3)));
+#pragma unroll
+    for (int nb = 0; nb < 8; ++nb) vrd[nb] = (vbase ^ (uint32_t)(nb << 4)) + wbase;
   } else {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int tok = 4 * j + q4;
       koff[j] = (uint32_t)(tok * p.k_stride_token) + (uint32_t)((t16 ^ tok) * 16);
-      voff[j] = (uint32_t)(tok * p.v_stride_token) + (uint32_t)((t16 ^ (2 * (tok & 7)) ^ (tok & 1)) * 16);
+      voff[j] = (uint32_t)(tok * p.v_stride_token) + (uint32_t)((t16 ^ (2 * (tok & 7))) * 16);
+      krd[j] = (uint32_t)(t16 * 256 + (((4 * j + q4) ^ t16) * 16));
     }
-  }
-#pragma unroll
-  for (int j = 0; j < 4; ++j) krd[j] = (uint32_t)(t16 * 256 + (((4 * j + q4) ^ t16) * 16));
-  {
-    // second product, output dims 16nb..16nb+15: the transposing read hands lane i of a 16-lane
-    // group element (i mod 4) of the 8-byte pieces addressed by lanes i/4, 4+i/4, 8+i/4, 12+i/4
+    // (as above, for the bf16 kernel's V image: piece pairs are 32-byte units at nb ^ (tv mod 8))
     const int tv = 4 * q4 + (t16 >> 2);
-    const uint32_t vbase = (uint32_t)(tv * 256 + ((((tv & 7) << 5) | ((tv & 1) << 4)) ^ ((t16 & 3) * 8)));
+    const uint32_t vbase = (uint32_t)(tv * 256 + ((tv & 7) << 5) + (t16 & 3) * 8);
 #pragma unroll
     for (int nb = 0; nb < 8; ++nb) vrd[nb] = (vbase ^ (uint32_t)(nb << 5)) + wbase;
   }
