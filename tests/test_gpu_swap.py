@@ -63,13 +63,15 @@ def test_plane_strides_and_fan_out():
     assert np.array_equal(got, ref)
 
 
-def test_swap_is_transparent_to_attention():
+@pytest.mark.parametrize("dtype,eb", [("bf16", 2), ("f8", 1)])
+def test_swap_is_transparent_to_attention(dtype, eb):
     """Evict a sequence to staging, bring it back into other blocks, rewrite its table:
-    the attention output is bit-identical (Sec. 5.1.2: the victim resumes where it stopped)."""
+    the attention output is bit-identical (Sec. 5.1.2: the victim resumes where it stopped).
+    The swap moves bytes, so 8-bit pools are the same call with blocks of half the size."""
     import torch
     from paper_2602_07878_amd import binding
     from helpers import run_hip, to_device
-    w = W.make_attn_workload("swapattn", 50, dtype="bf16", Hq=32, Hkv=8, D=128, block_size=16,
+    w = W.make_attn_workload("swapattn", 50, dtype=dtype, Hq=32, Hkv=8, D=128, block_size=16,
                              context_lens=[700, 1300, 90], pool_factor=2.5, poison=False)
     before = run_hip(w)
     victim = 1
@@ -78,7 +80,7 @@ def test_swap_is_transparent_to_attention():
     used = set(int(b) for b in w.block_tables[w.block_tables >= 0])
     free = np.array([b for b in range(w.num_pool_blocks) if b not in used], np.int32)
     new = np.random.default_rng(3).permutation(free)[:nb].astype(np.int32)
-    bb = 8 * 16 * 128 * 2
+    bb = 8 * 16 * 128 * eb
     dev = to_device(w)
     pools = torch.stack([dev["k_pool"], dev["v_pool"]])            # 2 planes
     staging = torch.zeros(2 * nb * bb, dtype=torch.uint8, device="cuda:0")
@@ -86,7 +88,7 @@ def test_swap_is_transparent_to_attention():
     g = torch.from_numpy(np.stack([old, slots], 1).astype(np.int32)).cuda()
     s = torch.from_numpy(np.stack([slots, new], 1).astype(np.int32)).cuda()
     binding.kv_block_swap(binding.swap_desc(2, bb, w.num_pool_blocks, nb), pools, staging, g)
-    pools[:, torch.from_numpy(old).long().cuda()] = float("nan")   # the old blocks are gone
+    pools[:, torch.from_numpy(old).long().cuda()] = float("nan") if eb == 2 else 0x7F   # the old blocks are gone (NaN)
     binding.kv_block_swap(binding.swap_desc(2, bb, nb, w.num_pool_blocks), staging, pools, s)
     torch.cuda.synchronize()
     w.block_tables[victim, :nb] = new
