@@ -91,7 +91,7 @@ int32_t check_swap_desc(const pkv_swap_desc* d) {
 
 extern "C" {
 
-int32_t pkv_version(void) { return 200; }
+int32_t pkv_version(void) { return 300; }
 
 int32_t pkv_init(void) {
   int dev = 0;
