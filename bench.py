@@ -158,8 +158,29 @@ def time_append(w, d, torch, binding, reps=200):
         e1.record()
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / reps * 1e3
+    plan = binding.attn_plan(desc, d["bt"], d["cl"])
+
+    def run_planned(fused):
+        # the planned call with the append as a launch of its own in front of it, or inside it
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(reps):
+            if i % PLAN_EVERY == 0:
+                binding.attn_plan(desc, d["bt"], d["cl"], plan)
+            if not fused:
+                binding.kv_append(desc, kn, vn, d["ks"][i % L], d["vs"][i % L], d["bt"], d["cl"])
+            binding.paged_decode_attention_planned(desc, plan, d["q"], d["ks"][i % L], d["vs"][i % L], d["bt"], d["cl"],
+                                                   w.scale, out, workspace=ws, k_new=kn if fused else None,
+                                                   v_new=vn if fused else None)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e3
     run(True)
+    run_planned(True)
     return {"append_us": run(False), "append_plus_attention_us": run(True),
+            "append_plus_planned_attention_us": run_planned(False),
+            "planned_attention_that_appends_us": run_planned(True),
             "bytes_written": 2 * w.B * w.Hkv * w.D * 2}
 
 

@@ -258,6 +258,27 @@ int32_t paged_decode_attention_planned(const pkv_attn_desc* desc, const void* pl
                                        size_t workspace_bytes, void* hip_stream);
 
 /*
+ * kv_append and paged_decode_attention_planned in one call (Sec. 2.2: every
+ * step appends the new token's K/V to the cache, then attends over it).  The
+ * result, in `out` and in the pools, is that of kv_append(desc, k_new, v_new,
+ * ...) followed by paged_decode_attention_planned(...) on the same stream.
+ * With bf16 pools and a usable plan no second kernel is launched: the
+ * wavefront that streams the last tile of a (sequence, KV head) takes the new
+ * rows from k_new / v_new, puts them into its on-chip copy of the tile and
+ * writes them to the pools.  In every other case (8-bit pools, fp32, shapes
+ * that take no plan) the call launches the append ahead of the attention
+ * itself.  Arguments as for the two calls; k_new / v_new must not be NULL.
+ */
+int32_t paged_decode_attention_planned_append(const pkv_attn_desc* desc, const void* plan,
+                                              size_t plan_bytes, const void* q,
+                                              const void* k_new, const void* v_new,
+                                              void* k_pool, void* v_pool,
+                                              const int32_t* block_tables,
+                                              const int32_t* context_lens, float scale,
+                                              void* out, void* workspace,
+                                              size_t workspace_bytes, void* hip_stream);
+
+/*
  * Causal prefill attention of a chunk over the paged cache (Sec. 2.1: masked
  * self-attention, a token attends to itself and to what precedes it; this is
  * the prefill phase and, after a preemption, the re-prefill of Sec. 5.1.2

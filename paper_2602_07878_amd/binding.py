@@ -21,7 +21,7 @@ FLAG_VECTOR_ALU = 1
 EXPORTS = [
     "pkv_version", "pkv_init", "pkv_static_scratch_bytes", "paged_decode_attention_static", "pkv_status_string", "pkv_last_hip_error_string", "pkv_attn_partition_tokens", "pkv_attn_workspace_bytes",
     "pkv_attn_plan_bytes", "pkv_attn_plan", "paged_decode_attention_planned",
-    "paged_decode_attention_planned_timed",
+    "paged_decode_attention_planned_timed", "paged_decode_attention_planned_append",
     "paged_decode_attention", "paged_decode_attention_timed", "paged_prefill_attention", "paged_prefill_attention_ws",
     "pkv_prefill_workspace_bytes", "kv_append", "kv_append_chunk", "kv_block_swap",
     "kv_swap_out_host", "kv_swap_in_host",
@@ -101,6 +101,9 @@ def lib() -> ctypes.CDLL:
         L.paged_decode_attention_planned.restype = i32
         L.paged_decode_attention_planned.argtypes = [ctypes.POINTER(AttnDesc), vp, sz, vp, vp, vp, vp, vp,
                                                      ctypes.c_float, vp, vp, sz, vp]
+        L.paged_decode_attention_planned_append.restype = i32
+        L.paged_decode_attention_planned_append.argtypes = [ctypes.POINTER(AttnDesc), vp, sz, vp, vp, vp, vp, vp, vp, vp,
+                                                            ctypes.c_float, vp, vp, sz, vp]
         L.paged_decode_attention_planned_timed.restype = i32
         L.paged_decode_attention_planned_timed.argtypes = [ctypes.POINTER(AttnDesc), vp, sz, vp, vp, vp, vp, vp,
                                                            ctypes.c_float, vp, vp, sz, vp, vp, vp]
@@ -249,8 +252,9 @@ def attn_plan(desc: AttnDesc, block_tables, context_lens, plan=None, *, stream=N
 
 
 def paged_decode_attention_planned(desc: AttnDesc, plan, q, k_pool, v_pool, block_tables, context_lens, scale, out, *,
-                                   workspace=None, stream=None, kernel_events=None):
-    """paged_decode_attention with a plan from attn_plan (same desc, tables and lengths).
+                                   workspace=None, stream=None, kernel_events=None, k_new=None, v_new=None):
+    """paged_decode_attention with a plan from attn_plan (same desc, tables and lengths); with
+    k_new / v_new the new token's rows are appended to the pools in the same call.
     Returns the workspace tensor used."""
     L = lib()
     need = int(L.pkv_attn_workspace_bytes(ctypes.byref(desc)))
@@ -261,7 +265,10 @@ def paged_decode_attention_planned(desc: AttnDesc, plan, q, k_pool, v_pool, bloc
     args = (ctypes.byref(desc), plan.data_ptr(), plan.numel() * plan.element_size(), q.data_ptr(), k_pool.data_ptr(),
             v_pool.data_ptr(), block_tables.data_ptr(), context_lens.data_ptr(), float(scale), out.data_ptr(),
             ws_ptr, ws_bytes, _stream_ptr(stream))
-    if kernel_events is None:
+    if k_new is not None:
+        assert kernel_events is None
+        st = L.paged_decode_attention_planned_append(*args[:4], k_new.data_ptr(), v_new.data_ptr(), *args[4:])
+    elif kernel_events is None:
         st = L.paged_decode_attention_planned(*args)
     else:
         st = L.paged_decode_attention_planned_timed(*args, ctypes.c_void_p(kernel_events[0].cuda_event),

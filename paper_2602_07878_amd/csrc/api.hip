@@ -216,11 +216,14 @@ int32_t pkv::attention_call(const pkv_attn_desc* desc, const void* q, const void
                             const void* v_pool, const int32_t* block_tables,
                             const int32_t* context_lens, float scale, void* out, void* workspace,
                             size_t workspace_bytes, void* hip_stream, void* ev_begin, void* ev_end,
-                            bool static_scratch, const void* plan, size_t plan_bytes) {
+                            bool static_scratch, const void* plan, size_t plan_bytes, const void* k_new,
+                            const void* v_new) {
   const int32_t st = check_attn_desc(desc);
   if (st != PKV_OK) return st;
   if (desc->batch == 0) return PKV_OK;
   if (!q || !k_pool || !v_pool || !block_tables || !context_lens || !out) return PKV_ERR_NULL;
+  if ((k_new == nullptr) != (v_new == nullptr)) return PKV_ERR_NULL;
+  if (!aligned16(k_new) || !aligned16(v_new)) return PKV_ERR_ALIGN;
   if (!aligned16(q) || !aligned16(k_pool) || !aligned16(v_pool) || !aligned16(out) ||
       !aligned16(workspace) || (reinterpret_cast<uintptr_t>(block_tables) & 3u) ||
       (reinterpret_cast<uintptr_t>(context_lens) & 3u))
@@ -246,6 +249,18 @@ int32_t pkv::attention_call(const pkv_attn_desc* desc, const void* q, const void
   p.q = q; p.k_pool = k_pool; p.v_pool = v_pool;
   p.block_tables = block_tables; p.context_lens = context_lens; p.out = out;
   fill_geometry(p, desc);
+  if (k_new) {
+    // the streaming kernel for bf16 pools with a plan appends by itself; everywhere else the
+    // append is a launch of its own in front of the attention
+    if (plan && desc->kv_dtype == PKV_BF16) {
+      p.k_new = k_new;
+      p.v_new = v_new;
+    } else {
+      const hipError_t e = launch_kv_append(p, k_new, v_new, elem_bytes(desc->kv_dtype),
+                                            static_cast<hipStream_t>(hip_stream));
+      if (e != hipSuccess) return hip_status(e);
+    }
+  }
   p.out_is_bf16 = desc->out_dtype == PKV_BF16;
   p.no_mfma = (desc->flags & PKV_ATTN_FLAG_VECTOR_ALU) != 0;
   p.scale_log2e = scale * pool_scale(desc, desc->k_scale) * 1.4426950408889634f;
@@ -285,7 +300,7 @@ int32_t paged_decode_attention(const pkv_attn_desc* desc, const void* q, const v
                                const int32_t* context_lens, float scale, void* out,
                                void* workspace, size_t workspace_bytes, void* hip_stream) {
   return attention_call(desc, q, k_pool, v_pool, block_tables, context_lens, scale, out, workspace,
-                        workspace_bytes, hip_stream, nullptr, nullptr, false, nullptr, 0);
+                        workspace_bytes, hip_stream, nullptr, nullptr, false, nullptr, 0, nullptr, nullptr);
 }
 
 int32_t paged_decode_attention_planned(const pkv_attn_desc* desc, const void* plan, size_t plan_bytes, const void* q,
@@ -293,7 +308,17 @@ int32_t paged_decode_attention_planned(const pkv_attn_desc* desc, const void* pl
                                        const int32_t* context_lens, float scale, void* out, void* workspace,
                                        size_t workspace_bytes, void* hip_stream) {
   return attention_call(desc, q, k_pool, v_pool, block_tables, context_lens, scale, out, workspace,
-                        workspace_bytes, hip_stream, nullptr, nullptr, false, plan, plan_bytes);
+                        workspace_bytes, hip_stream, nullptr, nullptr, false, plan, plan_bytes, nullptr, nullptr);
+}
+
+int32_t paged_decode_attention_planned_append(const pkv_attn_desc* desc, const void* plan, size_t plan_bytes,
+                                              const void* q, const void* k_new, const void* v_new, void* k_pool,
+                                              void* v_pool, const int32_t* block_tables, const int32_t* context_lens,
+                                              float scale, void* out, void* workspace, size_t workspace_bytes,
+                                              void* hip_stream) {
+  if (!k_new || !v_new) return PKV_ERR_NULL;
+  return attention_call(desc, q, k_pool, v_pool, block_tables, context_lens, scale, out, workspace,
+                        workspace_bytes, hip_stream, nullptr, nullptr, false, plan, plan_bytes, k_new, v_new);
 }
 
 int32_t paged_decode_attention_timed(const pkv_attn_desc* desc, const void* q, const void* k_pool,
@@ -302,7 +327,7 @@ int32_t paged_decode_attention_timed(const pkv_attn_desc* desc, const void* q, c
                                      void* workspace, size_t workspace_bytes, void* hip_stream,
                                      void* ev_kernel_begin, void* ev_kernel_end) {
   return attention_call(desc, q, k_pool, v_pool, block_tables, context_lens, scale, out, workspace,
-                        workspace_bytes, hip_stream, ev_kernel_begin, ev_kernel_end, false, nullptr, 0);
+                        workspace_bytes, hip_stream, ev_kernel_begin, ev_kernel_end, false, nullptr, 0, nullptr, nullptr);
 }
 
 int32_t paged_decode_attention_planned_timed(const pkv_attn_desc* desc, const void* plan, size_t plan_bytes, const void* q,
@@ -311,7 +336,7 @@ int32_t paged_decode_attention_planned_timed(const pkv_attn_desc* desc, const vo
                                              size_t workspace_bytes, void* hip_stream, void* ev_kernel_begin,
                                              void* ev_kernel_end) {
   return attention_call(desc, q, k_pool, v_pool, block_tables, context_lens, scale, out, workspace,
-                        workspace_bytes, hip_stream, ev_kernel_begin, ev_kernel_end, false, plan, plan_bytes);
+                        workspace_bytes, hip_stream, ev_kernel_begin, ev_kernel_end, false, plan, plan_bytes, nullptr, nullptr);
 }
 
 size_t pkv_prefill_workspace_bytes(const pkv_attn_desc* desc, int64_t total_query_tokens,

@@ -60,7 +60,7 @@ int32_t paged_decode_attention_static(const pkv_attn_desc* desc, const void* q, 
                                       const int32_t* context_lens, float scale, void* out,
                                       void* hip_stream) {
   return pkv::attention_call(desc, q, k_pool, v_pool, block_tables, context_lens, scale, out, nullptr, 0,
-                             hip_stream, nullptr, nullptr, /*static_scratch=*/true, nullptr, 0);
+                             hip_stream, nullptr, nullptr, /*static_scratch=*/true, nullptr, 0, nullptr, nullptr);
 }
 
 }  // extern "C"

@@ -34,9 +34,10 @@
 // a register moved while its load is in flight takes along whatever was there before (seen: a
 // query fetched ahead, copied, and the abandoned register reused for an address that the
 // arriving data then overwrote).  So the kernels are compiled with a register budget that ends
-// below v174 (8-bit pools) or v238 (bf16 pools), and the statements here name the registers
-// above it themselves: v174..v237 take the tile bytes of the four sets in flight, v238..v253 the
-// query rows fetched ahead.  Their contents enter the compiler's world only through statements
+// below v174 (8-bit pools) or v234 (bf16 pools), and the statements here name the registers
+// above it themselves: v174..v237 take the tile bytes of the four sets in flight (8-bit pools),
+// v234..v237 the new token's rows of a call that also appends (bf16 pools), v238..v253 the query
+// rows fetched ahead.  Their contents enter the compiler's world only through statements
 // that run after the wait that completes them.
 
 #include <atomic>
@@ -84,6 +85,7 @@ __device__ __forceinline__ void flat_body(const AttnParams& p) {
   // reach up to v253; the compiler remarks that v253 is outside its budget, which is the point)
   asm volatile("" ::: "v253");
   using G = FlatGeom<KV8>;
+  constexpr bool APPEND = !KV8 && PLANNED;      // the call may also append (see row_for below)
   constexpr int kSets = G::kSets, BT = G::kBatch, kTables = flat_tables<KV8>();
   constexpr int kWaveBytes = flat_wave_lds<KV8>();
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
@@ -301,7 +303,7 @@ __device__ __forceinline__ void flat_body(const AttnParams& p) {
   // `younger` of them (8-bit: up to three sets of four loads; bf16: at most the other stage's
   // eight loads, and query rows that were sent behind it).  Anything else that is on its way
   // (query rows, a plan's descriptors) only makes such a wait stricter.
-  auto arrive = [&](auto set_tag, int younger, bool q_behind) {
+  auto arrive = [&](auto set_tag, int younger, bool q_behind, bool row_behind) {
     constexpr int S = decltype(set_tag)::value;
     if constexpr (KV8) {
       if (younger >= 3) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
@@ -339,7 +341,9 @@ __device__ __forceinline__ void flat_body(const AttnParams& p) {
       *reinterpret_cast<u32x4*>(wlds + vwr[1][1]) = b3;
     } else {
       if (younger == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      else if (q_behind && row_behind) asm volatile("s_waitcnt vmcnt(13)" ::: "memory");
       else if (q_behind) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+      else if (row_behind) asm volatile("s_waitcnt vmcnt(9)" ::: "memory");
       else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
     }
   };
@@ -601,6 +605,13 @@ __device__ __forceinline__ void flat_body(const AttnParams& p) {
   bool fvalid = true;             // the fetch cursor has not run off the end of the work
   int q_for = -1;                 // the tile whose segment's query waits in qnext
   bool q_late = false;            // (bf16 pools) the last fetch put query rows in flight behind its tile
+  // Calls that also append (bf16 pools with a plan): the new token's K and V rows of a
+  // (sequence, KV head) are what the pair's last tile lacks.  The wavefront that streams that
+  // tile fetches the two rows (16 lanes x 16 bytes each, into v[234:237]) behind the tile, puts
+  // them into the tile's LDS images once it has arrived, and writes them to the pools; nobody
+  // else reads those pool rows in this call, so no wavefront waits for another.
+  int row_for = -1;               // the tile whose new rows are in (or on their way to) v[234:237]
+  bool row_late = false;          // the last fetch put such rows in flight behind its tile
   int seg_sp = 0, seg_info0 = 0, seg_x = 0;
 
   if (!need(0)) return;
@@ -617,8 +628,18 @@ __device__ __forceinline__ void flat_body(const AttnParams& p) {
   // unless v[238:253] still hold the query of a segment not yet opened: in front of the tile for
   // 8-bit pools, behind it for bf16 pools (where the wait for the tile before it must not have
   // to wait for them).
+  auto new_row_source = [&](int sp) {
+    const int seq = sp >> 8, pp = sp & 255;
+    const int kvh = pp / p.group_tiles;
+    // lanes 0..15: the K row, lanes 16..31: the V row (offsets, not a choice between two
+    // pointers: the compiler turns that into a table in scratch memory)
+    const int64_t v_from_k = reinterpret_cast<const uint8_t*>(p.v_new) - reinterpret_cast<const uint8_t*>(p.k_new);
+    return reinterpret_cast<const uint8_t*>(p.k_new) + (lane < 16 ? (int64_t)0 : v_from_k) +
+           ((int64_t)seq * p.num_kv_heads + kvh) * (D * 2) + (lane & 15) * 16;
+  };
   auto fetch_ahead = [&](auto set_tag, int opened) {   // opened: last tile whose segment has its query
     q_late = false;
+    row_late = false;
     if (!fvalid) return;
     const u32x4 d2 = dtabs[(fn % kTables) * BT + fj];
     const bool opens2 = ((int)d2[3] >> 7) & 1;
@@ -628,6 +649,15 @@ __device__ __forceinline__ void flat_body(const AttnParams& p) {
     if (!KV8 && with_q) load_q_ahead(rfl((int)d2[2]));
     if (with_q) q_for = fk;
     q_late = !KV8 && with_q;
+    if constexpr (APPEND) {
+      // (the registers are free once the tile they were fetched for has been consumed)
+      if (p.k_new != nullptr && (((int)d2[3] >> 6) & 1) && row_for < k) {
+        const uint8_t* src = new_row_source(rfl((int)d2[2]));
+        if (lane < 32) asm volatile("global_load_dwordx4 v[234:237], %0, off" : : "v"(src) : "memory");
+        row_for = fk;
+        row_late = true;
+      }
+    }
     ++fk;
     if (++fj == fnt) {               // on to the next batch, which may have to be described first
       if (need(fn + 1)) {
@@ -646,7 +676,31 @@ __device__ __forceinline__ void flat_body(const AttnParams& p) {
     const u32x4 dsc = dtabs[(cn % kTables) * BT + j];   // the same entry for every lane
     const int sp = rfl((int)dsc[2]), info = rfl((int)dsc[3]);
     if constexpr (!KV8) fetch_ahead(std::integral_constant<int, 1 - (S & 1)>{}, k - 1);
-    arrive(set_tag, fk - 1 - k, q_late);
+    arrive(set_tag, fk - 1 - k, q_late, row_late);
+    if constexpr (APPEND) {
+      if (p.k_new != nullptr && ((info >> 6) & 1)) {       // the pair's last tile: the new token's rows go in
+        if (row_for != k) {   // (not fetched ahead: pairs of a single tile in a row)
+          const uint8_t* src = new_row_source(sp);
+          if (lane < 32)
+            asm volatile("global_load_dwordx4 v[234:237], %0, off\n\ts_waitcnt vmcnt(0)" : : "v"(src) : "memory");
+          row_for = k;
+        }
+        const int r = (info & 31) - 1, l15 = lane & 15;    // the new token's row in the tile
+        const uint32_t image = wbase + (uint32_t)(img::value * kImageBytes + r * 256) +
+                               (uint32_t)(lane < 16 ? ((l15 ^ r) & 15) * 16 : kTileBytes + ((l15 ^ (2 * (r & 7))) & 15) * 16);
+        const int64_t in_k = (int64_t)((uint64_t)dsc[0] << 4) + (int64_t)r * p.k_stride_token;
+        const int64_t in_v = (vpool - kpool) + (int64_t)((uint64_t)dsc[1] << 4) + (int64_t)r * p.v_stride_token;
+        uint8_t* pool = const_cast<uint8_t*>(kpool) + (lane < 16 ? in_k : in_v) + l15 * 16;
+        if (lane < 32)
+          asm volatile(
+              "ds_write_b128 %0, v[234:237]\n\t"
+              "global_store_dwordx4 %1, v[234:237], off\n\t"
+              "s_waitcnt lgkmcnt(0)"
+              :
+              : "v"(image), "v"(pool)
+              : "memory");
+      }
+    }
     if ((info >> 7) & 1) {                                 // the tile opens a segment
       seg_sp = sp;
       seg_info0 = info;
@@ -760,14 +814,14 @@ __device__ __forceinline__ void flat_body(const AttnParams& p) {
 }
 
 // The register budgets: on this target the attribute counts in units of two registers, so 87
-// leaves the compiler v0..v173 and 119 leaves it v0..v237.
+// leaves the compiler v0..v173 and 117 leaves it v0..v233.
 template <int GH, bool PLANNED>
 __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_num_vgpr(87)))
 void attn_stream_flat_f8_d128(const AttnParams p) {
   flat_body<GH, true, PLANNED>(p);
 }
 template <int GH>
-__global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_num_vgpr(119)))
+__global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_num_vgpr(117)))
 void attn_stream_flat_bf16_d128(const AttnParams p) {
   flat_body<GH, false, true>(p);
 }

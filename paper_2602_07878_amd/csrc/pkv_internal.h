@@ -46,6 +46,8 @@ struct AttnParams {
   int32_t* ws_dir;          // stream kernel: [pairs][2] (first slot, partial count)
   const int32_t* plan_hdr;  // stream kernel, calls with a per-step plan: its header words, else null
   const void* plan_desc;    // ... and its tile descriptors, 16 bytes per tile of the axis
+  const void* k_new;        // stream kernel with a plan, bf16 pools: the new token's rows [B][Hkv][D] to append, else null
+  const void* v_new;
   int32_t plan_key;         // ... and the number that names the call geometry a plan is made for
   int32_t plan_tiles_cap;   // ... and how many descriptors the plan has room for
   int64_t k_stride_block, k_stride_head, k_stride_token;  // BYTES
@@ -84,11 +86,12 @@ struct SwapParams {
 // api.hip: checks and launch of the decode-attention call (every entry point that offers it ends
 // here).  static_scratch: the partials go to the library's static device array (attn_static.hip)
 // and `workspace` is ignored.  plan: a buffer written by pkv_attn_plan for this descriptor, tables
-// and lengths, or null.
+// and lengths, or null.  k_new, v_new: the new token's rows, appended to the pools ahead of (or
+// inside) the attention, or null.
 int32_t attention_call(const pkv_attn_desc* desc, const void* q, const void* k_pool, const void* v_pool,
                        const int32_t* block_tables, const int32_t* context_lens, float scale, void* out,
                        void* workspace, size_t workspace_bytes, void* hip_stream, void* ev_begin, void* ev_end,
-                       bool static_scratch, const void* plan, size_t plan_bytes);
+                       bool static_scratch, const void* plan, size_t plan_bytes, const void* k_new, const void* v_new);
 // attn_static.hip: size of the static scratch array, and its device address on the current device
 size_t static_scratch_bytes();
 hipError_t static_scratch_address(void** ptr);

@@ -63,14 +63,14 @@ def test_registers_that_wait_for_data_in_flight_are_left_alone():
     """The flat streaming kernels leave loads in flight across several tiles, into registers the
     compiler must not touch (it may move a value it manages at any join of control flow, and a
     register moved while its load is in flight takes the old contents along): v174 and up in the
-    8-bit kernels, v238 and up in the bf16 kernels.  Only the kernels' own statements (between
+    8-bit kernels, v234 and up in the bf16 kernels.  Only the kernels' own statements (between
     the compiler's inline-assembly markers) may name them, and the loads that stay in flight must
     target exactly them."""
     isa = isa_of("attn_stream_flat.hip")
     bodies = re.findall(r"^(_ZN\S*attn_stream_flat_(f8|bf16)_d128\S*):[^\n]*\n(.*?)s_endpgm", isa, re.S | re.M)
     assert len(bodies) == 12
     for name, kind, body in bodies:
-        first = 174 if kind == "f8" else 238
+        first = 174 if kind == "f8" else 234
         in_asm = False
         for line in body.splitlines():
             if "#ASMSTART" in line:
@@ -86,7 +86,7 @@ def test_registers_that_wait_for_data_in_flight_are_left_alone():
                 assert min(registers_named(dest)) >= first, (name, line)     # tile bytes
             elif re.search(r"global_load_dwordx4 v\[\d+:\d+\], v\[\d+:\d+\], off", text):
                 dest = min(registers_named(re.search(r"global_load_dwordx4 (v\[\d+:\d+\]),", text).group(1)))
-                assert dest >= 238 or "s_waitcnt vmcnt(0)" in body[body.index(line):body.index(line) + 400], (name, line)
+                assert dest >= first or "s_waitcnt vmcnt(0)" in body[body.index(line):body.index(line) + 400], (name, line)
 
 
 @pytest.mark.skipif(not os.path.exists(HIPCC), reason="needs hipcc")

@@ -145,3 +145,83 @@ def test_calls_that_have_no_use_for_a_plan_run_as_ordinary_calls():
 def test_benchmark_batch_reduced():
     for w in (W.config2_llama8b(B=32), W.config2_llama8b_f8(B=32)):
         check(w)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f8", "f32"])
+@pytest.mark.parametrize("Hq,Hkv,bs,tm", [(32, 8, 16, False), (64, 8, 16, False), (8, 8, 32, False), (32, 2, 16, True)])
+def test_append_inside_the_planned_call_equals_append_then_attention(dtype, Hq, Hkv, bs, tm):
+    """paged_decode_attention_planned_append against kv_append followed by the planned call: the
+    pools bit-identical, the outputs bit-identical (bf16 with a plan appends inside the streaming
+    kernel, the other cases launch the append themselves), and both against the oracle.  Lengths
+    put the new token at the first, a middle and the last slot of a tile and of a block, into
+    contexts of a single token and of one tile, next to an empty context; tm: token-major pools."""
+    import oracle
+    import torch
+    from paper_2602_07878_amd import binding
+    lens = [1, 2, 16, 17, 31, 32, 33, 48, 49, 640, 641, 1000, 0, 15, 1, 1, 16, 16, 2047]
+    D = 128 if dtype != "f32" else 64
+    w = W.make_attn_workload(f"fused_append_{dtype}", 511, dtype=dtype, Hq=Hq, Hkv=Hkv, D=D, block_size=bs,
+                             context_lens=lens, pool_factor=1.3)
+    rng = np.random.default_rng(512)
+    rows = [rng.standard_normal((w.B, w.Hkv, w.D)).astype(np.float32) for _ in range(2)]
+    conv = {"bf16": W.f32_to_bf16_bits, "f8": W.f32_to_f8e4m3_bits, "f32": lambda a: a}[dtype]
+    kn, vn = conv(rows[0]), conv(rows[1])
+
+    def dev_rows(a):
+        return (torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16) if a.dtype == np.uint16
+                else torch.from_numpy(a).cuda())
+
+    results = []
+    for fused in (False, True):
+        dev = to_device(w)
+        kp, vp = dev["k_pool"], dev["v_pool"]
+        if tm:      # [blocks][tokens][heads][D] in memory, seen through the same logical shape
+            kp = kp.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+            vp = vp.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+        desc = binding.attn_desc_for(dev["q"], kp, vp, dev["block_tables"], max_context_len=w.max_context_len,
+                                     k_scale=w.k_scale, v_scale=w.v_scale)
+        plan = binding.attn_plan(desc, dev["block_tables"], dev["context_lens"])
+        out = torch.full((w.B, w.Hq, w.D), -7.0, device="cuda:0")
+        if fused:
+            binding.paged_decode_attention_planned(desc, plan, dev["q"], kp, vp, dev["block_tables"], dev["context_lens"],
+                                                   w.scale, out, k_new=dev_rows(kn), v_new=dev_rows(vn))
+        else:
+            binding.kv_append(desc, dev_rows(kn), dev_rows(vn), kp, vp, dev["block_tables"], dev["context_lens"])
+            binding.paged_decode_attention_planned(desc, plan, dev["q"], kp, vp, dev["block_tables"], dev["context_lens"],
+                                                   w.scale, out)
+        torch.cuda.synchronize()
+        as_bits = lambda t: t.contiguous().view(torch.int16 if t.element_size() == 2 else torch.uint8 if t.element_size() == 1 else torch.int32).cpu().numpy()
+        results.append((as_bits(kp), as_bits(vp), out.cpu().numpy()))
+    assert np.array_equal(results[0][0], results[1][0]) and np.array_equal(results[0][1], results[1][1])
+    assert np.array_equal(results[0][2], results[1][2])
+    oracle.kv_append(w.k_pool, w.v_pool, kn, vn, w.block_tables, w.context_lens, block_size=w.block_size)
+    ref = run_oracle(w)
+    tol = 1e-5 if dtype == "f32" else TOL
+    assert np.abs(results[1][2].astype(np.float64) - ref).max() <= tol
+    assert np.all(results[1][2][12] == 0.0)
+
+
+def test_append_inside_the_planned_call_on_the_benchmark_batch_from_call_to_call():
+    """Several layers' worth of fused calls on one plan (other rows every time), each against the oracle."""
+    import oracle
+    import torch
+    from paper_2602_07878_amd import binding
+    w = W.config2_llama8b(B=24)
+    dev = to_device(w)
+    desc = binding.attn_desc_for(dev["q"], dev["k_pool"], dev["v_pool"], dev["block_tables"],
+                                 max_context_len=w.max_context_len)
+    plan = binding.attn_plan(desc, dev["block_tables"], dev["context_lens"])
+    rng = np.random.default_rng(513)
+    out = torch.zeros(w.B, w.Hq, w.D, device="cuda:0")
+    ws = None
+    up = lambda a: torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+    for layer in range(3):
+        kn = W.f32_to_bf16_bits(rng.standard_normal((w.B, w.Hkv, w.D)).astype(np.float32))
+        vn = W.f32_to_bf16_bits(rng.standard_normal((w.B, w.Hkv, w.D)).astype(np.float32))
+        ws = binding.paged_decode_attention_planned(desc, plan, dev["q"], dev["k_pool"], dev["v_pool"], dev["block_tables"],
+                                                    dev["context_lens"], w.scale, out, workspace=ws, k_new=up(kn), v_new=up(vn))
+        torch.cuda.synchronize()
+        oracle.kv_append(w.k_pool, w.v_pool, kn, vn, w.block_tables, w.context_lens, block_size=w.block_size)
+        assert np.array_equal(dev["k_pool"].view(torch.int16).cpu().numpy().view(np.uint16), w.k_pool)
+        assert np.array_equal(dev["v_pool"].view(torch.int16).cpu().numpy().view(np.uint16), w.v_pool)
+        assert np.abs(out.cpu().numpy().astype(np.float64) - run_oracle(w)).max() <= TOL
