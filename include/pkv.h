@@ -262,12 +262,11 @@ int32_t paged_decode_attention_planned(const pkv_attn_desc* desc, const void* pl
  * step appends the new token's K/V to the cache, then attends over it).  The
  * result, in `out` and in the pools, is that of kv_append(desc, k_new, v_new,
  * ...) followed by paged_decode_attention_planned(...) on the same stream.
- * With bf16 pools and a usable plan no second kernel is launched: the
- * wavefront that streams the last tile of a (sequence, KV head) takes the new
- * rows from k_new / v_new, puts them into its on-chip copy of the tile and
- * writes them to the pools.  In every other case (8-bit pools, fp32, shapes
- * that take no plan) the call launches the append ahead of the attention
- * itself.  Arguments as for the two calls; k_new / v_new must not be NULL.
+ * Where the call has use for a plan (pkv_attn_plan_bytes > 0: bf16 or 8-bit
+ * pools, head_dim 128) no second kernel is launched: the wavefront that streams
+ * the last tile of a (sequence, KV head) takes the new rows from k_new / v_new,
+ * puts them into its on-chip copy of the tile and writes them to the pools.  In
+ * every other case the call launches the append ahead of the attention itself.  Arguments as for the two calls; k_new / v_new must not be NULL.
  */
 int32_t paged_decode_attention_planned_append(const pkv_attn_desc* desc, const void* plan,
                                               size_t plan_bytes, const void* q,

@@ -250,9 +250,9 @@ int32_t pkv::attention_call(const pkv_attn_desc* desc, const void* q, const void
   p.block_tables = block_tables; p.context_lens = context_lens; p.out = out;
   fill_geometry(p, desc);
   if (k_new) {
-    // the streaming kernel for bf16 pools with a plan appends by itself; everywhere else the
-    // append is a launch of its own in front of the attention
-    if (plan && desc->kv_dtype == PKV_BF16) {
+    // the streaming kernels that take a plan append by themselves; everywhere else the append
+    // is a launch of its own in front of the attention
+    if (plan) {
       p.k_new = k_new;
       p.v_new = v_new;
     } else {

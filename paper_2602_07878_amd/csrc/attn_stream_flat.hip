@@ -36,8 +36,8 @@
 // arriving data then overwrote).  So the kernels are compiled with a register budget that ends
 // below v174 (8-bit pools) or v234 (bf16 pools), and the statements here name the registers
 // above it themselves: v174..v237 take the tile bytes of the four sets in flight (8-bit pools),
-// v234..v237 the new token's rows of a call that also appends (bf16 pools), v238..v253 the query
-// rows fetched ahead.  Their contents enter the compiler's world only through statements
+// v234..v237 (bf16 pools) or v170..v173 (8-bit pools with a plan) the new token's rows of a call
+// that also appends, v238..v253 the query rows fetched ahead.  Their contents enter the compiler's world only through statements
 // that run after the wait that completes them.
 
 #include <atomic>
@@ -85,7 +85,7 @@ __device__ __forceinline__ void flat_body(const AttnParams& p) {
   // reach up to v253; the compiler remarks that v253 is outside its budget, which is the point)
   asm volatile("" ::: "v253");
   using G = FlatGeom<KV8>;
-  constexpr bool APPEND = !KV8 && PLANNED;      // the call may also append (see row_for below)
+  constexpr bool APPEND = PLANNED;              // the call may also append (see row_for below)
   constexpr int kSets = G::kSets, BT = G::kBatch, kTables = flat_tables<KV8>();
   constexpr int kWaveBytes = flat_wave_lds<KV8>();
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
@@ -605,12 +605,14 @@ __device__ __forceinline__ void flat_body(const AttnParams& p) {
   bool fvalid = true;             // the fetch cursor has not run off the end of the work
   int q_for = -1;                 // the tile whose segment's query waits in qnext
   bool q_late = false;            // (bf16 pools) the last fetch put query rows in flight behind its tile
-  // Calls that also append (bf16 pools with a plan): the new token's K and V rows of a
-  // (sequence, KV head) are what the pair's last tile lacks.  The wavefront that streams that
-  // tile fetches the two rows (16 lanes x 16 bytes each, into v[234:237]) behind the tile, puts
-  // them into the tile's LDS images once it has arrived, and writes them to the pools; nobody
-  // else reads those pool rows in this call, so no wavefront waits for another.
-  int row_for = -1;               // the tile whose new rows are in (or on their way to) v[234:237]
+  // Calls that also append (with a plan): the new token's K and V rows of a (sequence, KV head)
+  // are what the pair's last tile lacks.  The wavefront that streams that tile fetches the two
+  // rows with it (one 16-byte piece per lane: 2 x 16 lanes into v[234:237] for bf16 pools,
+  // 2 x 8 lanes into v[170:173] for 8-bit pools), puts them into the tile's LDS images once it
+  // has arrived, and writes them to the pools; nobody else reads those pool rows in this call,
+  // so no wavefront waits for another.
+  constexpr int kRowLanes = KV8 ? 8 : 16;   // lanes per new row
+  int row_for = -1;               // the tile whose new rows are in (or on their way to) those registers
   bool row_late = false;          // the last fetch put such rows in flight behind its tile
   int seg_sp = 0, seg_info0 = 0, seg_x = 0;
 
@@ -634,8 +636,8 @@ __device__ __forceinline__ void flat_body(const AttnParams& p) {
     // lanes 0..15: the K row, lanes 16..31: the V row (offsets, not a choice between two
     // pointers: the compiler turns that into a table in scratch memory)
     const int64_t v_from_k = reinterpret_cast<const uint8_t*>(p.v_new) - reinterpret_cast<const uint8_t*>(p.k_new);
-    return reinterpret_cast<const uint8_t*>(p.k_new) + (lane < 16 ? (int64_t)0 : v_from_k) +
-           ((int64_t)seq * p.num_kv_heads + kvh) * (D * 2) + (lane & 15) * 16;
+    return reinterpret_cast<const uint8_t*>(p.k_new) + (lane < kRowLanes ? (int64_t)0 : v_from_k) +
+           ((int64_t)seq * p.num_kv_heads + kvh) * (kRowLanes * 16) + (lane & (kRowLanes - 1)) * 16;
   };
   auto fetch_ahead = [&](auto set_tag, int opened) {   // opened: last tile whose segment has its query
     q_late = false;
@@ -644,16 +646,24 @@ __device__ __forceinline__ void flat_body(const AttnParams& p) {
     const u32x4 d2 = dtabs[(fn % kTables) * BT + fj];
     const bool opens2 = ((int)d2[3] >> 7) & 1;
     const bool with_q = opens2 && q_for <= opened;
+    // (the registers of a new row are free once the tile they were fetched for has taken them)
+    const bool with_row = APPEND && p.k_new != nullptr && (((int)d2[3] >> 6) & 1) && row_for <= opened;
+    if constexpr (KV8) {
+      if (with_row) {
+        const uint8_t* src = new_row_source(rfl((int)d2[2]));
+        if (lane < 2 * kRowLanes) asm volatile("global_load_dwordx4 v[170:173], %0, off" : : "v"(src) : "memory");
+        row_for = fk;
+      }
+    }
     if (KV8 && with_q) load_q_ahead(rfl((int)d2[2]));
     fetch((uint32_t)rfl((int)d2[0]), (uint32_t)rfl((int)d2[1]), set_tag);
     if (!KV8 && with_q) load_q_ahead(rfl((int)d2[2]));
     if (with_q) q_for = fk;
     q_late = !KV8 && with_q;
-    if constexpr (APPEND) {
-      // (the registers are free once the tile they were fetched for has been consumed)
-      if (p.k_new != nullptr && (((int)d2[3] >> 6) & 1) && row_for < k) {
+    if constexpr (!KV8) {
+      if (with_row) {
         const uint8_t* src = new_row_source(rfl((int)d2[2]));
-        if (lane < 32) asm volatile("global_load_dwordx4 v[234:237], %0, off" : : "v"(src) : "memory");
+        if (lane < 2 * kRowLanes) asm volatile("global_load_dwordx4 v[234:237], %0, off" : : "v"(src) : "memory");
         row_for = fk;
         row_late = true;
       }
@@ -679,26 +689,54 @@ __device__ __forceinline__ void flat_body(const AttnParams& p) {
     arrive(set_tag, fk - 1 - k, q_late, row_late);
     if constexpr (APPEND) {
       if (p.k_new != nullptr && ((info >> 6) & 1)) {       // the pair's last tile: the new token's rows go in
-        if (row_for != k) {   // (not fetched ahead: pairs of a single tile in a row)
+        if (row_for != k) {   // (not fetched ahead: the last tiles of short pairs close together)
           const uint8_t* src = new_row_source(sp);
-          if (lane < 32)
-            asm volatile("global_load_dwordx4 v[234:237], %0, off\n\ts_waitcnt vmcnt(0)" : : "v"(src) : "memory");
+          if (lane < 2 * kRowLanes) {
+            if constexpr (KV8) asm volatile("global_load_dwordx4 v[170:173], %0, off\n\ts_waitcnt vmcnt(0)" : : "v"(src) : "memory");
+            else asm volatile("global_load_dwordx4 v[234:237], %0, off\n\ts_waitcnt vmcnt(0)" : : "v"(src) : "memory");
+          }
           row_for = k;
         }
-        const int r = (info & 31) - 1, l15 = lane & 15;    // the new token's row in the tile
-        const uint32_t image = wbase + (uint32_t)(img::value * kImageBytes + r * 256) +
-                               (uint32_t)(lane < 16 ? ((l15 ^ r) & 15) * 16 : kTileBytes + ((l15 ^ (2 * (r & 7))) & 15) * 16);
+        const int r = (info & 31) - 1, lr = lane & (kRowLanes - 1);   // the new token's row in the tile, this lane's piece
+        const bool is_k = lane < kRowLanes;
         const int64_t in_k = (int64_t)((uint64_t)dsc[0] << 4) + (int64_t)r * p.k_stride_token;
         const int64_t in_v = (vpool - kpool) + (int64_t)((uint64_t)dsc[1] << 4) + (int64_t)r * p.v_stride_token;
-        uint8_t* pool = const_cast<uint8_t*>(kpool) + (lane < 16 ? in_k : in_v) + l15 * 16;
-        if (lane < 32)
-          asm volatile(
-              "ds_write_b128 %0, v[234:237]\n\t"
-              "global_store_dwordx4 %1, v[234:237], off\n\t"
-              "s_waitcnt lgkmcnt(0)"
-              :
-              : "v"(image), "v"(pool)
-              : "memory");
+        uint8_t* pool = const_cast<uint8_t*>(kpool) + (is_k ? in_k : in_v) + lr * 16;
+        if constexpr (KV8) {
+          // 16 codes of this lane: to the pool as they are, decoded into two pieces of the images
+          if (lane < 2 * kRowLanes) {
+            uint32_t o0, o1, o2, o3, o4, o5, o6, o7;
+            asm volatile(
+                "global_store_dwordx4 %8, v[170:173], off\n\t"
+                "v_cvt_scalef32_pk_bf16_fp8 %0, v170, 1.0\n\t"
+                "v_cvt_scalef32_pk_bf16_fp8 %1, v170, 1.0 op_sel:[1,0,0]\n\t"
+                "v_cvt_scalef32_pk_bf16_fp8 %2, v171, 1.0\n\t"
+                "v_cvt_scalef32_pk_bf16_fp8 %3, v171, 1.0 op_sel:[1,0,0]\n\t"
+                "v_cvt_scalef32_pk_bf16_fp8 %4, v172, 1.0\n\t"
+                "v_cvt_scalef32_pk_bf16_fp8 %5, v172, 1.0 op_sel:[1,0,0]\n\t"
+                "v_cvt_scalef32_pk_bf16_fp8 %6, v173, 1.0\n\t"
+                "v_cvt_scalef32_pk_bf16_fp8 %7, v173, 1.0 op_sel:[1,0,0]\n\t"
+                "s_nop 0"
+                : "=&v"(o0), "=&v"(o1), "=&v"(o2), "=&v"(o3), "=&v"(o4), "=&v"(o5), "=&v"(o6), "=&v"(o7)
+                : "v"(pool)
+                : "memory");
+            const int rs = is_k ? r : (r & 7);
+            uint8_t* row = wlds + (is_k ? 0 : kTileBytes) + r * 256;
+            *reinterpret_cast<u32x4*>(row + ((sigma(2 * lr) ^ rs) * 16)) = u32x4{o0, o1, o2, o3};
+            *reinterpret_cast<u32x4*>(row + ((sigma(2 * lr + 1) ^ rs) * 16)) = u32x4{o4, o5, o6, o7};
+          }
+        } else {
+          const uint32_t image = wbase + (uint32_t)(img::value * kImageBytes + r * 256) +
+                                 (uint32_t)(is_k ? ((lr ^ r) & 15) * 16 : kTileBytes + ((lr ^ (2 * (r & 7))) & 15) * 16);
+          if (lane < 2 * kRowLanes)
+            asm volatile(
+                "ds_write_b128 %0, v[234:237]\n\t"
+                "global_store_dwordx4 %1, v[234:237], off\n\t"
+                "s_waitcnt lgkmcnt(0)"
+                :
+                : "v"(image), "v"(pool)
+                : "memory");
+        }
       }
     }
     if ((info >> 7) & 1) {                                 // the tile opens a segment
@@ -814,11 +852,16 @@ __device__ __forceinline__ void flat_body(const AttnParams& p) {
 }
 
 // The register budgets: on this target the attribute counts in units of two registers, so 87
-// leaves the compiler v0..v173 and 117 leaves it v0..v233.
-template <int GH, bool PLANNED>
+// leaves the compiler v0..v173, 85 leaves it v0..v169 and 117 leaves it v0..v233.
+template <int GH>
 __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_num_vgpr(87)))
 void attn_stream_flat_f8_d128(const AttnParams p) {
-  flat_body<GH, true, PLANNED>(p);
+  flat_body<GH, true, false>(p);
+}
+template <int GH>
+__global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_num_vgpr(85)))
+void attn_stream_flat_f8_planned_d128(const AttnParams p) {
+  flat_body<GH, true, true>(p);
 }
 template <int GH>
 __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_num_vgpr(117)))
@@ -934,8 +977,8 @@ hipError_t launch_flat_gh(const AttnParams& p, hipStream_t s) {
   const bool planned = p.plan_hdr != nullptr;
   const size_t lds8 = (size_t)(planned ? 0 : p.prefix_bytes) + (size_t)kNW * flat_wave_lds<true>();
   if (p.kv_is_f8)
-    return planned ? launch_flat_kernel(attn_stream_flat_f8_d128<GH, true>, lds8, p, s)
-                   : launch_flat_kernel(attn_stream_flat_f8_d128<GH, false>, lds8, p, s);
+    return planned ? launch_flat_kernel(attn_stream_flat_f8_planned_d128<GH>, lds8, p, s)
+                   : launch_flat_kernel(attn_stream_flat_f8_d128<GH>, lds8, p, s);
   return launch_flat_kernel(attn_stream_flat_bf16_d128<GH>, (size_t)kNW * flat_wave_lds<false>(), p, s);
 }
 
@@ -945,8 +988,8 @@ static_assert(kFlatLdsMax + 2 * kNW * 4 <= 160 * 1024, "one workgroup per CU has
 
 template <int GH>
 hipError_t prepare_gh() {
-  for (const void* f : {reinterpret_cast<const void*>(&attn_stream_flat_f8_d128<GH, false>),
-                        reinterpret_cast<const void*>(&attn_stream_flat_f8_d128<GH, true>),
+  for (const void* f : {reinterpret_cast<const void*>(&attn_stream_flat_f8_d128<GH>),
+                        reinterpret_cast<const void*>(&attn_stream_flat_f8_planned_d128<GH>),
                         reinterpret_cast<const void*>(&attn_stream_flat_bf16_d128<GH>)}) {
     const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, kFlatLdsMax);
     if (e != hipSuccess) return e;

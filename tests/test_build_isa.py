@@ -63,14 +63,14 @@ def test_registers_that_wait_for_data_in_flight_are_left_alone():
     """The flat streaming kernels leave loads in flight across several tiles, into registers the
     compiler must not touch (it may move a value it manages at any join of control flow, and a
     register moved while its load is in flight takes the old contents along): v174 and up in the
-    8-bit kernels, v234 and up in the bf16 kernels.  Only the kernels' own statements (between
+    8-bit kernels (v170 and up in those that take a plan), v234 and up in the bf16 kernels.  Only the kernels' own statements (between
     the compiler's inline-assembly markers) may name them, and the loads that stay in flight must
     target exactly them."""
     isa = isa_of("attn_stream_flat.hip")
-    bodies = re.findall(r"^(_ZN\S*attn_stream_flat_(f8|bf16)_d128\S*):[^\n]*\n(.*?)s_endpgm", isa, re.S | re.M)
+    bodies = re.findall(r"^(_ZN\S*attn_stream_flat_(f8_planned|f8|bf16)_d128\S*):[^\n]*\n(.*?)s_endpgm", isa, re.S | re.M)
     assert len(bodies) == 12
     for name, kind, body in bodies:
-        first = 174 if kind == "f8" else 234
+        first = {"f8": 174, "f8_planned": 170, "bf16": 234}[kind]
         in_asm = False
         for line in body.splitlines():
             if "#ASMSTART" in line:

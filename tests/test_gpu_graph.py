@@ -83,10 +83,12 @@ def test_decode_step_and_split_prefill_replayed_from_a_graph():
         assert np.abs(cout_g.cpu().numpy().astype(np.float64) - cref).max() <= 2e-3, replay
 
 
+@pytest.mark.parametrize("fused", [False, True])
 @pytest.mark.parametrize("dtype", ["bf16", "f8"])
-def test_planned_decode_step_replayed_from_a_graph(dtype):
+def test_planned_decode_step_replayed_from_a_graph(dtype, fused):
     """One decode step as a serving loop would capture it: pkv_attn_plan, then for each of three
-    layers kv_append and paged_decode_attention_planned on that layer's pools.  Between replays
+    layers kv_append and paged_decode_attention_planned on that layer's pools (fused: the append
+    inside the attention call).  Between replays
     the context lengths grow by a token (in place, as a scheduler does), so every replay builds
     another plan; each is checked against the eager calls and against the oracle."""
     import oracle
@@ -122,9 +124,11 @@ def test_planned_decode_step_replayed_from_a_graph(dtype):
         binding.attn_plan(desc, bt, cl, plan)
         for l in range(layers):
             d = devs[l]
-            binding.kv_append(desc, kn[l], vn[l], d["k_pool"], d["v_pool"], bt, cl)
+            if not fused:
+                binding.kv_append(desc, kn[l], vn[l], d["k_pool"], d["v_pool"], bt, cl)
             binding.paged_decode_attention_planned(desc, plan, d["q"], d["k_pool"], d["v_pool"], bt, cl, w0.scale,
-                                                   outs[l], workspace=wsp)
+                                                   outs[l], workspace=wsp, k_new=kn[l] if fused else None,
+                                                   v_new=vn[l] if fused else None)
 
     cl += 1
     step(outs_e)                                          # warm-up
