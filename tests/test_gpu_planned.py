@@ -225,3 +225,35 @@ def test_append_inside_the_planned_call_on_the_benchmark_batch_from_call_to_call
         assert np.array_equal(dev["k_pool"].view(torch.int16).cpu().numpy().view(np.uint16), w.k_pool)
         assert np.array_equal(dev["v_pool"].view(torch.int16).cpu().numpy().view(np.uint16), w.v_pool)
         assert np.abs(out.cpu().numpy().astype(np.float64) - run_oracle(w)).max() <= TOL
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f8"])
+def test_many_short_contexts_with_and_without_the_append(dtype):
+    """1 500 sequences of 1..40 tokens: most pairs are a single tile, so segments open and close at
+    every tile, the queries and new rows of consecutive tiles cannot all be fetched ahead, and the
+    descriptor batches are as short as the chunks."""
+    import oracle
+    import torch
+    from paper_2602_07878_amd import binding
+    rng = np.random.default_rng(520)
+    lens = [int(x) for x in rng.integers(1, 41, 1500)]
+    lens[7] = 0
+    w = mk(f"planned_short_{dtype}", 521, lens, dtype=dtype, Hq=16, Hkv=8)
+    check(w)
+    check(w, partition_tokens=64)
+    dev = to_device(w)
+    conv = W.f32_to_bf16_bits if dtype == "bf16" else W.f32_to_f8e4m3_bits
+    kn = conv(rng.standard_normal((w.B, w.Hkv, w.D)).astype(np.float32))
+    vn = conv(rng.standard_normal((w.B, w.Hkv, w.D)).astype(np.float32))
+    up = (lambda a: torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)) if dtype == "bf16" else (lambda a: torch.from_numpy(a).cuda())
+    desc = binding.attn_desc_for(dev["q"], dev["k_pool"], dev["v_pool"], dev["block_tables"],
+                                 max_context_len=w.max_context_len)
+    plan = binding.attn_plan(desc, dev["block_tables"], dev["context_lens"])
+    out = torch.zeros(w.B, w.Hq, w.D, device="cuda:0")
+    binding.paged_decode_attention_planned(desc, plan, dev["q"], dev["k_pool"], dev["v_pool"], dev["block_tables"],
+                                           dev["context_lens"], w.scale, out, k_new=up(kn), v_new=up(vn))
+    torch.cuda.synchronize()
+    oracle.kv_append(w.k_pool, w.v_pool, kn, vn, w.block_tables, w.context_lens, block_size=w.block_size)
+    bits = lambda t: t.view(torch.int16).cpu().numpy().view(np.uint16) if dtype == "bf16" else t.cpu().numpy()
+    assert np.array_equal(bits(dev["k_pool"]), w.k_pool) and np.array_equal(bits(dev["v_pool"]), w.v_pool)
+    assert np.abs(out.cpu().numpy().astype(np.float64) - run_oracle(w)).max() <= TOL
