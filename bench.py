@@ -707,7 +707,7 @@ def main():
 
     if not args.no_swap:
         swap = {}
-        for sw in (W.config4_squeeze(), W.config4_evict_all_256()):
+        for sw in (W.config4_squeeze(), W.config4_evict_all_256(), W.config4_squeeze_f8()):
             swap[sw.name] = time_swap(sw, 5, torch, binding)
             log(f"[bench] swap {sw.name}: {swap[sw.name]}")
         result["swap"] = swap

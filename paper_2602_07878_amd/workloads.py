@@ -321,6 +321,14 @@ def config4_squeeze(seed: int = 1004, victims: int = 64, lo: int = 512, hi: int 
                               num_planes=num_planes, block_bytes=16 * 8 * 128 * 2)
 
 
+def config4_squeeze_f8(seed: int = 1004, victims: int = 64, lo: int = 512, hi: int = 4096,
+                       num_planes: int = 64) -> SwapWorkload:
+    """The same victims with 8-bit (E4M3) pools: one byte per element, 16 KiB blocks."""
+    return make_swap_workload("cfg4_squeeze_swap64_f8", seed,
+                              victim_lens=lens_uniform(seed, victims, lo, hi),
+                              num_planes=num_planes, block_bytes=16 * 8 * 128)
+
+
 def config4_evict_all_256(seed: int = 1003, num_planes: int = 64) -> SwapWorkload:
     """Swap-out of all 256 sequences of the Fill-state length mix (the metric's
     'at batch 256' wording)."""

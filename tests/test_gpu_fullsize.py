@@ -67,10 +67,11 @@ def test_config5_long_context_full_as_configured_and_auto_split():
     assert np.abs(run_hip(w, dev, planned=True) - got).max() <= 1e-5
 
 
-def test_config4_swap_full_size_round_trip():
+@pytest.mark.parametrize("make", [W.config4_squeeze, W.config4_squeeze_f8], ids=["bf16_32KiB_blocks", "e4m3_16KiB_blocks"])
+def test_config4_swap_full_size_round_trip(make):
     import torch
     from paper_2602_07878_amd import binding
-    sw = W.config4_squeeze()
+    sw = make()
     P, bb, NB, n = sw.num_planes, sw.block_bytes, sw.num_pool_blocks, sw.n_blocks
     t0 = time.time()
     pool = W.random_bytes(sw.pool_bytes, 1004)
