@@ -230,15 +230,21 @@ def time_swap(sw, reps, torch, binding, oracle_check=True):
     if oracle_check:
         import oracle
         planes_ok = []
+        cpu_s = 0.0
         for p in (0, sw.num_planes - 1):
             before = pool_before[p]                                  # host copy taken before any swap
             st_ref = np.zeros(sw.n_blocks * sw.block_bytes, np.uint8)
+            t = time.perf_counter()
             oracle.kv_block_swap(before, st_ref, sw.gather_mapping, num_planes=1, block_bytes=sw.block_bytes)
+            cpu_s += time.perf_counter() - t
             pool_ref = before.copy()
             oracle.kv_block_swap(st_ref, pool_ref, smap, num_planes=1, block_bytes=sw.block_bytes)
             planes_ok.append(bool(np.array_equal(s[p].cpu().numpy().view(np.uint8).reshape(-1), st_ref)) and
                              bool(np.array_equal(v[p].cpu().numpy().view(np.uint8).reshape(-1), pool_ref)))
         res["bit_exact_vs_oracle_first_and_last_plane"] = all(planes_ok)
+        # the oracle's memcpy per block on this host's cores, for scale (two planes of the gather)
+        res["cpu_oracle_gather"] = {"payload_GBps": 2 * sw.n_blocks * sw.block_bytes / cpu_s / 1e9,
+                                    "cores": oracle.num_threads(), "sample": "two of the planes"}
     res["payload_GB"] = sw.payload_bytes / 1e9
     res["victims"] = int(sw.victim_lens.size)
     res["blocks"] = sw.n_blocks
@@ -603,10 +609,22 @@ def cpu_baseline(w, reps=3):
                                             w.context_lens, w.scale, block_size=w.block_size)
         dt = time.perf_counter() - t
         best = dt if best is None else min(best, dt)
-    return ref, {"value": w.kv_bytes / best / 1e9, "unit": "KV GB/s", "cores": oracle.num_threads(),
-                 "kind": "oracle", "seconds": best,
-                 "sample": f"the full {w.name} workload (all {w.B} sequences, {w.Hq} heads), "
-                           f"best of {reps} runs"}
+    res = {"value": w.kv_bytes / best / 1e9, "unit": "KV GB/s", "cores": oracle.num_threads(),
+           "kind": "oracle", "seconds": best,
+           "sample": f"the full {w.name} workload (all {w.B} sequences, {w.Hq} heads), "
+                     f"best of {reps} runs"}
+    try:                                    # the same on one thread, once
+        from threadpoolctl import threadpool_limits
+        with threadpool_limits(limits=1, user_api="openmp"):
+            if oracle.num_threads() == 1:
+                t = time.perf_counter()
+                oracle.paged_decode_attention(w.q, w.k_pool, w.v_pool, w.block_tables, w.context_lens, w.scale,
+                                              block_size=w.block_size)
+                dt = time.perf_counter() - t
+                res["one_thread"] = {"value": w.kv_bytes / dt / 1e9, "unit": "KV GB/s", "seconds": dt}
+    except ImportError:
+        pass
+    return ref, res
 
 
 def main():
