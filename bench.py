@@ -724,14 +724,14 @@ def main():
     torch.cuda.empty_cache()
 
     if not args.no_swap:
+        swh = W.config4_squeeze(victims=16)
+        result["swap_host_leg"] = time_swap_host(swh, torch, binding)
+        log(f"[bench] swap host leg {swh.name} ({int(swh.victim_lens.size)} victims): {result['swap_host_leg']}")
         swap = {}
         for sw in (W.config4_squeeze(), W.config4_evict_all_256(), W.config4_squeeze_f8()):
             swap[sw.name] = time_swap(sw, 5, torch, binding)
             log(f"[bench] swap {sw.name}: {swap[sw.name]}")
         result["swap"] = swap
-        swh = W.config4_squeeze(victims=16)
-        result["swap_host_leg"] = time_swap_host(swh, torch, binding)
-        log(f"[bench] swap host leg {swh.name} ({int(swh.victim_lens.size)} victims): {result['swap_host_leg']}")
 
     # every kernel family against the roofline that bounds it (the headline one is `roofline`)
     rl = {"paged_prefill_attention": {"bound": "mfma", "achieved": result["prefill"]["tflops"],
