@@ -267,7 +267,10 @@ def time_swap_host(sw, torch, binding, staging_mib=256, reps=2):
     d_in = binding.swap_desc(sw.num_planes, sw.block_bytes, sw.n_blocks, sw.num_pool_blocks)
     res = {}
     for name, fn in (("out", lambda: binding.kv_swap_out_host(d_out, pool, host, gm, staging)),
-                     ("in", lambda: binding.kv_swap_in_host(d_in, host, pool, sm, staging))):
+                     ("in", lambda: binding.kv_swap_in_host(d_in, host, pool, sm, staging)),
+                     # without a staging buffer: the copy kernel reads and writes the host memory itself
+                     ("out_unstaged", lambda: binding.kv_swap_out_host(d_out, pool, host, gm)),
+                     ("in_unstaged", lambda: binding.kv_swap_in_host(d_in, host, pool, sm))):
         fn()
         torch.cuda.synchronize()
         t0 = time.perf_counter()

@@ -419,6 +419,11 @@ int32_t kv_block_swap(const pkv_swap_desc* desc, const void* src_pool,
  * A piece is a group of whole planes, one contiguous copy, when
  * 2*n_pairs*block_bytes fits into `staging` and n_pairs*block_bytes equals the
  * host plane stride; else a range of pairs of every plane, one strided copy.
+ * With staging = NULL and staging_bytes = 0 nothing is staged: the copy kernel
+ * itself reads or writes the host buffer, which the device sees because it is
+ * page-locked (one launch of a few workgroups, bounded by the link like the
+ * staged form and measured as fast; an address the device cannot see gives
+ * PKV_ERR_HIP and nothing runs).
  * Both calls only enqueue work and keep no state.  After kv_swap_out_host,
  * completion of hip_stream implies that all of host_dst is written; after
  * kv_swap_in_host, that the pool blocks are.  The bytes arrive exactly; same

@@ -367,23 +367,25 @@ def kv_block_swap(desc: SwapDesc, src_pool, dst, block_mapping, *, stream=None):
     _check(st, "kv_block_swap")
 
 
-def kv_swap_out_host(desc: SwapDesc, src_pool, host_dst, block_mapping, staging, *, stream=None):
+def kv_swap_out_host(desc: SwapDesc, src_pool, host_dst, block_mapping, staging=None, *, stream=None):
     """Pool blocks block_mapping[:,0] (device) -> slots 0..n-1 of the pinned host tensor host_dst,
-    in pieces through the device tensor `staging`."""
+    in pieces through the device tensor `staging`, or (staging None) written by the kernel itself."""
     assert host_dst.is_pinned() and block_mapping.is_contiguous()
     st = lib().kv_swap_out_host(ctypes.byref(desc), src_pool.data_ptr(), host_dst.data_ptr(),
                                 block_mapping.data_ptr(), block_mapping.numel() // 2,
-                                staging.data_ptr(), staging.numel() * staging.element_size(),
+                                staging.data_ptr() if staging is not None else None,
+                                staging.numel() * staging.element_size() if staging is not None else 0,
                                 _stream_ptr(stream))
     _check(st, "kv_swap_out_host")
 
 
-def kv_swap_in_host(desc: SwapDesc, host_src, dst_pool, block_mapping, staging, *, stream=None):
+def kv_swap_in_host(desc: SwapDesc, host_src, dst_pool, block_mapping, staging=None, *, stream=None):
     """Slots 0..n-1 of the pinned host tensor host_src -> pool blocks block_mapping[:,1] (device)."""
     assert host_src.is_pinned() and block_mapping.is_contiguous()
     st = lib().kv_swap_in_host(ctypes.byref(desc), host_src.data_ptr(), dst_pool.data_ptr(),
                                block_mapping.data_ptr(), block_mapping.numel() // 2,
-                               staging.data_ptr(), staging.numel() * staging.element_size(),
+                               staging.data_ptr() if staging is not None else None,
+                               staging.numel() * staging.element_size() if staging is not None else 0,
                                _stream_ptr(stream))
     _check(st, "kv_swap_in_host")
 

@@ -503,12 +503,16 @@ static int32_t swap_host_impl(bool out, const pkv_swap_desc* desc, const void* s
   if (st != PKV_OK) return st;
   if (n_pairs < 0) return PKV_ERR_SHAPE;
   if (n_pairs == 0) return PKV_OK;
-  if (!src || !dst || !block_mapping || !staging) return PKV_ERR_NULL;
+  const bool direct = !staging && staging_bytes == 0;   // no staging buffer: the kernel touches the host memory itself
+  if (!src || !dst || !block_mapping || (!staging && !direct)) return PKV_ERR_NULL;
   if (!aligned16(src) || !aligned16(dst) || !aligned16(staging) ||
       (reinterpret_cast<uintptr_t>(block_mapping) & 3u))
     return PKV_ERR_ALIGN;
   // the host side holds one slot per pair
   if ((out ? desc->dst_num_blocks : desc->src_num_blocks) < n_pairs) return PKV_ERR_SHAPE;
+  if (direct)
+    return hip_status(swap_host_direct(out, *desc, static_cast<const uint8_t*>(src), static_cast<uint8_t*>(dst),
+                                       block_mapping, n_pairs, static_cast<hipStream_t>(hip_stream)));
   bool too_small = false;
   const hipError_t e =
       out ? swap_out_host(*desc, static_cast<const uint8_t*>(src), static_cast<uint8_t*>(dst),

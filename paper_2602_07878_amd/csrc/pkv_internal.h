@@ -120,7 +120,8 @@ PlanLayout plan_layout(const pkv_attn_desc& d);
 hipError_t launch_attn_flat(const AttnParams& p, int gh, hipStream_t s);
 hipError_t launch_attn_plan(AttnParams& p, int32_t* plan_hdr, hipStream_t s);
 // swap.hip
-hipError_t launch_swap(const SwapParams& p, hipStream_t s);
+// max_workgroups > 0 caps the grid (a copy that a slower link bounds needs few)
+hipError_t launch_swap(const SwapParams& p, hipStream_t s, int max_workgroups = 0);
 // attn_prefill_mfma.hip
 bool attn_prefill_supported(const pkv_attn_desc& d);
 hipError_t launch_attn_prefill(AttnParams& p, int max_query_len, int max_context_len, int64_t total_query_tokens,
@@ -139,6 +140,10 @@ hipError_t swap_out_host(const pkv_swap_desc& d, const uint8_t* pool, uint8_t* h
 hipError_t swap_in_host(const pkv_swap_desc& d, const uint8_t* host_src, uint8_t* pool, const int32_t* mapping,
                         int32_t n_pairs, uint8_t* staging, size_t staging_bytes, hipStream_t stream,
                         bool* too_small);
+// the same without a staging buffer: the copy kernel reads or writes the page-locked host memory
+// itself (out: pool -> host slots; else host slots -> pool)
+hipError_t swap_host_direct(bool out, const pkv_swap_desc& d, const uint8_t* src, uint8_t* dst,
+                            const int32_t* mapping, int32_t n_pairs, hipStream_t stream);
 hipError_t launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t s);
 hipError_t launch_probe_read(const void* src, void* sink, size_t bytes, hipStream_t s);
 

@@ -137,9 +137,10 @@ int grid_for_device(int wgs_per_cu) {
 
 }  // namespace
 
-hipError_t launch_swap(const SwapParams& p, hipStream_t s) {
+hipError_t launch_swap(const SwapParams& p, hipStream_t s, int max_workgroups) {
   const int64_t nchunks = (int64_t)p.num_planes * p.n_pairs;
   int64_t grid = grid_for_device(3) / 4;   // three workgroups per four CUs
+  if (max_workgroups > 0 && grid > max_workgroups) grid = max_workgroups;
   const int64_t need = (nchunks + kCopyWaves - 1) / kCopyWaves;
   if (grid > need) grid = need;
   if (grid < 1) grid = 1;

@@ -135,4 +135,33 @@ hipError_t swap_in_host(const pkv_swap_desc& d, const uint8_t* host_src, uint8_t
   return hipSuccess;
 }
 
+// Without a staging buffer.  Page-locked host memory is mapped into the device's address space,
+// so the copy kernel can take the host buffer as its source or destination: one launch, every
+// chunk crosses the link once, nothing is staged.  The link (some 57 GB/s) bounds it, not the
+// CUs, so the grid is a few workgroups: the rest of the device stays free for the requests that
+// keep decoding while a victim is swapped.  Kernel completion makes the host writes visible to
+// the host like any other result of a kernel.
+constexpr int kDirectWorkgroups = 32;
+
+hipError_t swap_host_direct(bool out, const pkv_swap_desc& d, const uint8_t* src, uint8_t* dst,
+                            const int32_t* mapping, int32_t n_pairs, hipStream_t stream) {
+  // the device's view of the host buffer (an error if the memory is not page-locked and mapped)
+  void* view = nullptr;
+  void* host = out ? static_cast<void*>(dst) : const_cast<uint8_t*>(src);
+  PKV_TRY(hipHostGetDevicePointer(&view, host, 0));
+  if (!view) return hipErrorInvalidValue;
+  SwapParams p;
+  p.src = out ? src : static_cast<const uint8_t*>(view);
+  p.dst = out ? static_cast<uint8_t*>(view) : dst;
+  p.mapping = mapping;
+  p.block_bytes = d.block_bytes;
+  p.src_plane_stride = d.src_plane_stride_bytes;
+  p.dst_plane_stride = d.dst_plane_stride_bytes;
+  p.num_planes = d.num_planes;
+  p.n_pairs = n_pairs;
+  p.src_slot_is_pair = out ? 0 : 1;   // the host slot of pair j is j
+  p.dst_slot_is_pair = out ? 1 : 0;
+  return launch_swap(p, stream, kDirectWorkgroups);
+}
+
 }  // namespace pkv

@@ -169,6 +169,9 @@ def test_swap_host_leg_rejects_bad_arguments_on_host():
         assert f(swap_desc(), n=-1) == ST["SHAPE"]
         assert f(swap_desc(), n=0, a=0, b=0, m=0, st=0) == ST["OK"]
         assert f(swap_desc(), sb=4 * 32768 - 16) == ST["WORKSPACE"]       # not even one pair of every plane
+        # no staging buffer at all: the kernel would touch the host memory itself, which must be
+        # page-locked memory the device can see; an address that is not is refused, nothing runs
+        assert f(swap_desc(), st=0, sb=0) == ST["HIP"]
     # the host side needs a slot per pair: 50 slots in the 100 -> 50 descriptor, 100 the other way round
     assert L.kv_swap_out_host(ctypes.byref(swap_desc()), 0x1000, 0x2000, 0x3000, 51, 0x4000, 1 << 22, None) == ST["SHAPE"]
     assert L.kv_swap_in_host(ctypes.byref(swap_desc()), 0x1000, 0x2000, 0x3000, 101, 0x4000, 1 << 22, None) == ST["SHAPE"]

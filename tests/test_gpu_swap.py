@@ -100,10 +100,12 @@ def test_swap_is_transparent_to_attention(dtype, eb):
 
 # ---- host leg (Sec. 5.1.2: the victims' blocks go to CPU host memory and come back) ---------
 @pytest.mark.parametrize("staging_pairs,side_stream,junk_slots", [(1, False, False), (7, True, False), (64, True, False),
-                                                                  (1000, False, False), (7, False, True), (64, False, True)])
+                                                                  (1000, False, False), (7, False, True), (64, False, True),
+                                                                  (0, False, False), (0, True, True)])
 def test_swap_out_to_pinned_host_and_back_is_bit_exact(staging_pairs, side_stream, junk_slots):
     """Pieces of 1 and 7 pairs of every plane (strided copies), of 2 and of all 6 whole planes
-    (contiguous copies); on the current stream or on another one.  junk_slots: the host-slot
+    (contiguous copies), or (0) no staging buffer: the kernel reads and writes the host memory
+    itself; on the current stream or on another one.  junk_slots: the host-slot
     column of the mappings holds arbitrary numbers; the host slot of pair j is j whatever it says,
     so the result is the same and nothing outside the buffers is touched."""
     import oracle
@@ -117,7 +119,9 @@ def test_swap_out_to_pinned_host_and_back_is_bit_exact(staging_pairs, side_strea
     d_pool = torch.from_numpy(pool).cuda()
     host = torch.zeros(planes * n * bb + 64, dtype=torch.uint8).pin_memory()
     host[-64:] = 0xA5                                                   # canary behind the slots
-    staging = torch.empty((1 if staging_pairs < 64 else 2) * staging_pairs * planes * bb, dtype=torch.uint8, device="cuda")
+    staging = None
+    if staging_pairs:
+        staging = torch.empty((1 if staging_pairs < 64 else 2) * staging_pairs * planes * bb, dtype=torch.uint8, device="cuda")
     stream = torch.cuda.Stream() if side_stream else torch.cuda.current_stream()
     stream.wait_stream(torch.cuda.current_stream())                     # the uploads above
     out_desc = binding.swap_desc(planes, bb, sw.num_pool_blocks, n)
