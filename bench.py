@@ -253,7 +253,7 @@ def time_swap(sw, reps, torch, binding, oracle_check=True):
     return res
 
 
-def time_swap_host(sw, torch, binding, staging_mib=256, reps=2):
+def time_swap_host(sw, torch, binding, staging_mib=256, reps=2, decode_batch=None):
     """The same victims' blocks out to pinned host memory and back in (PCIe-bound), in pieces
     through a device staging buffer."""
     g = torch.Generator(device="cuda:0")
@@ -295,6 +295,43 @@ def time_swap_host(sw, torch, binding, staging_mib=256, reps=2):
         torch.cuda.synchronize()
         plain[name] = n * reps / (time.perf_counter() - t0) / 1e9
     res["plain_pinned_copy_GBps"] = plain
+    # The paper's setting: the other requests keep decoding while a victim's blocks leave.  Decode
+    # calls of the benchmark batch on one stream, alone and while each form of the swap-out runs
+    # on another stream.
+    if decode_batch is not None:
+        w, d = decode_batch
+        out = torch.empty(w.B, w.Hq, w.D, dtype=torch.float32, device="cuda:0")
+        desc = binding.attn_desc_for(d["q"], d["ks"][0], d["vs"][0], d["bt"], max_context_len=w.max_context_len)
+        ws = binding.new_workspace(binding.attn_workspace_bytes(desc), "cuda:0")
+        plan = binding.attn_plan(desc, d["bt"], d["cl"])
+        L = len(d["ks"])
+        s_swap, s_dec = torch.cuda.Stream(), torch.cuda.Stream()
+        calls = 800                      # about as long as the swap-out
+
+        def decode(n):
+            for i in range(n):
+                if i % PLAN_EVERY == 0:
+                    binding.attn_plan(desc, d["bt"], d["cl"], plan, stream=s_dec)
+                binding.paged_decode_attention_planned(desc, plan, d["q"], d["ks"][i % L], d["vs"][i % L], d["bt"],
+                                                       d["cl"], w.scale, out, workspace=ws, stream=s_dec)
+        ov = {}
+        for mode in ("alone", "staged", "unstaged"):
+            torch.cuda.synchronize()
+            a0, a1, b0, b1 = (torch.cuda.Event(enable_timing=True) for _ in range(4))
+            decode(PLAN_EVERY)           # the decode stream is busy when the swap arrives
+            b0.record(s_dec)
+            if mode != "alone":
+                a0.record(s_swap)
+                binding.kv_swap_out_host(d_out, pool, host, gm, staging if mode == "staged" else None, stream=s_swap)
+                a1.record(s_swap)
+            decode(calls)
+            b1.record(s_dec)
+            torch.cuda.synchronize()
+            ov[mode] = {"decode_us_per_call": b0.elapsed_time(b1) / calls * 1e3}
+            if mode != "alone":
+                ov[mode]["swap_out_GBps"] = sw.payload_bytes / a0.elapsed_time(a1) / 1e6
+        res["decode_calls_while_swapping_out"] = ov
+        del out, ws, plan
     del pool, host, staging
     torch.cuda.empty_cache()
     return res
@@ -728,7 +765,8 @@ def main():
 
     if not args.no_swap:
         swh = W.config4_squeeze(victims=16)
-        result["swap_host_leg"] = time_swap_host(swh, torch, binding)
+        w2 = W.config2_llama8b()
+        result["swap_host_leg"] = time_swap_host(swh, torch, binding, decode_batch=(w2, upload_attn(w2, 8, torch)))
         log(f"[bench] swap host leg {swh.name} ({int(swh.victim_lens.size)} victims): {result['swap_host_leg']}")
         swap = {}
         for sw in (W.config4_squeeze(), W.config4_evict_all_256(), W.config4_squeeze_f8()):
