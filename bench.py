@@ -266,6 +266,22 @@ def time_swap_host(sw, torch, binding, staging_mib=256, reps=2, decode_batch=Non
     d_out = binding.swap_desc(sw.num_planes, sw.block_bytes, sw.num_pool_blocks, sw.n_blocks)
     d_in = binding.swap_desc(sw.num_planes, sw.block_bytes, sw.n_blocks, sw.num_pool_blocks)
     res = {}
+    # both forms once for the bytes: the host slots of the first and the last plane against the
+    # pool blocks they came from, and the pool's new blocks against the host slots afterwards
+    P, NB, nb_, bb = sw.num_planes, sw.num_pool_blocks, sw.n_blocks, sw.block_bytes
+    pv, hv = pool.view(torch.uint8).view(P, NB, bb), host.view(P, nb_, bb)
+    src_i, new_i = (torch.from_numpy(a).long().cuda() for a in (sw.src_blocks, sw.new_blocks))
+    checks = {}
+    for form, st in (("staged", staging), ("unstaged", None)):
+        host.zero_()
+        binding.kv_swap_out_host(d_out, pool, host, gm, st)
+        torch.cuda.synchronize()
+        ok = all(bool(torch.equal(hv[p], pv[p][src_i].cpu())) for p in (0, P - 1))
+        binding.kv_swap_in_host(d_in, host, pool, sm, st)
+        torch.cuda.synchronize()
+        ok = ok and all(bool(torch.equal(pv[p][new_i].cpu(), hv[p])) for p in (0, P - 1))
+        checks[form] = ok
+    res["bit_exact_first_and_last_plane_pool_vs_host"] = checks
     for name, fn in (("out", lambda: binding.kv_swap_out_host(d_out, pool, host, gm, staging)),
                      ("in", lambda: binding.kv_swap_in_host(d_in, host, pool, sm, staging)),
                      # without a staging buffer: the copy kernel reads and writes the host memory itself
