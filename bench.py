@@ -691,6 +691,8 @@ def main():
     ap.add_argument("--layers", type=int, default=16, help="distinct KV layer pools cycled over")
     ap.add_argument("--no-swap", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-overlap", action="store_true",
+                    help="skip the decode calls timed while a swap-out runs (keeps a kernel trace's rows apart)")
     ap.add_argument("--no-extra", action="store_true", help="skip the Fill and long-context configurations")
     ap.add_argument("--no-sweep", action="store_true",
                     help="skip the fit of the paper's linear execution-time model to a sweep of the cached context")
@@ -782,7 +784,8 @@ def main():
     if not args.no_swap:
         swh = W.config4_squeeze(victims=16)
         w2 = W.config2_llama8b()
-        result["swap_host_leg"] = time_swap_host(swh, torch, binding, decode_batch=(w2, upload_attn(w2, 8, torch)))
+        result["swap_host_leg"] = time_swap_host(
+            swh, torch, binding, decode_batch=None if args.no_overlap else (w2, upload_attn(w2, 8, torch)))
         log(f"[bench] swap host leg {swh.name} ({int(swh.victim_lens.size)} victims): {result['swap_host_leg']}")
         swap = {}
         for sw in (W.config4_squeeze(), W.config4_evict_all_256(), W.config4_squeeze_f8()):
