@@ -388,6 +388,11 @@ int32_t kv_append_chunk(const pkv_attn_desc* desc, const void* k_new, const void
  * twice is a data race (undefined); a source block may repeat.  n_pairs = 0
  * enqueues nothing.  The order of the pairs does not change the result; pairs
  * listed by ascending destination block copy fastest (sequential writes).
+ * src_pool or dst may also be page-locked host memory that the device can
+ * address (a swap area in CPU memory whose slots the caller's block manager
+ * hands out): the kernel then moves those bytes over the link, which bounds
+ * it; kv_swap_out_host / kv_swap_in_host below are that case with the host
+ * slots in swap order and a smaller grid.
  */
 int32_t kv_block_swap(const pkv_swap_desc* desc, const void* src_pool,
                       void* dst, const int32_t* block_mapping,

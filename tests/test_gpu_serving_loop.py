@@ -22,11 +22,15 @@ def rows_of(rid, n):
     return k, v
 
 
-@pytest.mark.parametrize("mode,chunked", [("swap", False), ("recompute", False), ("swap", True), ("recompute", True)])
-def test_scheduler_driven_decode_with_preemption(mode, chunked):
+@pytest.mark.parametrize("mode,chunked,swap_area", [("swap", False, "device"), ("recompute", False, "device"),
+                                                    ("swap", True, "device"), ("recompute", True, "device"),
+                                                    ("swap", False, "pinned host")])
+def test_scheduler_driven_decode_with_preemption(mode, chunked, swap_area):
     """With chunked=True prompts are prefilled in chunks under a 64-token budget, and the chunks'
     causal attention over the paged cache (paged_prefill_attention on the scheduler's tables,
-    query_lens = chunk, context_lens = tokens cached after it) is checked against the oracle."""
+    query_lens = chunk, context_lens = tokens cached after it) is checked against the oracle.
+    swap_area: where the scheduler's host blocks live: a device buffer standing in for host
+    memory, or page-locked host memory that kv_block_swap reads and writes over the link."""
     import oracle
     import torch
     from paper_2602_07878_amd import binding, sched
@@ -45,6 +49,8 @@ def test_scheduler_driven_decode_with_preemption(mode, chunked):
     hv = hk.copy()
     sk, sv = np.zeros((n_cpu, HKV, BS, D), np.uint16), np.zeros((n_cpu, HKV, BS, D), np.uint16)
     dk, dv, dsk, dsv = up(hk), up(hv), up(sk), up(sv)
+    if swap_area == "pinned host":
+        dsk, dsv = (torch.from_numpy(a.view(np.int16).copy()).pin_memory().view(torch.bfloat16) for a in (sk, sv))
     block_bytes = HKV * BS * D * 2
     out_desc = binding.swap_desc(1, block_bytes, n_gpu, n_cpu)
     in_desc = binding.swap_desc(1, block_bytes, n_cpu, n_gpu)
