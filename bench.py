@@ -522,13 +522,15 @@ def time_model_sweep(torch, binding, B=64, Hq=32, Hkv=8, seed=1009, tables=16, r
     return res
 
 
-def serve_loop(torch, binding, steps, mode="recompute", seed=1007, chunked=False):
+def serve_loop(torch, binding, steps, mode="recompute", seed=1007, chunked=False, swap_area="device"):
     """The scheduler model driving the GPU calls for `steps` engine iterations under a benign
     Poisson load that saturates the pool (the Fill state, with preemptions): per iteration the
     swaps, the prefills (new and recomputed requests: their K/V rows into the cache, then their
     attention), the KV append and the decode attention of one layer, 8B-shaped heads.  K/V contents are random; only shapes and tables matter here.
     chunked: prefills proceed in chunks under a 512-token budget per iteration (the example the
-    paper's section on chunked prefill gives) instead of whole within 8192 tokens."""
+    paper's section on chunked prefill gives) instead of whole within 8192 tokens.
+    swap_area: the scheduler's host blocks in a device buffer (the gather/scatter alone) or in
+    page-locked host memory (the swap as the paper has it: over PCIe)."""
     import numpy as np
     from paper_2602_07878_amd import sched, workloads as W
     Hq, Hkv, D, bs = 32, 8, 128, 16
@@ -543,8 +545,10 @@ def serve_loop(torch, binding, steps, mode="recompute", seed=1007, chunked=False
     g.manual_seed(seed)
     kp = torch.randn(n_gpu, Hkv, bs, D, device="cuda:0", generator=g).bfloat16()
     vp = torch.randn(n_gpu, Hkv, bs, D, device="cuda:0", generator=g).bfloat16()
-    sk, sv = torch.empty(n_cpu, Hkv, bs, D, device="cuda:0", dtype=torch.bfloat16), \
-        torch.empty(n_cpu, Hkv, bs, D, device="cuda:0", dtype=torch.bfloat16)
+    if swap_area == "pinned host":
+        sk, sv = (torch.empty(n_cpu, Hkv, bs, D, dtype=torch.bfloat16).pin_memory() for _ in range(2))
+    else:
+        sk, sv = (torch.empty(n_cpu, Hkv, bs, D, device="cuda:0", dtype=torch.bfloat16) for _ in range(2))
     bb = Hkv * bs * D * 2
     d_out, d_in = binding.swap_desc(1, bb, n_gpu, n_cpu), binding.swap_desc(1, bb, n_cpu, n_gpu)
     q_all = torch.randn(8192, Hq, D, device="cuda:0", generator=g).bfloat16()
@@ -621,7 +625,12 @@ def serve_loop(torch, binding, steps, mode="recompute", seed=1007, chunked=False
     quiet = steady & (pft == 0) & (pre == 0) & (dec > 0)     # iterations that only decode
     t = s.totals()
     q = lambda a, f: float(np.percentile(a, f)) if a.size else None
-    return {"iterations": len(rec), "mode": mode, "chunked_prefill_budget": 512 if chunked else None,
+    swp = np.array([r[6] for r in rec])
+    swapping = steady & (swp > 0)
+    return {"iterations": len(rec), "mode": mode, "swap_area": swap_area if mode == "swap" else None,
+            "iteration_us_with_swaps_p50_p90": [q(us[swapping], 50), q(us[swapping], 90)] if swapping.any() else None,
+            "blocks_per_swapping_iteration_mean": float(swp[swapping].mean()) if swapping.any() else None,
+            "chunked_prefill_budget": 512 if chunked else None,
             "finished": t["finished"], "preemptions": t["preemptions"],
             "head_blocked_iterations": t["blocked"], "recomputed_tokens": t["recomputed"],
             "swapped_blocks": t["swap_out"] + t["swap_in"],
@@ -882,6 +891,8 @@ def main():
         log(f"[bench] time model: {result['time_model']}")
     if args.serve > 0:
         result["serving_loop"] = {m: serve_loop(torch, binding, args.serve, mode=m) for m in ("recompute", "swap")}
+        result["serving_loop"]["swap_to_pinned_host"] = serve_loop(torch, binding, args.serve, mode="swap",
+                                                                   swap_area="pinned host")
         result["serving_loop"]["recompute_chunked_prefill"] = serve_loop(torch, binding, args.serve, mode="recompute",
                                                                          chunked=True)
         log(f"[bench] serving loop: {result['serving_loop']}")
