@@ -146,3 +146,44 @@ def test_swap_out_to_pinned_host_and_back_is_bit_exact(staging_pairs, side_strea
     ref_pool = np.full(sw.pool_bytes, 0x5A, np.uint8)
     oracle.kv_block_swap(ref, ref_pool, sw.scatter_mapping, num_planes=planes, block_bytes=bb)
     assert np.array_equal(d_new.cpu().numpy(), ref_pool)                # blocks in place, nothing else touched
+
+
+def test_swap_out_to_host_beside_decode_calls_on_another_stream():
+    """The paper's setting: a victim's blocks leave while the other requests keep decoding.  The
+    unstaged swap-out runs on one stream, planned decode calls over other pools on a second one;
+    the calls share nothing, so both results are what they are alone."""
+    import oracle
+    import torch
+    from helpers import run_oracle, to_device
+    from paper_2602_07878_amd import binding
+    planes, bb = 8, 32768
+    sw = W.make_swap_workload("beside", 91, victim_lens=(3000, 2000, 4000, 1500), num_planes=planes, block_bytes=bb)
+    n = sw.n_blocks
+    pool = W.random_bytes(sw.pool_bytes, 92)
+    d_pool = torch.from_numpy(pool).cuda()
+    host = torch.zeros(planes * n * bb, dtype=torch.uint8).pin_memory()
+    gm = torch.from_numpy(sw.gather_mapping).cuda()
+    out_desc = binding.swap_desc(planes, bb, sw.num_pool_blocks, n)
+    w = W.config2_llama8b(B=16)
+    dev = to_device(w)
+    desc = binding.attn_desc_for(dev["q"], dev["k_pool"], dev["v_pool"], dev["block_tables"],
+                                 max_context_len=w.max_context_len)
+    plan = binding.attn_plan(desc, dev["block_tables"], dev["context_lens"])
+    outs = [torch.zeros(w.B, w.Hq, w.D, device="cuda:0") for _ in range(40)]
+    s_swap, s_dec = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    ws = None
+    for i, o in enumerate(outs):
+        if i == 3:                                    # the decode stream is busy when the swap arrives
+            binding.kv_swap_out_host(out_desc, d_pool, host, gm, stream=s_swap)
+        ws = binding.paged_decode_attention_planned(desc, plan, dev["q"], dev["k_pool"], dev["v_pool"],
+                                                    dev["block_tables"], dev["context_lens"], w.scale, o,
+                                                    workspace=ws, stream=s_dec)
+    torch.cuda.synchronize()
+    ref_host = np.zeros(planes * n * bb, np.uint8)
+    oracle.kv_block_swap(pool, ref_host, sw.gather_mapping, num_planes=planes, block_bytes=bb)
+    assert np.array_equal(host.numpy(), ref_host)
+    ref = run_oracle(w)
+    for o in outs:
+        assert torch.equal(o, outs[0])                # the same bits every call
+    assert np.abs(outs[0].cpu().numpy().astype(np.float64) - ref).max() <= 2e-3
