@@ -494,8 +494,8 @@ __device__ __forceinline__ bool plan_ok(const AttnParams& p) {
 
 template <int GH>
 __global__ __launch_bounds__(kMergeThreads) void attn_stream_merge(const AttnParams p) {
-  __shared__ float sM[kMW], sL[kMW];
-  __shared__ __attribute__((aligned(16))) float sO[kMW][D];
+  __shared__ float sM[kMW], sL[2 * kMW];
+  __shared__ __attribute__((aligned(16))) float sO[2 * kMW][D];
   const int h = blockIdx.x, seq = blockIdx.y, tid = threadIdx.x;
   const int lane = tid & (kWaveSize - 1), wave = tid / kWaveSize;
   const int kvh = h / p.group, gi = h - kvh * p.group;
@@ -522,7 +522,9 @@ __global__ __launch_bounds__(kMergeThreads) void attn_stream_merge(const AttnPar
   if (count <= 1) return;                // finished by the stream kernel (block-uniform)
   const int64_t s0 = de[0];
   const float* ml = p.ws_ml + (s0 * GH + g) * 2;            // partial q at ml[q*GH*2]
-  const float* ov = p.ws_o + (s0 * GH + g) * D + 2 * lane;  // partial q at ov[q*GH*D]
+  // a partial's row is 32 pieces of 16 bytes: each half of a wavefront takes one partial per step
+  const int half = lane >> 5, l32 = lane & 31;
+  const float* ov = p.ws_o + (s0 * GH + g) * D + 4 * l32;   // partial q at ov[q*GH*D]
 
   // reference maximum over all partials
   float M = kNegBig;
@@ -533,24 +535,26 @@ __global__ __launch_bounds__(kMergeThreads) void attn_stream_merge(const AttnPar
   __syncthreads();
   M = fmaxf(fmaxf(sM[0], sM[1]), fmaxf(sM[2], sM[3]));
 
-  // wave w sums partials w, w+4, ... (ascending); lane covers output dims 2*lane, 2*lane+1
-  float L = 0.f, O0 = 0.f, O1 = 0.f;
-#pragma unroll 4
-  for (int q = wave; q < count; q += kMW) {
+  // half-wavefront u = 2 * wave + half sums partials u, u+8, ... (ascending), eight rows in
+  // flight each; a lane covers output dims 4*l32 .. 4*l32+3
+  float L = 0.f;
+  f32x4 O = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 8
+  for (int q = 2 * wave + half; q < count; q += 2 * kMW) {
     const f32x2 mlq = *reinterpret_cast<const f32x2*>(ml + (int64_t)q * GH * 2);
-    const f32x2 oq = *reinterpret_cast<const f32x2*>(ov + (int64_t)q * GH * D);
+    const f32x4 oq = *reinterpret_cast<const f32x4*>(ov + (int64_t)q * GH * D);
     const float f = __builtin_amdgcn_exp2f(mlq[0] - M);
     L = fmaf(mlq[1], f, L);
-    O0 = fmaf(oq[0], f, O0);
-    O1 = fmaf(oq[1], f, O1);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) O[i] = fmaf(oq[i], f, O[i]);
   }
-  sO[wave][2 * lane] = O0;
-  sO[wave][2 * lane + 1] = O1;
-  if (lane == 0) sL[wave] = L;
+  *reinterpret_cast<f32x4*>(&sO[2 * wave + half][4 * l32]) = O;
+  if (l32 == 0) sL[2 * wave + half] = L;
   __syncthreads();
   if (tid < D) {
-    const float Lt = (sL[0] + sL[1]) + (sL[2] + sL[3]);
-    const float r = ((sO[0][tid] + sO[1][tid]) + (sO[2][tid] + sO[3][tid])) / Lt * p.v_scale;
+    const float Lt = ((sL[0] + sL[1]) + (sL[2] + sL[3])) + ((sL[4] + sL[5]) + (sL[6] + sL[7]));
+    const float r = (((sO[0][tid] + sO[1][tid]) + (sO[2][tid] + sO[3][tid])) +
+                     ((sO[4][tid] + sO[5][tid]) + (sO[6][tid] + sO[7][tid]))) / Lt * p.v_scale;
     if (p.out_is_bf16) reinterpret_cast<uint16_t*>(p.out)[o + tid] = (uint16_t)(pack_bf16x2_rne(r, 0.f) & 0xFFFFu);
     else reinterpret_cast<float*>(p.out)[o + tid] = r;
   }
