@@ -30,6 +30,13 @@ struct alignas(16) U4 { uint32_t x, y, z, w; };
 __device__ __forceinline__ U4 load16(const uint8_t* p) {
   return *reinterpret_cast<const U4*>(p);
 }
+// K/V bytes that no other workgroup reads again: marked as such, they do not push the tables and
+// query rows out of L2
+__device__ __forceinline__ U4 load16_once(const uint8_t* p) {
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+  return U4{v[0], v[1], v[2], v[3]};
+}
 
 // ---- 16-lane (and narrower) all-reduce sums through DPP -------------------
 template <int CTRL>
@@ -175,8 +182,16 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_valu(const AttnPara
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
       const int slot = slot0 + j * TPL + rg;   // < block_size: tiles never straddle blocks
-      t.k[j] = load16(kb + slot * p.k_stride_token);
-      t.v[j] = load16(vb + slot * p.v_stride_token);
+      // (with one or two heads per workgroup the loads bound the kernel and the hint pays: 16/8
+      // heads of 256 dims 52 -> 55 % of the HBM peak; with four or more the vector ALU does, and
+      // it cost 2 %: those keep the plain load)
+      if constexpr (GT <= 2) {
+        t.k[j] = load16_once(kb + slot * p.k_stride_token);
+        t.v[j] = load16_once(vb + slot * p.v_stride_token);
+      } else {
+        t.k[j] = load16(kb + slot * p.k_stride_token);
+        t.v[j] = load16(vb + slot * p.v_stride_token);
+      }
     }
   };
 
