@@ -293,7 +293,8 @@ int32_t paged_decode_attention_planned_append(const pkv_attn_desc* desc, const v
  * of a block table row: at most 16 Ki blocks per sequence); max_query_len is a
  * host-known upper bound of all query_lens (it sizes the grid).  Supported: bf16 K/V/q, head_dim 128,
  * block_size a power-of-two multiple of 16 (PKV_ERR_SHAPE / PKV_ERR_DTYPE
- * otherwise); out is fp32 or bf16 per desc->out_dtype.  No workspace.  Rows of
+ * otherwise); out is fp32 or bf16 per desc->out_dtype.  No workspace (8-bit
+ * pools need one: paged_prefill_attention_ws below, PKV_ERR_WORKSPACE here).  Rows of
  * sequences with query_lens[i] = 0 do not exist; query_lens[i] > context_lens[i]
  * is clipped.  batch = 0 or max_query_len = 0 enqueues nothing.
  */
@@ -325,6 +326,17 @@ int32_t paged_prefill_attention(const pkv_attn_desc* desc, const void* q, const 
  * total_query_tokens must not be smaller than cu_query_lens[batch].  Contents
  * of the workspace on return are unspecified; one buffer must not serve two
  * calls at the same time.  Results agree with the unsplit call to rounding.
+ *
+ * 8-bit pools (desc->kv_dtype = PKV_F8_E4M3 beside a bf16 q; K = k_scale times
+ * the stored value, V = v_scale times, as in paged_decode_attention): the call
+ * first decodes the blocks of the call's sequences into a bf16 copy at the head
+ * of the workspace (exactly; block j of sequence i becomes block
+ * i * ceil(max_context_len / block_size) + j of the copy) and walks the copy;
+ * the scales act on the softmax scale and on the output.  The workspace is
+ * then required, also for an unsplit walk, and pkv_prefill_workspace_bytes
+ * counts the copy: 2 * batch * ceil(max_context_len / block_size) blocks of
+ * num_kv_heads * block_size * head_dim bf16 values, their table, then what
+ * the split needs.
  */
 size_t pkv_prefill_workspace_bytes(const pkv_attn_desc* desc, int64_t total_query_tokens,
                                    int32_t max_query_len);

@@ -204,7 +204,7 @@ def kv_append_chunk(k_pool, v_pool, k_new, v_new, block_tables, context_lens, qu
 
 
 def paged_prefill_attention(q, k_pool, v_pool, block_tables, context_lens, query_lens, scale,
-                            *, block_size, k_strides=None, v_strides=None):
+                            *, block_size, k_strides=None, v_strides=None, k_scale=1.0, v_scale=1.0):
     """Causal attention of the last query_lens[i] tokens of every sequence over the paged cache
     (the prefill / re-prefill of the recompute recovery path, arXiv 2602.07878 Sec. 2.1 and
     Sec. 5.1.2: a token attends to itself and to everything before it).
@@ -235,5 +235,6 @@ def paged_prefill_attention(q, k_pool, v_pool, block_tables, context_lens, query
     keep = j < live[rows_seq]
     if keep.any():
         out[keep] = paged_decode_attention(q[keep], k_pool, v_pool, bt[rows_seq[keep]], ctx[keep], scale,
-                                           block_size=block_size, k_strides=k_strides, v_strides=v_strides)
+                                           block_size=block_size, k_strides=k_strides, v_strides=v_strides,
+                                           k_scale=k_scale, v_scale=v_scale)
     return out

@@ -312,7 +312,8 @@ def swap_desc(num_planes: int, block_bytes: int, src_num_blocks: int, dst_num_bl
 
 
 def prefill_workspace_bytes(desc: AttnDesc, total_query_tokens: int, max_query_len: int) -> int:
-    """Bytes of device workspace with which paged_prefill_attention splits the walks (0: it will not)."""
+    """Bytes of device workspace with which paged_prefill_attention splits the walks (0: it will
+    not), plus, for 8-bit pools, the bf16 copy of the sequences' blocks that the call walks."""
     return int(lib().pkv_prefill_workspace_bytes(ctypes.byref(desc), int(total_query_tokens), int(max_query_len)))
 
 

@@ -353,8 +353,11 @@ int32_t paged_decode_attention_planned_timed(const pkv_attn_desc* desc, const vo
 size_t pkv_prefill_workspace_bytes(const pkv_attn_desc* desc, int64_t total_query_tokens,
                                    int32_t max_query_len) {
   if (check_attn_desc(desc) != PKV_OK || max_query_len <= 0 || total_query_tokens <= 0) return 0;
-  if (desc->kv_dtype != PKV_BF16 || !attn_prefill_supported(*desc)) return 0;
-  return prefill_workspace_bytes(*desc, total_query_tokens, max_query_len);
+  pkv_attn_desc b = *desc;                     // the kernel's own view: bf16 pools (8-bit ones are copied)
+  if (desc->kv_dtype == PKV_F8_E4M3) b.kv_dtype = PKV_BF16;
+  if (b.kv_dtype != PKV_BF16 || !attn_prefill_supported(b)) return 0;
+  const size_t split = prefill_workspace_bytes(b, total_query_tokens, max_query_len);
+  return desc->kv_dtype == PKV_F8_E4M3 ? f8_prefill_copy_layout(*desc).total() + split : split;
 }
 
 int32_t paged_prefill_attention(const pkv_attn_desc* desc, const void* q, const void* k_pool,
@@ -376,8 +379,11 @@ int32_t paged_prefill_attention_ws(const pkv_attn_desc* desc, const void* q, con
   if (st != PKV_OK) return st;
   if (max_query_len < 0 || total_query_tokens < 0) return PKV_ERR_SHAPE;
   if (desc->batch == 0 || max_query_len == 0) return PKV_OK;
-  if (desc->kv_dtype != PKV_BF16) return PKV_ERR_DTYPE;
-  if (!attn_prefill_supported(*desc)) return PKV_ERR_SHAPE;
+  const bool f8 = desc->kv_dtype == PKV_F8_E4M3;
+  if (desc->kv_dtype != PKV_BF16 && !f8) return PKV_ERR_DTYPE;
+  pkv_attn_desc bdesc = *desc;                 // what the kernel walks: bf16 pools
+  bdesc.kv_dtype = PKV_BF16;
+  if (!attn_prefill_supported(bdesc)) return PKV_ERR_SHAPE;
   if (!q || !k_pool || !v_pool || !block_tables || !context_lens || !query_lens || !cu_query_lens || !out)
     return PKV_ERR_NULL;
   if (!aligned16(q) || !aligned16(k_pool) || !aligned16(v_pool) || !aligned16(out) ||
@@ -401,18 +407,46 @@ int32_t paged_prefill_attention_ws(const pkv_attn_desc* desc, const void* q, con
   p.max_blocks_per_seq = desc->max_blocks_per_seq;
   p.group = desc->num_q_heads / desc->num_kv_heads;
   p.out_is_bf16 = desc->out_dtype == PKV_BF16;
-  p.scale_log2e = scale * 1.4426950408889634f;
-  p.v_scale = 1.0f;
+  p.scale_log2e = scale * pool_scale(desc, desc->k_scale) * 1.4426950408889634f;
+  p.v_scale = pool_scale(desc, desc->v_scale);
+  if (!std::isfinite(p.scale_log2e) || !std::isfinite(p.v_scale)) return PKV_ERR_SHAPE;
+  uint8_t* ws = static_cast<uint8_t*>(workspace);
+  size_t ws_left = workspace ? workspace_bytes : 0;
+  if (f8) {
+    // 8-bit pools: the blocks of the call's sequences are decoded into a bf16 copy at the head
+    // of the workspace, and the kernel walks the copy through the copy's own block table
+    const F8PrefillCopy c = f8_prefill_copy_layout(*desc);
+    if (!workspace || ws_left < c.total()) return PKV_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return PKV_ERR_ALIGN;
+    AttnParams src = p;                        // the 8-bit pools: one byte per element
+    src.k_stride_block = desc->k_stride_block; src.k_stride_head = desc->k_stride_head;
+    src.k_stride_token = desc->k_stride_token;
+    src.v_stride_block = desc->v_stride_block; src.v_stride_head = desc->v_stride_head;
+    src.v_stride_token = desc->v_stride_token;
+    uint8_t* k_copy = ws;
+    uint8_t* v_copy = ws + c.pool_bytes;
+    int32_t* table = reinterpret_cast<int32_t*>(ws + 2 * c.pool_bytes);
+    const hipError_t e = launch_f8_blocks_to_bf16(src, k_copy, v_copy, table, c.blocks_per_seq,
+                                                  static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return hip_status(e);
+    p.k_pool = k_copy; p.v_pool = v_copy; p.block_tables = table;
+    p.max_blocks_per_seq = c.blocks_per_seq;
+    p.k_stride_token = p.v_stride_token = (int64_t)desc->head_dim * 2;
+    p.k_stride_head = p.v_stride_head = p.k_stride_token * desc->block_size;
+    p.k_stride_block = p.v_stride_block = p.k_stride_head * desc->num_kv_heads;
+    ws += c.total();
+    ws_left -= c.total();
+  }
   // the walks are split only if the caller brought the workspace for it
   p.max_partitions = 1;
-  if (workspace && total_query_tokens > 0) {
-    const int ns = prefill_splits(*desc, max_query_len);
-    const size_t need = prefill_workspace_bytes(*desc, total_query_tokens, max_query_len);
+  if (ws_left > 0 && total_query_tokens > 0) {
+    const int ns = prefill_splits(bdesc, max_query_len);
+    const size_t need = prefill_workspace_bytes(bdesc, total_query_tokens, max_query_len);
     if (ns > 1) {
-      if (workspace_bytes < need) return PKV_ERR_WORKSPACE;
-      if (!aligned16(workspace)) return PKV_ERR_ALIGN;
+      if (ws_left < need) return PKV_ERR_WORKSPACE;
+      if (!aligned16(ws)) return PKV_ERR_ALIGN;
       p.max_partitions = ns;
-      p.ws_ml = static_cast<float*>(workspace);
+      p.ws_ml = reinterpret_cast<float*>(ws);
       p.ws_o = p.ws_ml + (size_t)total_query_tokens * desc->num_q_heads * ns * 2;
     }
   }

@@ -590,7 +590,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_mfma_d128(const Attn
     for (int e = 0; e < 4; ++e) {
       const int qq = 8 * k + 4 * hl + e;                 // query of accumulator register 4k + e
       if (qw + qq < ql) {
-        const float inv = 1.0f / (xchg[qq] + xchg[32 + qq]);
+        const float inv = (1.0f / (xchg[qq] + xchg[32 + qq])) * p.v_scale;   // (the V factor of 8-bit pools, else 1)
         const int64_t o = ((row0 + qq) * p.num_q_heads + head) * D + c32;
 #pragma unroll
         for (int nb = 0; nb < 4; ++nb) {
@@ -638,7 +638,7 @@ __global__ __launch_bounds__(256) void attn_prefill_merge(const AttnParams p) {
     o0 += o.x * w;
     o1 += o.y * w;
   }
-  const float inv = 1.0f / l;
+  const float inv = (1.0f / l) * p.v_scale;
   if (p.out_is_bf16) reinterpret_cast<uint32_t*>(p.out)[item * (D / 2) + lane] = bf16x2_rne(o0 * inv, o1 * inv);
   else *reinterpret_cast<float2*>(reinterpret_cast<float*>(p.out) + item * D + 2 * lane) = float2{o0 * inv, o1 * inv};
 }

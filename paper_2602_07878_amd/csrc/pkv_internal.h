@@ -128,6 +128,17 @@ hipError_t launch_attn_prefill(AttnParams& p, int max_query_len, int max_context
                                hipStream_t s);
 int prefill_splits(const pkv_attn_desc& d, int max_query_len);
 size_t prefill_workspace_bytes(const pkv_attn_desc& d, int64_t total_query_tokens, int max_query_len);
+
+// dequant.hip: the bf16 copy of the blocks a prefill call over 8-bit pools reads
+struct F8PrefillCopy {
+  int32_t blocks_per_seq;   // rows of the copy's block table
+  size_t pool_bytes;        // of the K copy, and of the V copy
+  size_t table_bytes;
+  size_t total() const { return 2 * pool_bytes + table_bytes; }
+};
+F8PrefillCopy f8_prefill_copy_layout(const pkv_attn_desc& d);
+hipError_t launch_f8_blocks_to_bf16(const AttnParams& p, uint8_t* k_copy, uint8_t* v_copy, int32_t* copy_table,
+                                    int blocks_per_seq, hipStream_t s);
 // append.hip (uses the pointers, strides and shapes of AttnParams; q/out unused)
 hipError_t launch_kv_append(const AttnParams& p, const void* k_new, const void* v_new, int elem_bytes,
                             hipStream_t s);

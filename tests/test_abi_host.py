@@ -155,6 +155,14 @@ def test_prefill_workspace_size_and_host_side_rejections():
     assert f(0x9008, need) == ST["ALIGN"]
     assert f(0x9000, need, total=-1) == ST["SHAPE"]
     assert f(0x9000, need, q=0) == ST["NULL"]
+    # 8-bit pools: the call decodes the sequences' blocks into a bf16 copy at the head of the
+    # workspace (K and V images of batch x ceil(max context / block) blocks, then their table)
+    d8 = good_desc(batch=1, max_context_len=8192, max_blocks_per_seq=512, num_pool_blocks=1024, kv_dtype=2)
+    copy = 2 * 512 * (8 * 16 * 128 * 2) + 512 * 4
+    assert L.pkv_prefill_workspace_bytes(ctypes.byref(d8), 512, 512) == copy + need
+    f8 = lambda ws, wsb: L.paged_prefill_attention_ws(
+        ctypes.byref(d8), 0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, 0x7000, 512, 512, 0.1, 0x8000, ws, wsb, None)
+    assert f8(None, 0) == ST["WORKSPACE"] and f8(0x9000, copy - 16) == ST["WORKSPACE"] and f8(0x9008, copy) == ST["ALIGN"]
 
 
 def test_swap_host_leg_rejects_bad_arguments_on_host():

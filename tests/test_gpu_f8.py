@@ -164,7 +164,7 @@ def test_unsupported_combinations_are_refused():
                                                   dev["v_pool"].data_ptr(), dev["block_tables"].data_ptr(),
                                                   dev["context_lens"].data_ptr(), 0.1, out.data_ptr(), None, 0, None)
         assert binding.status_string(st) == status
-    # the prefill call has no 8-bit variant
+    # the prefill call over 8-bit pools needs a workspace (for the bf16 copy of the blocks): refused without
     z = torch.zeros(4, dtype=torch.int32, device="cuda:0")
     with pytest.raises(binding.PkvError):
         binding.paged_prefill_attention(desc, dev["q"], dev["k_pool"], dev["v_pool"], dev["block_tables"],

@@ -659,6 +659,25 @@ def test_f8_scales_equal_prescaled_wider_pools_and_poison_is_not_read():
     assert np.array_equal(got, wide)
 
 
+def test_f8_prefill_is_the_prefill_of_prescaled_wider_pools():
+    """The prefill oracle over 8-bit pools hands the pools' scales on to its decode rows: a chunk
+    over a cached prefix equals, bit for bit, the same chunk over bf16 pools that hold
+    scale * value (powers of two: exact in bf16); with the scales left out it does not."""
+    w = W.make_attn_workload("t8p", 17, dtype="f8", Hq=4, Hkv=2, D=16, block_size=16,
+                             context_lens=(40, 7, 33), pool_factor=1.5, poison=True)
+    ql = np.array([9, 7, 1], np.int32)
+    q = W.f32_to_bf16_bits(np.random.default_rng(18).standard_normal((int(ql.sum()), 4, 16)).astype(np.float32))
+    got = oracle.paged_prefill_attention(q, w.k_pool, w.v_pool, w.block_tables, w.context_lens, ql, w.scale,
+                                         block_size=16, k_scale=0.5, v_scale=8.0)
+    kb = W.f32_to_bf16_bits((torch_f8_to_f64(w.k_pool) * 0.5).astype(np.float32))
+    vb = W.f32_to_bf16_bits((torch_f8_to_f64(w.v_pool) * 8.0).astype(np.float32))
+    wide = oracle.paged_prefill_attention(q, kb, vb, w.block_tables, w.context_lens, ql, w.scale, block_size=16)
+    assert np.isfinite(got).all() and np.array_equal(got, wide)
+    plain = oracle.paged_prefill_attention(q, w.k_pool, w.v_pool, w.block_tables, w.context_lens, ql, w.scale,
+                                           block_size=16)
+    assert np.abs(plain - got).max() > 0.1
+
+
 def test_f8_generator_rounds_to_nearest_even_and_saturates():
     """The input generator's float32 -> E4M3 rounding against the library conversion (in range), and
     its closed-form corner cases."""
