@@ -356,16 +356,19 @@ def time_swap_host(sw, torch, binding, staging_mib=256, reps=2, decode_batch=Non
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 matrix-core rate
 
 
-def time_prefill(torch, binding, B=16, n=4096, Hq=32, Hkv=8, reps=5, oracle_rows=256):
+def time_prefill(torch, binding, B=16, n=4096, Hq=32, Hkv=8, reps=5, oracle_rows=256, f8=False):
     """Re-prefill of B preempted requests of n tokens each (the recompute recovery path): causal
     attention of all n tokens over the paged cache, 8B-shaped heads.  Flops counted: 4*D per
-    (query, visible key) pair and query head, i.e. the causal half only."""
+    (query, visible key) pair and query head, i.e. the causal half only.  f8: the pools hold E4M3
+    codes (the call then walks a bf16 copy it makes in its workspace)."""
     D, bs = 128, 16
     nblk = B * ((n + bs - 1) // bs)
     g = torch.Generator(device="cuda:0")
     g.manual_seed(1006)
     kp = torch.randn(nblk, Hkv, bs, D, device="cuda:0", generator=g).bfloat16()
     vp = torch.randn(nblk, Hkv, bs, D, device="cuda:0", generator=g).bfloat16()
+    if f8:
+        kp, vp = (t.to(torch.float8_e4m3fn).view(torch.uint8) for t in (kp, vp))
     bt = torch.randperm(nblk, device="cuda:0", generator=g).int().view(B, -1)
     cl = torch.full((B,), n, dtype=torch.int32, device="cuda:0")
     cu = torch.arange(0, (B + 1) * n, n, dtype=torch.int32, device="cuda:0")
@@ -373,7 +376,9 @@ def time_prefill(torch, binding, B=16, n=4096, Hq=32, Hkv=8, reps=5, oracle_rows
     out = torch.empty(B * n, Hq, D, device="cuda:0")
     desc = binding.attn_desc_for(q, kp, vp, bt, max_context_len=n)
     desc.batch = B
-    f = lambda: binding.paged_prefill_attention(desc, q, kp, vp, bt, cl, cl, cu, n, D ** -0.5, out)
+    need = binding.prefill_workspace_bytes(desc, B * n, n)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda:0") if need else None
+    f = lambda: binding.paged_prefill_attention(desc, q, kp, vp, bt, cl, cl, cu, n, D ** -0.5, out, workspace=ws)
     f()
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -384,7 +389,8 @@ def time_prefill(torch, binding, B=16, n=4096, Hq=32, Hkv=8, reps=5, oracle_rows
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1) / reps
     flops = 4.0 * D * (n * (n + 1) // 2) * Hq * B
-    res = {"workload": f"causal re-prefill, {B} sequences x {n} tokens, {Hq}/{Hkv} heads, bf16", "ms": ms,
+    res = {"workload": f"causal re-prefill, {B} sequences x {n} tokens, {Hq}/{Hkv} heads, "
+                       f"{'bf16 q over 8-bit (E4M3) pools' if f8 else 'bf16'}", "ms": ms, "workspace_MiB": need >> 20,
            "tflops": flops / ms / 1e9, "bound": "mfma", "peak_tflops": MFMA_BF16_PEAK_TFLOPS,
            "frac": flops / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS}
     if oracle_rows:
@@ -398,7 +404,8 @@ def prefill_error(torch, q, kp, vp, bt, ctx_lens, q_lens, out, rows, scale):
     """Max abs error of the sampled packed output rows (all heads) against the fp64 oracle: a query
     token is one decode-oracle row over the positions it may see."""
     import oracle
-    bits = lambda t: t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+    bits = lambda t: (t.contiguous().cpu().numpy() if t.dtype == torch.uint8      # E4M3 codes as they are
+                      else t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16))
     cu = np.concatenate([[0], np.cumsum(q_lens)])
     seq = np.searchsorted(cu, rows, side="right") - 1
     ctx = (np.asarray(ctx_lens)[seq] - np.asarray(q_lens)[seq] + (rows - cu[seq]) + 1).astype(np.int32)
@@ -776,6 +783,8 @@ def main():
     result["ceilings"] = probe_ceilings(torch, binding)
     result["prefill"] = time_prefill(torch, binding)
     log(f"[bench] prefill: {result['prefill']}")
+    result["prefill_kv_f8e4m3"] = time_prefill(torch, binding, f8=True)
+    log(f"[bench] prefill over 8-bit pools: {result['prefill_kv_f8e4m3']}")
     result["prefill_chunk"] = time_prefill_chunk(torch, binding)
     log(f"[bench] prefill chunk: {result['prefill_chunk']}")
     log(f"[bench] ceilings: {result['ceilings']}")
