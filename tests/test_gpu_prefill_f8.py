@@ -116,3 +116,40 @@ def test_bf16_output():
 def test_a_short_workspace_is_refused():
     lens = (300, 100)
     run(mk(607, lens), (300, 100), short_workspace=True)
+
+
+def test_chunk_of_8_bit_rows_appended_then_attended():
+    """A step of chunked prefill on a quantised cache: the chunk's K/V codes join the pools
+    (kv_append_chunk: bytes), then the chunk attends over prefix and itself; pools bit-identical
+    to the oracle's, attention within tolerance."""
+    import oracle
+    import torch
+    from paper_2602_07878_amd import binding
+    lens, qlens = (600, 90, 1300), (100, 90, 512)
+    w = mk(608, lens, Hq=16, Hkv=4, k_scale=0.8, v_scale=1.5)
+    ql = np.asarray(qlens, np.int32)
+    total = int(ql.sum())
+    rng = np.random.default_rng(609)
+    kn = W.f32_to_f8e4m3_bits(rng.standard_normal((total, w.Hkv, w.D)).astype(np.float32))
+    vn = W.f32_to_f8e4m3_bits(rng.standard_normal((total, w.Hkv, w.D)).astype(np.float32))
+    q = W.f32_to_bf16_bits(rng.standard_normal((total, w.Hq, w.D)).astype(np.float32))
+    dev = to_device(w)
+    dq = torch.from_numpy(q.view(np.int16)).cuda().view(torch.bfloat16)
+    d_ql = torch.from_numpy(ql).cuda()
+    cu = torch.from_numpy(np.concatenate([[0], np.cumsum(ql)]).astype(np.int32)).cuda()
+    desc = binding.attn_desc_for(dq, dev["k_pool"], dev["v_pool"], dev["block_tables"], max_context_len=w.max_context_len,
+                                 k_scale=w.k_scale, v_scale=w.v_scale)
+    desc.batch = w.B
+    binding.kv_append_chunk(desc, torch.from_numpy(kn).cuda(), torch.from_numpy(vn).cuda(), dev["k_pool"], dev["v_pool"],
+                            dev["block_tables"], dev["context_lens"], d_ql, cu)
+    out = torch.zeros(total, w.Hq, w.D, device="cuda")
+    ws = torch.empty(binding.prefill_workspace_bytes(desc, total, int(ql.max())), dtype=torch.uint8, device="cuda")
+    binding.paged_prefill_attention(desc, dq, dev["k_pool"], dev["v_pool"], dev["block_tables"], dev["context_lens"],
+                                    d_ql, cu, int(ql.max()), w.scale, out, workspace=ws)
+    torch.cuda.synchronize()
+    oracle.kv_append_chunk(w.k_pool, w.v_pool, kn, vn, w.block_tables, w.context_lens, ql, block_size=w.block_size)
+    assert np.array_equal(dev["k_pool"].cpu().numpy(), w.k_pool) and np.array_equal(dev["v_pool"].cpu().numpy(), w.v_pool)
+    ref = oracle.paged_prefill_attention(q, w.k_pool, w.v_pool, w.block_tables, w.context_lens, ql, w.scale,
+                                         block_size=w.block_size, k_scale=w.k_scale, v_scale=w.v_scale)
+    got = out.cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(got)) and np.abs(got - ref).max() <= TOL * max(1.0, w.v_scale)
